@@ -1,0 +1,203 @@
+/*
+ * spin.h -- C ABI of the per-decode-step sparse-attention hot path on MI355X.
+ *
+ * One decode step of one layer runs four stages, each a call below:
+ *
+ *   spin_score_partitions   Select, scoring half   (Section 4.1 "Select"; Table 1, score(q, k_sums))
+ *   spin_select_topk        Select, top-k half     (Table 1, "-> topk"; Section 4.2)
+ *   spin_resolve_slots      Retrieve, lookup half  (Section 5.2 steps 1-2; Section 5.3 bucketed LRU;
+ *                                                   Section 5.4 two-level tables)
+ *   spin_sparse_decode      Attention              (Section 4.1 "Attention")
+ *
+ * plus two set-up calls that materialise the layouts the stages read
+ * (spin_pack_kv_pages: Offload's "materialise the partitioned layout";
+ *  spin_build_summaries: Index's per-partition summaries, Section 4.1 / Table 1).
+ *
+ * Conventions
+ * -----------
+ * - Every pointer named below as DEVICE points to HBM owned by the caller; the
+ *   library never allocates, frees or synchronises inside a stage call.  The
+ *   library owns only the host-side spin_ctx.
+ * - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   Calls enqueue kernels on it and return.
+ * - Return value: SPIN_OK (0) or a negative spin_status.  Host-checkable
+ *   mistakes (NULL pointer, batch > max_batch, unsupported shape) are returned
+ *   before anything is launched.  Faults only the device can see (a selected
+ *   page that is not resident, a slot id outside the pool, a budget smaller
+ *   than the step's selection) set a sticky status word inside `workspace`,
+ *   read back by spin_poll_status(); the offending page/row is skipped so no
+ *   access leaves its buffer.
+ * - A "row" is one (request b, KV head h) pair, row = b * num_kv_heads + h.
+ *   Everything is independent per row.
+ * - Identical inputs give identical output bits, run to run.
+ *
+ * Data layout in HBM (all little endian, bf16 = upper half of an IEEE binary32)
+ * ---------------------------------------------------------------------------
+ * q            bf16 [batch][num_q_heads][128]
+ * kv_pool      one SLOT = one physical page of ONE KV head (head-wise pages,
+ *              Section 5.2) = 8192 bytes: the K tile (4096 B) then the V tile
+ *              (4096 B) of 16 tokens x 128 channels, each stored in the register
+ *              image of the matrix-core operand that consumes it, so that every
+ *              wavefront load is one contiguous 1 KiB transaction:
+ *                K[t][d] at element ((d/32)*64 + ((d%32)/8)*16 + t)*8 + d%8
+ *                V[t][d] at element ((((d/32)*64 + (t/4)*16 + d%16)*2 + (d/16)%2)*4) + t%4
+ *              Use spin_pack_kv_pages to write pages in this layout.
+ * part_offsets int32 [batch+1], prefix sum over requests of their partition
+ *              count rounded up to a multiple of 16 (SPIN_PART_ALIGN).  Row
+ *              (b,h) owns entries [num_kv_heads*part_offsets[b] + h*PP_b, +PP_b)
+ *              of `scores` and of the summary array, PP_b = part_offsets[b+1]-part_offsets[b].
+ * summaries    per 16 consecutive partition-rows one TILE, chunk-major
+ *              [KD/8][16][8] bf16 where KD is the contraction length:
+ *                MINMAX  row = partition,       KD = 256: [max(128) | min(128)]
+ *                REPMAX  row = partition*R + r, KD = 128: representative r
+ *                SKETCH  row = token,           KD = sketch_channels (16)
+ *              (written by spin_build_summaries).
+ * dir          int32 [rows][dir_stride], dir_stride = ceil(ceil(max_context/page_tokens)/leaf_entries);
+ *              entry = index of a leaf chunk in leaf_pool, or -1 (no leaf allocated).
+ * leaf_pool    int32 [chunks][leaf_entries]; entry = slot of that logical page, or -1.
+ */
+#ifndef SPIN_H
+#define SPIN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct spin_ctx spin_ctx; /* opaque, host side */
+
+enum spin_status {
+  SPIN_OK = 0,
+  SPIN_ERR_INVALID = -1,      /* bad argument */
+  SPIN_ERR_UNSUPPORTED = -2,  /* shape or mode not built */
+  SPIN_ERR_WORKSPACE = -3,    /* workspace missing */
+  SPIN_ERR_HIP = -4,          /* a HIP runtime call failed */
+  SPIN_ERR_BUDGET = -5,       /* device: a row's slot budget cannot hold its selection */
+  SPIN_ERR_NOT_RESIDENT = -6, /* device: a selected page has no leaf or no slot */
+  SPIN_ERR_SLOT_RANGE = -7    /* device: a slot id lies outside the pool */
+};
+
+enum spin_score_kind { SPIN_SCORE_MINMAX = 0, SPIN_SCORE_SKETCH = 1, SPIN_SCORE_REPMAX = 2 };
+
+#define SPIN_PART_ALIGN 16
+#define SPIN_SLOT_BYTES 8192
+
+typedef struct spin_config {
+  int32_t max_batch;
+  int32_t num_q_heads;          /* multiple of num_kv_heads; group size <= 16 */
+  int32_t num_kv_heads;
+  int32_t head_dim;             /* 128 */
+  int32_t page_tokens;          /* 16 */
+  int32_t partition_tokens;     /* divides 16, or a multiple of 16 */
+  int32_t score_kind;           /* spin_score_kind */
+  int32_t sketch_channels;      /* 16 (SKETCH) */
+  int32_t reps_per_partition;   /* 4  (REPMAX) */
+  int32_t topk;                 /* partitions per row (tokens when partition_tokens == 1) */
+  int32_t topk_includes_forced; /* 1: forced partitions count against topk; 0: they come on top */
+  int32_t sink_pages;           /* first pages of a context, always attended */
+  int32_t recent_pages;         /* last pages of a context, always attended */
+  int32_t max_context;          /* tokens; sizes strides and the workspace */
+  int32_t leaf_entries;         /* entries per second-level table chunk (512) */
+  int32_t lru_timestamps;       /* 0 = all-resident mode; n > 0 = bucketed LRU with n timestamp values */
+  int32_t lru_evict_exact;      /* 0 = evict whole buckets <= x; 1 = only as many pages of bucket x as needed */
+  int32_t decode_splits;        /* split-K factor of spin_sparse_decode; 0 = choose from the shape */
+  float softmax_scale;          /* 0 = 1/sqrt(head_dim) */
+} spin_config;
+
+/* Create / destroy the host-side context.  `*out` is set only on SPIN_OK. */
+int spin_create(const spin_config *cfg, spin_ctx **out);
+void spin_destroy(spin_ctx *ctx);
+const char *spin_status_string(int status);
+
+/* Sizes the caller needs to allocate buffers. */
+size_t spin_workspace_bytes(const spin_ctx *ctx); /* DEVICE scratch, 256-byte aligned */
+int32_t spin_sel_stride(const spin_ctx *ctx);     /* entries per row of `sel` */
+int32_t spin_page_stride(const spin_ctx *ctx);    /* entries per row of slots / page_ids / valid_mask */
+int32_t spin_dir_stride(const spin_ctx *ctx);     /* entries per row of `dir` */
+int32_t spin_decode_splits(const spin_ctx *ctx);  /* the split-K factor in use */
+/* bytes of the summary array for `padded_partitions` = part_offsets[batch] */
+size_t spin_summary_bytes(const spin_ctx *ctx, int64_t padded_partitions);
+
+/* Clear the workspace's status word (a fill kernel on `stream`; call once after
+ * allocating the workspace and whenever a reported device fault was handled). */
+int spin_workspace_init(spin_ctx *ctx, void *workspace, void *stream);
+/* Synchronise `stream` and return the first device-detected fault since the
+ * last init (SPIN_OK if none). */
+int spin_poll_status(spin_ctx *ctx, const void *workspace, void *stream);
+
+/* Offload, layout half: write `n_pages` pages given in plain token-major order
+ * (src_k, src_v: DEVICE bf16 [n_pages][16][128]) into pool slots `slots[i]`
+ * (DEVICE int32 [n_pages], each in [0, pool_slots)) in the slot layout above. */
+int spin_pack_kv_pages(spin_ctx *ctx, int64_t n_pages, const void *src_k, const void *src_v,
+                       const int32_t *slots, void *kv_pool, int64_t pool_slots, void *stream);
+
+/* Index: build the summaries of every partition of every row from the keys in
+ * the pool, reached through the two-level table (every page must be resident).
+ * MINMAX: elementwise min and max key over the partition's valid tokens.
+ * REPMAX: mean key of each of the R equal sub-ranges, rounded to bf16 (an empty
+ *         sub-range of a ragged last partition repeats representative 0).
+ * SKETCH: the key restricted to chan_idx[h][0..C) (DEVICE int32 [num_kv_heads][C]).
+ * Rows of a tile beyond the row's last partition are zero-filled. */
+int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv_pool, int64_t pool_slots,
+                         const int32_t *dir, const int32_t *leaf_pool, int64_t leaf_chunks,
+                         const int32_t *part_offsets, const int32_t *seq_lens,
+                         const int32_t *chan_idx, void *summaries, void *workspace, void *stream);
+
+/* Stage 1.  scores[row][p] (DEVICE fp32, indexed like the summaries) =
+ *   MINMAX  max_g sum_d max(q[g][d]*min[p][d], q[g][d]*max[p][d])
+ *   SKETCH  max_g sum_c q[g][chan_idx[h][c]] * sketch[t][c]
+ *   REPMAX  max_g max_r q[g] . rep[p][r]
+ * over the G query heads of the row's group; bf16 inputs, exact products, fp32
+ * accumulation on the matrix cores.  Entries beyond a row's partition count are
+ * unspecified. */
+int spin_score_partitions(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries,
+                          const int32_t *chan_idx, const int32_t *part_offsets,
+                          const int32_t *seq_lens, float *scores, void *workspace, void *stream);
+
+/* Stage 2.  Per row: the forced partitions (all of whose pages are sink or
+ * recent pages) plus the k' best-scoring other partitions, k' = topk - forced
+ * (topk_includes_forced) or topk; ties go to the lower id, +0 and -0 tie, NaN
+ * ranks lowest.  sel (DEVICE int32 [rows][sel_stride]) ascending, padded with
+ * -1; nsel (DEVICE int32 [rows]). */
+int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
+                     const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace,
+                     void *stream);
+
+/* Stage 3.  Expand each row's selection (plus forced pages that lie in no
+ * selected partition) to logical pages, walk dir -> leaf -> slot, and emit, in
+ * ascending page order, slots / page_ids (DEVICE int32 [rows][page_stride]),
+ * valid_mask (DEVICE uint16, bit t = token t of the page is attended) and
+ * npages (DEVICE int32 [rows]).
+ * All-resident mode (lru_timestamps == 0): rev_table, slot_base, miss_* are
+ * NULL; a missing leaf or slot sets SPIN_ERR_NOT_RESIDENT and drops the page.
+ * Budget mode (lru_timestamps == n): row r owns pool slots
+ * [slot_base[r], slot_base[r+1]) (DEVICE int32 [rows+1]); rev_table (DEVICE
+ * int32 [total slots][2] = {resident logical page or -1, timestamp}) and the
+ * leaf entries are updated by the four bucketed-LRU steps; missed pages are
+ * admitted to freed slots (ascending page id -> ascending free slot) and
+ * listed in miss_pages / miss_slots (DEVICE int32 [rows][page_stride]) with
+ * nmiss (DEVICE int32 [rows]) for the copy that must complete before stage 4.
+ * Leaves must exist for every page range a row can select. */
+int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, const int32_t *sel,
+                       const int32_t *nsel, const int32_t *seq_lens, const int32_t *dir,
+                       int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev_table,
+                       const int32_t *slot_base, int32_t *slots, int32_t *page_ids,
+                       uint16_t *valid_mask, int32_t *npages, int32_t *miss_pages,
+                       int32_t *miss_slots, int32_t *nmiss, void *workspace, void *stream);
+
+/* Stage 4.  out[b][hq] (DEVICE bf16 [batch][num_q_heads][128]) =
+ * softmax(scale * q K_S^T) V_S over the tokens whose mask bit is set in the
+ * row's resolved pages; fp32 online softmax, split over the page list and
+ * merged in a fixed order.  lse (DEVICE fp32 [batch][num_q_heads], natural log;
+ * may be NULL).  A row with no valid token gives out = 0, lse = -inf. */
+int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool,
+                       int64_t pool_slots, const int32_t *slots, const uint16_t *valid_mask,
+                       const int32_t *npages, void *out, float *lse, void *workspace,
+                       void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPIN_H */

@@ -1,0 +1,210 @@
+"""ctypes binding of ``libspin.so``: same names as the C ABI, argument
+marshalling only.  torch supplies device memory and the current stream."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+from . import build as _build
+
+_LIB: Optional[C.CDLL] = None
+
+SPIN_OK = 0
+STATUS_NAMES = {0: "SPIN_OK", -1: "SPIN_ERR_INVALID", -2: "SPIN_ERR_UNSUPPORTED", -3: "SPIN_ERR_WORKSPACE",
+                -4: "SPIN_ERR_HIP", -5: "SPIN_ERR_BUDGET", -6: "SPIN_ERR_NOT_RESIDENT",
+                -7: "SPIN_ERR_SLOT_RANGE"}
+
+EXPORTS = [
+    "spin_create", "spin_destroy", "spin_status_string", "spin_workspace_bytes", "spin_sel_stride",
+    "spin_page_stride", "spin_dir_stride", "spin_decode_splits", "spin_summary_bytes",
+    "spin_workspace_init", "spin_poll_status", "spin_pack_kv_pages", "spin_build_summaries",
+    "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
+]
+
+
+class SpinConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "max_batch", "num_q_heads", "num_kv_heads", "head_dim", "page_tokens", "partition_tokens",
+        "score_kind", "sketch_channels", "reps_per_partition", "topk", "topk_includes_forced",
+        "sink_pages", "recent_pages", "max_context", "leaf_entries", "lru_timestamps",
+        "lru_evict_exact", "decode_splits")] + [("softmax_scale", C.c_float)]
+
+
+class SpinError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {STATUS_NAMES.get(code, code)}")
+
+
+def load_library() -> C.CDLL:
+    """Load the in-tree library; there is no fallback if it is missing."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(_build.LIB_PATH):
+        raise RuntimeError(f"{_build.LIB_PATH} is not built: run `python -m paper_2604_26837_amd.build` "
+                           "(the HIP library is required; there is no CPU fallback)")
+    lib = C.CDLL(_build.LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.spin_create.argtypes = [C.POINTER(SpinConfig), C.POINTER(vp)]
+    lib.spin_destroy.argtypes = [vp]
+    lib.spin_destroy.restype = None
+    lib.spin_status_string.argtypes = [C.c_int]
+    lib.spin_status_string.restype = C.c_char_p
+    lib.spin_workspace_bytes.argtypes = [vp]
+    lib.spin_workspace_bytes.restype = C.c_size_t
+    for n in ("spin_sel_stride", "spin_page_stride", "spin_dir_stride", "spin_decode_splits"):
+        getattr(lib, n).argtypes = [vp]
+        getattr(lib, n).restype = i32
+    lib.spin_summary_bytes.argtypes = [vp, i64]
+    lib.spin_summary_bytes.restype = C.c_size_t
+    lib.spin_workspace_init.argtypes = [vp, vp, vp]
+    lib.spin_poll_status.argtypes = [vp, vp, vp]
+    lib.spin_pack_kv_pages.argtypes = [vp, i64, vp, vp, vp, vp, i64, vp]
+    lib.spin_build_summaries.argtypes = [vp, i32, vp, i64, vp, vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.spin_score_partitions.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.spin_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
+    lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
+    for n in EXPORTS:
+        if getattr(lib, n).restype is C.c_int:
+            pass
+    _LIB = lib
+    return lib
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, name="tensor") -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Spin:
+    """Owns one ``spin_ctx``; methods mirror the C entry points one to one."""
+
+    def __init__(self, **cfg):
+        self.lib = load_library()
+        c = SpinConfig()
+        defaults = dict(head_dim=128, page_tokens=16, partition_tokens=16, score_kind=0, sketch_channels=16,
+                        reps_per_partition=4, topk_includes_forced=1, sink_pages=0, recent_pages=0,
+                        leaf_entries=512, lru_timestamps=0, lru_evict_exact=0, decode_splits=0,
+                        softmax_scale=0.0)
+        defaults.update(cfg)
+        for k, v in defaults.items():
+            if not hasattr(c, k):
+                raise TypeError(f"unknown config field {k}")
+            setattr(c, k, v)
+        self.cfg = c
+        h = C.c_void_p()
+        st = self.lib.spin_create(C.byref(c), C.byref(h))
+        if st != SPIN_OK:
+            raise SpinError(st, "spin_create")
+        self.h = h
+        self.sel_stride = self.lib.spin_sel_stride(h)
+        self.page_stride = self.lib.spin_page_stride(h)
+        self.dir_stride = self.lib.spin_dir_stride(h)
+        self.decode_splits = self.lib.spin_decode_splits(h)
+        self.workspace_bytes = self.lib.spin_workspace_bytes(h)
+
+    @classmethod
+    def for_workload(cls, w, **over):
+        cfg = dict(max_batch=w.batch, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads,
+                   head_dim=w.head_dim, page_tokens=w.page_tokens, partition_tokens=w.partition_tokens,
+                   score_kind=w.score_kind, sketch_channels=w.sketch_channels,
+                   reps_per_partition=w.reps_per_partition, topk=w.topk,
+                   topk_includes_forced=int(w.topk_includes_forced), sink_pages=w.sink_pages,
+                   recent_pages=w.recent_pages, max_context=max(max(w.seq_lens), 1),
+                   leaf_entries=w.leaf_entries)
+        cfg.update(over)
+        return cls(**cfg)
+
+    def __del__(self):
+        try:
+            if getattr(self, "h", None):
+                self.lib.spin_destroy(self.h)
+                self.h = None
+        except Exception:
+            pass
+
+    def _check(self, st: int, where: str):
+        if st != SPIN_OK:
+            raise SpinError(st, where)
+
+    # -- plumbing ---------------------------------------------------------
+    def new_workspace(self, device="cuda:0") -> torch.Tensor:
+        ws = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
+        self.workspace_init(ws)
+        return ws
+
+    def workspace_init(self, ws):
+        self._check(self.lib.spin_workspace_init(self.h, _ptr(ws), _stream()), "spin_workspace_init")
+
+    def poll_status(self, ws) -> int:
+        return self.lib.spin_poll_status(self.h, _ptr(ws), _stream())
+
+    def summary_bytes(self, padded_partitions: int) -> int:
+        return self.lib.spin_summary_bytes(self.h, padded_partitions)
+
+    # -- set-up calls -----------------------------------------------------
+    def pack_kv_pages(self, src_k, src_v, slots, kv_pool):
+        n = src_k.shape[0]
+        pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192
+        self._check(self.lib.spin_pack_kv_pages(
+            self.h, n, _ptr(src_k, torch.bfloat16, "src_k"), _ptr(src_v, torch.bfloat16, "src_v"),
+            _ptr(slots, torch.int32, "slots"), _ptr(kv_pool, None, "kv_pool"), pool_slots, _stream()),
+            "spin_pack_kv_pages")
+
+    def build_summaries(self, batch, kv_pool, dir_, leaf_pool, part_offsets, seq_lens, chan_idx, summaries, ws):
+        pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192
+        self._check(self.lib.spin_build_summaries(
+            self.h, batch, _ptr(kv_pool), pool_slots, _ptr(dir_, torch.int32, "dir"),
+            _ptr(leaf_pool, torch.int32, "leaf_pool"), leaf_pool.shape[0],
+            _ptr(part_offsets, torch.int32, "part_offsets"), _ptr(seq_lens, torch.int32, "seq_lens"),
+            _ptr(chan_idx, torch.int32, "chan_idx"), _ptr(summaries), _ptr(ws), _stream()),
+            "spin_build_summaries")
+
+    # -- the four stages --------------------------------------------------
+    def score_partitions(self, batch, q, summaries, chan_idx, part_offsets, seq_lens, scores, ws):
+        self._check(self.lib.spin_score_partitions(
+            self.h, batch, _ptr(q, torch.bfloat16, "q"), _ptr(summaries), _ptr(chan_idx, torch.int32, "chan_idx"),
+            _ptr(part_offsets, torch.int32, "part_offsets"), _ptr(seq_lens, torch.int32, "seq_lens"),
+            _ptr(scores, torch.float32, "scores"), _ptr(ws), _stream()), "spin_score_partitions")
+
+    def select_topk(self, batch, scores, part_offsets, seq_lens, sel, nsel, ws):
+        self._check(self.lib.spin_select_topk(
+            self.h, batch, _ptr(scores, torch.float32, "scores"), _ptr(part_offsets, torch.int32, "part_offsets"),
+            _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(sel, torch.int32, "sel"),
+            _ptr(nsel, torch.int32, "nsel"), _ptr(ws), _stream()), "spin_select_topk")
+
+    def resolve_slots(self, batch, step, sel, nsel, seq_lens, dir_, leaf_pool, slots, page_ids, valid_mask,
+                      npages, ws, rev_table=None, slot_base=None, miss_pages=None, miss_slots=None, nmiss=None):
+        self._check(self.lib.spin_resolve_slots(
+            self.h, batch, step, _ptr(sel, torch.int32, "sel"), _ptr(nsel, torch.int32, "nsel"),
+            _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(dir_, torch.int32, "dir"),
+            _ptr(leaf_pool, torch.int32, "leaf_pool"), leaf_pool.shape[0],
+            _ptr(rev_table, torch.int32, "rev_table"), _ptr(slot_base, torch.int32, "slot_base"),
+            _ptr(slots, torch.int32, "slots"), _ptr(page_ids, torch.int32, "page_ids"),
+            _ptr(valid_mask, torch.int16, "valid_mask"), _ptr(npages, torch.int32, "npages"),
+            _ptr(miss_pages, torch.int32, "miss_pages"), _ptr(miss_slots, torch.int32, "miss_slots"),
+            _ptr(nmiss, torch.int32, "nmiss"), _ptr(ws), _stream()), "spin_resolve_slots")
+
+    def sparse_decode(self, batch, q, kv_pool, slots, valid_mask, npages, out, lse, ws):
+        pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192
+        self._check(self.lib.spin_sparse_decode(
+            self.h, batch, _ptr(q, torch.bfloat16, "q"), _ptr(kv_pool), pool_slots,
+            _ptr(slots, torch.int32, "slots"), _ptr(valid_mask, torch.int16, "valid_mask"),
+            _ptr(npages, torch.int32, "npages"), _ptr(out, torch.bfloat16, "out"),
+            _ptr(lse, torch.float32, "lse"), _ptr(ws), _stream()), "spin_sparse_decode")

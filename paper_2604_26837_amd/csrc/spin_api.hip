@@ -1,0 +1,140 @@
+// Context, sizing and status plumbing of the C ABI (host side).
+#include <math.h>
+#include <new>
+#include <string.h>
+
+#include "spin_common.h"
+
+static inline int32_t cdiv32(int64_t a, int64_t b) { return (int32_t)((a + b - 1) / b); }
+
+extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
+  if (!c || !out) return SPIN_ERR_INVALID;
+  if (c->max_batch <= 0 || c->num_q_heads <= 0 || c->num_kv_heads <= 0 || c->max_context <= 0 ||
+      c->topk < 0 || c->sink_pages < 0 || c->recent_pages < 0 || c->leaf_entries <= 0 ||
+      c->lru_timestamps < 0 || c->decode_splits < 0)
+    return SPIN_ERR_INVALID;
+  if (c->num_q_heads % c->num_kv_heads != 0) return SPIN_ERR_INVALID;
+  if (c->head_dim != SPIN_HEAD_DIM || c->page_tokens != SPIN_PAGE_TOKENS) return SPIN_ERR_UNSUPPORTED;
+  const int32_t group = c->num_q_heads / c->num_kv_heads;
+  if (group > 16) return SPIN_ERR_UNSUPPORTED;
+  const int32_t tp = c->partition_tokens;
+  if (tp <= 0) return SPIN_ERR_INVALID;
+  if (!((tp < 16 && 16 % tp == 0) || (tp >= 16 && tp % 16 == 0))) return SPIN_ERR_UNSUPPORTED;
+  if (c->lru_timestamps > 256) return SPIN_ERR_UNSUPPORTED;
+
+  spin_ctx *x = new (std::nothrow) spin_ctx;
+  if (!x) return SPIN_ERR_INVALID;
+  memset(x, 0, sizeof(*x));
+  x->cfg = *c;
+  x->group = group;
+  x->max_rows = c->max_batch * c->num_kv_heads;
+  x->max_pages = cdiv32(c->max_context, SPIN_PAGE_TOKENS);
+  x->max_parts = cdiv32(c->max_context, tp);
+  x->pages_per_part = tp >= 16 ? tp / 16 : 0;
+  x->parts_per_page = tp < 16 ? 16 / tp : 0;
+
+  switch (c->score_kind) {
+    case SPIN_SCORE_MINMAX: x->kd = 256; x->rows_per_part = 1; break;
+    case SPIN_SCORE_REPMAX:
+      if (c->reps_per_partition != 4 || tp % 4 != 0) { delete x; return SPIN_ERR_UNSUPPORTED; }
+      x->kd = 128; x->rows_per_part = 4; break;
+    case SPIN_SCORE_SKETCH:
+      if (c->sketch_channels != 16) { delete x; return SPIN_ERR_UNSUPPORTED; }
+      x->kd = 16; x->rows_per_part = 1; break;
+    default: delete x; return SPIN_ERR_INVALID;
+  }
+
+  // upper bound of the partitions all of whose pages are forced
+  int64_t forced_max;
+  if (tp >= 16) {
+    const int32_t m = x->pages_per_part;
+    forced_max = cdiv32(c->sink_pages, m) + cdiv32(c->recent_pages, m) + 1;
+    if (c->sink_pages + c->recent_pages == 0) forced_max = 0;
+  } else {
+    forced_max = (int64_t)(c->sink_pages + c->recent_pages) * x->parts_per_page;
+  }
+  int64_t sel = c->topk_includes_forced ? (c->topk > forced_max ? c->topk : forced_max)
+                                        : (int64_t)c->topk + forced_max;
+  if (sel > x->max_parts) sel = x->max_parts;
+  if (sel < 1) sel = 1;
+  x->sel_stride = (int32_t)sel;
+  // forced pages outside every selected partition exist only when a partition spans several pages
+  int64_t pg = tp > 16 ? sel * x->pages_per_part + c->sink_pages + c->recent_pages : sel;
+  if (pg > x->max_pages) pg = x->max_pages;
+  if (pg < 1) pg = 1;
+  x->page_stride = (int32_t)pg;
+  x->dir_stride = cdiv32(x->max_pages, c->leaf_entries);
+
+  int32_t splits = c->decode_splits;
+  if (splits == 0) {
+    // enough workgroups to put about four on each of the 256 compute units,
+    // but at least two pages per wave of a workgroup
+    splits = 1024 / x->max_rows;
+    int32_t cap = x->page_stride / (2 * SPIN_DECODE_WAVES);
+    if (splits > cap) splits = cap;
+    if (splits < 1) splits = 1;
+  }
+  if (splits > 64) splits = 64;
+  x->splits = splits;
+  x->scale = c->softmax_scale > 0.f ? c->softmax_scale : 1.0f / sqrtf((float)c->head_dim);
+
+  size_t off = SPIN_WS_HEADER;
+  x->ws_ml_off = off;
+  off += (size_t)x->max_rows * splits * group * 2 * sizeof(float);
+  off = (off + 255) & ~(size_t)255;
+  x->ws_acc_off = off;
+  off += (size_t)x->max_rows * splits * group * SPIN_HEAD_DIM * sizeof(float);
+  x->ws_bytes = (off + 255) & ~(size_t)255;
+  *out = x;
+  return SPIN_OK;
+}
+
+extern "C" void spin_destroy(spin_ctx *ctx) { delete ctx; }
+
+extern "C" const char *spin_status_string(int s) {
+  switch (s) {
+    case SPIN_OK: return "ok";
+    case SPIN_ERR_INVALID: return "invalid argument";
+    case SPIN_ERR_UNSUPPORTED: return "unsupported shape or mode";
+    case SPIN_ERR_WORKSPACE: return "workspace missing";
+    case SPIN_ERR_HIP: return "HIP runtime error";
+    case SPIN_ERR_BUDGET: return "slot budget smaller than the step's selection";
+    case SPIN_ERR_NOT_RESIDENT: return "selected page not resident";
+    case SPIN_ERR_SLOT_RANGE: return "slot id outside the pool";
+    default: return "unknown status";
+  }
+}
+
+extern "C" size_t spin_workspace_bytes(const spin_ctx *c) { return c ? c->ws_bytes : 0; }
+extern "C" int32_t spin_sel_stride(const spin_ctx *c) { return c ? c->sel_stride : 0; }
+extern "C" int32_t spin_page_stride(const spin_ctx *c) { return c ? c->page_stride : 0; }
+extern "C" int32_t spin_dir_stride(const spin_ctx *c) { return c ? c->dir_stride : 0; }
+extern "C" int32_t spin_decode_splits(const spin_ctx *c) { return c ? c->splits : 0; }
+
+extern "C" size_t spin_summary_bytes(const spin_ctx *c, int64_t padded_partitions) {
+  if (!c || padded_partitions < 0) return 0;
+  // one summary row = kd bf16; rows are padded per KV head to whole 16-row tiles
+  return (size_t)padded_partitions * c->cfg.num_kv_heads * c->rows_per_part * c->kd * 2;
+}
+
+__global__ void spin_fill_i32_kernel(int32_t *p, int32_t v, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+extern "C" int spin_workspace_init(spin_ctx *ctx, void *workspace, void *stream) {
+  if (!ctx) return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  hipLaunchKernelGGL(spin_fill_i32_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream,
+                     (int32_t *)workspace, 0, SPIN_WS_HEADER / 4);
+  return spin_launch_status();
+}
+
+extern "C" int spin_poll_status(spin_ctx *ctx, const void *workspace, void *stream) {
+  if (!ctx) return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  int32_t st = 0;
+  SPIN_HIP_CHECK(hipMemcpyAsync(&st, workspace, sizeof(st), hipMemcpyDeviceToHost, (hipStream_t)stream));
+  SPIN_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+  return st;
+}
