@@ -52,4 +52,40 @@ static inline int spin_launch_status() {
 __device__ inline void spin_raise(int32_t *status, int32_t err) { atomicCAS(status, 0, err); }
 
 __device__ inline float spin_bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// fp32 -> bf16 bits, round to nearest even
+__device__ inline uint16_t spin_f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+// logical page -> slot through the two-level table; -1 when the leaf or the
+// entry is missing
+__device__ inline int32_t spin_walk(const int32_t *__restrict__ dir, const int32_t *__restrict__ leaf_pool,
+                                    int64_t leaf_chunks, int row, int dir_stride, int leaf_entries, int page) {
+  const int ci = page / leaf_entries;
+  if (ci >= dir_stride) return -1;
+  const int32_t chunk = dir[(size_t)row * dir_stride + ci];
+  if (chunk < 0 || (int64_t)chunk >= leaf_chunks) return -1;
+  return leaf_pool[(size_t)chunk * leaf_entries + (page - ci * leaf_entries)];
+}
+
+// DPP lane exchanges inside a row of 16 lanes
+#define SPIN_DPP_XOR1 0xB1        /* quad_perm [1,0,3,2] */
+#define SPIN_DPP_XOR2 0x4E        /* quad_perm [2,3,0,1] */
+#define SPIN_DPP_HALF_MIRROR 0x141
+#define SPIN_DPP_MIRROR 0x140
+template <int CTRL>
+__device__ inline float spin_dpp(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+// maximum over the 16 lanes of a row, result in every lane
+__device__ inline float spin_row16_max(float v) {
+  v = fmaxf(v, spin_dpp<SPIN_DPP_XOR1>(v));
+  v = fmaxf(v, spin_dpp<SPIN_DPP_XOR2>(v));
+  v = fmaxf(v, spin_dpp<SPIN_DPP_HALF_MIRROR>(v));
+  v = fmaxf(v, spin_dpp<SPIN_DPP_MIRROR>(v));
+  return v;
+}
 #endif

@@ -1,0 +1,200 @@
+// Index: per-partition summaries from the keys in the pool (Section 4.1, Index;
+// Table 1: per-page pooling of keys).  Set-up work, not on the per-step path.
+//
+// Summary rows are written in tiles of 16 rows, chunk-major
+// [KD/KC chunks][16 rows][KC elements], the operand image stage 1 loads:
+//   MINMAX  row = partition, KD = 256 = [max(128) | min(128)], KC = 8
+//   REPMAX  row = partition*4 + r,  KD = 128, KC = 8
+//   SKETCH  row = token,            KD = 16,  KC = 4
+#include "spin_common.h"
+
+// element offset of (summary row R, element e)
+__device__ inline size_t summ_off(size_t R, int e, int kd, int kc) {
+  return (R >> 4) * (size_t)(16 * kd) + ((size_t)(e / kc) * 16 + (R & 15)) * kc + (e % kc);
+}
+
+// One workgroup per 16 partitions of a row: thread = (partition r = tid%16, 8-channel chunk ch = tid/16).
+__global__ __launch_bounds__(256) void spin_index_minmax_kernel(
+    const uint4 *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
+    const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
+    const int32_t *__restrict__ seq_lens, int Hkv, int tp, int dir_stride, int leaf_entries, int max_tiles,
+    uint16_t *__restrict__ summ, int32_t *status) {
+  const int row = blockIdx.x / max_tiles, tile = blockIdx.x - row * max_tiles;
+  const int b = row / Hkv, h = row - b * Hkv;
+  const int PP = part_offsets[b + 1] - part_offsets[b];
+  if (tile * 16 >= PP) return;
+  const int N = seq_lens[b];
+  const int P = (N + tp - 1) / tp;
+  const size_t base = (size_t)Hkv * part_offsets[b] + (size_t)h * PP;
+  const int r = threadIdx.x & 15, ch = threadIdx.x >> 4;
+  const int p = tile * 16 + r;
+  float mn[8], mx[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { mn[i] = __builtin_inff(); mx[i] = -__builtin_inff(); }
+  bool any = false;
+  if (p < P) {
+    const int t0 = p * tp, t1 = min(t0 + tp, N);
+    for (int pg = t0 >> 4; pg <= (t1 - 1) >> 4; ++pg) {
+      const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
+      if (slot < 0 || (int64_t)slot >= pool_slots) { spin_raise(status, SPIN_ERR_NOT_RESIDENT); continue; }
+      const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + ch * 16;
+      const int a = max(t0 - pg * 16, 0), e = min(t1 - pg * 16, 16);
+      for (int t = a; t < e; ++t) {
+        const uint4 v = kt[t];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
+          mn[2 * i] = fminf(mn[2 * i], lo); mx[2 * i] = fmaxf(mx[2 * i], lo);
+          mn[2 * i + 1] = fminf(mn[2 * i + 1], hi); mx[2 * i + 1] = fmaxf(mx[2 * i + 1], hi);
+        }
+        any = true;
+      }
+    }
+  }
+  uint32_t omx[4], omn[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    // values are bf16 to begin with: the upper halves are exact
+    omx[i] = any ? ((__float_as_uint(mx[2 * i]) >> 16) | (__float_as_uint(mx[2 * i + 1]) & 0xffff0000u)) : 0u;
+    omn[i] = any ? ((__float_as_uint(mn[2 * i]) >> 16) | (__float_as_uint(mn[2 * i + 1]) & 0xffff0000u)) : 0u;
+  }
+  const size_t R = base + p;
+  uint4 *o = (uint4 *)summ;
+  // 16-byte unit index of (row R, chunk): tile*(16*256/8) + chunk*16 + R%16
+  const size_t tbase = (R >> 4) * (size_t)(16 * 256 / 8);
+  o[tbase + (size_t)ch * 16 + (R & 15)] = make_uint4(omx[0], omx[1], omx[2], omx[3]);
+  o[tbase + (size_t)(16 + ch) * 16 + (R & 15)] = make_uint4(omn[0], omn[1], omn[2], omn[3]);
+}
+
+// fp64 -> bf16 with a single rounding: truncate to fp32 with a sticky low bit
+// (round to odd), then round the 16 dropped bits to nearest even.
+__device__ inline uint16_t spin_f64_to_bf16(double x) {
+  float f = __double2float_rz(x);
+  uint32_t u = __float_as_uint(f);
+  if ((double)f != x) u |= 1u;
+  return spin_f32_to_bf16(__uint_as_float(u));
+}
+
+// One workgroup per tile of 16 summary rows (4 partitions x 4 representatives):
+// thread = (summary row r = tid%16, 8-channel chunk ch = tid/16).  Sums run in
+// fp64, where they are exact for bf16 addends, so the mean has one rounding.
+__global__ __launch_bounds__(256) void spin_index_repmean_kernel(
+    const uint4 *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
+    const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
+    const int32_t *__restrict__ seq_lens, int Hkv, int tp, int reps, int dir_stride, int leaf_entries,
+    int max_tiles, uint16_t *__restrict__ summ, int32_t *status) {
+  const int row = blockIdx.x / max_tiles, tile = blockIdx.x - row * max_tiles;
+  const int b = row / Hkv, h = row - b * Hkv;
+  const int PP = part_offsets[b + 1] - part_offsets[b];
+  if (tile * 16 >= PP * reps) return;
+  const int N = seq_lens[b];
+  const int P = (N + tp - 1) / tp;
+  const size_t base = ((size_t)Hkv * part_offsets[b] + (size_t)h * PP) * reps;
+  const int r = threadIdx.x & 15, ch = threadIdx.x >> 4;
+  const int sr = tile * 16 + r;            // summary row inside this KV row
+  const int p = sr / reps, rep = sr - p * reps;
+  const int sub = tp / reps;
+  uint32_t outw[4] = {0, 0, 0, 0};
+  if (p < P) {
+    // an empty sub-range repeats representative 0 of the partition
+    int t0 = p * tp + rep * sub, t1 = min(t0 + sub, N);
+    if (t1 <= t0) { t0 = p * tp; t1 = min(t0 + sub, N); }
+    double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int pg = t0 >> 4; pg <= (t1 - 1) >> 4; ++pg) {
+      const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
+      if (slot < 0 || (int64_t)slot >= pool_slots) { spin_raise(status, SPIN_ERR_NOT_RESIDENT); continue; }
+      const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + ch * 16;
+      const int a = max(t0 - pg * 16, 0), e = min(t1 - pg * 16, 16);
+      for (int t = a; t < e; ++t) {
+        const uint4 v = kt[t];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc[2 * i] += (double)__uint_as_float(w[i] << 16);
+          acc[2 * i + 1] += (double)__uint_as_float(w[i] & 0xffff0000u);
+        }
+      }
+    }
+    const double cnt = (double)(t1 - t0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      outw[i] = (uint32_t)spin_f64_to_bf16(acc[2 * i] / cnt) | ((uint32_t)spin_f64_to_bf16(acc[2 * i + 1] / cnt) << 16);
+  }
+  const size_t R = base + sr;
+  uint4 *o = (uint4 *)summ;
+  const size_t tbase = (R >> 4) * (size_t)(16 * 128 / 8);
+  o[tbase + (size_t)ch * 16 + (R & 15)] = make_uint4(outw[0], outw[1], outw[2], outw[3]);
+}
+
+// One thread per (token, channel quad): gathers the sketched channels of a key.
+__global__ __launch_bounds__(256) void spin_index_sketch_kernel(
+    const uint16_t *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
+    const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
+    const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ chan, int Hkv, int dir_stride,
+    int leaf_entries, int max_blocks, uint16_t *__restrict__ summ, int32_t *status) {
+  const int row = blockIdx.x / max_blocks, blk = blockIdx.x - row * max_blocks;
+  const int b = row / Hkv, h = row - b * Hkv;
+  const int PP = part_offsets[b + 1] - part_offsets[b];
+  const int t = blk * 64 + (threadIdx.x & 63);   // token; 64 tokens x 4 channel quads per workgroup
+  const int cq = threadIdx.x >> 6;
+  if (t >= PP) return;
+  const int N = seq_lens[b];
+  const size_t base = (size_t)Hkv * part_offsets[b] + (size_t)h * PP;
+  uint16_t e[4] = {0, 0, 0, 0};
+  if (t < N) {
+    const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, t >> 4);
+    if (slot < 0 || (int64_t)slot >= pool_slots) {
+      spin_raise(status, SPIN_ERR_NOT_RESIDENT);
+    } else {
+      const uint16_t *kt = pool + (size_t)slot * (SPIN_SLOT_U4 * 8);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int d = chan[h * 16 + cq * 4 + i];
+        e[i] = kt[(((d >> 5) * 64 + ((d & 31) >> 3) * 16 + (t & 15)) << 3) + (d & 7)];
+      }
+    }
+  }
+  const size_t R = base + t;
+  // tile [4 chunks][16 rows][4 elements]
+  uint2 *o = (uint2 *)summ;
+  o[(R >> 4) * 64 + (size_t)cq * 16 + (R & 15)] =
+      make_uint2(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16));
+}
+
+extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv_pool, int64_t pool_slots,
+                                    const int32_t *dir, const int32_t *leaf_pool, int64_t leaf_chunks,
+                                    const int32_t *part_offsets, const int32_t *seq_lens,
+                                    const int32_t *chan_idx, void *summaries, void *workspace, void *stream) {
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || pool_slots <= 0 || leaf_chunks <= 0) return SPIN_ERR_INVALID;
+  if (batch == 0) return SPIN_OK;
+  if (!kv_pool || !dir || !leaf_pool || !part_offsets || !seq_lens || !summaries) return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  const spin_config &c = ctx->cfg;
+  const int rows = batch * c.num_kv_heads;
+  const int max_pp = ((ctx->max_parts + 15) / 16) * 16;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t *status = (int32_t *)workspace;
+  if (c.score_kind == SPIN_SCORE_MINMAX) {
+    const int max_tiles = max_pp / 16;
+    hipLaunchKernelGGL(spin_index_minmax_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
+                       (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
+                       c.num_kv_heads, c.partition_tokens, ctx->dir_stride, c.leaf_entries, max_tiles,
+                       (uint16_t *)summaries, status);
+  } else if (c.score_kind == SPIN_SCORE_REPMAX) {
+    const int max_tiles = max_pp * c.reps_per_partition / 16;
+    hipLaunchKernelGGL(spin_index_repmean_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
+                       (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
+                       c.num_kv_heads, c.partition_tokens, c.reps_per_partition, ctx->dir_stride, c.leaf_entries,
+                       max_tiles, (uint16_t *)summaries, status);
+  } else {
+    if (!chan_idx) return SPIN_ERR_INVALID;
+    if (c.partition_tokens != 1) return SPIN_ERR_UNSUPPORTED;
+    const int max_blocks = (max_pp + 63) / 64;
+    hipLaunchKernelGGL(spin_index_sketch_kernel, dim3((unsigned)rows * max_blocks), dim3(256), 0, st,
+                       (const uint16_t *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
+                       chan_idx, c.num_kv_heads, ctx->dir_stride, c.leaf_entries, max_blocks,
+                       (uint16_t *)summaries, status);
+  }
+  return spin_launch_status();
+}

@@ -55,3 +55,50 @@ class DeviceWorkload:
     def check_ok(self):
         st = self.spin.poll_status(self.ws)
         assert st == 0, binding.STATUS_NAMES.get(st, st)
+
+
+# ---------------------------------------------------------------------------
+# running the stages
+# ---------------------------------------------------------------------------
+def alloc_step_buffers(dw: "DeviceWorkload"):
+    sp, w = dw.spin, dw.w
+    rows = w.rows
+    padded = int(dw.part_offsets_np[-1])
+    dw.summaries = torch.zeros(sp.summary_bytes(padded), dtype=torch.uint8, device=DEV)
+    dw.scores = torch.zeros(padded * w.num_kv_heads, dtype=torch.float32, device=DEV)
+    dw.sel = torch.zeros((rows, sp.sel_stride), dtype=torch.int32, device=DEV)
+    dw.nsel = torch.zeros(rows, dtype=torch.int32, device=DEV)
+    dw.slots = torch.zeros((rows, sp.page_stride), dtype=torch.int32, device=DEV)
+    dw.page_ids = torch.zeros((rows, sp.page_stride), dtype=torch.int32, device=DEV)
+    dw.valid_mask = torch.zeros((rows, sp.page_stride), dtype=torch.int16, device=DEV)
+    dw.npages = torch.zeros(rows, dtype=torch.int32, device=DEV)
+    dw.out = torch.zeros((w.batch, w.num_q_heads, w.head_dim), dtype=torch.bfloat16, device=DEV)
+    dw.lse = torch.zeros((w.batch, w.num_q_heads), dtype=torch.float32, device=DEV)
+    dw.chan = None
+
+
+def build_summaries(dw: "DeviceWorkload", chan_np=None):
+    if not hasattr(dw, "summaries"):
+        alloc_step_buffers(dw)
+    if chan_np is not None:
+        dw.chan = torch.from_numpy(np.ascontiguousarray(chan_np, dtype=np.int32)).to(DEV)
+    dw.spin.build_summaries(dw.w.batch, dw.kv_pool, dw.dir, dw.leaf_pool, dw.part_offsets, dw.seq_lens,
+                            dw.chan, dw.summaries, dw.ws)
+
+
+def run_step(dw: "DeviceWorkload", q=None):
+    """score -> select -> resolve -> decode on the current stream."""
+    sp, w = dw.spin, dw.w
+    q = dw.q if q is None else q
+    sp.score_partitions(w.batch, q, dw.summaries, dw.chan, dw.part_offsets, dw.seq_lens, dw.scores, dw.ws)
+    sp.select_topk(w.batch, dw.scores, dw.part_offsets, dw.seq_lens, dw.sel, dw.nsel, dw.ws)
+    sp.resolve_slots(w.batch, 0, dw.sel, dw.nsel, dw.seq_lens, dw.dir, dw.leaf_pool, dw.slots, dw.page_ids,
+                     dw.valid_mask, dw.npages, dw.ws)
+    sp.sparse_decode(w.batch, q, dw.kv_pool, dw.slots, dw.valid_mask, dw.npages, dw.out, dw.lse, dw.ws)
+
+
+def unpack_summary_rows(raw_u8: torch.Tensor, kd: int, kc: int) -> np.ndarray:
+    """Undo the tile layout [KD/KC chunks][16 rows][KC]: returns uint16 [rows][kd]."""
+    bits = raw_u8.cpu().numpy().view(np.uint16)
+    tiles = bits.reshape(-1, kd // kc, 16, kc)
+    return tiles.transpose(0, 2, 1, 3).reshape(-1, kd)

@@ -1,0 +1,269 @@
+"""GPU parity of Index, stage 1 (score), stage 2 (select) and stage 3 (resolve)
+against the oracle, stage by stage and end to end.
+
+Bars: summaries, selected ids, page ids, slots and masks bit-exact.  Scores are
+fp32 matrix-core sums of exact bf16 products compared with the fp64 oracle
+within the first-order summation bound K * 2^-24 * sum|terms|.  Where fp32
+scores decide the top-k, the oracle takes the decision on the same fp32 score
+bits (copied back); against fp64 scores the selection must agree outside the
+rounding band around the k-th score.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import attend, bf16, index, resolve, score, select
+from paper_2604_26837_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+ATOL, RTOL = 2e-2, 1e-2
+
+
+def _workloads():
+    c0 = synth.config0()
+    return {
+        "cfg0": c0,
+        "ragged_pages": c0.with_(seq_lens=(700, 16, 333, 2049, 5), topk=24, sink_pages=2, recent_pages=3,
+                                 planted_frac=0.02, name="ragged_pages"),
+        "blocks": c0.with_(seq_lens=(131 * 16 + 5, 40 * 128, 129), partition_tokens=128,
+                           score_kind=synth.SCORE_REPMAX, topk=6, topk_includes_forced=False,
+                           sink_pages=4, recent_pages=11, block_mean_std=0.5, name="blocks"),
+        "tokens": c0.with_(seq_lens=(3000, 777), partition_tokens=1, score_kind=synth.SCORE_SKETCH,
+                           topk=200, sink_pages=1, recent_pages=2, planted_frac=0.01, name="tokens"),
+        "minmax_blocks": c0.with_(seq_lens=(2000, 4096), partition_tokens=64, topk=9,
+                                  topk_includes_forced=True, sink_pages=3, recent_pages=6, name="mm_blocks"),
+        "minmax_quarter": c0.with_(seq_lens=(500,), partition_tokens=4, topk=50, sink_pages=1,
+                                   recent_pages=1, name="mm_quarter"),
+    }
+
+
+def _oracle_row_inputs(dw, b, h, chan):
+    w = dw.w
+    g = w.group
+    kb, vb = dw.data.logical_kv_bits(b, h)
+    K = bf16.decode(kb)
+    q = bf16.decode(dw.data.q_bits[b, h * g:(h + 1) * g])
+    n = w.seq_lens[b]
+    if w.score_kind == synth.SCORE_MINMAX:
+        mins, maxs = index.minmax_summaries(K, n, w.partition_tokens)
+        summ = (mins, maxs)
+        rows = np.concatenate([maxs, mins], axis=1)
+        s = score.score_minmax(q, mins, maxs)
+        sabs = np.maximum(np.abs(q[:, None, :] * mins[None]), np.abs(q[:, None, :] * maxs[None])).sum(-1).max()
+        kterms = 256
+    elif w.score_kind == synth.SCORE_REPMAX:
+        reps = index.block_representatives(K, n, w.partition_tokens, w.reps_per_partition)
+        summ = reps
+        rows = reps.reshape(-1, w.head_dim)
+        s = score.score_repmax(q, reps)
+        sabs = np.abs(np.einsum("prd,gd->prgd", reps, q)).sum(-1).max() if len(reps) else 0.0
+        kterms = 128
+    else:
+        sk = index.key_sketch(K, n, chan[h])
+        summ = sk
+        rows = sk
+        s = score.score_sketch(q, sk, chan[h])
+        sabs = np.abs(sk[:, None, :] * q[None][:, :, chan[h]]).sum(-1).max() if len(sk) else 0.0
+        kterms = 16
+    return q, K, bf16.decode(vb), summ, rows, s, kterms * 2.0 ** -24 * sabs
+
+
+def _kd_kc(w):
+    return {synth.SCORE_MINMAX: (256, 8), synth.SCORE_REPMAX: (128, 8), synth.SCORE_SKETCH: (16, 4)}[w.score_kind]
+
+
+@pytest.mark.parametrize("name", list(_workloads()))
+def test_stage_by_stage(name):
+    from gpu_harness import DeviceWorkload, bf16_to_bits, build_summaries, run_step, unpack_summary_rows
+    w = _workloads()[name]
+    data = synth.generate(w, spare_slots=3)
+    dw = DeviceWorkload(data)
+    sp = dw.spin
+    chan = synth.sketch_channels(data) if w.score_kind == synth.SCORE_SKETCH else None
+    build_summaries(dw, chan)
+    run_step(dw)
+    torch.cuda.synchronize()
+    dw.check_ok()
+
+    kd, kc = _kd_kc(w)
+    summ_rows = unpack_summary_rows(dw.summaries, kd, kc)
+    scores = dw.scores.cpu().numpy()
+    sel = dw.sel.cpu().numpy()
+    nsel = dw.nsel.cpu().numpy()
+    slots = dw.slots.cpu().numpy()
+    page_ids = dw.page_ids.cpu().numpy()
+    masks = dw.valid_mask.cpu().numpy().view(np.uint16)
+    npages = dw.npages.cpu().numpy()
+    out = bf16.decode(bf16_to_bits(dw.out))
+    lse = dw.lse.cpu().numpy()
+    rpp = w.reps_per_partition if w.score_kind == synth.SCORE_REPMAX else 1
+    band_rows = 0
+
+    r = 0
+    for b in range(w.batch):
+        n = w.seq_lens[b]
+        P = w.partitions(b)
+        for h in range(w.num_kv_heads):
+            q, K, V, summ, ref_rows, s64, eps = _oracle_row_inputs(dw, b, h, chan)
+            base = dw.row_base(b, h)
+            # --- Index: stored summaries bit-exact
+            got_rows = bf16.decode(summ_rows[base * rpp: base * rpp + ref_rows.shape[0]])
+            assert np.array_equal(got_rows, ref_rows), f"summaries differ row {r}"
+            # --- stage 1: scores within the fp32 summation bound
+            s32 = scores[base: base + P].astype(np.float64)
+            assert np.all(np.abs(s32 - s64) <= eps + 1e-30), f"score err {np.abs(s32 - s64).max()} > {eps}"
+            # --- stage 2 (i): decision taken on the same fp32 bits
+            want = select.select_topk(scores[base: base + P], n, 16, w.partition_tokens, w.topk,
+                                      w.topk_includes_forced, w.sink_pages, w.recent_pages)
+            got = sel[r, :nsel[r]].tolist()
+            assert got == want, f"sel differs row {r}"
+            assert (sel[r, nsel[r]:] == -1).all()
+            # --- stage 2 (ii): against fp64 scores, outside the rounding band
+            want64 = select.select_topk(s64, n, 16, w.partition_tokens, w.topk, w.topk_includes_forced,
+                                        w.sink_pages, w.recent_pages)
+            if want64 != got:
+                band_rows += 1
+                forced = set(select.forced_partitions(n, 16, w.partition_tokens, w.sink_pages, w.recent_pages))
+                cand_sel = [p for p in want64 if p not in forced]
+                tau = min(s64[p] for p in cand_sel)
+                assert len(got) == len(want64)
+                for p in set(got) ^ set(want64):
+                    assert abs(s64[p] - tau) <= 2 * eps, "selection differs outside the rounding band"
+            # --- stage 3: dictionary lookup on the GPU's own selection
+            pg_w, sl_w, mk_w = resolve.resolve_slots(got, n, 16, w.partition_tokens, w.sink_pages,
+                                                     w.recent_pages, dw.page_map, r)
+            assert npages[r] == len(pg_w)
+            assert page_ids[r, :npages[r]].tolist() == pg_w
+            assert slots[r, :npages[r]].tolist() == sl_w
+            assert masks[r, :npages[r]].tolist() == mk_w
+            assert (slots[r, npages[r]:] == -1).all()
+            # --- stage 4: attention restricted to the GPU's own page list
+            pages = bf16.decode(data.pool_bits[np.asarray(sl_w, dtype=np.int64)]) if sl_w else \
+                np.zeros((0, 2, 16, w.head_dim))
+            K_S, V_S = attend.gather_tokens(pages[:, 0], pages[:, 1], mk_w)
+            ref, lref = attend.attend(q, K_S, V_S, dw.scale)
+            g = w.group
+            o = out[b, h * g:(h + 1) * g]
+            assert np.all(np.abs(o - ref) <= ATOL + RTOL * np.abs(ref)), f"attention err {np.abs(o - ref).max()}"
+            if np.isfinite(lref).all():
+                assert np.allclose(lse[b, h * g:(h + 1) * g], lref, rtol=2e-3, atol=2e-3)
+            r += 1
+    print(f"{name}: rows inside the rounding band: {band_rows}/{w.rows}")
+
+
+def test_quest_bound_holds_for_gpu_scores():
+    from gpu_harness import DeviceWorkload, build_summaries, run_step
+    w = synth.config0()
+    dw = DeviceWorkload(synth.generate(w))
+    build_summaries(dw)
+    run_step(dw)
+    scores = dw.scores.cpu().numpy().astype(np.float64)
+    for h in range(w.num_kv_heads):
+        q, K, V, summ, rows, s64, eps = _oracle_row_inputs(dw, 0, h, None)
+        true_max = (q @ K[:4096].T).reshape(w.group, 256, 16).max(axis=2).max(axis=0)
+        base = dw.row_base(0, h)
+        assert np.all(scores[base: base + 256] >= true_max - eps)
+
+
+def _select_only(w, score_rows):
+    """Run stage 2 alone on hand-made score rows (one per KV row)."""
+    from gpu_harness import DEV, DeviceWorkload, alloc_step_buffers
+    from paper_2604_26837_amd import binding, tables
+    sp = binding.Spin.for_workload(w)
+    ws = sp.new_workspace(DEV)
+    po = tables.part_offsets(w.seq_lens, w.partition_tokens)
+    buf = np.zeros(int(po[-1]) * w.num_kv_heads, dtype=np.float32)
+    r = 0
+    for b in range(w.batch):
+        for h in range(w.num_kv_heads):
+            base = tables.row_base(po, b, h, w.num_kv_heads)
+            buf[base: base + len(score_rows[r])] = score_rows[r]
+            r += 1
+    d_scores = torch.from_numpy(buf).to(DEV)
+    sel = torch.zeros((w.rows, sp.sel_stride), dtype=torch.int32, device=DEV)
+    nsel = torch.zeros(w.rows, dtype=torch.int32, device=DEV)
+    sp.select_topk(w.batch, d_scores, torch.from_numpy(po).to(DEV),
+                   torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV), sel, nsel, ws)
+    torch.cuda.synchronize()
+    assert sp.poll_status(ws) == 0
+    sel, nsel = sel.cpu().numpy(), nsel.cpu().numpy()
+    return [sel[r, :nsel[r]].tolist() for r in range(w.rows)], sel
+
+
+def _check_select(w, score_rows):
+    got, raw = _select_only(w, score_rows)
+    r = 0
+    for b in range(w.batch):
+        for h in range(w.num_kv_heads):
+            want = select.select_topk(score_rows[r], w.seq_lens[b], 16, w.partition_tokens, w.topk,
+                                      w.topk_includes_forced, w.sink_pages, w.recent_pages)
+            assert got[r] == want, f"row {r}"
+            assert (raw[r, len(want):] == -1).all()
+            r += 1
+
+
+def test_select_adversarial_ties_and_specials():
+    base = synth.config0().with_(num_q_heads=4, num_kv_heads=1)
+    rng = np.random.default_rng(0)
+    P = 300
+    w = base.with_(seq_lens=(P * 16,) * 8, topk=40, sink_pages=2, recent_pages=3, name="adv")
+    rows = [
+        np.zeros(P, dtype=np.float32),                                           # all equal
+        rng.integers(-2, 3, size=P).astype(np.float32),                          # heavy ties
+        np.where(rng.random(P) < 0.5, 0.0, -0.0).astype(np.float32),              # signed zeros
+        np.where(rng.random(P) < 0.3, -np.inf, rng.standard_normal(P)).astype(np.float32),
+        np.where(rng.random(P) < 0.9, np.nan, rng.standard_normal(P)).astype(np.float32),   # mostly NaN
+        np.full(P, np.inf, dtype=np.float32),
+        (rng.standard_normal(P) * 1e-38).astype(np.float32),                     # subnormals
+        np.concatenate([np.full(150, 3.0), np.full(150, 3.0000002)]).astype(np.float32),
+    ]
+    _check_select(w, rows)
+
+
+def test_select_k_extremes():
+    base = synth.config0().with_(num_q_heads=4, num_kv_heads=1)
+    rng = np.random.default_rng(1)
+    for topk, sinks, recents, seq in [(0, 0, 0, 800), (0, 2, 2, 800), (1000, 1, 1, 800), (3, 4, 4, 800),
+                                      (5, 0, 0, 7), (5, 3, 3, 40), (50, 0, 0, 50 * 16)]:
+        w = base.with_(seq_lens=(seq, 1, seq + 9), topk=topk, sink_pages=sinks, recent_pages=recents, name="kx")
+        rows = [rng.standard_normal(w.partitions(b)).astype(np.float32) for b in range(w.batch)]
+        _check_select(w, rows)
+
+
+def test_select_large_rows_token_partitions():
+    base = synth.config0().with_(num_q_heads=4, num_kv_heads=1)
+    rng = np.random.default_rng(2)
+    w = base.with_(seq_lens=(65536, 40000), partition_tokens=1, topk=1024, sink_pages=0, recent_pages=0,
+                   score_kind=synth.SCORE_SKETCH, name="big_tokens")
+    rows = [np.round(rng.standard_normal(n) * 50).astype(np.float32) / 50 for n in w.seq_lens]  # many ties
+    _check_select(w, rows)
+    w2 = base.with_(seq_lens=(262144,), topk=128, sink_pages=4, recent_pages=8, name="big_pages")
+    _check_select(w2, [rng.standard_normal(16384).astype(np.float32)])
+
+
+def test_resolve_reports_missing_leaf_and_missing_slot():
+    from gpu_harness import DEV, DeviceWorkload, build_summaries, run_step
+    w = synth.config0().with_(seq_lens=(4096,), name="holes")
+    data = synth.generate(w)
+    dw = DeviceWorkload(data)
+    build_summaries(dw)
+    run_step(dw)
+    dw.check_ok()
+    sel0 = dw.sel.cpu().numpy()[0]
+    # knock out the slot of one selected page
+    victim = int(sel0[5])
+    chunk = int(dw.dir.cpu().numpy()[0, victim // 512])
+    dw.leaf_pool[chunk, victim % 512] = -1
+    run_step(dw)
+    assert dw.spin.poll_status(dw.ws) == -6
+    slots = dw.slots.cpu().numpy()[0]
+    assert slots[5] == -1 and (slots[:5] >= 0).all()
+    assert dw.valid_mask.cpu().numpy()[0, 5] == 0
+    dw.spin.workspace_init(dw.ws)
+    # missing leaf
+    dw.dir[0, 0] = -1
+    run_step(dw)
+    assert dw.spin.poll_status(dw.ws) == -6
