@@ -127,6 +127,21 @@ int spin_workspace_init(spin_ctx *ctx, void *workspace, void *stream);
  * last init (SPIN_OK if none). */
 int spin_poll_status(spin_ctx *ctx, const void *workspace, void *stream);
 
+/* Per-kernel timing for benchmarks.  spin_profile_enable(ctx, capacity > 0)
+ * creates `capacity` HIP event pairs per kernel; from then on each kernel
+ * launch of a stage call carries a start and a stop event on its stream (up to
+ * `capacity` launches per kernel, later ones are not timed).
+ * spin_profile_read() waits for the recorded events of kernel `which`, returns
+ * how many launches were timed and their mean and minimum duration in
+ * microseconds, and resets that kernel's counter.  capacity == 0 disables and
+ * releases the events.  Not for concurrent use with stage calls. */
+enum spin_kernel_id {
+  SPIN_K_SCORE = 0, SPIN_K_SELECT = 1, SPIN_K_RESOLVE = 2, SPIN_K_DECODE = 3, SPIN_K_MERGE = 4,
+  SPIN_K_INDEX = 5, SPIN_K_PACK = 6
+};
+int spin_profile_enable(spin_ctx *ctx, int32_t capacity);
+int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_us, float *min_us);
+
 /* Offload, layout half: write `n_pages` pages given in plain token-major order
  * (src_k, src_v: DEVICE bf16 [n_pages][16][128]) into pool slots `slots[i]`
  * (DEVICE int32 [n_pages], each in [0, pool_slots)) in the slot layout above. */

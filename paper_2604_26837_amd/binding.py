@@ -20,7 +20,7 @@ STATUS_NAMES = {0: "SPIN_OK", -1: "SPIN_ERR_INVALID", -2: "SPIN_ERR_UNSUPPORTED"
 EXPORTS = [
     "spin_create", "spin_destroy", "spin_status_string", "spin_workspace_bytes", "spin_sel_stride",
     "spin_page_stride", "spin_dir_stride", "spin_decode_splits", "spin_summary_bytes",
-    "spin_workspace_init", "spin_poll_status", "spin_pack_kv_pages", "spin_build_summaries",
+    "spin_workspace_init", "spin_poll_status", "spin_profile_enable", "spin_profile_read", "spin_pack_kv_pages", "spin_build_summaries",
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
 ]
 
@@ -63,15 +63,14 @@ def load_library() -> C.CDLL:
     lib.spin_summary_bytes.restype = C.c_size_t
     lib.spin_workspace_init.argtypes = [vp, vp, vp]
     lib.spin_poll_status.argtypes = [vp, vp, vp]
+    lib.spin_profile_enable.argtypes = [vp, i32]
+    lib.spin_profile_read.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(C.c_float), C.POINTER(C.c_float)]
     lib.spin_pack_kv_pages.argtypes = [vp, i64, vp, vp, vp, vp, i64, vp]
     lib.spin_build_summaries.argtypes = [vp, i32, vp, i64, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.spin_score_partitions.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
-    for n in EXPORTS:
-        if getattr(lib, n).restype is C.c_int:
-            pass
     _LIB = lib
     return lib
 
@@ -157,6 +156,18 @@ class Spin:
 
     def summary_bytes(self, padded_partitions: int) -> int:
         return self.lib.spin_summary_bytes(self.h, padded_partitions)
+
+    KERNEL_IDS = dict(score=0, select=1, resolve=2, decode=3, merge=4, index=5, pack=6)
+
+    def profile_enable(self, capacity: int):
+        self._check(self.lib.spin_profile_enable(self.h, capacity), "spin_profile_enable")
+
+    def profile_read(self, which: str):
+        """(count, mean_us, min_us) of the timed launches of one kernel."""
+        n, mean, mn = C.c_int32(), C.c_float(), C.c_float()
+        self._check(self.lib.spin_profile_read(self.h, self.KERNEL_IDS[which], C.byref(n), C.byref(mean),
+                                               C.byref(mn)), "spin_profile_read")
+        return n.value, mean.value, mn.value
 
     # -- set-up calls -----------------------------------------------------
     def pack_kv_pages(self, src_k, src_v, slots, kv_pool):

@@ -89,7 +89,58 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   return SPIN_OK;
 }
 
-extern "C" void spin_destroy(spin_ctx *ctx) { delete ctx; }
+static void prof_release(spin_ctx *ctx) {
+  for (int k = 0; k < SPIN_KERNEL_IDS; ++k) {
+    if (ctx->prof_ev[k]) {
+      for (int i = 0; i < 2 * ctx->prof_cap; ++i)
+        if (ctx->prof_ev[k][i]) (void)hipEventDestroy(ctx->prof_ev[k][i]);
+      delete[] ctx->prof_ev[k];
+      ctx->prof_ev[k] = nullptr;
+    }
+    ctx->prof_n[k] = 0;
+  }
+  ctx->prof_cap = 0;
+}
+
+extern "C" void spin_destroy(spin_ctx *ctx) {
+  if (!ctx) return;
+  prof_release(ctx);
+  delete ctx;
+}
+
+extern "C" int spin_profile_enable(spin_ctx *ctx, int32_t capacity) {
+  if (!ctx || capacity < 0 || capacity > (1 << 16)) return SPIN_ERR_INVALID;
+  prof_release(ctx);
+  if (capacity == 0) return SPIN_OK;
+  for (int k = 0; k < SPIN_KERNEL_IDS; ++k) {
+    ctx->prof_ev[k] = new (std::nothrow) hipEvent_t[2 * capacity];
+    if (!ctx->prof_ev[k]) { prof_release(ctx); return SPIN_ERR_INVALID; }
+    for (int i = 0; i < 2 * capacity; ++i) ctx->prof_ev[k][i] = nullptr;
+  }
+  ctx->prof_cap = capacity;
+  for (int k = 0; k < SPIN_KERNEL_IDS; ++k)
+    for (int i = 0; i < 2 * capacity; ++i)
+      if (hipEventCreate(&ctx->prof_ev[k][i]) != hipSuccess) { prof_release(ctx); return SPIN_ERR_HIP; }
+  return SPIN_OK;
+}
+
+extern "C" int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_us, float *min_us) {
+  if (!ctx || which < 0 || which >= SPIN_KERNEL_IDS || !count || !mean_us || !min_us) return SPIN_ERR_INVALID;
+  *count = 0; *mean_us = 0.f; *min_us = 0.f;
+  if (ctx->prof_cap == 0) return SPIN_OK;
+  const int n = ctx->prof_n[which];
+  double sum = 0.0; float mn = 3.4e38f;
+  for (int i = 0; i < n; ++i) {
+    float ms = 0.f;
+    SPIN_HIP_CHECK(hipEventSynchronize(ctx->prof_ev[which][2 * i + 1]));
+    SPIN_HIP_CHECK(hipEventElapsedTime(&ms, ctx->prof_ev[which][2 * i], ctx->prof_ev[which][2 * i + 1]));
+    sum += ms; if (ms < mn) mn = ms;
+  }
+  ctx->prof_n[which] = 0;
+  *count = n;
+  if (n > 0) { *mean_us = (float)(sum / n * 1e3); *min_us = mn * 1e3f; }
+  return SPIN_OK;
+}
 
 extern "C" const char *spin_status_string(int s) {
   switch (s) {
@@ -125,8 +176,8 @@ __global__ void spin_fill_i32_kernel(int32_t *p, int32_t v, int n) {
 extern "C" int spin_workspace_init(spin_ctx *ctx, void *workspace, void *stream) {
   if (!ctx) return SPIN_ERR_INVALID;
   if (!workspace) return SPIN_ERR_WORKSPACE;
-  hipLaunchKernelGGL(spin_fill_i32_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream,
-                     (int32_t *)workspace, 0, SPIN_WS_HEADER / 4);
+  hipLaunchKernelGGL(spin_fill_i32_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (int32_t *)workspace, 0,
+                     SPIN_WS_HEADER / 4);
   return spin_launch_status();
 }
 

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "spin.h"
@@ -12,6 +13,8 @@
 #define SPIN_KTILE_U4 256     // 4096-byte K tile in 16-byte units
 #define SPIN_WS_HEADER 256    // bytes reserved in front of the workspace (status word)
 #define SPIN_DECODE_WAVES 4
+
+#define SPIN_KERNEL_IDS 8
 
 struct spin_ctx {
   spin_config cfg;
@@ -30,6 +33,10 @@ struct spin_ctx {
   float scale;
   size_t ws_bytes;
   size_t ws_ml_off, ws_acc_off;
+  // optional per-kernel timing: pairs of HIP events handed to the launches
+  int32_t prof_cap;
+  int32_t prof_n[SPIN_KERNEL_IDS];
+  hipEvent_t *prof_ev[SPIN_KERNEL_IDS];   // [2 * prof_cap]: start, stop, start, stop, ...
 };
 
 typedef __attribute__((ext_vector_type(8))) __bf16 spin_bf16x8;
@@ -48,6 +55,20 @@ static inline int spin_launch_status() {
 }
 
 #ifdef __HIPCC__
+// Launch `kernel` on `st`; when timing is enabled the launch carries a start
+// and a stop event that take the kernel's own begin and end timestamps.
+template <typename K, typename... Args>
+static inline void spin_launch(spin_ctx *ctx, int kid, K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st,
+                               Args... args) {
+  if (ctx->prof_cap > 0 && ctx->prof_n[kid] < ctx->prof_cap) {
+    const int i = ctx->prof_n[kid]++;
+    hipExtLaunchKernelGGL(kernel, grid, block, lds, st, ctx->prof_ev[kid][2 * i], ctx->prof_ev[kid][2 * i + 1], 0,
+                          args...);
+  } else {
+    hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
+  }
+}
+
 // first device-detected fault wins; later ones are dropped
 __device__ inline void spin_raise(int32_t *status, int32_t err) { atomicCAS(status, 0, err); }
 

@@ -217,13 +217,13 @@ extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, c
   const float scale_log2e = ctx->scale * 1.4426950408889634f;
   const size_t lds = (size_t)SPIN_DECODE_WAVES * G * (SPIN_HEAD_DIM + 2) * sizeof(float);
   hipStream_t st = (hipStream_t)stream;
-  hipLaunchKernelGGL(spin_decode_kernel<SPIN_DECODE_WAVES>, dim3((unsigned)(rows * nsplit)),
-                     dim3(SPIN_DECODE_WAVES * 64), lds, st, (const uint16_t *)q, (const uint4 *)kv_pool,
+  spin_launch(ctx, SPIN_K_DECODE, spin_decode_kernel<SPIN_DECODE_WAVES>, dim3((unsigned)(rows * nsplit)),
+              dim3(SPIN_DECODE_WAVES * 64), lds, st, (const uint16_t *)q, (const uint4 *)kv_pool,
                      pool_slots, slots, valid_mask, npages, ctx->page_stride, G, ctx->cfg.num_q_heads,
                      ctx->cfg.num_kv_heads, nsplit, scale_log2e, part_ml, part_acc, (uint16_t *)out, lse,
                      (int32_t *)workspace);
   if (nsplit > 1)
-    hipLaunchKernelGGL(spin_decode_merge_kernel, dim3((unsigned)rows), dim3(256), 0, st, part_ml, part_acc, G,
+    spin_launch(ctx, SPIN_K_MERGE, spin_decode_merge_kernel, dim3((unsigned)rows), dim3(256), 0, st, part_ml, part_acc, G,
                        ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, (uint16_t *)out, lse);
   return spin_launch_status();
 }

@@ -182,7 +182,7 @@ extern "C" int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, co
     (void)rev_table; (void)slot_base; (void)miss_pages; (void)miss_slots; (void)nmiss;
     return SPIN_ERR_UNSUPPORTED;
   }
-  hipLaunchKernelGGL(spin_resolve_kernel, dim3((unsigned)rows), dim3(RES_BLOCK), 0, (hipStream_t)stream, sel, nsel,
+  spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_kernel, dim3((unsigned)rows), dim3(RES_BLOCK), 0, (hipStream_t)stream, sel, nsel,
                      seq_lens, dir, leaf_pool, leaf_chunks, c.num_kv_heads, c.partition_tokens, c.sink_pages,
                      c.recent_pages, ctx->sel_stride, ctx->page_stride, ctx->dir_stride, c.leaf_entries, slots,
                      page_ids, valid_mask, npages, (int32_t *)workspace);

@@ -143,20 +143,20 @@ extern "C" int spin_score_partitions(spin_ctx *ctx, int32_t batch, const void *q
   if (c.score_kind == SPIN_SCORE_MINMAX) {
     const int tiles_per_wg = 16, max_tiles = max_pp / 16;
     const int wgs = (max_tiles + tiles_per_wg - 1) / tiles_per_wg;
-    hipLaunchKernelGGL((spin_score_k32_kernel<8, true>), dim3((unsigned)rows * wgs), dim3(SCORE_WAVES * 64), 0, st,
+    spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_kernel<8, true>, dim3((unsigned)rows * wgs), dim3(SCORE_WAVES * 64), 0, st,
                        (const uint16_t *)q, (const uint4 *)summaries, part_offsets, c.num_q_heads, c.num_kv_heads,
                        ctx->group, 1, tiles_per_wg, wgs, scores);
   } else if (c.score_kind == SPIN_SCORE_REPMAX) {
     const int tiles_per_wg = 32, max_tiles = max_pp * 4 / 16;
     const int wgs = (max_tiles + tiles_per_wg - 1) / tiles_per_wg;
-    hipLaunchKernelGGL((spin_score_k32_kernel<4, false>), dim3((unsigned)rows * wgs), dim3(SCORE_WAVES * 64), 0, st,
+    spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_kernel<4, false>, dim3((unsigned)rows * wgs), dim3(SCORE_WAVES * 64), 0, st,
                        (const uint16_t *)q, (const uint4 *)summaries, part_offsets, c.num_q_heads, c.num_kv_heads,
                        ctx->group, 4, tiles_per_wg, wgs, scores);
   } else {
     if (!chan_idx) return SPIN_ERR_INVALID;
     const int tiles_per_wg = 128, max_tiles = max_pp / 16;
     const int wgs = (max_tiles + tiles_per_wg - 1) / tiles_per_wg;
-    hipLaunchKernelGGL(spin_score_sketch_kernel, dim3((unsigned)rows * wgs), dim3(SCORE_WAVES * 64), 0, st,
+    spin_launch(ctx, SPIN_K_SCORE, spin_score_sketch_kernel, dim3((unsigned)rows * wgs), dim3(SCORE_WAVES * 64), 0, st,
                        (const uint16_t *)q, (const uint2 *)summaries, chan_idx, part_offsets, c.num_q_heads,
                        c.num_kv_heads, ctx->group, tiles_per_wg, wgs, scores);
   }

@@ -152,7 +152,7 @@ extern "C" int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *score
   (void)workspace;
   const spin_config &c = ctx->cfg;
   const int rows = batch * c.num_kv_heads;
-  hipLaunchKernelGGL(spin_select_kernel, dim3((unsigned)rows), dim3(SEL_BLOCK), 0, (hipStream_t)stream, scores,
+  spin_launch(ctx, SPIN_K_SELECT, spin_select_kernel, dim3((unsigned)rows), dim3(SEL_BLOCK), 0, (hipStream_t)stream, scores,
                      part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk,
                      c.topk_includes_forced, c.sink_pages, c.recent_pages, ctx->sel_stride, sel, nsel);
   return spin_launch_status();
