@@ -120,8 +120,9 @@ int32_t spin_decode_splits(const spin_ctx *ctx);  /* the split-K factor in use *
 /* bytes of the summary array for `padded_partitions` = part_offsets[batch] */
 size_t spin_summary_bytes(const spin_ctx *ctx, int64_t padded_partitions);
 
-/* Clear the workspace's status word (a fill kernel on `stream`; call once after
- * allocating the workspace and whenever a reported device fault was handled). */
+/* Clear the workspace's status word and arrival counters (a fill kernel on
+ * `stream`; call once after allocating the workspace, whenever a reported device
+ * fault was handled, and after a launch was abandoned mid-way). */
 int spin_workspace_init(spin_ctx *ctx, void *workspace, void *stream);
 /* Synchronise `stream` and return the first device-detected fault since the
  * last init (SPIN_OK if none). */

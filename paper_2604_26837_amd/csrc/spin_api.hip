@@ -67,10 +67,10 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
 
   int32_t splits = c->decode_splits;
   if (splits == 0) {
-    // enough workgroups to put about four on each of the 256 compute units,
-    // but at least two pages per wave of a workgroup
-    splits = 1024 / x->max_rows;
-    int32_t cap = x->page_stride / (2 * SPIN_DECODE_WAVES);
+    // about two workgroups on each of the 256 compute units, all resident at
+    // once, and at least four pages per wavefront
+    splits = 512 / x->max_rows;
+    int32_t cap = x->page_stride / (4 * SPIN_DECODE_WAVES);
     if (splits > cap) splits = cap;
     if (splits < 1) splits = 1;
   }
@@ -79,6 +79,10 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   x->scale = c->softmax_scale > 0.f ? c->softmax_scale : 1.0f / sqrtf((float)c->head_dim);
 
   size_t off = SPIN_WS_HEADER;
+  x->ws_ticket_off = off;                       // one arrival counter per row, zero between launches
+  off += (size_t)x->max_rows * sizeof(int32_t);
+  off = (off + 255) & ~(size_t)255;
+  x->ws_zero_bytes = off;
   x->ws_ml_off = off;
   off += (size_t)x->max_rows * splits * group * 2 * sizeof(float);
   off = (off + 255) & ~(size_t)255;
@@ -176,8 +180,9 @@ __global__ void spin_fill_i32_kernel(int32_t *p, int32_t v, int n) {
 extern "C" int spin_workspace_init(spin_ctx *ctx, void *workspace, void *stream) {
   if (!ctx) return SPIN_ERR_INVALID;
   if (!workspace) return SPIN_ERR_WORKSPACE;
-  hipLaunchKernelGGL(spin_fill_i32_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (int32_t *)workspace, 0,
-                     SPIN_WS_HEADER / 4);
+  const int n = (int)(ctx->ws_zero_bytes / 4);
+  hipLaunchKernelGGL(spin_fill_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream,
+                     (int32_t *)workspace, 0, n);
   return spin_launch_status();
 }
 

@@ -32,7 +32,8 @@ struct spin_ctx {
   int32_t rows_per_part;  // summary rows per partition (REPMAX: reps, else 1)
   float scale;
   size_t ws_bytes;
-  size_t ws_ml_off, ws_acc_off;
+  size_t ws_ticket_off, ws_ml_off, ws_acc_off;
+  size_t ws_zero_bytes;   // leading part of the workspace that spin_workspace_init clears
   // optional per-kernel timing: pairs of HIP events handed to the launches
   int32_t prof_cap;
   int32_t prof_n[SPIN_KERNEL_IDS];

@@ -9,24 +9,112 @@
 // on its four logits per lane, and accumulates O[head][dim] += P V with eight
 // 16x16x16 instructions; the logit tile's register layout is exactly the
 // operand layout of P, so nothing moves between lanes except two max
-// exchanges.  Wavefront partials (m, l, O) are merged through LDS in wave
-// order; with more than one split the workgroup partials go to the workspace
-// and a second kernel merges them in split order, so results are reproducible.
+// exchanges.  The loads of the next page are issued before the current page is
+// consumed (two register buffers), and a wavefront fetches the slot ids and
+// masks of all its pages with one load up front, so the only dependent memory
+// round trips per wavefront are that one and the first page.
+//
+// Wavefront partials (m, l, O) are merged through LDS in wave order.  With
+// more than one split the workgroup partials go to the workspace and the
+// last workgroup of the row to arrive (a ticket counter in the workspace
+// header) merges them in split order, so results are reproducible.
 #include "spin_common.h"
 
 #define NEG_INF (-__builtin_inff())
+
+__device__ inline void dev_store(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float dev_load(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct page_regs {
+  uint4 k[4], v[4];
+};
+
+__device__ inline void load_page(page_regs &r, const uint4 *__restrict__ pool, int slot, int lane) {
+  const uint4 *kp = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) r.k[j] = kp[j * 64];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) r.v[j] = kp[SPIN_KTILE_U4 + j * 64];
+}
+
+struct softmax_state {
+  float m, l;
+  spin_f32x4 acc[8];
+};
+
+__device__ inline void consume_page(softmax_state &st, const page_regs &r, const spin_bf16x8 (&qf)[4],
+                                    unsigned mask, int c, float scale_log2e) {
+  // S[token 4c+i][head n]
+  spin_f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(spin_bf16x8, r.k[j]), qf[j], s, 0, 0, 0);
+
+  const unsigned mbits = (mask >> (4 * c)) & 0xFu;
+  float sv[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) sv[i] = ((mbits >> i) & 1u) ? s[i] * scale_log2e : NEG_INF;
+  float pm = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+  pm = fmaxf(pm, __shfl_xor(pm, 16));
+  pm = fmaxf(pm, __shfl_xor(pm, 32));
+  const float m_new = fmaxf(st.m, pm);
+  const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
+  float pr[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) pr[i] = __builtin_amdgcn_exp2f(sv[i] - m_safe);
+  st.l = st.l * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
+  st.m = m_new;
+
+  // rescale the accumulator rows (head 4c+i) by that head's alpha, only when some maximum moved
+  if (__any(alpha != 1.0f)) {
+    float ar[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ar[i] = __shfl(alpha, 4 * c + i);
+#pragma unroll
+    for (int jn = 0; jn < 8; ++jn)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) st.acc[jn][i] *= ar[i];
+  }
+
+  // P as the A operand: row n = head, k = tokens 4c..4c+3
+  spin_bf16x2 p01 = {(__bf16)pr[0], (__bf16)pr[1]};
+  spin_bf16x2 p23 = {(__bf16)pr[2], (__bf16)pr[3]};
+  uint2 pk = {__builtin_bit_cast(uint32_t, p01), __builtin_bit_cast(uint32_t, p23)};
+  const spin_s16x4 pa = __builtin_bit_cast(spin_s16x4, pk);
+#pragma unroll
+  for (int jv = 0; jv < 4; ++jv) {
+    uint2 lo = {r.v[jv].x, r.v[jv].y}, hi = {r.v[jv].z, r.v[jv].w};
+    st.acc[2 * jv] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(spin_s16x4, lo),
+                                                               st.acc[2 * jv], 0, 0, 0);
+    st.acc[2 * jv + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(spin_s16x4, hi),
+                                                                   st.acc[2 * jv + 1], 0, 0, 0);
+  }
+}
+
+__device__ inline void write_out(uint16_t *__restrict__ out, float *__restrict__ lse, int qhead, int d, float M,
+                                 float L, float O) {
+  const float r = L > 0.f ? O / L : 0.f;
+  out[(size_t)qhead * SPIN_HEAD_DIM + d] = __builtin_bit_cast(uint16_t, (__bf16)r);
+  if (lse && d == 0) lse[qhead] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f : NEG_INF;
+}
 
 template <int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
     const uint16_t *__restrict__ q, const uint4 *__restrict__ pool, int64_t pool_slots,
     const int32_t *__restrict__ slots, const uint16_t *__restrict__ masks,
     const int32_t *__restrict__ npages, int page_stride, int G, int Hq, int Hkv, int nsplit,
-    float scale_log2e, float *__restrict__ part_ml, float *__restrict__ part_acc,
-    uint16_t *__restrict__ out, float *__restrict__ lse, int32_t *status) {
+    float scale_log2e, float *part_ml, float *part_acc, int32_t *tickets, uint16_t *__restrict__ out,
+    float *__restrict__ lse, int32_t *status) {
   extern __shared__ float smem[];
   float *s_acc = smem;                                  // [WAVES][G][128]
   float *s_m = smem + WAVES * G * SPIN_HEAD_DIM;        // [WAVES][G]
   float *s_l = s_m + WAVES * G;                         // [WAVES][G]
+  __shared__ int s_last;
 
   const int row = blockIdx.x / nsplit;
   const int split = blockIdx.x - row * nsplit;
@@ -55,75 +143,44 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
     }
   }
 
-  float m = NEG_INF, l = 0.f;
-  spin_f32x4 acc[8];
+  softmax_state st;
+  st.m = NEG_INF;
+  st.l = 0.f;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) acc[i] = (spin_f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int i = 0; i < 8; ++i) st.acc[i] = (spin_f32x4){0.f, 0.f, 0.f, 0.f};
 
   const int32_t *rslots = slots + (size_t)row * page_stride;
   const uint16_t *rmask = masks + (size_t)row * page_stride;
 
-  for (int p = p0 + wave; p < p1; p += WAVES) {
-    const int slot = __builtin_amdgcn_readfirstlane(rslots[p]);
-    const unsigned mask = (unsigned)__builtin_amdgcn_readfirstlane((int)rmask[p]);
-    if (slot < 0 || (int64_t)slot >= pool_slots) {
-      if (lane == 0) spin_raise(status, SPIN_ERR_SLOT_RANGE);
-      continue;
+  // this wavefront's pages: p0 + wave + i * WAVES, i < nw
+  const int nw = (p1 - p0 - wave + WAVES - 1) / WAVES;
+  for (int base = 0; base < nw; base += 64) {
+    const int cnt = (nw - base) < 64 ? (nw - base) : 64;
+    int myslot = 0;
+    unsigned mymask = 0;
+    if (lane < cnt) {
+      const int p = p0 + wave + (base + lane) * WAVES;
+      myslot = rslots[p];
+      mymask = rmask[p];
+      if (myslot < 0 || (int64_t)myslot >= pool_slots) {
+        spin_raise(status, SPIN_ERR_SLOT_RANGE);
+        myslot = 0;   // read a valid slot, attend to none of it
+        mymask = 0;
+      }
     }
-    const uint4 *kp = pool + (size_t)slot * SPIN_SLOT_U4;
-    uint4 kv[4], vv[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) kv[j] = kp[j * 64 + lane];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) vv[j] = kp[SPIN_KTILE_U4 + j * 64 + lane];
-
-    // S[token 4c+i][head n]
-    spin_f32x4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(spin_bf16x8, kv[j]), qf[j], s, 0, 0, 0);
-
-    const unsigned mbits = (mask >> (4 * c)) & 0xFu;
-    float sv[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) sv[i] = ((mbits >> i) & 1u) ? s[i] * scale_log2e : NEG_INF;
-    float pm = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-    pm = fmaxf(pm, __shfl_xor(pm, 16));
-    pm = fmaxf(pm, __shfl_xor(pm, 32));
-    const float m_new = fmaxf(m, pm);
-    const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m - m_safe);
-    float pr[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) pr[i] = __builtin_amdgcn_exp2f(sv[i] - m_safe);
-    l = l * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
-    m = m_new;
-
-    // rescale the accumulator rows (head 4c+i) by that head's alpha
-    float ar[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) ar[i] = __shfl(alpha, 4 * c + i);
-#pragma unroll
-    for (int jn = 0; jn < 8; ++jn)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) acc[jn][i] *= ar[i];
-
-    // P as the A operand: row n = head, k = tokens 4c..4c+3
-    spin_bf16x2 p01 = {(__bf16)pr[0], (__bf16)pr[1]};
-    spin_bf16x2 p23 = {(__bf16)pr[2], (__bf16)pr[3]};
-    uint2 pk = {__builtin_bit_cast(uint32_t, p01), __builtin_bit_cast(uint32_t, p23)};
-    const spin_s16x4 pa = __builtin_bit_cast(spin_s16x4, pk);
-#pragma unroll
-    for (int jv = 0; jv < 4; ++jv) {
-      uint2 lo = {vv[jv].x, vv[jv].y}, hi = {vv[jv].z, vv[jv].w};
-      acc[2 * jv] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(spin_s16x4, lo),
-                                                              acc[2 * jv], 0, 0, 0);
-      acc[2 * jv + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(spin_s16x4, hi),
-                                                                  acc[2 * jv + 1], 0, 0, 0);
+    page_regs ra, rb;
+    load_page(ra, pool, __builtin_amdgcn_readlane(myslot, 0), lane);
+    for (int i = 0; i < cnt; i += 2) {
+      if (i + 1 < cnt) load_page(rb, pool, __builtin_amdgcn_readlane(myslot, i + 1), lane);
+      consume_page(st, ra, qf, (unsigned)__builtin_amdgcn_readlane((int)mymask, i), c, scale_log2e);
+      if (i + 2 < cnt) load_page(ra, pool, __builtin_amdgcn_readlane(myslot, i + 2), lane);
+      if (i + 1 < cnt)
+        consume_page(st, rb, qf, (unsigned)__builtin_amdgcn_readlane((int)mymask, i + 1), c, scale_log2e);
     }
   }
 
   // denominators: sum the four token-quad lanes of each head
+  float l = st.l;
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
 
@@ -133,11 +190,11 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
     const int head = 4 * c + i;
     if (head < G) {
 #pragma unroll
-      for (int jn = 0; jn < 8; ++jn) s_acc[(wave * G + head) * SPIN_HEAD_DIM + 16 * jn + n] = acc[jn][i];
+      for (int jn = 0; jn < 8; ++jn) s_acc[(wave * G + head) * SPIN_HEAD_DIM + 16 * jn + n] = st.acc[jn][i];
     }
   }
   if (c == 0 && n < G) {
-    s_m[wave * G + n] = m;
+    s_m[wave * G + n] = st.m;
     s_l[wave * G + n] = l;
   }
   __syncthreads();
@@ -156,49 +213,47 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
       O += s_acc[(w * G + g) * SPIN_HEAD_DIM + d] * wgt;
     }
     if (nsplit == 1) {
-      const size_t o = ((size_t)(b * Hq + h * G + g)) * SPIN_HEAD_DIM + d;
-      const float r = L > 0.f ? O / L : 0.f;
-      out[o] = __builtin_bit_cast(uint16_t, (__bf16)r);
-      if (lse && d == 0)
-        lse[b * Hq + h * G + g] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f : NEG_INF;
+      write_out(out, lse, b * Hq + h * G + g, d, M, L, O);
     } else {
+      // device-scope stores: written through to where every compute die sees them
       const size_t pi = ((size_t)row * nsplit + split) * G + g;
-      part_acc[pi * SPIN_HEAD_DIM + d] = O;
+      dev_store(&part_acc[pi * SPIN_HEAD_DIM + d], O);
       if (d == 0) {
-        part_ml[pi * 2 + 0] = M;
-        part_ml[pi * 2 + 1] = L;
+        dev_store(&part_ml[pi * 2 + 0], M);
+        dev_store(&part_ml[pi * 2 + 1], L);
       }
     }
   }
-}
+  if (nsplit == 1) return;
 
-// merge the split partials of one row in split order
-__global__ __launch_bounds__(256) void spin_decode_merge_kernel(const float *__restrict__ part_ml,
-                                                                const float *__restrict__ part_acc, int G,
-                                                                int Hq, int Hkv, int nsplit,
-                                                                uint16_t *__restrict__ out,
-                                                                float *__restrict__ lse) {
-  const int row = blockIdx.x;
-  const int b = row / Hkv, h = row - b * Hkv;
-  for (int idx = threadIdx.x; idx < G * SPIN_HEAD_DIM; idx += 256) {
+  // Ticket: the last workgroup of the row to arrive merges all splits in split
+  // order.  Partials travel through device-scope atomic stores and loads (no
+  // cache-wide write-back or invalidate); each thread waits for its own stores
+  // to be acknowledged, the barrier orders them before thread 0's ticket.
+  __builtin_amdgcn_s_waitcnt(0);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+  if (threadIdx.x == 0)
+    s_last = (__hip_atomic_fetch_add(&tickets[row], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nsplit - 1);
+  __syncthreads();
+  if (!s_last) return;
+  for (int idx = threadIdx.x; idx < G * SPIN_HEAD_DIM; idx += WAVES * 64) {
     const int g = idx >> 7, d = idx & 127;
     const size_t base = (size_t)row * nsplit * G;
     float M = NEG_INF;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, part_ml[(base + (size_t)s * G + g) * 2]);
+    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, dev_load(&part_ml[(base + (size_t)s * G + g) * 2]));
     const float Ms = (M == NEG_INF) ? 0.f : M;
     float L = 0.f, O = 0.f;
     for (int s = 0; s < nsplit; ++s) {
       const size_t pi = base + (size_t)s * G + g;
-      const float wgt = __builtin_amdgcn_exp2f(part_ml[pi * 2] - Ms);
-      L += part_ml[pi * 2 + 1] * wgt;
-      O += part_acc[pi * SPIN_HEAD_DIM + d] * wgt;
+      const float wgt = __builtin_amdgcn_exp2f(dev_load(&part_ml[pi * 2]) - Ms);
+      L += dev_load(&part_ml[pi * 2 + 1]) * wgt;
+      O += dev_load(&part_acc[pi * SPIN_HEAD_DIM + d]) * wgt;
     }
-    const size_t o = ((size_t)(b * Hq + h * G + g)) * SPIN_HEAD_DIM + d;
-    const float r = L > 0.f ? O / L : 0.f;
-    out[o] = __builtin_bit_cast(uint16_t, (__bf16)r);
-    if (lse && d == 0)
-      lse[b * Hq + h * G + g] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f : NEG_INF;
+    write_out(out, lse, b * Hq + h * G + g, d, M, L, O);
   }
+  if (threadIdx.x == 0)   // ready for the next launch
+    __hip_atomic_store(&tickets[row], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool,
@@ -214,16 +269,13 @@ extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, c
   char *ws = (char *)workspace;
   float *part_ml = (float *)(ws + ctx->ws_ml_off);
   float *part_acc = (float *)(ws + ctx->ws_acc_off);
+  int32_t *tickets = (int32_t *)(ws + ctx->ws_ticket_off);
   const float scale_log2e = ctx->scale * 1.4426950408889634f;
   const size_t lds = (size_t)SPIN_DECODE_WAVES * G * (SPIN_HEAD_DIM + 2) * sizeof(float);
-  hipStream_t st = (hipStream_t)stream;
   spin_launch(ctx, SPIN_K_DECODE, spin_decode_kernel<SPIN_DECODE_WAVES>, dim3((unsigned)(rows * nsplit)),
-              dim3(SPIN_DECODE_WAVES * 64), lds, st, (const uint16_t *)q, (const uint4 *)kv_pool,
-                     pool_slots, slots, valid_mask, npages, ctx->page_stride, G, ctx->cfg.num_q_heads,
-                     ctx->cfg.num_kv_heads, nsplit, scale_log2e, part_ml, part_acc, (uint16_t *)out, lse,
-                     (int32_t *)workspace);
-  if (nsplit > 1)
-    spin_launch(ctx, SPIN_K_MERGE, spin_decode_merge_kernel, dim3((unsigned)rows), dim3(256), 0, st, part_ml, part_acc, G,
-                       ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, (uint16_t *)out, lse);
+              dim3(SPIN_DECODE_WAVES * 64), lds, (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool,
+              pool_slots, slots, valid_mask, npages, ctx->page_stride, G, ctx->cfg.num_q_heads,
+              ctx->cfg.num_kv_heads, nsplit, scale_log2e, part_ml, part_acc, tickets, (uint16_t *)out, lse,
+              (int32_t *)workspace);
   return spin_launch_status();
 }
