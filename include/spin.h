@@ -103,6 +103,7 @@ typedef struct spin_config {
   int32_t lru_timestamps;       /* 0 = all-resident mode; n > 0 = bucketed LRU with n timestamp values */
   int32_t lru_evict_exact;      /* 0 = evict whole buckets <= x; 1 = only as many pages of bucket x as needed */
   int32_t decode_splits;        /* split-K factor of spin_sparse_decode; 0 = choose from the shape */
+  int32_t decode_waves;         /* wavefronts per decode workgroup: 2, 4 or 8; 0 = 8 */
   float softmax_scale;          /* 0 = 1/sqrt(head_dim) */
 } spin_config;
 

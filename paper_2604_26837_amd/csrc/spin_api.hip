@@ -65,12 +65,17 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   x->page_stride = (int32_t)pg;
   x->dir_stride = cdiv32(x->max_pages, c->leaf_entries);
 
+  if (c->decode_waves != 0 && c->decode_waves != 2 && c->decode_waves != 4 && c->decode_waves != 8) {
+    delete x;
+    return SPIN_ERR_INVALID;
+  }
+  x->waves = c->decode_waves ? c->decode_waves : 8;
   int32_t splits = c->decode_splits;
   if (splits == 0) {
-    // about two workgroups on each of the 256 compute units, all resident at
-    // once, and at least four pages per wavefront
-    splits = 512 / x->max_rows;
-    int32_t cap = x->page_stride / (4 * SPIN_DECODE_WAVES);
+    // about one 8-wave workgroup on each of the 256 compute units, all resident
+    // at once, and at least four pages per wavefront (measured best on MI355X)
+    splits = 256 / x->max_rows;
+    int32_t cap = x->page_stride / (4 * x->waves);
     if (splits > cap) splits = cap;
     if (splits < 1) splits = 1;
   }

@@ -12,7 +12,6 @@
 #define SPIN_SLOT_U4 512      // 8192-byte slot in 16-byte units
 #define SPIN_KTILE_U4 256     // 4096-byte K tile in 16-byte units
 #define SPIN_WS_HEADER 256    // bytes reserved in front of the workspace (status word)
-#define SPIN_DECODE_WAVES 4
 
 #define SPIN_KERNEL_IDS 8
 
@@ -28,6 +27,7 @@ struct spin_ctx {
   int32_t page_stride;
   int32_t dir_stride;
   int32_t splits;
+  int32_t waves;          // wavefronts per decode workgroup
   int32_t kd;             // contraction length of one summary row
   int32_t rows_per_part;  // summary rows per partition (REPMAX: reps, else 1)
   float scale;

@@ -125,11 +125,15 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
   const int b = row / Hkv;
   const int h = row - b * Hkv;
 
+  // Pages are dealt round-robin: page p belongs to split p % nsplit and, inside
+  // it, to wavefront (p / nsplit) % WAVES.  The addresses of this wavefront's
+  // slot entries therefore do not depend on the row's page count, and their
+  // load is issued together with it.
+  const int32_t *rslots = slots + (size_t)row * page_stride;
+  const uint16_t *rmask = masks + (size_t)row * page_stride;
+  const int first = wave * nsplit + split, stride = WAVES * nsplit;
   int np = npages[row];
   np = np < 0 ? 0 : (np > page_stride ? page_stride : np);
-  const int per = (np + nsplit - 1) / nsplit;
-  const int p0 = split * per;
-  const int p1 = (p0 + per) < np ? (p0 + per) : np;
 
   // the group's queries as the B operand: column n = head, k = channels 32j+8c..+8
   spin_bf16x8 qf[4];
@@ -149,19 +153,20 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
 #pragma unroll
   for (int i = 0; i < 8; ++i) st.acc[i] = (spin_f32x4){0.f, 0.f, 0.f, 0.f};
 
-  const int32_t *rslots = slots + (size_t)row * page_stride;
-  const uint16_t *rmask = masks + (size_t)row * page_stride;
-
-  // this wavefront's pages: p0 + wave + i * WAVES, i < nw
-  const int nw = (p1 - p0 - wave + WAVES - 1) / WAVES;
-  for (int base = 0; base < nw; base += 64) {
-    const int cnt = (nw - base) < 64 ? (nw - base) : 64;
+  // this wavefront's pages: first + i * stride, i < nw
+  const int nw_max = (page_stride - first + stride - 1) / stride;   // entries that exist in the buffer
+  for (int base = 0; base < nw_max; base += 64) {
     int myslot = 0;
     unsigned mymask = 0;
-    if (lane < cnt) {
-      const int p = p0 + wave + (base + lane) * WAVES;
+    const int p = first + (base + lane) * stride;
+    if (p < page_stride) {
       myslot = rslots[p];
       mymask = rmask[p];
+    }
+    const int nw = np > first ? (np - first + stride - 1) / stride : 0;
+    if (base >= nw) break;
+    const int cnt = (nw - base) < 64 ? (nw - base) : 64;
+    if (lane < cnt) {
       if (myslot < 0 || (int64_t)myslot >= pool_slots) {
         spin_raise(status, SPIN_ERR_SLOT_RANGE);
         myslot = 0;   // read a valid slot, attend to none of it
@@ -271,11 +276,16 @@ extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, c
   float *part_acc = (float *)(ws + ctx->ws_acc_off);
   int32_t *tickets = (int32_t *)(ws + ctx->ws_ticket_off);
   const float scale_log2e = ctx->scale * 1.4426950408889634f;
-  const size_t lds = (size_t)SPIN_DECODE_WAVES * G * (SPIN_HEAD_DIM + 2) * sizeof(float);
-  spin_launch(ctx, SPIN_K_DECODE, spin_decode_kernel<SPIN_DECODE_WAVES>, dim3((unsigned)(rows * nsplit)),
-              dim3(SPIN_DECODE_WAVES * 64), lds, (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool,
-              pool_slots, slots, valid_mask, npages, ctx->page_stride, G, ctx->cfg.num_q_heads,
-              ctx->cfg.num_kv_heads, nsplit, scale_log2e, part_ml, part_acc, tickets, (uint16_t *)out, lse,
-              (int32_t *)workspace);
+  const int W = ctx->waves;
+  const size_t lds = (size_t)W * G * (SPIN_HEAD_DIM + 2) * sizeof(float);
+#define SPIN_DECODE_LAUNCH(WV)                                                                                   \
+  spin_launch(ctx, SPIN_K_DECODE, spin_decode_kernel<WV>, dim3((unsigned)(rows * nsplit)), dim3(WV * 64), lds,   \
+              (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, slots, valid_mask,   \
+              npages, ctx->page_stride, G, ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, scale_log2e,     \
+              part_ml, part_acc, tickets, (uint16_t *)out, lse, (int32_t *)workspace)
+  if (W == 2) SPIN_DECODE_LAUNCH(2);
+  else if (W == 8) SPIN_DECODE_LAUNCH(8);
+  else SPIN_DECODE_LAUNCH(4);
+#undef SPIN_DECODE_LAUNCH
   return spin_launch_status();
 }
