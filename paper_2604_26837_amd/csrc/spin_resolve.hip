@@ -44,11 +44,15 @@ struct res_out {
   uint16_t *mask;
 };
 
+#define RES_DIR_LDS 256
+
+// `dir` points at the row's directory entries (a copy in LDS when it fits)
 __device__ inline void emit_page(const res_out &o, int pos, int page_stride, int page, uint32_t mask,
                                  const int32_t *dir, const int32_t *leaf_pool, int64_t leaf_chunks, int row,
                                  int dir_stride, int leaf_entries, int32_t *status) {
   if (pos < 0 || pos >= page_stride) return;
-  int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, page);
+  (void)row;
+  int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, 0, dir_stride, leaf_entries, page);
   if (slot < 0) {
     spin_raise(status, SPIN_ERR_NOT_RESIDENT);
     slot = -1;
@@ -61,14 +65,22 @@ __device__ inline void emit_page(const res_out &o, int pos, int page_stride, int
 
 __global__ __launch_bounds__(RES_BLOCK) void spin_resolve_kernel(
     const int32_t *__restrict__ sel, const int32_t *__restrict__ nsel, const int32_t *__restrict__ seq_lens,
-    const int32_t *__restrict__ dir, const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, int Hkv, int tp,
+    const int32_t *dir, const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, int Hkv, int tp,
     int sink_pages, int recent_pages, int sel_stride, int page_stride, int dir_stride, int leaf_entries,
     int32_t *__restrict__ slots, int32_t *__restrict__ page_ids, uint16_t *__restrict__ valid_mask,
     int32_t *__restrict__ npages, int32_t *status) {
   __shared__ int s_wave[RES_WAVES];
   __shared__ int s_flagA, s_flagB, s_cntB;
+  __shared__ int32_t s_dir[RES_DIR_LDS];
   const int row = blockIdx.x, tid = threadIdx.x;
   const int b = row / Hkv;
+  // the row's directory entries are fetched together with its selection, so the
+  // leaf lookups below are the only dependent round trip
+  const int32_t *gdir = dir + (size_t)row * dir_stride;
+  const bool dir_in_lds = dir_stride <= RES_DIR_LDS;
+  if (dir_in_lds)
+    for (int i = tid; i < dir_stride; i += RES_BLOCK) s_dir[i] = gdir[i];
+  dir = dir_in_lds ? s_dir : gdir;
   const int N = seq_lens[b];
   const int pages = (N + 15) >> 4;
   int ns = nsel[row];
@@ -77,7 +89,24 @@ __global__ __launch_bounds__(RES_BLOCK) void spin_resolve_kernel(
   res_out o = {slots + (size_t)row * page_stride, page_ids + (size_t)row * page_stride,
                valid_mask + (size_t)row * page_stride};
 
-  if (tp >= 16) {
+  if (dir_in_lds) __syncthreads();
+
+  if (tp == 16) {
+    // partition == page: the selection is the page list.  The entry is loaded
+    // before the row's counts are known (the buffer is sel_stride wide), so the
+    // leaf lookup is the only dependent round trip.
+    for (int i0 = 0; i0 < sel_stride; i0 += RES_BLOCK) {
+      const int i = i0 + tid;
+      const int s = i < sel_stride ? rsel[i] : -1;
+      if (i < ns && s >= 0 && s < pages)
+        emit_page(o, i, page_stride, s, page_mask(s, N), dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries,
+                  status);
+      if (i0 + RES_BLOCK >= ns) break;
+    }
+    const int total = min(ns, page_stride);
+    for (int i = total + tid; i < page_stride; i += RES_BLOCK) { o.slots[i] = -1; o.page_ids[i] = -1; o.mask[i] = 0; }
+    if (tid == 0) npages[row] = total;
+  } else if (tp > 16) {
     const int m = tp >> 4;
     int sink_end = min(sink_pages, pages);
     int recent_begin = max(pages - recent_pages, 0);
