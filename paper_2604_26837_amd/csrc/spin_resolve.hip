@@ -194,6 +194,237 @@ __global__ __launch_bounds__(RES_BLOCK) void spin_resolve_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------
+// Budget mode: bucketed-LRU replacement (Section 5.3), page partitions.
+//
+// One workgroup per row.  The row owns S = slot_base[row+1]-slot_base[row] pool
+// slots; rev_table[slot] = {resident logical page or -1, timestamp}; the leaf
+// entries are the forward map page -> slot.  The four steps run in the paper's
+// order: (1) classify the selected pages by a leaf lookup, (2)+(3) one scan of
+// the row's slots updates timestamps and builds the per-timestamp histogram in
+// LDS, a single wavefront finds the smallest threshold x whose cumulative
+// count covers the net demand, and the pages at or below x are evicted,
+// (4) the misses (ascending page id) take the free slots (ascending slot id),
+// found with one prefix sum over the slots.
+#define LRU_BLOCK 256
+#define LRU_WAVES (LRU_BLOCK / 64)
+#define LRU_MAX_TS 256
+
+__device__ inline int lru_scan(int v, int *s_wave, int &total) {   // exclusive prefix sum over the workgroup
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int o = __shfl_up(inc, d);
+    if (lane >= d) inc += o;
+  }
+  __syncthreads();
+  if (lane == 63) s_wave[wave] = inc;
+  __syncthreads();
+  int off = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < LRU_WAVES; ++w) {
+    const int x = s_wave[w];
+    if (w < wave) off += x;
+    tot += x;
+  }
+  total = tot;
+  return off + inc - v;
+}
+
+__global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_lru_kernel(
+    const int32_t *__restrict__ sel, const int32_t *__restrict__ nsel, const int32_t *__restrict__ seq_lens,
+    const int32_t *__restrict__ dir, int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev,
+    const int32_t *__restrict__ slot_base, int Hkv, int sel_stride, int page_stride, int dir_stride,
+    int leaf_entries, int step, int n_ts, int evict_exact, int max_slots_lds, int32_t *__restrict__ slots,
+    int32_t *__restrict__ page_ids, uint16_t *__restrict__ valid_mask, int32_t *__restrict__ npages,
+    int32_t *__restrict__ miss_pages, int32_t *__restrict__ miss_slots, int32_t *__restrict__ nmiss,
+    int32_t *status) {
+  extern __shared__ int32_t lds[];
+  int32_t *s_loc = lds;                                  // [page_stride]  leaf entry address (as chunk*LE+idx) per selected page
+  int32_t *s_free = lds + page_stride;                   // [page_stride]  free slot (local) by rank
+  uint8_t *s_flag = (uint8_t *)(lds + 2 * page_stride);  // [S] 1 = holds a selected page
+  __shared__ int s_hist[LRU_MAX_TS];
+  __shared__ int s_wave[LRU_WAVES];
+  __shared__ int s_x, s_need_x, s_err;
+
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int b = row / Hkv;
+  const int N = seq_lens[b];
+  const int pages = (N + 15) >> 4;
+  int ns = nsel[row];
+  ns = ns < 0 ? 0 : (ns > sel_stride ? sel_stride : ns);
+  if (ns > page_stride) ns = page_stride;
+  const int32_t *rsel = sel + (size_t)row * sel_stride;
+  int32_t *o_slots = slots + (size_t)row * page_stride;
+  int32_t *o_pages = page_ids + (size_t)row * page_stride;
+  uint16_t *o_mask = valid_mask + (size_t)row * page_stride;
+  int32_t *o_mpages = miss_pages + (size_t)row * page_stride;
+  int32_t *o_mslots = miss_slots + (size_t)row * page_stride;
+  const int sb = slot_base[row];
+  const int S = slot_base[row + 1] - sb;
+  const int32_t *gdir = dir + (size_t)row * dir_stride;
+
+  if (tid == 0) s_err = 0;
+  for (int i = tid; i < n_ts; i += LRU_BLOCK) s_hist[i] = 0;
+  for (int j = tid; j < S && j < max_slots_lds; j += LRU_BLOCK) s_flag[j] = 0;
+  __syncthreads();
+  if (ns > S || S > max_slots_lds || S < 0) {
+    if (tid == 0) { spin_raise(status, SPIN_ERR_BUDGET); npages[row] = 0; nmiss[row] = 0; }
+    for (int i = tid; i < page_stride; i += LRU_BLOCK) { o_slots[i] = -1; o_pages[i] = -1; o_mask[i] = 0; }
+    return;
+  }
+  const int ts_star = min(step, n_ts - 1);
+
+  // (1) classification: hit when the leaf holds a slot of this row
+  int my_miss = 0;
+  for (int i = tid; i < ns; i += LRU_BLOCK) {
+    const int pg = rsel[i];
+    int loc = -1, slot = -1;
+    if (pg >= 0 && pg < pages) {
+      const int ci = pg / leaf_entries;
+      const int32_t chunk = ci < dir_stride ? gdir[ci] : -1;
+      if (chunk >= 0 && (int64_t)chunk < leaf_chunks) {
+        loc = chunk * leaf_entries + (pg - ci * leaf_entries);
+        slot = leaf_pool[loc];
+      }
+    }
+    if (loc < 0) s_err = 1;                       // no leaf for a selected page
+    if (slot >= sb && slot < sb + S) s_flag[slot - sb] = 1;
+    else slot = -1;
+    s_loc[i] = loc;
+    o_slots[i] = slot;                            // hits are final, misses are filled in step (4)
+    o_pages[i] = pg;
+    o_mask[i] = (uint16_t)page_mask(pg, N);
+  }
+  __syncthreads();
+  if (s_err) {
+    if (tid == 0) { spin_raise(status, SPIN_ERR_NOT_RESIDENT); npages[row] = 0; nmiss[row] = 0; }
+    for (int i = tid; i < page_stride; i += LRU_BLOCK) { o_slots[i] = -1; o_pages[i] = -1; o_mask[i] = 0; }
+    return;
+  }
+
+  // (2)+(3a) one scan over the row's slots: timestamps, histogram of evictable pages, empty count
+  const int chunk = (S + LRU_BLOCK - 1) / LRU_BLOCK;
+  const int j0 = min(tid * chunk, S), j1 = min(j0 + chunk, S);
+  int my_free = 0;
+  for (int j = j0; j < j1; ++j) {
+    int2 e = *(const int2 *)(rev + 2 * (size_t)(sb + j));
+    if (e.x < 0) { ++my_free; continue; }
+    int ts = e.y;
+    if (s_flag[j]) ts = ts_star;
+    else {
+      if (step > n_ts - 1) ts = max(ts - 1, 0);
+      ts = min(max(ts, 0), n_ts - 1);
+      atomicAdd(&s_hist[ts], 1);
+    }
+    if (ts != e.y) rev[2 * (size_t)(sb + j) + 1] = ts;
+  }
+  // miss ranks in page order (index order of the ascending selection)
+  for (int i = tid; i < ns; i += LRU_BLOCK) my_miss += (o_slots[i] < 0);
+  int demand, nfree;
+  // ranks need the misses of lower indices: selection entries are dealt round-robin
+  // above, so rank them with a second, contiguous pass
+  (void)lru_scan(my_miss, s_wave, demand);
+  (void)lru_scan(my_free, s_wave, nfree);
+  const int net = max(0, demand - nfree);
+
+  // (3b) threshold search, oldest bucket first
+  if (tid == 0) { s_x = -1; s_need_x = 0; }
+  __syncthreads();
+  if (net > 0 && tid < 64) {
+    // each lane owns a contiguous run of buckets
+    const int per = (n_ts + 63) / 64;
+    const int t0 = min(tid * per, n_ts), t1 = min(t0 + per, n_ts);
+    int local = 0;
+    for (int t = t0; t < t1; ++t) local += s_hist[t];
+    int inc = local;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int o = __shfl_up(inc, d);
+      if (tid >= d) inc += o;
+    }
+    int running = inc - local;
+    for (int t = t0; t < t1; ++t) {
+      if (running < net && running + s_hist[t] >= net) { s_x = t; s_need_x = net - running; }
+      running += s_hist[t];
+    }
+  }
+  __syncthreads();
+  const int x = s_x;
+  if (net > 0 && x < 0) {   // cannot happen when ns <= S; keep the state untouched
+    if (tid == 0) { spin_raise(status, SPIN_ERR_BUDGET); npages[row] = 0; nmiss[row] = 0; }
+    return;
+  }
+
+  // (3c) eviction and free-slot ranking in one pass over the slots
+  int my_eq = 0;
+  if (net > 0 && evict_exact)
+    for (int j = j0; j < j1; ++j) {
+      const int2 e = *(const int2 *)(rev + 2 * (size_t)(sb + j));
+      my_eq += (e.x >= 0 && !s_flag[j] && e.y == x);
+    }
+  int tot_eq = 0, eq_before = 0;
+  if (evict_exact) eq_before = lru_scan(my_eq, s_wave, tot_eq);   // uniform branch: evict_exact is a kernel argument
+  int eq_quota = max(min(s_need_x - eq_before, my_eq), 0);
+  int my_newfree = 0;
+  for (int j = j0; j < j1; ++j) {
+    const int2 e = *(const int2 *)(rev + 2 * (size_t)(sb + j));
+    bool is_free = e.x < 0;
+    if (!is_free && net > 0 && !s_flag[j]) {
+      bool ev = e.y < x || (e.y == x && !evict_exact);
+      if (e.y == x && evict_exact && eq_quota > 0) { ev = true; --eq_quota; }
+      if (ev) {
+        // clear the forward entry of the evicted page and the slot
+        const int pg = e.x, ci = pg / leaf_entries;
+        const int32_t ch = ci < dir_stride ? gdir[ci] : -1;
+        if (ch >= 0 && (int64_t)ch < leaf_chunks) leaf_pool[(size_t)ch * leaf_entries + (pg - ci * leaf_entries)] = -1;
+        *(int2 *)(rev + 2 * (size_t)(sb + j)) = make_int2(-1, 0);
+        is_free = true;
+      }
+    }
+    my_newfree += is_free;
+  }
+  int tot_free;
+  int frank = lru_scan(my_newfree, s_wave, tot_free);
+  for (int j = j0; j < j1; ++j) {
+    const int2 e = *(const int2 *)(rev + 2 * (size_t)(sb + j));
+    if (e.x < 0) {
+      if (frank < page_stride) s_free[frank] = j;
+      ++frank;
+    }
+  }
+  __syncthreads();
+
+  // (4) admission: misses in ascending page order take free slots in ascending slot order
+  const int pchunk = (ns + LRU_BLOCK - 1) / LRU_BLOCK;
+  const int i0 = min(tid * pchunk, ns), i1 = min(i0 + pchunk, ns);
+  int cnt = 0;
+  for (int i = i0; i < i1; ++i) cnt += (o_slots[i] < 0);
+  int tot_miss;
+  int mrank = lru_scan(cnt, s_wave, tot_miss);
+  for (int i = i0; i < i1; ++i) {
+    if (o_slots[i] >= 0) continue;
+    if (mrank >= tot_free || mrank >= page_stride) {   // cannot happen when ns <= S; never index past the free list
+      spin_raise(status, SPIN_ERR_BUDGET);
+      o_mask[i] = 0;
+      ++mrank;
+      continue;
+    }
+    const int j = s_free[mrank];
+    const int pg = o_pages[i];
+    *(int2 *)(rev + 2 * (size_t)(sb + j)) = make_int2(pg, ts_star);
+    leaf_pool[s_loc[i]] = sb + j;
+    o_slots[i] = sb + j;
+    o_mpages[mrank] = pg;
+    o_mslots[mrank] = sb + j;
+    ++mrank;
+  }
+  for (int i = ns + tid; i < page_stride; i += LRU_BLOCK) { o_slots[i] = -1; o_pages[i] = -1; o_mask[i] = 0; }
+  for (int i = tot_miss + tid; i < page_stride; i += LRU_BLOCK) { o_mpages[i] = -1; o_mslots[i] = -1; }
+  if (tid == 0) { npages[row] = ns; nmiss[row] = tot_miss; }
+}
+
 extern "C" int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, const int32_t *sel,
                                   const int32_t *nsel, const int32_t *seq_lens, const int32_t *dir,
                                   int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev_table,
@@ -208,8 +439,18 @@ extern "C" int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, co
   const spin_config &c = ctx->cfg;
   const int rows = batch * c.num_kv_heads;
   if (c.lru_timestamps > 0) {
-    (void)rev_table; (void)slot_base; (void)miss_pages; (void)miss_slots; (void)nmiss;
-    return SPIN_ERR_UNSUPPORTED;
+    if (!rev_table || !slot_base || !miss_pages || !miss_slots || !nmiss) return SPIN_ERR_INVALID;
+    if (c.partition_tokens != 16 || c.lru_timestamps > LRU_MAX_TS) return SPIN_ERR_UNSUPPORTED;
+    // LDS: two int32 per output entry plus one flag byte per slot of the row
+    const int max_slots_lds = 48 * 1024;
+    const size_t lds = (size_t)ctx->page_stride * 8 + max_slots_lds;
+    if (lds > 64 * 1024) return SPIN_ERR_UNSUPPORTED;
+    spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_lru_kernel, dim3((unsigned)rows), dim3(LRU_BLOCK), lds,
+                (hipStream_t)stream, sel, nsel, seq_lens, dir, leaf_pool, leaf_chunks, rev_table, slot_base,
+                c.num_kv_heads, ctx->sel_stride, ctx->page_stride, ctx->dir_stride, c.leaf_entries, step,
+                c.lru_timestamps, c.lru_evict_exact, max_slots_lds, slots, page_ids, valid_mask, npages, miss_pages,
+                miss_slots, nmiss, (int32_t *)workspace);
+    return spin_launch_status();
   }
   spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_kernel, dim3((unsigned)rows), dim3(RES_BLOCK), 0, (hipStream_t)stream, sel, nsel,
                      seq_lens, dir, leaf_pool, leaf_chunks, c.num_kv_heads, c.partition_tokens, c.sink_pages,

@@ -35,13 +35,15 @@ def row_base(offsets: np.ndarray, b: int, h: int, num_kv_heads: int) -> int:
     return num_kv_heads * int(offsets[b]) + h * pp
 
 
-def build_two_level(slot_of: List[np.ndarray], dir_stride: int, leaf_entries: int
-                    ) -> Tuple[np.ndarray, np.ndarray]:
+def build_two_level(slot_of: List[np.ndarray], dir_stride: int, leaf_entries: int,
+                    allocate_all: bool = False) -> Tuple[np.ndarray, np.ndarray]:
     """``slot_of[b]`` = int32 ``[H_kv][pages_b]`` (-1 = page not resident).
 
     Returns ``(dir [rows][dir_stride], leaf_pool [chunks][leaf_entries])``.  A
     leaf chunk is allocated for a 512-page range of a row only if that range
-    holds at least one resident page; everything else stays -1."""
+    holds at least one resident page (``allocate_all``: for every range inside
+    the row's context, as budget mode needs, where any page may be admitted
+    later); everything else stays -1."""
     rows = sum(s.shape[0] for s in slot_of)
     directory = np.full((rows, dir_stride), -1, dtype=np.int32)
     leaves = []
@@ -51,7 +53,7 @@ def build_two_level(slot_of: List[np.ndarray], dir_stride: int, leaf_entries: in
             pages = s.shape[1]
             for ci in range(cdiv(pages, leaf_entries)):
                 seg = s[h, ci * leaf_entries:(ci + 1) * leaf_entries]
-                if (seg >= 0).any():
+                if allocate_all or (seg >= 0).any():
                     leaf = np.full(leaf_entries, -1, dtype=np.int32)
                     leaf[:len(seg)] = seg
                     directory[r, ci] = len(leaves)

@@ -1,0 +1,149 @@
+"""GPU parity of budget-mode resolve (bucketed LRU) against the step-by-step
+oracle: slots of every selected page, the miss list, timestamps and the
+forward/reverse tables, bit-exact, over multi-step traces."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lru
+from paper_2604_26837_amd import binding, synth, tables
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+class Budget:
+    """Device state of budget mode for a workload with page partitions; the
+    selection of each step is fed in directly (stage 3b takes `sel` as input)."""
+
+    def __init__(self, w, budgets, n_ts, evict_exact=False):
+        self.w = w
+        self.sp = binding.Spin.for_workload(w, lru_timestamps=n_ts, lru_evict_exact=int(evict_exact))
+        sp = self.sp
+        self.ws = sp.new_workspace(DEV)
+        rows = w.rows
+        self.budgets = budgets
+        base = np.zeros(rows + 1, dtype=np.int32)
+        base[1:] = np.cumsum(budgets)
+        self.slot_base_np = base
+        self.slot_base = torch.from_numpy(base).to(DEV)
+        empty = [np.full((w.num_kv_heads, w.pages(b)), -1, dtype=np.int32) for b in range(w.batch)]
+        d, l = tables.build_two_level(empty, sp.dir_stride, w.leaf_entries, allocate_all=True)
+        self.dir = torch.from_numpy(d).to(DEV)
+        self.leaf = torch.from_numpy(l).to(DEV)
+        rev = np.zeros((int(base[-1]), 2), dtype=np.int32)
+        rev[:, 0] = -1
+        self.rev = torch.from_numpy(rev).to(DEV)
+        self.seq_lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+        z = lambda *s, dt=torch.int32: torch.zeros(s, dtype=dt, device=DEV)
+        self.sel = z(rows, sp.sel_stride)
+        self.nsel = z(rows)
+        self.slots, self.page_ids = z(rows, sp.page_stride), z(rows, sp.page_stride)
+        self.mask = z(rows, sp.page_stride, dt=torch.int16)
+        self.npages = z(rows)
+        self.miss_pages, self.miss_slots = z(rows, sp.page_stride), z(rows, sp.page_stride)
+        self.nmiss = z(rows)
+
+    def step(self, step, selections):
+        sp, w = self.sp, self.w
+        sel = np.full((w.rows, sp.sel_stride), -1, dtype=np.int32)
+        ns = np.zeros(w.rows, dtype=np.int32)
+        for r, pages in enumerate(selections):
+            sel[r, :len(pages)] = pages
+            ns[r] = len(pages)
+        self.sel.copy_(torch.from_numpy(sel))
+        self.nsel.copy_(torch.from_numpy(ns))
+        sp.resolve_slots(w.batch, step, self.sel, self.nsel, self.seq_lens, self.dir, self.leaf, self.slots,
+                         self.page_ids, self.mask, self.npages, self.ws, rev_table=self.rev,
+                         slot_base=self.slot_base, miss_pages=self.miss_pages, miss_slots=self.miss_slots,
+                         nmiss=self.nmiss)
+        torch.cuda.synchronize()
+        return (self.slots.cpu().numpy(), self.npages.cpu().numpy(), self.miss_pages.cpu().numpy(),
+                self.miss_slots.cpu().numpy(), self.nmiss.cpu().numpy())
+
+
+def _trace(rng, rows, pages_per_row, k, steps, hot_frac=0.7):
+    hot = [rng.choice(pages_per_row[r], size=min(3 * k, pages_per_row[r]), replace=False) for r in range(rows)]
+    out = []
+    for s in range(steps):
+        cur = []
+        for r in range(rows):
+            kk = min(k, pages_per_row[r])
+            nh = min(int(round(hot_frac * kk)), len(hot[r]))
+            a = set(int(x) for x in rng.choice(hot[r], size=nh, replace=False))
+            while len(a) < kk:
+                a.add(int(rng.integers(0, pages_per_row[r])))
+            cur.append(sorted(a))
+        out.append(cur)
+    return out
+
+
+@pytest.mark.parametrize("n_ts,exact,budget_mult", [(64, False, 3.0), (64, True, 3.0), (4, False, 2.0),
+                                                     (4, True, 1.2), (3, False, 1.0)])
+def test_traces_match_oracle(n_ts, exact, budget_mult):
+    k = 12
+    w = synth.config0().with_(seq_lens=(1600, 700, 16 * 600 + 3), num_q_heads=4, num_kv_heads=2, topk=k,
+                              sink_pages=0, recent_pages=0, name="lru")
+    rows = w.rows
+    pages_per_row = [w.pages(r // w.num_kv_heads) for r in range(rows)]
+    rng = np.random.default_rng(n_ts * 7 + int(exact))
+    budgets = [max(k, int(budget_mult * k) + r) for r in range(rows)]
+    bd = Budget(w, budgets, n_ts, exact)
+    caches = [lru.RowCache(budgets[r]) for r in range(rows)]
+    trace = _trace(rng, rows, pages_per_row, k, 20)
+    for step, selections in enumerate(trace):
+        slots, npg, mpages, mslots, nmiss = bd.step(step, selections)
+        assert bd.sp.poll_status(bd.ws) == 0
+        rev = bd.rev.cpu().numpy()
+        for r in range(rows):
+            want_slots, want_miss, hits = lru.lru_step(caches[r], selections[r], step, n_ts, evict_exact=exact)
+            base = int(bd.slot_base_np[r])
+            assert npg[r] == len(selections[r])
+            assert slots[r, :npg[r]].tolist() == [base + s for s in want_slots], f"step {step} row {r}"
+            assert nmiss[r] == len(want_miss)
+            assert mpages[r, :nmiss[r]].tolist() == [p for p, _ in want_miss]
+            assert mslots[r, :nmiss[r]].tolist() == [base + s for _, s in want_miss]
+            # reverse table: resident page and timestamp of every slot
+            got_pages = rev[base:base + budgets[r], 0].tolist()
+            assert got_pages == caches[r].page, f"step {step} row {r}"
+            got_ts = [t if p >= 0 else 0 for p, t in zip(got_pages, rev[base:base + budgets[r], 1].tolist())]
+            assert got_ts == [t if p >= 0 else 0 for p, t in zip(caches[r].page, caches[r].ts)]
+        # forward table consistent with the reverse table
+        leaf = bd.leaf.cpu().numpy()
+        d = bd.dir.cpu().numpy()
+        for r in range(rows):
+            base = int(bd.slot_base_np[r])
+            fwd = {}
+            for ci in range(d.shape[1]):
+                if d[r, ci] >= 0:
+                    for i, s in enumerate(leaf[d[r, ci]]):
+                        if s >= 0:
+                            fwd[ci * w.leaf_entries + i] = int(s) - base
+            assert fwd == caches[r].where
+
+
+def test_budget_smaller_than_selection_is_reported():
+    w = synth.config0().with_(seq_lens=(1600,), num_q_heads=4, num_kv_heads=2, topk=12, sink_pages=0,
+                              recent_pages=0, name="lru_small")
+    bd = Budget(w, [12, 5], 64)
+    sel = [list(range(0, 24, 2)), list(range(1, 25, 2))]
+    slots, npg, _, _, nmiss = bd.step(0, sel)
+    assert bd.sp.poll_status(bd.ws) == -5
+    assert npg[0] == 12 and npg[1] == 0 and nmiss[1] == 0
+    assert (slots[1] == -1).all()
+
+
+def test_large_row_many_slots():
+    """A 256K-token row with a 4096-slot budget, 128 pages per step."""
+    w = synth.config0().with_(seq_lens=(262144,), num_q_heads=4, num_kv_heads=1, topk=128, sink_pages=4,
+                              recent_pages=8, name="lru_big")
+    bd = Budget(w, [4096], 64)
+    cache = lru.RowCache(4096)
+    rng = np.random.default_rng(3)
+    trace = _trace(rng, 1, [16384], 128, 40, hot_frac=0.8)
+    for step, selections in enumerate(trace):
+        slots, npg, mpages, mslots, nmiss = bd.step(step, selections)
+        want_slots, want_miss, _ = lru.lru_step(cache, selections[0], step, 64)
+        assert slots[0, :npg[0]].tolist() == want_slots
+        assert mslots[0, :nmiss[0]].tolist() == [s for _, s in want_miss]
+    assert bd.sp.poll_status(bd.ws) == 0
