@@ -46,11 +46,12 @@
  *              count rounded up to a multiple of 16 (SPIN_PART_ALIGN).  Row
  *              (b,h) owns entries [num_kv_heads*part_offsets[b] + h*PP_b, +PP_b)
  *              of `scores` and of the summary array, PP_b = part_offsets[b+1]-part_offsets[b].
- * summaries    per 16 consecutive partition-rows one TILE, chunk-major
- *              [KD/8][16][8] bf16 where KD is the contraction length:
- *                MINMAX  row = partition,       KD = 256: [max(128) | min(128)]
- *                REPMAX  row = partition*R + r, KD = 128: representative r
- *                SKETCH  row = token,           KD = sketch_channels (16)
+ * summaries    per 16 consecutive summary rows one TILE, chunk-major
+ *              [KD/KC][16][KC] bf16 (KD = contraction length, KC = elements one lane
+ *              feeds to one matrix instruction):
+ *                MINMAX  row = partition,       KD = 256: [max(128) | min(128)], KC = 8
+ *                REPMAX  row = partition*R + r, KD = 128: representative r,      KC = 8
+ *                SKETCH  row = token,           KD = sketch_channels (16),       KC = 4
  *              (written by spin_build_summaries).
  * dir          int32 [rows][dir_stride], dir_stride = ceil(ceil(max_context/page_tokens)/leaf_entries);
  *              entry = index of a leaf chunk in leaf_pool, or -1 (no leaf allocated).

@@ -1,0 +1,72 @@
+"""The C-ABI library loads, exports every function include/spin.h declares, and
+its host-side argument checks work without a GPU (no kernel is launched here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_26837_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    txt = open(os.path.join(ROOT, "include", "spin.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(spin_[a-z_0-9]+)\s*\(", txt)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(build.LIB_PATH):
+        build.build_library()
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert len(names) >= 17
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(binding.EXPORTS) == set(names)
+
+
+def test_create_validates_and_sizes(lib):
+    sp = binding.Spin(max_batch=16, num_q_heads=32, num_kv_heads=8, topk=128, sink_pages=4, recent_pages=8,
+                      max_context=32768)
+    assert sp.sel_stride == 128 and sp.page_stride == 128 and sp.dir_stride == 4
+    assert sp.decode_splits == 2
+    assert sp.workspace_bytes % 256 == 0 and sp.workspace_bytes > 0
+    assert sp.summary_bytes(2048 * 16) == 2048 * 16 * 8 * 512
+    # block partitions: 32 blocks on top of the forced ones, 8 pages each plus stand-alone forced pages
+    sp3 = binding.Spin(max_batch=4, num_q_heads=32, num_kv_heads=8, partition_tokens=128, score_kind=2, topk=32,
+                       topk_includes_forced=0, sink_pages=4, recent_pages=64, max_context=131072)
+    assert sp3.sel_stride == 32 + 1 + 8 + 1 and sp3.page_stride == 42 * 8 + 68 and sp3.dir_stride == 16
+    for bad in (dict(head_dim=64), dict(page_tokens=8), dict(partition_tokens=24), dict(num_q_heads=33),
+                dict(num_q_heads=8 * 17), dict(score_kind=7), dict(decode_waves=3), dict(topk=-1)):
+        cfg = dict(max_batch=1, num_q_heads=32, num_kv_heads=8, topk=8, max_context=1024)
+        cfg.update(bad)
+        with pytest.raises(binding.SpinError):
+            binding.Spin(**cfg)
+
+
+def test_stage_calls_reject_bad_arguments_before_launching(lib):
+    sp = binding.Spin(max_batch=2, num_q_heads=8, num_kv_heads=2, topk=8, max_context=1024)
+    h = sp.h
+    null = None
+    assert lib.spin_sparse_decode(h, 3, null, null, 1, null, null, null, null, null, null, null) == -1   # batch > max
+    assert lib.spin_sparse_decode(h, 1, null, null, 1, null, null, null, null, null, null, null) == -1   # NULL pointers
+    assert lib.spin_sparse_decode(h, 0, null, null, 1, null, null, null, null, null, null, null) == 0    # empty batch
+    assert lib.spin_score_partitions(h, 1, null, null, null, null, null, null, null, null) == -1
+    assert lib.spin_select_topk(h, 1, null, null, null, null, null, null, null) == -1
+    assert lib.spin_workspace_init(h, null, null) == -3
+    assert lib.spin_status_string(-5) == b"slot budget smaller than the step's selection"
+    assert lib.spin_profile_enable(h, -1) == -1
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(build, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        binding.load_library()
