@@ -97,6 +97,8 @@ def build_device_layer(w: synth.Workload, device: str = "cuda:0", keep_natural: 
     dd = synth.generate_on_device(w, device=device)
     layer = LayerState.from_natural_pool(w, dd.slot_of, dd.pool, device=device, **cfg_over)
     layer.q0 = dd.q
+    if w.score_kind == synth.SCORE_SKETCH:
+        layer.set_channels(synth.sketch_channels_on_device(dd))
     layer.build_summaries()
     torch.cuda.synchronize()
     natural = dd.pool if keep_natural else None

@@ -300,8 +300,6 @@ def generate_on_device(w: Workload, device: str = "cuda:0", seed: Optional[int] 
     import torch
 
     seed = w.seed if seed is None else seed
-    if w.block_mean_std > 0.0:
-        raise NotImplementedError("mixture workloads use the host generator")
     d, pt, g = w.head_dim, w.page_tokens, w.group
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
@@ -310,12 +308,6 @@ def generate_on_device(w: Workload, device: str = "cuda:0", seed: Optional[int] 
     q = torch.randn((w.batch, w.num_q_heads, d), generator=gen, device=device,
                     dtype=torch.float32).to(torch.bfloat16)
     nslots = w.total_slots
-    pool = torch.empty((nslots, 2, pt, d), device=device, dtype=torch.bfloat16)
-    for s0 in range(0, nslots, chunk_slots):
-        s1 = min(nslots, s0 + chunk_slots)
-        pool[s0:s1] = torch.randn((s1 - s0, 2, pt, d), generator=gen, device=device,
-                                  dtype=torch.float32).to(torch.bfloat16)
-
     perm = rng.permutation(nslots).astype(np.int32)
     slot_of: List[np.ndarray] = []
     cursor = 0
@@ -323,6 +315,27 @@ def generate_on_device(w: Workload, device: str = "cuda:0", seed: Optional[int] 
         pages = w.pages(b)
         slot_of.append(perm[cursor:cursor + w.num_kv_heads * pages].reshape(w.num_kv_heads, pages))
         cursor += w.num_kv_heads * pages
+
+    pool = torch.empty((nslots, 2, pt, d), device=device, dtype=torch.bfloat16)
+    if w.block_mean_std > 0.0:
+        # per-partition Gaussian mixture: filled row by row in logical order
+        tp = max(w.partition_tokens, 1)
+        for b in range(w.batch):
+            pages = w.pages(b)
+            ntok = pages * pt
+            nblk = -(-ntok // tp)
+            for h in range(w.num_kv_heads):
+                kv = torch.randn((2, ntok, d), generator=gen, device=device, dtype=torch.float32)
+                means = torch.randn((2, nblk, d), generator=gen, device=device,
+                                    dtype=torch.float32) * w.block_mean_std
+                kv += means.repeat_interleave(tp, dim=1)[:, :ntok]
+                slots = torch.from_numpy(slot_of[b][h].astype(np.int64)).to(device)
+                pool[slots] = kv.to(torch.bfloat16).reshape(2, pages, pt, d).transpose(0, 1)
+    else:
+        for s0 in range(0, nslots, chunk_slots):
+            s1 = min(nslots, s0 + chunk_slots)
+            pool[s0:s1] = torch.randn((s1 - s0, 2, pt, d), generator=gen, device=device,
+                                      dtype=torch.float32).to(torch.bfloat16)
 
     if w.planted_frac > 0.0:
         qf = q.to(torch.float32)
@@ -341,6 +354,28 @@ def generate_on_device(w: Workload, device: str = "cuda:0", seed: Optional[int] 
                 base = torch.randn((cnt, d), generator=gen, device=device, dtype=torch.float32)
                 pool[slots, 0, tin] = (base + w.planted_sigma * qhat[b, hq]).to(torch.bfloat16)
     return DeviceData(workload=w, q=q, pool=pool, slot_of=slot_of)
+
+
+def sketch_channels_on_device(dd: DeviceData) -> np.ndarray:
+    """Device-side twin of :func:`sketch_channels` for pools that live in HBM."""
+    import torch
+
+    w = dd.workload
+    acc = torch.zeros((w.num_kv_heads, w.head_dim), dtype=torch.float64, device=dd.pool.device)
+    cnt = 0
+    for b in range(w.batch):
+        n = w.seq_lens[b]
+        for h in range(w.num_kv_heads):
+            slots = torch.from_numpy(dd.slot_of[b][h].astype(np.int64)).to(dd.pool.device)
+            k = dd.pool[slots, 0].reshape(-1, w.head_dim)[:n]
+            acc[h] += k.to(torch.float64).abs().sum(dim=0)
+        cnt += n
+    acc = (acc / max(cnt, 1)).cpu().numpy()
+    out = np.zeros((w.num_kv_heads, w.sketch_channels), dtype=np.int32)
+    for h in range(w.num_kv_heads):
+        order = sorted(range(w.head_dim), key=lambda c: (-acc[h, c], c))
+        out[h] = np.sort(np.array(order[: w.sketch_channels], dtype=np.int32))
+    return out
 
 
 def make_queries_on_device(w: Workload, seed: int, device: str = "cuda:0"):

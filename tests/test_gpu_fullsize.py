@@ -1,0 +1,142 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py
+times (same set-up code, default splits/waves): the whole four-call step runs
+on the device-generated workload and sampled rows are checked one by one
+against the oracle (summaries bit-exact, scores within the fp32 bound, top-k on
+the device's own fp32 scores bit-exact, slots bit-exact, attention within
+2e-2 + 1e-2 |ref|).  Properties that hold at any size are checked on all rows."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attend, bf16, index, resolve, score, select
+from paper_2604_26837_amd import runner, synth
+
+pytestmark = pytest.mark.gpu
+ATOL, RTOL = 2e-2, 1e-2
+KD_KC = {synth.SCORE_MINMAX: (256, 8), synth.SCORE_REPMAX: (128, 8), synth.SCORE_SKETCH: (16, 4)}
+
+
+def _row_pages(natural, layer, b, h):
+    slots = torch.from_numpy(layer.slot_of[b][h].astype(np.int64)).to(natural.device)
+    return natural[slots].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)   # [pages][2][16][D]
+
+
+def _summary_rows(layer, first_row, nrows, kd, kc):
+    """Undo the tile layout for summary rows [first_row, first_row+nrows) (first_row % 16 == 0)."""
+    t0, t1 = first_row // 16, -(-(first_row + nrows) // 16)
+    raw = layer.summaries[t0 * 16 * kd * 2: t1 * 16 * kd * 2].cpu().numpy().view(np.uint16)
+    tiles = raw.reshape(-1, kd // kc, 16, kc).transpose(0, 2, 1, 3).reshape(-1, kd)
+    return tiles[:nrows]
+
+
+def _check_sampled_rows(w, layer, natural, sample):
+    layer.step(layer.q0)
+    torch.cuda.synchronize()
+    assert layer.status() == 0
+    q_bits = layer.q0.view(torch.int16).cpu().numpy().view(np.uint16)
+    scores = layer.scores.cpu().numpy()
+    sel, nsel = layer.sel.cpu().numpy(), layer.nsel.cpu().numpy()
+    slots, npages = layer.slots.cpu().numpy(), layer.npages.cpu().numpy()
+    page_ids = layer.page_ids.cpu().numpy()
+    masks = layer.valid_mask.cpu().numpy().view(np.uint16)
+    out = bf16.decode(layer.out.view(torch.int16).cpu().numpy().view(np.uint16))
+    chan = layer.chan.cpu().numpy() if layer.chan is not None else None
+    g = w.group
+    kd, kc = KD_KC[w.score_kind]
+    rpp = w.reps_per_partition if w.score_kind == synth.SCORE_REPMAX else 1
+
+    # properties on every row
+    for r in range(w.rows):
+        b = r // w.num_kv_heads
+        s = sel[r, :nsel[r]]
+        assert (np.diff(s) > 0).all() and (sel[r, nsel[r]:] == -1).all()
+        assert (np.diff(page_ids[r, :npages[r]]) > 0).all()
+        fp = select.forced_pages(w.seq_lens[b], 16, w.sink_pages, w.recent_pages)
+        assert set(fp) <= set(page_ids[r, :npages[r]].tolist())
+        sl = slots[r, :npages[r]]
+        assert np.array_equal(sl, layer.slot_of[b][r % w.num_kv_heads][page_ids[r, :npages[r]]])
+
+    band = 0
+    for r in sample:
+        b, h = divmod(r, w.num_kv_heads)
+        n, P = w.seq_lens[b], w.partitions(b)
+        pages = _row_pages(natural, layer, b, h)
+        K = bf16.decode(pages[:, 0].reshape(-1, w.head_dim))
+        q = bf16.decode(q_bits[b, h * g:(h + 1) * g])
+        if w.score_kind == synth.SCORE_MINMAX:
+            mins, maxs = index.minmax_summaries(K, n, w.partition_tokens)
+            ref_rows = np.concatenate([maxs, mins], axis=1)
+            s64 = score.score_minmax(q, mins, maxs)
+            eps = 256 * 2.0 ** -24 * np.maximum(np.abs(q[:, None] * mins[None]), np.abs(q[:, None] * maxs[None])).sum(-1).max()
+        elif w.score_kind == synth.SCORE_REPMAX:
+            reps = index.block_representatives(K, n, w.partition_tokens, w.reps_per_partition)
+            ref_rows = reps.reshape(-1, w.head_dim)
+            s64 = score.score_repmax(q, reps)
+            eps = 128 * 2.0 ** -24 * np.abs(np.einsum("prd,gd->prgd", reps, q)).sum(-1).max()
+        else:
+            sk = index.key_sketch(K, n, chan[h])
+            ref_rows = sk
+            s64 = score.score_sketch(q, sk, chan[h])
+            eps = 16 * 2.0 ** -24 * np.abs(sk[:, None, :] * q[None][:, :, chan[h]]).sum(-1).max()
+        base = layer.row_base(b, h)
+        got_rows = bf16.decode(_summary_rows(layer, base * rpp, ref_rows.shape[0], kd, kc))
+        assert np.array_equal(got_rows, ref_rows), f"summaries differ row {r}"
+        s32 = scores[base: base + P]
+        assert np.all(np.abs(s32.astype(np.float64) - s64) <= eps), f"row {r}: score error beyond the fp32 bound"
+        want = select.select_topk(s32, n, 16, w.partition_tokens, w.topk, w.topk_includes_forced,
+                                  w.sink_pages, w.recent_pages)
+        got = sel[r, :nsel[r]].tolist()
+        assert got == want, f"row {r}: selection differs"
+        want64 = select.select_topk(s64, n, 16, w.partition_tokens, w.topk, w.topk_includes_forced,
+                                    w.sink_pages, w.recent_pages)
+        if want64 != got:
+            band += 1
+            forced = set(select.forced_partitions(n, 16, w.partition_tokens, w.sink_pages, w.recent_pages))
+            tau = min(s64[p] for p in want64 if p not in forced)
+            assert len(got) == len(want64)
+            assert all(abs(s64[p] - tau) <= 2 * eps for p in set(got) ^ set(want64))
+        page_map = {(r, pg): int(s) for pg, s in enumerate(layer.slot_of[b][h])}
+        pg_w, sl_w, mk_w = resolve.resolve_slots(got, n, 16, w.partition_tokens, w.sink_pages, w.recent_pages,
+                                                 page_map, r)
+        assert page_ids[r, :npages[r]].tolist() == pg_w and slots[r, :npages[r]].tolist() == sl_w
+        assert masks[r, :npages[r]].tolist() == mk_w
+        sel_pages = bf16.decode(pages[np.asarray(pg_w, dtype=np.int64)])
+        ks, vs = attend.gather_tokens(sel_pages[:, 0], sel_pages[:, 1], mk_w)
+        ref, _ = attend.attend(q, ks, vs, layer.scale)
+        o = out[b, h * g:(h + 1) * g]
+        assert np.all(np.abs(o - ref) <= ATOL + RTOL * np.abs(ref)), f"row {r}: attention err {np.abs(o - ref).max()}"
+    return band
+
+
+def test_config1_headline_sampled_rows():
+    w = synth.config1()
+    layer, natural = runner.build_device_layer(w, keep_natural=True)
+    assert layer.spin.decode_splits == 2
+    band = _check_sampled_rows(w, layer, natural, [0, 37, 70, 127])
+    # bits identical run to run in this launch configuration
+    a = layer.out.clone()
+    layer.step(layer.q0)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), layer.out.view(torch.int16))
+    print("cfg1 rows in the rounding band:", band)
+
+
+def test_config2_token_sketch_sampled_rows():
+    w = synth.config2()
+    layer, natural = runner.build_device_layer(w, keep_natural=True)
+    band = _check_sampled_rows(w, layer, natural, [0, 29, 63])
+    npages = layer.npages.cpu().numpy()
+    masks = layer.valid_mask.cpu().numpy().view(np.uint16)
+    # 1024 selected tokens per row, spread over at most 1024 pages
+    for r in range(w.rows):
+        assert sum(bin(int(m)).count("1") for m in masks[r, :npages[r]]) == 1024
+    print("cfg2 rows in the rounding band:", band, "mean pages/row", npages.mean())
+
+
+def test_config3_block_repmax_sampled_rows():
+    w = synth.config3()
+    layer, natural = runner.build_device_layer(w, keep_natural=True)
+    band = _check_sampled_rows(w, layer, natural, [0, 31])
+    npages = layer.npages.cpu().numpy()
+    assert (npages <= 32 * 8 + 64 + 4).all() and (npages >= 32 * 8 + 64).all()
+    print("cfg3 rows in the rounding band:", band)
