@@ -140,7 +140,7 @@ int spin_poll_status(spin_ctx *ctx, const void *workspace, void *stream);
  * releases the events.  Not for concurrent use with stage calls. */
 enum spin_kernel_id {
   SPIN_K_SCORE = 0, SPIN_K_SELECT = 1, SPIN_K_RESOLVE = 2, SPIN_K_DECODE = 3, SPIN_K_MERGE = 4,
-  SPIN_K_INDEX = 5, SPIN_K_PACK = 6
+  SPIN_K_INDEX = 5, SPIN_K_PACK = 6, SPIN_K_GATHER = 7
 };
 int spin_profile_enable(spin_ctx *ctx, int32_t capacity);
 int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_us, float *min_us);
@@ -204,6 +204,27 @@ int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, const int32_t
                        const int32_t *slot_base, int32_t *slots, int32_t *page_ids,
                        uint16_t *valid_mask, int32_t *npages, int32_t *miss_pages,
                        int32_t *miss_slots, int32_t *nmiss, void *workspace, void *stream);
+
+/* Retrieve steps 3-4 (Section 5.2), after budget-mode stage 3: copy every missed
+ * page into the slot assigned to it.  The full KV lives in pinned host memory as
+ * pages in the slot layout; page `p` of row r is page host_row_base[r] + p.
+ *
+ * spin_copy_misses_host: host-driven.  nmiss / miss_pages / miss_slots and
+ * host_row_base (int64 [rows]) are HOST copies; one 8 KiB hipMemcpyAsync per
+ * miss is issued on `copy_stream`; *pages_copied (may be NULL) gets the count.
+ * The caller orders the copies before stage 4 (event on copy_stream).
+ *
+ * spin_gather_misses: device-driven copy kernel (Section 5.5: one wavefront
+ * per page, pages spread over all wavefronts regardless of owner).  host_kv is
+ * the device-visible address of the pinned buffer; row_base, nmiss, miss_pages,
+ * miss_slots are DEVICE arrays (stage 3's outputs, untouched by the host);
+ * enqueued on `stream`, so stage 4 on the same stream simply follows it. */
+int spin_copy_misses_host(spin_ctx *ctx, int32_t batch, const void *host_kv, const int64_t *host_row_base,
+                          const int32_t *nmiss, const int32_t *miss_pages, const int32_t *miss_slots,
+                          void *kv_pool, int64_t pool_slots, void *copy_stream, int64_t *pages_copied);
+int spin_gather_misses(spin_ctx *ctx, int32_t batch, const void *host_kv, const int64_t *row_base,
+                       const int32_t *nmiss, const int32_t *miss_pages, const int32_t *miss_slots,
+                       void *kv_pool, int64_t pool_slots, void *workspace, void *stream);
 
 /* Stage 4.  out[b][hq] (DEVICE bf16 [batch][num_q_heads][128]) =
  * softmax(scale * q K_S^T) V_S over the tokens whose mask bit is set in the

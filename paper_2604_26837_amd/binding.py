@@ -22,6 +22,7 @@ EXPORTS = [
     "spin_page_stride", "spin_dir_stride", "spin_decode_splits", "spin_summary_bytes",
     "spin_workspace_init", "spin_poll_status", "spin_profile_enable", "spin_profile_read", "spin_pack_kv_pages", "spin_build_summaries",
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
+    "spin_copy_misses_host", "spin_gather_misses",
 ]
 
 
@@ -71,6 +72,8 @@ def load_library() -> C.CDLL:
     lib.spin_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
+    lib.spin_copy_misses_host.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(i64)]
+    lib.spin_gather_misses.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i64, vp, vp]
     _LIB = lib
     return lib
 
@@ -157,7 +160,7 @@ class Spin:
     def summary_bytes(self, padded_partitions: int) -> int:
         return self.lib.spin_summary_bytes(self.h, padded_partitions)
 
-    KERNEL_IDS = dict(score=0, select=1, resolve=2, decode=3, merge=4, index=5, pack=6)
+    KERNEL_IDS = dict(score=0, select=1, resolve=2, decode=3, merge=4, index=5, pack=6, gather=7)
 
     def profile_enable(self, capacity: int):
         self._check(self.lib.spin_profile_enable(self.h, capacity), "spin_profile_enable")
@@ -211,6 +214,32 @@ class Spin:
             _ptr(valid_mask, torch.int16, "valid_mask"), _ptr(npages, torch.int32, "npages"),
             _ptr(miss_pages, torch.int32, "miss_pages"), _ptr(miss_slots, torch.int32, "miss_slots"),
             _ptr(nmiss, torch.int32, "nmiss"), _ptr(ws), _stream()), "spin_resolve_slots")
+
+    def copy_misses_host(self, batch, host_kv, host_row_base, nmiss, miss_pages, miss_slots, kv_pool,
+                         copy_stream) -> int:
+        """All list arguments are HOST (pinned) tensors; returns the pages copied."""
+        pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192
+        n = C.c_int64(0)
+        for t, dt in ((host_row_base, torch.int64), (nmiss, torch.int32), (miss_pages, torch.int32),
+                      (miss_slots, torch.int32)):
+            if t.is_cuda or not t.is_contiguous() or t.dtype != dt:
+                raise ValueError("host lists must be contiguous CPU tensors of the documented dtype")
+        self._check(self.lib.spin_copy_misses_host(
+            self.h, batch, host_kv.data_ptr(), host_row_base.data_ptr(), nmiss.data_ptr(), miss_pages.data_ptr(),
+            miss_slots.data_ptr(), _ptr(kv_pool), pool_slots, copy_stream.cuda_stream, C.byref(n)),
+            "spin_copy_misses_host")
+        return n.value
+
+    def gather_misses(self, batch, host_kv, row_base, nmiss, miss_pages, miss_slots, kv_pool, ws):
+        """host_kv: pinned CPU tensor (read by the kernel); the lists are DEVICE tensors."""
+        pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192
+        if not host_kv.is_pinned():
+            raise ValueError("host_kv must be pinned host memory")
+        self._check(self.lib.spin_gather_misses(
+            self.h, batch, host_kv.data_ptr(), _ptr(row_base, torch.int64, "row_base"),
+            _ptr(nmiss, torch.int32, "nmiss"), _ptr(miss_pages, torch.int32, "miss_pages"),
+            _ptr(miss_slots, torch.int32, "miss_slots"), _ptr(kv_pool), pool_slots, _ptr(ws), _stream()),
+            "spin_gather_misses")
 
     def sparse_decode(self, batch, q, kv_pool, slots, valid_mask, npages, out, lse, ws):
         pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192

@@ -1,0 +1,83 @@
+// Retrieve steps 3-4 (Section 5.2): bring the missed pages from pinned host
+// memory into the slots stage 3b assigned to them.
+//
+// Two copiers.  The host-driven one issues one 8 KiB hipMemcpyAsync per miss on
+// a side stream (needs the miss list on the host).  The device-driven one is
+// the paper's copy kernel (Section 5.5): one wavefront copies one page with
+// 16-byte lane transactions straight out of pinned host memory; workgroups are
+// dealt (row, chunk of misses) pairs so pages spread over the whole chip
+// whatever row owns them, and the miss list never leaves the device.
+#include "spin_common.h"
+
+extern "C" int spin_copy_misses_host(spin_ctx *ctx, int32_t batch, const void *host_kv,
+                                     const int64_t *host_row_base, const int32_t *nmiss,
+                                     const int32_t *miss_pages, const int32_t *miss_slots, void *kv_pool,
+                                     int64_t pool_slots, void *copy_stream, int64_t *pages_copied) {
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || pool_slots <= 0) return SPIN_ERR_INVALID;
+  if (pages_copied) *pages_copied = 0;
+  if (batch == 0) return SPIN_OK;
+  if (!host_kv || !host_row_base || !nmiss || !miss_pages || !miss_slots || !kv_pool) return SPIN_ERR_INVALID;
+  const int rows = batch * ctx->cfg.num_kv_heads;
+  const int stride = ctx->page_stride;
+  int64_t total = 0;
+  for (int r = 0; r < rows; ++r) {
+    const int n = nmiss[r];
+    if (n < 0 || n > stride) return SPIN_ERR_INVALID;
+    for (int i = 0; i < n; ++i) {
+      const int32_t pg = miss_pages[(size_t)r * stride + i], slot = miss_slots[(size_t)r * stride + i];
+      if (pg < 0 || slot < 0 || (int64_t)slot >= pool_slots) return SPIN_ERR_INVALID;
+      const char *src = (const char *)host_kv + (size_t)(host_row_base[r] + pg) * SPIN_SLOT_BYTES;
+      char *dst = (char *)kv_pool + (size_t)slot * SPIN_SLOT_BYTES;
+      SPIN_HIP_CHECK(hipMemcpyAsync(dst, src, SPIN_SLOT_BYTES, hipMemcpyHostToDevice, (hipStream_t)copy_stream));
+      ++total;
+    }
+  }
+  if (pages_copied) *pages_copied = total;
+  return SPIN_OK;
+}
+
+#define GATHER_WAVES 4
+#define GATHER_PAGES_PER_WG 16
+
+__global__ __launch_bounds__(GATHER_WAVES * 64) void spin_gather_kernel(
+    const uint4 *__restrict__ host_kv, const int64_t *__restrict__ row_base, const int32_t *__restrict__ nmiss,
+    const int32_t *__restrict__ miss_pages, const int32_t *__restrict__ miss_slots, uint4 *__restrict__ pool,
+    int64_t pool_slots, int page_stride, int chunks_per_row, int32_t *status) {
+  const int row = blockIdx.x / chunks_per_row, chunk = blockIdx.x - row * chunks_per_row;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int n = nmiss[row];
+  n = n < 0 ? 0 : (n > page_stride ? page_stride : n);
+  const int begin = chunk * GATHER_PAGES_PER_WG;
+  const int end = min(begin + GATHER_PAGES_PER_WG, n);
+  const int64_t rb = row_base[row];
+  for (int i = begin + wave; i < end; i += GATHER_WAVES) {
+    const int32_t pg = miss_pages[(size_t)row * page_stride + i];
+    const int32_t slot = miss_slots[(size_t)row * page_stride + i];
+    if (pg < 0 || slot < 0 || (int64_t)slot >= pool_slots) {
+      if (lane == 0) spin_raise(status, SPIN_ERR_SLOT_RANGE);
+      continue;
+    }
+    const uint4 *src = host_kv + (size_t)(rb + pg) * SPIN_SLOT_U4 + lane;
+    uint4 *dst = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
+    uint4 v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = src[k * 64];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) dst[k * 64] = v[k];
+  }
+}
+
+extern "C" int spin_gather_misses(spin_ctx *ctx, int32_t batch, const void *host_kv, const int64_t *row_base,
+                                  const int32_t *nmiss, const int32_t *miss_pages, const int32_t *miss_slots,
+                                  void *kv_pool, int64_t pool_slots, void *workspace, void *stream) {
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || pool_slots <= 0) return SPIN_ERR_INVALID;
+  if (batch == 0) return SPIN_OK;
+  if (!host_kv || !row_base || !nmiss || !miss_pages || !miss_slots || !kv_pool) return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  const int rows = batch * ctx->cfg.num_kv_heads;
+  const int chunks = (ctx->page_stride + GATHER_PAGES_PER_WG - 1) / GATHER_PAGES_PER_WG;
+  spin_launch(ctx, SPIN_K_GATHER, spin_gather_kernel, dim3((unsigned)(rows * chunks)), dim3(GATHER_WAVES * 64), 0,
+              (hipStream_t)stream, (const uint4 *)host_kv, row_base, nmiss, miss_pages, miss_slots,
+              (uint4 *)kv_pool, pool_slots, ctx->page_stride, chunks, (int32_t *)workspace);
+  return spin_launch_status();
+}

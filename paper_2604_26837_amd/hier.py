@@ -1,0 +1,149 @@
+"""Hierarchical-KV layer: the full KV of every request lives in pinned host
+memory, each (request, KV head) row owns a fixed budget of HBM slots, and a
+decode step is score -> select -> resolve under the budget (bucketed LRU) ->
+copy of the missed pages -> attention.  Orchestration only; the compute is in
+libspin.so."""
+from __future__ import annotations
+
+import math
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding, runner, synth, tables
+
+
+def request_workload(w: synth.Workload, b: int) -> synth.Workload:
+    """The single-request workload request ``b`` of ``w`` is generated from."""
+    return w.with_(seq_lens=(w.seq_lens[b],), seed=w.seed * 100 + b, name=f"{w.name}_req{b}")
+
+
+class HierLayer:
+    def __init__(self, w: synth.Workload, budget_frac: float = 0.25, n_ts: int = 64, evict_exact: bool = False,
+                 device: str = "cuda:0", copy_mode: str = "memcpy", keep_natural: bool = False, **cfg_over):
+        assert w.partition_tokens == 16 and w.score_kind == synth.SCORE_MINMAX
+        assert copy_mode in ("memcpy", "gather")
+        self.w, self.device, self.copy_mode = w, device, copy_mode
+        self.spin = binding.Spin.for_workload(w, lru_timestamps=n_ts, lru_evict_exact=int(evict_exact), **cfg_over)
+        sp = self.spin
+        self.ws = sp.new_workspace(device)
+        rows, hkv = w.rows, w.num_kv_heads
+        # slot budget per row: a fraction of the request's pages, never below one step's selection
+        self.budgets = [max(int(math.ceil(budget_frac * w.pages(r // hkv))), sp.page_stride) for r in range(rows)]
+        base = np.zeros(rows + 1, dtype=np.int64)
+        base[1:] = np.cumsum(self.budgets)
+        self.pool_slots = int(base[-1])
+        self.slot_base_np = base.astype(np.int32)
+        self.slot_base = torch.from_numpy(self.slot_base_np).to(device)
+        self.kv_pool = torch.zeros((self.pool_slots, 4096), dtype=torch.bfloat16, device=device)
+        # host side: all pages of all rows, in slot layout, row after row
+        hrb = np.zeros(rows + 1, dtype=np.int64)
+        hrb[1:] = np.cumsum([w.pages(r // hkv) for r in range(rows)])
+        self.host_row_base_np = hrb
+        self.host_row_base = torch.from_numpy(hrb[:-1].copy())                  # host int64 [rows]
+        self.host_row_base_dev = self.host_row_base.to(device)
+        self.host_kv = torch.empty((int(hrb[-1]), 4096), dtype=torch.bfloat16, pin_memory=True)
+        # metadata: leaves for every page range inside a row's context, nothing resident yet
+        empty = [np.full((hkv, w.pages(b)), -1, dtype=np.int32) for b in range(w.batch)]
+        d, l = tables.build_two_level(empty, sp.dir_stride, w.leaf_entries, allocate_all=True)
+        self.dir = torch.from_numpy(d).to(device)
+        self.leaf_pool = torch.from_numpy(l).to(device)
+        rev = np.zeros((self.pool_slots, 2), dtype=np.int32)
+        rev[:, 0] = -1
+        self.rev = torch.from_numpy(rev).to(device)
+        self.seq_lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=device)
+        self.part_offsets_np = tables.part_offsets(w.seq_lens, 16)
+        self.part_offsets = torch.from_numpy(self.part_offsets_np).to(device)
+        padded = int(self.part_offsets_np[-1])
+        self.summaries = torch.zeros(sp.summary_bytes(padded), dtype=torch.uint8, device=device)
+        self.scores = torch.zeros(padded * hkv, dtype=torch.float32, device=device)
+        z = lambda *s, dt=torch.int32: torch.zeros(s, dtype=dt, device=device)
+        self.sel, self.nsel = z(rows, sp.sel_stride), z(rows)
+        self.slots, self.page_ids = z(rows, sp.page_stride), z(rows, sp.page_stride)
+        self.valid_mask, self.npages = z(rows, sp.page_stride, dt=torch.int16), z(rows)
+        self.miss_pages, self.miss_slots, self.nmiss = z(rows, sp.page_stride), z(rows, sp.page_stride), z(rows)
+        self.out = torch.zeros((w.batch, w.num_q_heads, w.head_dim), dtype=torch.bfloat16, device=device)
+        self.lse = torch.zeros((w.batch, w.num_q_heads), dtype=torch.float32, device=device)
+        hp = lambda *s: torch.zeros(s, dtype=torch.int32, pin_memory=True)
+        self.h_nmiss, self.h_miss_pages, self.h_miss_slots = hp(rows), hp(rows, sp.page_stride), hp(rows, sp.page_stride)
+        self.copy_stream = torch.cuda.Stream(device=device)
+        self.scale = 1.0 / math.sqrt(w.head_dim)
+        self.natural: List[Optional[torch.Tensor]] = []
+        self.natural_slot_of: List[np.ndarray] = []
+        self.stats = dict(steps=0, selected=0, misses=0, misses_after_first=0, selected_after_first=0)
+        self._materialise(keep_natural)
+
+    # ------------------------------------------------------------------
+    def _materialise(self, keep_natural: bool):
+        """Generate every request in HBM, build its summaries there, and move its
+        packed pages to pinned host memory (the prefill-side Index and Offload)."""
+        w, hkv = self.w, self.w.num_kv_heads
+        qs = []
+        for b in range(w.batch):
+            wb = request_workload(w, b)
+            tmp, natural = runner.build_device_layer(wb, device=self.device, keep_natural=True)
+            qs.append(tmp.q0)
+            pp = int(self.part_offsets_np[b + 1] - self.part_offsets_np[b])
+            off = hkv * int(self.part_offsets_np[b]) * 512
+            self.summaries[off: off + hkv * pp * 512] = tmp.summaries[: hkv * pp * 512]
+            for h in range(hkv):
+                r = b * hkv + h
+                slots = torch.from_numpy(tmp.slot_of[0][h].astype(np.int64)).to(self.device)
+                lo, hi = int(self.host_row_base_np[r]), int(self.host_row_base_np[r + 1])
+                self.host_kv[lo:hi].copy_(tmp.kv_pool[slots])
+            if keep_natural:
+                self.natural.append(natural.cpu())
+                self.natural_slot_of.append(tmp.slot_of[0])
+            del tmp, natural
+        self.q0 = torch.cat(qs, dim=0).contiguous()
+        torch.cuda.synchronize()
+
+    # ------------------------------------------------------------------
+    def step(self, q: torch.Tensor, step: int, summaries: Optional[torch.Tensor] = None, count: bool = True):
+        sp, w = self.spin, self.w
+        summ = self.summaries if summaries is None else summaries
+        sp.score_partitions(w.batch, q, summ, None, self.part_offsets, self.seq_lens, self.scores, self.ws)
+        sp.select_topk(w.batch, self.scores, self.part_offsets, self.seq_lens, self.sel, self.nsel, self.ws)
+        sp.resolve_slots(w.batch, step, self.sel, self.nsel, self.seq_lens, self.dir, self.leaf_pool, self.slots,
+                         self.page_ids, self.valid_mask, self.npages, self.ws, rev_table=self.rev,
+                         slot_base=self.slot_base, miss_pages=self.miss_pages, miss_slots=self.miss_slots,
+                         nmiss=self.nmiss)
+        main = torch.cuda.current_stream()
+        if self.copy_mode == "memcpy":
+            self.h_nmiss.copy_(self.nmiss, non_blocking=True)
+            self.h_miss_pages.copy_(self.miss_pages, non_blocking=True)
+            self.h_miss_slots.copy_(self.miss_slots, non_blocking=True)
+            main.synchronize()                       # the host needs the miss list
+            copied = sp.copy_misses_host(w.batch, self.host_kv, self.host_row_base, self.h_nmiss,
+                                         self.h_miss_pages, self.h_miss_slots, self.kv_pool, self.copy_stream)
+            ev = torch.cuda.Event()
+            ev.record(self.copy_stream)
+            main.wait_event(ev)
+        else:
+            sp.gather_misses(w.batch, self.host_kv, self.host_row_base_dev, self.nmiss, self.miss_pages,
+                             self.miss_slots, self.kv_pool, self.ws)
+            copied = None
+        sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
+                         self.ws)
+        if count:
+            if copied is None:
+                copied = int(self.nmiss.sum().item())
+            selected = int(self.npages.sum().item())
+            st = self.stats
+            st["steps"] += 1
+            st["selected"] += selected
+            st["misses"] += copied
+            if step > 0:
+                st["selected_after_first"] += selected
+                st["misses_after_first"] += copied
+        return copied
+
+    def hit_rates(self):
+        st = self.stats
+        overall = 1.0 - st["misses"] / max(st["selected"], 1)
+        warm = 1.0 - st["misses_after_first"] / max(st["selected_after_first"], 1)
+        return overall, warm
+
+    def status(self) -> int:
+        return self.spin.poll_status(self.ws)

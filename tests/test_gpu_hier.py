@@ -1,0 +1,70 @@
+"""End-to-end budget mode on a small hierarchical workload: full KV in pinned
+host memory, bucketed LRU on the device, misses copied in (both copiers), then
+attention.  Every step is checked against the oracle: selection on the device's
+fp32 scores, slots and miss list against the step-by-step LRU, and attention
+against fp64 attention over the LOGICAL pages -- which only holds if every
+missed page was copied into exactly the slot the LRU assigned."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attend, bf16, lru, select
+from paper_2604_26837_amd import hier, synth
+
+pytestmark = pytest.mark.gpu
+ATOL, RTOL = 2e-2, 1e-2
+
+
+def _small():
+    return synth.config4().with_(seq_lens=(2048, 5000, 9001), num_q_heads=8, num_kv_heads=2, topk=24,
+                                 sink_pages=2, recent_pages=3, name="hier_small")
+
+
+@pytest.mark.parametrize("copy_mode,exact", [("memcpy", False), ("gather", False), ("gather", True)])
+def test_steps_match_oracle(copy_mode, exact):
+    w = _small()
+    n_ts = 6                      # small range: demotion kicks in within the trace
+    layer = hier.HierLayer(w, budget_frac=0.06, n_ts=n_ts, evict_exact=exact, copy_mode=copy_mode, keep_natural=True)
+    rows, g = w.rows, w.group
+    caches = [lru.RowCache(layer.budgets[r]) for r in range(rows)]
+    nat = [n.view(torch.int16).numpy().view(np.uint16) for n in layer.natural]      # per request [slots][2][16][D]
+    q = layer.q0
+    trace = [[] for _ in range(rows)]
+    for step in range(14):
+        layer.step(q, step)
+        torch.cuda.synchronize()
+        assert layer.status() == 0
+        scores = layer.scores.cpu().numpy()
+        sel, nsel = layer.sel.cpu().numpy(), layer.nsel.cpu().numpy()
+        slots, npages = layer.slots.cpu().numpy(), layer.npages.cpu().numpy()
+        mp, ms, nm = layer.miss_pages.cpu().numpy(), layer.miss_slots.cpu().numpy(), layer.nmiss.cpu().numpy()
+        out = bf16.decode(layer.out.view(torch.int16).cpu().numpy().view(np.uint16))
+        q_bits = q.view(torch.int16).cpu().numpy().view(np.uint16)
+        for r in range(rows):
+            b, h = divmod(r, w.num_kv_heads)
+            n, P = w.seq_lens[b], w.partitions(b)
+            base = w.num_kv_heads * int(layer.part_offsets_np[b]) + h * int(layer.part_offsets_np[b + 1] - layer.part_offsets_np[b])
+            want_sel = select.select_topk(scores[base:base + P], n, 16, 16, w.topk, True, w.sink_pages, w.recent_pages)
+            assert sel[r, :nsel[r]].tolist() == want_sel
+            trace[r].append(want_sel)
+            want_slots, want_miss, _ = lru.lru_step(caches[r], want_sel, step, n_ts, evict_exact=exact)
+            sb = int(layer.slot_base_np[r])
+            assert slots[r, :npages[r]].tolist() == [sb + s for s in want_slots], f"step {step} row {r}"
+            assert mp[r, :nm[r]].tolist() == [p for p, _ in want_miss]
+            assert ms[r, :nm[r]].tolist() == [sb + s for _, s in want_miss]
+            # attention over the logical pages
+            pages = bf16.decode(nat[b][layer.natural_slot_of[b][h][np.asarray(want_sel, dtype=np.int64)]])
+            masks = [(1 << min(16, n - 16 * p)) - 1 for p in want_sel]
+            ks, vs = attend.gather_tokens(pages[:, 0], pages[:, 1], masks)
+            qh = bf16.decode(q_bits[b, h * g:(h + 1) * g])
+            ref, _ = attend.attend(qh, ks, vs, layer.scale)
+            o = out[b, h * g:(h + 1) * g]
+            assert np.all(np.abs(o - ref) <= ATOL + RTOL * np.abs(ref)), f"step {step} row {r}: {np.abs(o - ref).max()}"
+        q = torch.from_numpy(synth.next_query_ar1(q_bits, 0.9, w.seed + 5000 + step).view(np.int16)).to(q.device).view(torch.bfloat16)
+    overall, warm = layer.hit_rates()
+    # compulsory misses and the clairvoyant policy bound the measured misses from below
+    compulsory = sum(len(set().union(*[set(x) for x in t])) for t in trace)
+    belady = sum(lru.belady_min_misses(trace[r], layer.budgets[r]) for r in range(rows))
+    assert compulsory <= belady <= layer.stats["misses"]
+    assert 0.0 < warm < 1.0
+    print(f"{copy_mode} exact={exact}: hit rate overall {overall:.3f}, after step 0 {warm:.3f}")
