@@ -21,6 +21,8 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   if (tp <= 0) return SPIN_ERR_INVALID;
   if (!((tp < 16 && 16 % tp == 0) || (tp >= 16 && tp % 16 == 0))) return SPIN_ERR_UNSUPPORTED;
   if (c->lru_timestamps > 256) return SPIN_ERR_UNSUPPORTED;
+  if (c->score_tiles_per_wg < 0 || (c->score_waves != 0 && c->score_waves != 4 && c->score_waves != 8))
+    return SPIN_ERR_INVALID;
 
   spin_ctx *x = new (std::nothrow) spin_ctx;
   if (!x) return SPIN_ERR_INVALID;
