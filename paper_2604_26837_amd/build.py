@@ -11,7 +11,8 @@ import sys
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
-LIB_PATH = os.path.join(PKG_DIR, "libspin.so")
+# SPIN_LIB_PATH lets a developer load an experimental build instead of the in-tree one
+LIB_PATH = os.environ.get("SPIN_LIB_PATH") or os.path.join(PKG_DIR, "libspin.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -75,6 +75,12 @@ __device__ inline void spin_raise(int32_t *status, int32_t err) { atomicCAS(stat
 
 __device__ inline float spin_bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
+// 16-byte load marked non-temporal (streamed once, not worth keeping in cache)
+typedef __attribute__((ext_vector_type(4))) unsigned int spin_u32x4;
+__device__ inline uint4 spin_nt_load(const uint4 *p) {
+  return __builtin_bit_cast(uint4, __builtin_nontemporal_load((const spin_u32x4 *)p));
+}
+
 // fp32 -> bf16 bits, round to nearest even
 __device__ inline uint16_t spin_f32_to_bf16(float f) {
   uint32_t u = __float_as_uint(f);

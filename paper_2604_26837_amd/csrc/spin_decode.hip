@@ -1,7 +1,7 @@
 // Stage 4: paged GQA decode attention over the resolved pages of each row
 // (Section 4.1, Attention: standard attention restricted to the selected KV).
 //
-// One workgroup = one (row, split) pair; its four wavefronts walk the split's
+// One workgroup = one (row, split) pair; its wavefronts are dealt the split's
 // pages round-robin.  Per page a wavefront issues eight contiguous 1 KiB loads
 // (K tile then V tile of the slot), forms the 16 x 16 logit tile
 // S[token][head] = K Q^T with four 16x16x32 bf16 matrix instructions (the
@@ -36,9 +36,9 @@ struct page_regs {
 __device__ inline void load_page(page_regs &r, const uint4 *__restrict__ pool, int slot, int lane) {
   const uint4 *kp = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) r.k[j] = kp[j * 64];
+  for (int j = 0; j < 4; ++j) r.k[j] = spin_nt_load(kp + j * 64);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) r.v[j] = kp[SPIN_KTILE_U4 + j * 64];
+  for (int j = 0; j < 4; ++j) r.v[j] = spin_nt_load(kp + SPIN_KTILE_U4 + j * 64);
 }
 
 struct softmax_state {
@@ -242,18 +242,47 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
     s_last = (__hip_atomic_fetch_add(&tickets[row], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nsplit - 1);
   __syncthreads();
   if (!s_last) return;
+  // All loads of the merge are independent of each other: the (m, l) pairs are
+  // staged through LDS by one thread each, and every thread issues its
+  // accumulator loads eight splits at a time, the first batch before the
+  // barrier, so the merge costs about one memory round trip.
+  const size_t pbase = (size_t)row * nsplit * G;
+  float *t_m = s_acc, *t_l = s_acc + nsplit * G;   // s_acc is free: the wave partials were consumed above
+  constexpr int CH = 8;
+  float a0[CH];
+  {
+    const int g = threadIdx.x >> 7, d = threadIdx.x & 127;
+#pragma unroll
+    for (int s = 0; s < CH; ++s)
+      a0[s] = (threadIdx.x < G * SPIN_HEAD_DIM && s < nsplit)
+                  ? dev_load(&part_acc[(pbase + (size_t)s * G + g) * SPIN_HEAD_DIM + d]) : 0.f;
+  }
+  for (int i = threadIdx.x; i < nsplit * G; i += WAVES * 64) {
+    t_m[i] = dev_load(&part_ml[(pbase + i) * 2]);
+    t_l[i] = dev_load(&part_ml[(pbase + i) * 2 + 1]);
+  }
+  __syncthreads();
   for (int idx = threadIdx.x; idx < G * SPIN_HEAD_DIM; idx += WAVES * 64) {
     const int g = idx >> 7, d = idx & 127;
-    const size_t base = (size_t)row * nsplit * G;
     float M = NEG_INF;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, dev_load(&part_ml[(base + (size_t)s * G + g) * 2]));
+    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, t_m[s * G + g]);
     const float Ms = (M == NEG_INF) ? 0.f : M;
     float L = 0.f, O = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-      const size_t pi = base + (size_t)s * G + g;
-      const float wgt = __builtin_amdgcn_exp2f(dev_load(&part_ml[pi * 2]) - Ms);
-      L += dev_load(&part_ml[pi * 2 + 1]) * wgt;
-      O += dev_load(&part_acc[pi * SPIN_HEAD_DIM + d]) * wgt;
+    for (int s0 = 0; s0 < nsplit; s0 += CH) {
+      float a[CH];
+#pragma unroll
+      for (int s = 0; s < CH; ++s) {
+        if (idx == (int)threadIdx.x && s0 == 0) a[s] = a0[s];
+        else a[s] = (s0 + s < nsplit) ? dev_load(&part_acc[(pbase + (size_t)(s0 + s) * G + g) * SPIN_HEAD_DIM + d]) : 0.f;
+      }
+#pragma unroll
+      for (int s = 0; s < CH; ++s) {
+        if (s0 + s < nsplit) {
+          const float wgt = __builtin_amdgcn_exp2f(t_m[(s0 + s) * G + g] - Ms);
+          L += t_l[(s0 + s) * G + g] * wgt;
+          O += a[s] * wgt;
+        }
+      }
     }
     write_out(out, lse, b * Hq + h * G + g, d, M, L, O);
   }

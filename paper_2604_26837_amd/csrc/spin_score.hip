@@ -38,7 +38,7 @@ struct score_tile {
 template <int NJ>
 __device__ inline void load_tile(score_tile<NJ> &r, const uint4 *__restrict__ tp, int lane) {
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) r.a[j] = tp[j * 64 + lane];
+  for (int j = 0; j < NJ; ++j) r.a[j] = spin_nt_load(tp + j * 64 + lane);
 }
 
 template <int NJ, bool MINMAX>
