@@ -38,6 +38,8 @@ def parse_args():
                     help="cfg1: the headline all-resident layer; cfg4: hierarchical HBM budget, 64 decode steps")
     ap.add_argument("--copy-mode", default="both", choices=["memcpy", "gather", "both"])
     ap.add_argument("--budget-frac", type=float, default=0.25)
+    ap.add_argument("--four-calls", action="store_true",
+                    help="time the four separate stage calls as the step (default: stages 2+3 share one launch)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events during the timed region")
     return ap.parse_args()
@@ -194,8 +196,15 @@ def main():
     summ_copies = [layer.summaries] + [layer.summaries.clone() for _ in range(1, args.layers)]
     torch.cuda.synchronize()
 
-    def run(i):
+    def run_four(i):
         layer.step(qsets[i % len(qsets)], summ_copies[i % len(summ_copies)])
+
+    def run_three(i):
+        layer.step3(qsets[i % len(qsets)], summ_copies[i % len(summ_copies)])
+
+    # the step as timed: score, select+resolve in one launch, attention (three
+    # launches, same results bit for bit); the four separate calls are timed beside it
+    run = run_four if args.four_calls else run_three
 
     for i in range(args.warmup):
         run(i)
@@ -212,6 +221,17 @@ def main():
     us_per_step = dt * 1e6 / args.steps
     assert layer.status() == 0, "device fault during the timed region"
 
+    # --- the other launch shape of the same step, for reference
+    other = run_three if args.four_calls else run_four
+    for i in range(5):
+        other(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        other(i)
+    torch.cuda.synchronize()
+    us_per_step_other = (time.perf_counter() - t0) * 1e6 / args.steps
+
     # --- the same K steps again with every kernel bracketed by HIP events on the
     # launch stream (start/stop timestamps of the kernel itself); the bracketing
     # slows the step down, so it is kept out of `value`
@@ -227,7 +247,9 @@ def main():
         us_per_step_events = (time.perf_counter() - t0) * 1e6 / args.steps
         for name in ("score", "select", "resolve", "decode"):
             n, mean, mn = sp.profile_read(name)
-            kernels[name] = dict(launches=n, mean_us=round(mean, 3), min_us=round(mn, 3))
+            if n:
+                label = "select+resolve" if (name == "select" and not args.four_calls) else name
+                kernels[label] = dict(launches=n, mean_us=round(mean, 3), min_us=round(mn, 3))
         sp.profile_enable(0)
         assert layer.status() == 0, "device fault during the event-bracketed pass"
 
@@ -284,6 +306,8 @@ def main():
                    "summary_copies": len(summ_copies)},
         "attended_kv_gbps": roofline["achieved"] if roofline else None,
         "attended_kv_pct_peak": round(100 * roofline["frac"], 2) if roofline else None,
+        "step_launches": "four stage calls" if args.four_calls else "score, select+resolve, attention (3 launches)",
+        ("us_per_layer_three_launches" if args.four_calls else "us_per_layer_four_calls"): round(us_per_step_other, 2),
         "us_per_layer_with_kernel_events": round(us_per_step_events, 2) if us_per_step_events else None,
         "kernel_us_sum": round(sum(k["mean_us"] for k in kernels.values()), 2) if kernels else None,
         "kernels": kernels,

@@ -207,6 +207,15 @@ int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, const int32_t
                        uint16_t *valid_mask, int32_t *npages, int32_t *miss_pages,
                        int32_t *miss_slots, int32_t *nmiss, void *workspace, void *stream);
 
+/* Stages 2 and 3 in ONE launch (all-resident mode, rows of at most 16384
+ * partitions; otherwise SPIN_ERR_UNSUPPORTED and the two calls above apply).
+ * Arguments and results are exactly those of spin_select_topk followed by
+ * spin_resolve_slots, bit for bit: the workgroup that selected a row resolves it. */
+int spin_select_resolve(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
+                        const int32_t *seq_lens, int32_t *sel, int32_t *nsel, const int32_t *dir,
+                        const int32_t *leaf_pool, int64_t leaf_chunks, int32_t *slots, int32_t *page_ids,
+                        uint16_t *valid_mask, int32_t *npages, void *workspace, void *stream);
+
 /* Retrieve steps 3-4 (Section 5.2), after budget-mode stage 3: copy every missed
  * page into the slot assigned to it.  The full KV lives in pinned host memory as
  * pages in the slot layout; page `p` of row r is page host_row_base[r] + p.

@@ -22,7 +22,7 @@ EXPORTS = [
     "spin_page_stride", "spin_dir_stride", "spin_decode_splits", "spin_summary_bytes",
     "spin_workspace_init", "spin_poll_status", "spin_profile_enable", "spin_profile_read", "spin_pack_kv_pages", "spin_build_summaries",
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
-    "spin_copy_misses_host", "spin_gather_misses",
+    "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve",
 ]
 
 
@@ -73,6 +73,7 @@ def load_library() -> C.CDLL:
     lib.spin_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
+    lib.spin_select_resolve.argtypes = [vp, i32] + [vp] * 7 + [i64] + [vp] * 6
     lib.spin_copy_misses_host.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(i64)]
     lib.spin_gather_misses.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i64, vp, vp]
     _LIB = lib
@@ -215,6 +216,16 @@ class Spin:
             _ptr(valid_mask, torch.int16, "valid_mask"), _ptr(npages, torch.int32, "npages"),
             _ptr(miss_pages, torch.int32, "miss_pages"), _ptr(miss_slots, torch.int32, "miss_slots"),
             _ptr(nmiss, torch.int32, "nmiss"), _ptr(ws), _stream()), "spin_resolve_slots")
+
+    def select_resolve(self, batch, scores, part_offsets, seq_lens, sel, nsel, dir_, leaf_pool, slots, page_ids,
+                       valid_mask, npages, ws):
+        self._check(self.lib.spin_select_resolve(
+            self.h, batch, _ptr(scores, torch.float32, "scores"), _ptr(part_offsets, torch.int32, "part_offsets"),
+            _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(sel, torch.int32, "sel"), _ptr(nsel, torch.int32, "nsel"),
+            _ptr(dir_, torch.int32, "dir"), _ptr(leaf_pool, torch.int32, "leaf_pool"), leaf_pool.shape[0],
+            _ptr(slots, torch.int32, "slots"), _ptr(page_ids, torch.int32, "page_ids"),
+            _ptr(valid_mask, torch.int16, "valid_mask"), _ptr(npages, torch.int32, "npages"), _ptr(ws), _stream()),
+            "spin_select_resolve")
 
     def copy_misses_host(self, batch, host_kv, host_row_base, nmiss, miss_pages, miss_slots, kv_pool,
                          copy_stream) -> int:

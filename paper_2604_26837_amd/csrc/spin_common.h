@@ -75,6 +75,15 @@ __device__ inline void spin_raise(int32_t *status, int32_t err) { atomicCAS(stat
 
 __device__ inline float spin_bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
+// device-scope (all compute dies) relaxed accesses: written through / read from
+// the level every die sees, without cache-wide write-back or invalidate
+__device__ inline void spin_dev_store(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float spin_dev_load(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // 16-byte load marked non-temporal (streamed once, not worth keeping in cache)
 typedef __attribute__((ext_vector_type(4))) unsigned int spin_u32x4;
 __device__ inline uint4 spin_nt_load(const uint4 *p) {

@@ -1,0 +1,105 @@
+// Device code of stage 1 shared by the stand-alone kernel and the fused launch.
+#pragma once
+#include "spin_common.h"
+
+__device__ inline uint32_t relu_pack(uint32_t w, bool pos) {
+  // keep the halves whose sign matches: positive part (pos) or negative part
+  const uint32_t lo = w & 0xffffu, hi = w >> 16;
+  const bool lo_neg = lo & 0x8000u, hi_neg = hi & 0x8000u;
+  const uint32_t l = (lo_neg != pos) ? lo : 0u, h = (hi_neg != pos) ? hi : 0u;
+  return l | (h << 16);
+}
+
+// MINMAX and REPMAX: NJ instructions of 16x16x32 per tile (NJ = KD/32).  The
+// workgroup's tiles are dealt round-robin to its wavefronts; the next tile's
+// loads are issued before the current tile is consumed.
+template <int NJ>
+struct score_tile {
+  uint4 a[NJ];
+};
+
+template <int NJ>
+__device__ inline void load_tile(score_tile<NJ> &r, const uint4 *__restrict__ tp, int lane) {
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) r.a[j] = spin_nt_load(tp + j * 64 + lane);
+}
+
+template <int NJ, bool MINMAX, bool COH>
+__device__ inline void consume_tile(const score_tile<NJ> &r, const spin_bf16x8 (&qf)[NJ], int n, int c, int G,
+                                    float *__restrict__ scores, size_t base, int t) {
+  spin_f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int j = 0; j < NJ; ++j)
+    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(spin_bf16x8, r.a[j]), qf[j], s, 0, 0, 0);
+  // s[i] = value of summary row 4c+i for head n
+  float v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = spin_row16_max(n < G ? s[i] : -__builtin_inff());
+  if (MINMAX) {
+    if (n == 0) {
+      float *o = scores + base + (size_t)t * 16 + 4 * c;
+      if (COH) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) spin_dev_store(o + i, v[i]);
+      } else {
+        *(float4 *)o = make_float4(v[0], v[1], v[2], v[3]);
+      }
+    }
+  } else {
+    // rows 4c..4c+3 are the four representatives of partition 4t + c
+    const float m = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
+    if (n == 0) {
+      if (COH) spin_dev_store(&scores[base + (size_t)t * 4 + c], m);
+      else scores[base + (size_t)t * 4 + c] = m;
+    }
+  }
+}
+
+// Scores the tiles [chunk*tiles_per_wg, +tiles_per_wg) of one row with the calling
+// workgroup (WAVES wavefronts).  COH: store scores with device-scope stores so a
+// workgroup on another compute die can read them within the same launch.
+template <int NJ, bool MINMAX, int WAVES, bool COH>
+__device__ inline void score_row_tiles(
+    const uint16_t *__restrict__ q, const uint4 *__restrict__ summ, const int32_t *__restrict__ part_offsets,
+    int Hq, int Hkv, int G, int rows_per_part, int tiles_per_wg, int row, int chunk, float *__restrict__ scores) {
+  const int b = row / Hkv, h = row - b * Hkv;
+  const int off_b = part_offsets[b];
+  const int PP = part_offsets[b + 1] - off_b;
+  const int ntiles = PP * rows_per_part / 16;
+  const int t_begin = chunk * tiles_per_wg;
+  if (t_begin >= ntiles) return;
+  const int t_end = min(t_begin + tiles_per_wg, ntiles);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 15, c = lane >> 4;
+  const size_t base = (size_t)Hkv * off_b + (size_t)h * PP;   // in partitions
+
+  // B operand: column n = query head, k = elements 32j + 8c .. +8 of the query-side vector
+  spin_bf16x8 qf[NJ];
+  {
+    const uint4 *qrow = (const uint4 *)(q + ((size_t)(b * Hq + h * G + (n < G ? n : 0))) * SPIN_HEAD_DIM);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      uint4 v = qrow[(j & 3) * 4 + c];
+      if (MINMAX) {
+        const bool pos = j < 4;   // first 128 elements pair with max, the rest with min
+        v = make_uint4(relu_pack(v.x, pos), relu_pack(v.y, pos), relu_pack(v.z, pos), relu_pack(v.w, pos));
+      }
+      if (n >= G) v = make_uint4(0, 0, 0, 0);
+      qf[j] = __builtin_bit_cast(spin_bf16x8, v);
+    }
+  }
+
+  const uint4 *tiles = summ + base * rows_per_part * (NJ * 4);   // NJ*32 elements = NJ*4 units per row
+  int t = t_begin + wave;
+  if (t >= t_end) return;
+  score_tile<NJ> ra, rb;
+  load_tile<NJ>(ra, tiles + (size_t)t * (NJ * 64), lane);
+  for (; t < t_end; t += 2 * WAVES) {
+    const int t1 = t + WAVES, t2 = t + 2 * WAVES;
+    if (t1 < t_end) load_tile<NJ>(rb, tiles + (size_t)t1 * (NJ * 64), lane);
+    consume_tile<NJ, MINMAX, COH>(ra, qf, n, c, G, scores, base, t);
+    if (t2 < t_end) load_tile<NJ>(ra, tiles + (size_t)t2 * (NJ * 64), lane);
+    if (t1 < t_end) consume_tile<NJ, MINMAX, COH>(rb, qf, n, c, G, scores, base, t1);
+  }
+}
+

@@ -1,0 +1,162 @@
+// Device code of stage 2 (register-resident variant) shared by the stand-alone
+// kernel and the fused launch.
+#pragma once
+#include "spin_common.h"
+
+__device__ inline uint32_t score_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) u = 0xff800000u;  // NaN ranks as -inf
+  if (u == 0x80000000u) u = 0u;                          // -0 ties +0
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Register-resident variant for rows of at most BLOCK * KPT partitions: every
+// thread keeps KPT consecutive keys in registers, so scores are read once; the
+// digit histograms alternate between two LDS buffers, the 256-bin suffix scan
+// is done by one wavefront, and the two compaction prefix sums share one scan.
+// COH: read the scores with device-scope loads (they were produced by other
+// workgroups of the same launch).  Returns the number of selected partitions.
+template <int BLOCK, int KPT, bool COH>
+__device__ inline int select_reg_row(
+    const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
+    const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
+    int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel, int row) {
+  constexpr int NW = BLOCK / 64;
+  __shared__ int s_hist[2][256];
+  __shared__ unsigned s_wtot[NW];
+  __shared__ int s_digit, s_remaining;
+
+  const int b = row / Hkv, h = row - b * Hkv;
+  const int N = seq_lens[b];
+  const int off_b = part_offsets[b];
+  const int PP = part_offsets[b + 1] - off_b;
+  const float *rs = scores + (size_t)Hkv * off_b + (size_t)h * PP;
+  int32_t *rsel = sel + (size_t)row * sel_stride;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int P = N > 0 ? (N + tp - 1) / tp : 0;
+  if (P > PP) P = PP;
+  if (P > BLOCK * KPT) P = BLOCK * KPT;   // the host picks a variant that fits; keep indexing in range
+
+  // keys of partitions c0 .. c0+KPT-1
+  const int c0 = tid * KPT;
+  uint32_t key[KPT];
+#pragma unroll
+  for (int k4 = 0; k4 < KPT; k4 += 4) {
+    float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c0 + k4 < PP) {
+      if (COH) f = make_float4(spin_dev_load(rs + c0 + k4), spin_dev_load(rs + c0 + k4 + 1),
+                               spin_dev_load(rs + c0 + k4 + 2), spin_dev_load(rs + c0 + k4 + 3));
+      else f = *(const float4 *)(rs + c0 + k4);
+    }
+    key[k4] = score_key(f.x); key[k4 + 1] = score_key(f.y); key[k4 + 2] = score_key(f.z); key[k4 + 3] = score_key(f.w);
+  }
+
+  // forced partitions: a prefix [0, nf_lo) and a suffix [first_hi, P)
+  const int pages = (N + 15) >> 4;
+  int sink_end = min(sink_pages, pages);
+  int recent_begin = max(pages - recent_pages, 0);
+  if (sink_end >= recent_begin) { sink_end = pages; recent_begin = pages; }
+  int nf_lo = (N <= sink_end * 16) ? P : min((sink_end * 16) / tp, P);
+  int first_hi = min((recent_begin * 16 + tp - 1) / tp, P);
+  if (first_hi <= nf_lo) { nf_lo = P; first_hi = P; }
+  const int nforced = nf_lo + (P - first_hi);
+  const int ncand = P - nforced;
+  int kprime = includes_forced ? max(topk - nforced, 0) : topk;
+  kprime = min(kprime, ncand);
+  int take = nforced + kprime;
+  if (take > sel_stride) {
+    kprime = max(sel_stride - nforced, 0);
+    take = min(nforced + kprime, sel_stride);
+  }
+  // candidates of this thread form the index range [ca, cb)
+  const int ca = max(c0, nf_lo), cb = min(c0 + KPT, first_hi);
+
+  uint32_t prefix = 0;
+  int remaining = kprime;
+  if (kprime > 0) {
+    if (tid < 256) s_hist[0][tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass, cur = pass & 1;
+#pragma unroll
+      for (int k = 0; k < KPT; ++k) {
+        const int p = c0 + k;
+        if (p >= ca && p < cb && (pass == 0 || (key[k] >> (shift + 8)) == prefix))
+          atomicAdd(&s_hist[cur][(key[k] >> shift) & 255u], 1);
+      }
+      if (tid < 256) s_hist[cur ^ 1][tid] = 0;
+      __syncthreads();
+      if (wave == 0) {
+        // lane handles digits 255-4*lane .. 252-4*lane, in descending order
+        int hv[4], local = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { hv[j] = s_hist[cur][255 - 4 * lane - j]; local += hv[j]; }
+        int inc = local;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+          const int o = __shfl_up(inc, d);
+          if (lane >= d) inc += o;
+        }
+        int running = inc - local;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (running < remaining && running + hv[j] >= remaining) {
+            s_digit = 255 - 4 * lane - j;
+            s_remaining = remaining - running;
+          }
+          running += hv[j];
+        }
+      }
+      __syncthreads();
+      prefix = (prefix << 8) | (uint32_t)s_digit;
+      remaining = s_remaining;
+    }
+  }
+  const uint32_t T = prefix;
+  const unsigned need_eq = kprime > 0 ? (unsigned)remaining : 0u;
+
+  // counts of this thread: low half = forced or above threshold, high half = equal to it
+  unsigned mine = 0;
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) {
+    const int p = c0 + k;
+    if (p >= P) continue;
+    if (p < nf_lo || p >= first_hi) { mine += 1u; continue; }
+    if (kprime == 0) continue;
+    mine += (key[k] > T) ? 1u : 0u;
+    mine += (key[k] == T) ? 0x10000u : 0u;
+  }
+  unsigned inc = mine;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const unsigned o = __shfl_up(inc, d);
+    if (lane >= d) inc += o;
+  }
+  if (lane == 63) s_wtot[wave] = inc;
+  __syncthreads();
+  unsigned before = inc - mine;
+#pragma unroll
+  for (int w = 0; w < NW; ++w)
+    if (w < wave) before += s_wtot[w];
+  const unsigned gt_before = before & 0xffffu, eq_before = before >> 16;
+  unsigned eq_quota = need_eq > eq_before ? need_eq - eq_before : 0u;
+  int pos = (int)(gt_before + min(eq_before, need_eq));
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) {
+    const int p = c0 + k;
+    if (p >= P) continue;
+    bool pick;
+    if (p < nf_lo || p >= first_hi) pick = true;
+    else if (kprime == 0) pick = false;
+    else {
+      pick = key[k] > T;
+      if (key[k] == T && eq_quota > 0) { pick = true; --eq_quota; }
+    }
+    if (pick && pos < sel_stride) rsel[pos++] = p;
+  }
+  for (int i = take + tid; i < sel_stride; i += BLOCK) rsel[i] = -1;
+  if (tid == 0) nsel[row] = take;
+  return take;
+}
+

@@ -1,0 +1,53 @@
+// Stages 2 and 3 in one launch (all-resident mode, rows of at most 16384
+// partitions).  Both stages work on one row per workgroup, so the workgroup
+// that selected a row resolves it straight away: the same device functions run
+// as in the two stage calls, the results are the same bits, and one launch with
+// its start-up latency chain is saved.
+#include "spin_resolve_dev.h"
+#include "spin_select_dev.h"
+
+template <int BLOCK, int KPT>
+__global__ __launch_bounds__(BLOCK) void spin_select_resolve_kernel(
+    const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
+    const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
+    int recent_pages, int sel_stride, int32_t *sel, int32_t *nsel, const int32_t *dir,
+    const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, int page_stride, int dir_stride, int leaf_entries,
+    int32_t *__restrict__ slots, int32_t *__restrict__ page_ids, uint16_t *__restrict__ valid_mask,
+    int32_t *__restrict__ npages, int32_t *status) {
+  const int row = blockIdx.x;
+  const int take = select_reg_row<BLOCK, KPT, false>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced,
+                                                     sink_pages, recent_pages, sel_stride, sel, nsel, row);
+  __syncthreads();   // the selection was written by this workgroup: visible to all its threads from here
+  resolve_row<BLOCK>(row, take, sel, seq_lens, dir, leaf_pool, leaf_chunks, Hkv, tp, sink_pages, recent_pages,
+                     sel_stride, page_stride, dir_stride, leaf_entries, slots, page_ids, valid_mask, npages, status);
+}
+
+extern "C" int spin_select_resolve(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
+                                   const int32_t *seq_lens, int32_t *sel, int32_t *nsel, const int32_t *dir,
+                                   const int32_t *leaf_pool, int64_t leaf_chunks, int32_t *slots,
+                                   int32_t *page_ids, uint16_t *valid_mask, int32_t *npages, void *workspace,
+                                   void *stream) {
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || leaf_chunks <= 0) return SPIN_ERR_INVALID;
+  if (batch == 0) return SPIN_OK;
+  if (!scores || !part_offsets || !seq_lens || !sel || !nsel || !dir || !leaf_pool || !slots || !page_ids ||
+      !valid_mask || !npages)
+    return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  const spin_config &c = ctx->cfg;
+  if (c.lru_timestamps > 0 || ctx->max_parts > 16384) return SPIN_ERR_UNSUPPORTED;
+  const int rows = batch * c.num_kv_heads;
+#define SPIN_SR_ARGS                                                                                          \
+  0, (hipStream_t)stream, scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk,         \
+      c.topk_includes_forced, c.sink_pages, c.recent_pages, ctx->sel_stride, sel, nsel, dir, leaf_pool,       \
+      leaf_chunks, ctx->page_stride, ctx->dir_stride, c.leaf_entries, slots, page_ids, valid_mask, npages,    \
+      (int32_t *)workspace
+  if (ctx->max_parts <= 2048)
+    spin_launch(ctx, SPIN_K_SELECT, spin_select_resolve_kernel<256, 8>, dim3((unsigned)rows), dim3(256), SPIN_SR_ARGS);
+  else if (ctx->max_parts <= 4096)
+    spin_launch(ctx, SPIN_K_SELECT, spin_select_resolve_kernel<512, 8>, dim3((unsigned)rows), dim3(512), SPIN_SR_ARGS);
+  else
+    spin_launch(ctx, SPIN_K_SELECT, spin_select_resolve_kernel<1024, 16>, dim3((unsigned)rows), dim3(1024),
+                SPIN_SR_ARGS);
+#undef SPIN_SR_ARGS
+  return spin_launch_status();
+}

@@ -82,6 +82,16 @@ class LayerState:
         sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
                          self.ws)
 
+    def step3(self, q: torch.Tensor, summaries: Optional[torch.Tensor] = None):
+        """The same step in three launches: stages 2 and 3 share one."""
+        sp, w = self.spin, self.w
+        summ = self.summaries if summaries is None else summaries
+        sp.score_partitions(w.batch, q, summ, self.chan, self.part_offsets, self.seq_lens, self.scores, self.ws)
+        sp.select_resolve(w.batch, self.scores, self.part_offsets, self.seq_lens, self.sel, self.nsel, self.dir,
+                          self.leaf_pool, self.slots, self.page_ids, self.valid_mask, self.npages, self.ws)
+        sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
+                         self.ws)
+
     def row_base(self, b: int, h: int) -> int:
         return tables.row_base(self.part_offsets_np, b, h, self.w.num_kv_heads)
 
