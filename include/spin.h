@@ -105,6 +105,7 @@ typedef struct spin_config {
   int32_t lru_evict_exact;      /* 0 = evict whole buckets <= x; 1 = only as many pages of bucket x as needed */
   int32_t decode_splits;        /* split-K factor of spin_sparse_decode; 0 = choose from the shape */
   int32_t decode_waves;         /* wavefronts per decode workgroup: 2, 4 or 8; 0 = 8 */
+  int32_t decode_depth;         /* page buffers per decode wavefront (pages in flight + 1): 2, 3 or 4; 0 = choose */
   int32_t score_tiles_per_wg;   /* 16-row summary tiles per stage-1 workgroup; 0 = choose */
   int32_t score_waves;          /* wavefronts per stage-1 workgroup: 4 or 8; 0 = 4 */
   float softmax_scale;          /* 0 = 1/sqrt(head_dim) */

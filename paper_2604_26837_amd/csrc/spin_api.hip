@@ -21,6 +21,7 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   if (tp <= 0) return SPIN_ERR_INVALID;
   if (!((tp < 16 && 16 % tp == 0) || (tp >= 16 && tp % 16 == 0))) return SPIN_ERR_UNSUPPORTED;
   if (c->lru_timestamps > 256) return SPIN_ERR_UNSUPPORTED;
+  if (c->decode_depth != 0 && (c->decode_depth < 2 || c->decode_depth > 4)) return SPIN_ERR_INVALID;
   if (c->score_tiles_per_wg < 0 || (c->score_waves != 0 && c->score_waves != 4 && c->score_waves != 8))
     return SPIN_ERR_INVALID;
 
@@ -72,6 +73,7 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
     return SPIN_ERR_INVALID;
   }
   x->waves = c->decode_waves ? c->decode_waves : 8;
+  x->depth = c->decode_depth ? c->decode_depth : 2;
   int32_t splits = c->decode_splits;
   if (splits == 0) {
     // about one 8-wave workgroup on each of the 256 compute units, all resident

@@ -28,6 +28,7 @@ struct spin_ctx {
   int32_t dir_stride;
   int32_t splits;
   int32_t waves;          // wavefronts per decode workgroup
+  int32_t depth;          // page buffers per decode wavefront
   int32_t kd;             // contraction length of one summary row
   int32_t rows_per_part;  // summary rows per partition (REPMAX: reps, else 1)
   float scale;

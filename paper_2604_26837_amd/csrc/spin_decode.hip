@@ -103,7 +103,7 @@ __device__ inline void write_out(uint16_t *__restrict__ out, float *__restrict__
   if (lse && d == 0) lse[qhead] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f : NEG_INF;
 }
 
-template <int WAVES>
+template <int WAVES, int DEPTH>
 __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
     const uint16_t *__restrict__ q, const uint4 *__restrict__ pool, int64_t pool_slots,
     const int32_t *__restrict__ slots, const uint16_t *__restrict__ masks,
@@ -173,14 +173,19 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
         mymask = 0;
       }
     }
-    page_regs ra, rb;
-    load_page(ra, pool, __builtin_amdgcn_readlane(myslot, 0), lane);
-    for (int i = 0; i < cnt; i += 2) {
-      if (i + 1 < cnt) load_page(rb, pool, __builtin_amdgcn_readlane(myslot, i + 1), lane);
-      consume_page(st, ra, qf, (unsigned)__builtin_amdgcn_readlane((int)mymask, i), c, scale_log2e);
-      if (i + 2 < cnt) load_page(ra, pool, __builtin_amdgcn_readlane(myslot, i + 2), lane);
-      if (i + 1 < cnt)
-        consume_page(st, rb, qf, (unsigned)__builtin_amdgcn_readlane((int)mymask, i + 1), c, scale_log2e);
+    // ring of DEPTH register buffers: DEPTH-1 pages are in flight while one is consumed
+    page_regs r[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH - 1; ++d)
+      if (d < cnt) load_page(r[d], pool, __builtin_amdgcn_readlane(myslot, d), lane);
+    for (int i = 0; i < cnt; i += DEPTH) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        const int ahead = i + d + DEPTH - 1;
+        if (ahead < cnt) load_page(r[(d + DEPTH - 1) % DEPTH], pool, __builtin_amdgcn_readlane(myslot, ahead), lane);
+        if (i + d < cnt)
+          consume_page(st, r[d], qf, (unsigned)__builtin_amdgcn_readlane((int)mymask, i + d), c, scale_log2e);
+      }
     }
   }
 
@@ -307,14 +312,21 @@ extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, c
   const float scale_log2e = ctx->scale * 1.4426950408889634f;
   const int W = ctx->waves;
   const size_t lds = (size_t)W * G * (SPIN_HEAD_DIM + 2) * sizeof(float);
-#define SPIN_DECODE_LAUNCH(WV)                                                                                   \
-  spin_launch(ctx, SPIN_K_DECODE, spin_decode_kernel<WV>, dim3((unsigned)(rows * nsplit)), dim3(WV * 64), lds,   \
+#define SPIN_DECODE_LAUNCH2(WV, DP)                                                                              \
+  spin_launch(ctx, SPIN_K_DECODE, spin_decode_kernel<WV, DP>, dim3((unsigned)(rows * nsplit)), dim3(WV * 64), lds, \
               (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, slots, valid_mask,   \
               npages, ctx->page_stride, G, ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, scale_log2e,     \
               part_ml, part_acc, tickets, (uint16_t *)out, lse, (int32_t *)workspace)
+#define SPIN_DECODE_LAUNCH(WV)                          \
+  do {                                                  \
+    if (ctx->depth == 2) SPIN_DECODE_LAUNCH2(WV, 2);    \
+    else if (ctx->depth == 4) SPIN_DECODE_LAUNCH2(WV, 4); \
+    else SPIN_DECODE_LAUNCH2(WV, 3);                    \
+  } while (0)
   if (W == 2) SPIN_DECODE_LAUNCH(2);
   else if (W == 8) SPIN_DECODE_LAUNCH(8);
   else SPIN_DECODE_LAUNCH(4);
 #undef SPIN_DECODE_LAUNCH
+#undef SPIN_DECODE_LAUNCH2
   return spin_launch_status();
 }
