@@ -166,6 +166,22 @@ int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv_pool, int6
                          const int32_t *part_offsets, const int32_t *seq_lens,
                          const int32_t *chan_idx, void *summaries, void *workspace, void *stream);
 
+/* Index at decode time (Section 4.1: Index also runs during decode to take in
+ * newly generated tokens).  Appends ONE token per request: k_new / v_new are
+ * DEVICE bf16 [batch][num_kv_heads][128]; seq_lens (DEVICE int32 [batch]) holds
+ * the lengths BEFORE the append, so the token lands at position seq_lens[b].
+ * Its page must already have a slot in the table (the caller maps a fresh slot
+ * when the position starts a new page) and part_offsets must leave room for its
+ * partition; otherwise SPIN_ERR_NOT_RESIDENT / SPIN_ERR_INVALID is raised in the
+ * status word and the row is left untouched.  The K/V values are written into
+ * the slot and the summaries of the partition are updated to exactly what
+ * spin_build_summaries would store for the longer context.  The caller then
+ * increments its seq_lens. */
+int spin_append_kv(spin_ctx *ctx, int32_t batch, const void *k_new, const void *v_new,
+                   const int32_t *seq_lens, void *kv_pool, int64_t pool_slots, const int32_t *dir,
+                   const int32_t *leaf_pool, int64_t leaf_chunks, const int32_t *part_offsets,
+                   const int32_t *chan_idx, void *summaries, void *workspace, void *stream);
+
 /* Stage 1.  scores[row][p] (DEVICE fp32, indexed like the summaries) =
  *   MINMAX  max_g sum_d max(q[g][d]*min[p][d], q[g][d]*max[p][d])
  *   SKETCH  max_g sum_c q[g][chan_idx[h][c]] * sketch[t][c]

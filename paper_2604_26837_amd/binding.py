@@ -22,7 +22,7 @@ EXPORTS = [
     "spin_page_stride", "spin_dir_stride", "spin_decode_splits", "spin_summary_bytes",
     "spin_workspace_init", "spin_poll_status", "spin_profile_enable", "spin_profile_read", "spin_pack_kv_pages", "spin_build_summaries",
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
-    "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve",
+    "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv",
 ]
 
 
@@ -73,6 +73,7 @@ def load_library() -> C.CDLL:
     lib.spin_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
+    lib.spin_append_kv.argtypes = [vp, i32, vp, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp, vp, vp]
     lib.spin_select_resolve.argtypes = [vp, i32] + [vp] * 7 + [i64] + [vp] * 6
     lib.spin_copy_misses_host.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(i64)]
     lib.spin_gather_misses.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i64, vp, vp]
@@ -191,6 +192,16 @@ class Spin:
             _ptr(part_offsets, torch.int32, "part_offsets"), _ptr(seq_lens, torch.int32, "seq_lens"),
             _ptr(chan_idx, torch.int32, "chan_idx"), _ptr(summaries), _ptr(ws), _stream()),
             "spin_build_summaries")
+
+    def append_kv(self, batch, k_new, v_new, seq_lens, kv_pool, dir_, leaf_pool, part_offsets, chan_idx,
+                  summaries, ws):
+        pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192
+        self._check(self.lib.spin_append_kv(
+            self.h, batch, _ptr(k_new, torch.bfloat16, "k_new"), _ptr(v_new, torch.bfloat16, "v_new"),
+            _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(kv_pool), pool_slots, _ptr(dir_, torch.int32, "dir"),
+            _ptr(leaf_pool, torch.int32, "leaf_pool"), leaf_pool.shape[0],
+            _ptr(part_offsets, torch.int32, "part_offsets"), _ptr(chan_idx, torch.int32, "chan_idx"),
+            _ptr(summaries), _ptr(ws), _stream()), "spin_append_kv")
 
     # -- the four stages --------------------------------------------------
     def score_partitions(self, batch, q, summaries, chan_idx, part_offsets, seq_lens, scores, ws):
