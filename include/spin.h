@@ -77,7 +77,8 @@ enum spin_status {
   SPIN_ERR_HIP = -4,          /* a HIP runtime call failed */
   SPIN_ERR_BUDGET = -5,       /* device: a row's slot budget cannot hold its selection */
   SPIN_ERR_NOT_RESIDENT = -6, /* device: a selected page has no leaf or no slot */
-  SPIN_ERR_SLOT_RANGE = -7    /* device: a slot id lies outside the pool */
+  SPIN_ERR_SLOT_RANGE = -7,   /* device: a slot id lies outside the pool */
+  SPIN_ERR_LEAF_POOL = -8     /* device: no free leaf chunk left in the segment pool */
 };
 
 enum spin_score_kind { SPIN_SCORE_MINMAX = 0, SPIN_SCORE_SKETCH = 1, SPIN_SCORE_REPMAX = 2 };
@@ -207,10 +208,11 @@ int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const in
  * ascending page order, slots / page_ids (DEVICE int32 [rows][page_stride]),
  * valid_mask (DEVICE uint16, bit t = token t of the page is attended) and
  * npages (DEVICE int32 [rows]).
- * All-resident mode (lru_timestamps == 0): rev_table, slot_base, miss_* are
+ * All-resident mode (lru_timestamps == 0): rev_table, slot_range, miss_* are
  * NULL; a missing leaf or slot sets SPIN_ERR_NOT_RESIDENT and drops the page.
- * Budget mode (lru_timestamps == n): row r owns pool slots
- * [slot_base[r], slot_base[r+1]) (DEVICE int32 [rows+1]); rev_table (DEVICE
+ * Budget mode (lru_timestamps == n): row r owns the slot_range[r][1] pool slots
+ * starting at slot_range[r][0] (DEVICE int32 [rows][2]; ranges of different rows
+ * must not overlap; spin_reclaim_tail changes the counts); rev_table (DEVICE
  * int32 [total slots][2] = {resident logical page or -1, timestamp}) and the
  * leaf entries are updated by the four bucketed-LRU steps; missed pages are
  * admitted to freed slots (ascending page id -> ascending free slot) and
@@ -220,7 +222,7 @@ int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const in
 int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, const int32_t *sel,
                        const int32_t *nsel, const int32_t *seq_lens, const int32_t *dir,
                        int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev_table,
-                       const int32_t *slot_base, int32_t *slots, int32_t *page_ids,
+                       const int32_t *slot_range, int32_t *slots, int32_t *page_ids,
                        uint16_t *valid_mask, int32_t *npages, int32_t *miss_pages,
                        int32_t *miss_slots, int32_t *nmiss, void *workspace, void *stream);
 
@@ -232,6 +234,34 @@ int spin_select_resolve(spin_ctx *ctx, int32_t batch, const float *scores, const
                         const int32_t *seq_lens, int32_t *sel, int32_t *nsel, const int32_t *dir,
                         const int32_t *leaf_pool, int64_t leaf_chunks, int32_t *slots, int32_t *page_ids,
                         uint16_t *valid_mask, int32_t *npages, void *workspace, void *stream);
+
+/* Buffer elasticity, mechanism only (Section 5.3: buffer pages are reclaimed from
+ * the tail of a request's GPU page table).  Sets the slot count of every row to
+ * new_count[r] (DEVICE int32 [rows]): pages resident in slots at or beyond the
+ * new count are evicted (forward entry cleared, slot marked empty) and
+ * slot_range[r][1] is updated in place.  Growing only raises the count; the added
+ * slots must belong to the row and be empty in rev_table.  Which rows give up how
+ * many slots is the serving scheduler's policy and not part of this library. */
+int spin_reclaim_tail(spin_ctx *ctx, int32_t batch, int32_t *slot_range, const int32_t *new_count,
+                      const int32_t *dir, int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev_table,
+                      void *workspace, void *stream);
+
+/* On-demand second-level tables (Section 5.4: segments come from a pre-allocated
+ * GPU-resident pool managed by a bitmap allocator, so metadata grows with the
+ * mapped pages).  spin_alloc_leaves makes sure a leaf chunk exists for every page
+ * range that a row's current selection (and its forced pages) touches: missing
+ * ones are taken from leaf_pool by setting a bit of leaf_bitmap (DEVICE uint32
+ * [ceil(leaf_chunks/32)], bit c = chunk c in use), filled with -1 and entered in
+ * `dir`.  Run it between stage 2 and a budget-mode stage 3.  SPIN_ERR_LEAF_POOL is
+ * raised when the pool is exhausted.  spin_free_leaves returns every chunk of the
+ * given rows to the pool (for a request that left; its pages must no longer be
+ * resident) and clears their directory entries.  Which chunk a range receives
+ * depends on arrival order; slots and page ids never do. */
+int spin_alloc_leaves(spin_ctx *ctx, int32_t batch, const int32_t *sel, const int32_t *nsel,
+                      const int32_t *seq_lens, int32_t *dir, int32_t *leaf_pool, int64_t leaf_chunks,
+                      uint32_t *leaf_bitmap, void *workspace, void *stream);
+int spin_free_leaves(spin_ctx *ctx, int32_t batch, int32_t *dir, int64_t leaf_chunks, uint32_t *leaf_bitmap,
+                     void *workspace, void *stream);
 
 /* Retrieve steps 3-4 (Section 5.2), after budget-mode stage 3: copy every missed
  * page into the slot assigned to it.  The full KV lives in pinned host memory as

@@ -44,6 +44,23 @@ class RowCache:
         assert seen == self.where, "forward and reverse tables disagree"
 
 
+def reclaim_tail(cache: RowCache, keep: int) -> None:
+    """Shrink (or grow) the row's budget to ``keep`` slots.  Buffer pages are
+    reclaimed from the tail of the slot table (Section 5.3, buffer elasticity):
+    pages resident in slots >= keep are evicted; growing appends empty slots."""
+    S = len(cache.page)
+    for s in range(keep, S):
+        p = cache.page[s]
+        if p >= 0:
+            del cache.where[p]
+    if keep <= S:
+        del cache.page[keep:]
+        del cache.ts[keep:]
+    else:
+        cache.page.extend([-1] * (keep - S))
+        cache.ts.extend([0] * (keep - S))
+
+
 def lru_step(cache: RowCache, pages: List[int], step: int, n: int,
              evict_exact: bool = False) -> Tuple[List[int], List[Tuple[int, int]], int]:
     """Apply one decode step.  ``pages`` = the selected logical pages, ascending.

@@ -15,14 +15,14 @@ _LIB: Optional[C.CDLL] = None
 SPIN_OK = 0
 STATUS_NAMES = {0: "SPIN_OK", -1: "SPIN_ERR_INVALID", -2: "SPIN_ERR_UNSUPPORTED", -3: "SPIN_ERR_WORKSPACE",
                 -4: "SPIN_ERR_HIP", -5: "SPIN_ERR_BUDGET", -6: "SPIN_ERR_NOT_RESIDENT",
-                -7: "SPIN_ERR_SLOT_RANGE"}
+                -7: "SPIN_ERR_SLOT_RANGE", -8: "SPIN_ERR_LEAF_POOL"}
 
 EXPORTS = [
     "spin_create", "spin_destroy", "spin_status_string", "spin_workspace_bytes", "spin_sel_stride",
     "spin_page_stride", "spin_dir_stride", "spin_decode_splits", "spin_summary_bytes",
     "spin_workspace_init", "spin_poll_status", "spin_profile_enable", "spin_profile_read", "spin_pack_kv_pages", "spin_build_summaries",
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
-    "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv",
+    "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv", "spin_reclaim_tail", "spin_alloc_leaves", "spin_free_leaves",
 ]
 
 
@@ -73,6 +73,9 @@ def load_library() -> C.CDLL:
     lib.spin_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
+    lib.spin_reclaim_tail.argtypes = [vp, i32, vp, vp, vp, vp, i64, vp, vp, vp]
+    lib.spin_alloc_leaves.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, vp, vp, vp]
+    lib.spin_free_leaves.argtypes = [vp, i32, vp, i64, vp, vp, vp]
     lib.spin_append_kv.argtypes = [vp, i32, vp, vp, vp, vp, i64, vp, vp, i64, vp, vp, vp, vp, vp]
     lib.spin_select_resolve.argtypes = [vp, i32] + [vp] * 7 + [i64] + [vp] * 6
     lib.spin_copy_misses_host.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(i64)]
@@ -202,6 +205,24 @@ class Spin:
             _ptr(leaf_pool, torch.int32, "leaf_pool"), leaf_pool.shape[0],
             _ptr(part_offsets, torch.int32, "part_offsets"), _ptr(chan_idx, torch.int32, "chan_idx"),
             _ptr(summaries), _ptr(ws), _stream()), "spin_append_kv")
+
+    def reclaim_tail(self, batch, slot_range, new_count, dir_, leaf_pool, rev_table, ws):
+        self._check(self.lib.spin_reclaim_tail(
+            self.h, batch, _ptr(slot_range, torch.int32, "slot_range"), _ptr(new_count, torch.int32, "new_count"),
+            _ptr(dir_, torch.int32, "dir"), _ptr(leaf_pool, torch.int32, "leaf_pool"), leaf_pool.shape[0],
+            _ptr(rev_table, torch.int32, "rev_table"), _ptr(ws), _stream()), "spin_reclaim_tail")
+
+    def alloc_leaves(self, batch, sel, nsel, seq_lens, dir_, leaf_pool, leaf_bitmap, ws):
+        self._check(self.lib.spin_alloc_leaves(
+            self.h, batch, _ptr(sel, torch.int32, "sel"), _ptr(nsel, torch.int32, "nsel"),
+            _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(dir_, torch.int32, "dir"),
+            _ptr(leaf_pool, torch.int32, "leaf_pool"), leaf_pool.shape[0],
+            _ptr(leaf_bitmap, torch.int32, "leaf_bitmap"), _ptr(ws), _stream()), "spin_alloc_leaves")
+
+    def free_leaves(self, batch, dir_, leaf_chunks, leaf_bitmap, ws):
+        self._check(self.lib.spin_free_leaves(
+            self.h, batch, _ptr(dir_, torch.int32, "dir"), leaf_chunks, _ptr(leaf_bitmap, torch.int32, "leaf_bitmap"),
+            _ptr(ws), _stream()), "spin_free_leaves")
 
     # -- the four stages --------------------------------------------------
     def score_partitions(self, batch, q, summaries, chan_idx, part_offsets, seq_lens, scores, ws):

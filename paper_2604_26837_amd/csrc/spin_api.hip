@@ -165,6 +165,7 @@ extern "C" const char *spin_status_string(int s) {
     case SPIN_ERR_BUDGET: return "slot budget smaller than the step's selection";
     case SPIN_ERR_NOT_RESIDENT: return "selected page not resident";
     case SPIN_ERR_SLOT_RANGE: return "slot id outside the pool";
+    case SPIN_ERR_LEAF_POOL: return "leaf segment pool exhausted";
     default: return "unknown status";
   }
 }

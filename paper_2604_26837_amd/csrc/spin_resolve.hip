@@ -25,8 +25,8 @@ __global__ __launch_bounds__(RES_BLOCK) void spin_resolve_kernel(
 // ---------------------------------------------------------------------------
 // Budget mode: bucketed-LRU replacement (Section 5.3), page partitions.
 //
-// One workgroup per row.  The row owns S = slot_base[row+1]-slot_base[row] pool
-// slots; rev_table[slot] = {resident logical page or -1, timestamp}; the leaf
+// One workgroup per row.  The row owns the S = slot_range[row][1] pool slots
+// starting at slot_range[row][0]; rev_table[slot] = {resident logical page or -1, timestamp}; the leaf
 // entries are the forward map page -> slot.  The four steps run in the paper's
 // order: (1) classify the selected pages by a leaf lookup, (2)+(3) one scan of
 // the row's slots updates timestamps and builds the per-timestamp histogram in
@@ -89,8 +89,8 @@ __global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_lru_kernel(
   uint16_t *o_mask = valid_mask + (size_t)row * page_stride;
   int32_t *o_mpages = miss_pages + (size_t)row * page_stride;
   int32_t *o_mslots = miss_slots + (size_t)row * page_stride;
-  const int sb = slot_base[row];
-  const int S = slot_base[row + 1] - sb;
+  const int sb = slot_base[2 * row];
+  const int S = slot_base[2 * row + 1];
   const int32_t *gdir = dir + (size_t)row * dir_stride;
 
   if (tid == 0) s_err = 0;

@@ -35,7 +35,8 @@ class HierLayer:
         base[1:] = np.cumsum(self.budgets)
         self.pool_slots = int(base[-1])
         self.slot_base_np = base.astype(np.int32)
-        self.slot_base = torch.from_numpy(self.slot_base_np).to(device)
+        rng = np.stack([self.slot_base_np[:-1], np.asarray(self.budgets, dtype=np.int32)], axis=1)
+        self.slot_base = torch.from_numpy(np.ascontiguousarray(rng, dtype=np.int32)).to(device)   # [rows][2]
         self.kv_pool = torch.zeros((self.pool_slots, 4096), dtype=torch.bfloat16, device=device)
         # host side: all pages of all rows, in slot layout, row after row
         hrb = np.zeros(rows + 1, dtype=np.int64)

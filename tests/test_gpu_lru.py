@@ -26,7 +26,8 @@ class Budget:
         base = np.zeros(rows + 1, dtype=np.int32)
         base[1:] = np.cumsum(budgets)
         self.slot_base_np = base
-        self.slot_base = torch.from_numpy(base).to(DEV)
+        rng = np.stack([base[:-1], np.asarray(budgets, dtype=np.int32)], axis=1).astype(np.int32)
+        self.slot_base = torch.from_numpy(np.ascontiguousarray(rng)).to(DEV)          # [rows][2] = {first, count}
         empty = [np.full((w.num_kv_heads, w.pages(b)), -1, dtype=np.int32) for b in range(w.batch)]
         d, l = tables.build_two_level(empty, sp.dir_stride, w.leaf_entries, allocate_all=True)
         self.dir = torch.from_numpy(d).to(DEV)

@@ -139,3 +139,19 @@ def test_belady_is_a_lower_bound_and_handles_batches():
         assert lru.belady_min_misses(trace, 10) <= m
     # compulsory misses only when everything fits
     assert lru.belady_min_misses(trace, 25) == len({p for pg in trace for p in pg})
+
+
+def test_reclaim_tail_evicts_only_tail_slots_and_growth_adds_empty_ones():
+    cache = lru.RowCache(6)
+    lru.lru_step(cache, [10, 11, 12, 13, 14], 0, 64)
+    assert cache.page == [10, 11, 12, 13, 14, -1]
+    lru.reclaim_tail(cache, 3)
+    assert cache.page == [10, 11, 12] and set(cache.where) == {10, 11, 12}
+    cache.check()
+    slots, misses, hits = lru.lru_step(cache, [10, 13], 1, 64)        # 13 was evicted by the shrink
+    assert hits == 1 and misses == [(13, 1)]          # bucket 0 held 11 and 12: both evicted, slot 2 left empty
+    lru.reclaim_tail(cache, 5)
+    assert cache.page[3:] == [-1, -1] and len(cache.ts) == 5
+    slots, misses, _ = lru.lru_step(cache, [20, 21], 2, 64)
+    assert [s for _, s in misses] == [2, 3]
+    cache.check()
