@@ -115,6 +115,7 @@ def run_cfg4(args):
             layer = hier.HierLayer(w, budget_frac=args.budget_frac, n_ts=64, evict_exact=exact, copy_mode=mode)
             q = layer.q0
             lat, persist, prev = [], [], None
+            layer.spin.profile_enable(steps)          # kernels bracketed by HIP events on the launch stream
             trace = [[] for _ in range(w.rows)] if (mode == modes[-1] and not exact and not args.no_cpu) else None
             for s in range(steps):
                 torch.cuda.synchronize()
@@ -134,6 +135,12 @@ def run_cfg4(args):
                 q_bits = q.view(torch.int16).cpu().numpy().view(np.uint16)
                 q = torch.from_numpy(synth.next_query_ar1(q_bits, 0.9, w.seed + 7000 + s).view(np.int16)).to(dev).view(torch.bfloat16)
             assert layer.status() == 0, "device fault in the budget workload"
+            kern = {}
+            for name in ("score", "select", "resolve", "gather", "decode"):
+                n, mean, mn = layer.spin.profile_read(name)
+                if n:
+                    kern[name] = dict(mean_us=round(mean, 1), min_us=round(mn, 1))
+            layer.spin.profile_enable(0)
             overall, warm = layer.hit_rates()
             lat_w = sorted(lat[1:])
             key = f"{mode}{'_evict_exact' if exact else ''}"
@@ -142,7 +149,7 @@ def run_cfg4(args):
                                 selected_per_step=round(layer.stats["selected"] / steps, 1),
                                 step_us_median=round(lat_w[len(lat_w) // 2], 1), step_us_p90=round(lat_w[int(0.9 * len(lat_w))], 1),
                                 first_step_us=round(lat[0], 1), topk_persistence=round(float(np.mean(persist)), 4),
-                                pool_gib=round(layer.pool_slots * 8192 / 2**30, 2),
+                                kernel_us=kern, pool_gib=round(layer.pool_slots * 8192 / 2**30, 2),
                                 host_kv_gib=round(layer.host_kv.numel() * 2 / 2**30, 2))
             if trace is not None:
                 from oracle import lru as olru

@@ -67,6 +67,90 @@ __global__ __launch_bounds__(256) void spin_index_minmax_kernel(
   o[tbase + (size_t)(16 + ch) * 16 + (R & 15)] = make_uint4(omn[0], omn[1], omn[2], omn[3]);
 }
 
+// MINMAX for partitions made of whole pages (partition_tokens >= 16), the hot
+// Index shape: one workgroup per tile of 16 partitions, each of its four
+// wavefronts folds four partitions.  A page's K tile is fetched with four
+// contiguous 1 KiB loads, passed through the wavefront's own 4 KiB of LDS to
+// regroup it (lane = 8-channel chunk x token quad), folded over the lane's four
+// tokens in registers and over the four token quads with two DPP exchanges.
+__global__ __launch_bounds__(256) void spin_index_minmax_pages_kernel(
+    const uint4 *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
+    const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
+    const int32_t *__restrict__ seq_lens, int Hkv, int tp, int dir_stride, int leaf_entries, int max_tiles,
+    uint16_t *__restrict__ summ, int32_t *status) {
+  __shared__ uint4 s_tile[4][SPIN_KTILE_U4];
+  const int row = blockIdx.x / max_tiles, tile = blockIdx.x - row * max_tiles;
+  const int b = row / Hkv, h = row - b * Hkv;
+  const int PP = part_offsets[b + 1] - part_offsets[b];
+  if (tile * 16 >= PP) return;
+  const int N = seq_lens[b];
+  const int P = (N + tp - 1) / tp;
+  const size_t base = (size_t)Hkv * part_offsets[b] + (size_t)h * PP;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ch = lane >> 2, tq = lane & 3;      // after regrouping: chunk of 8 channels, tokens 4tq..4tq+3
+  uint4 *lds = s_tile[wave];
+  uint4 *o = (uint4 *)summ;
+  for (int k = 0; k < 4; ++k) {
+    const int r = wave * 4 + k;                  // partition inside the tile
+    const int p = tile * 16 + r;
+    float mn[8], mx[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { mn[i] = __builtin_inff(); mx[i] = -__builtin_inff(); }
+    bool any = false;
+    if (p < P) {
+      const int t0 = p * tp, t1 = min(t0 + tp, N);
+      for (int pg = t0 >> 4; pg <= (t1 - 1) >> 4; ++pg) {
+        const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
+        if (slot < 0 || (int64_t)slot >= pool_slots) {
+          if (lane == 0) spin_raise(status, SPIN_ERR_NOT_RESIDENT);
+          continue;
+        }
+        const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
+        uint4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = spin_nt_load(kt + j * 64);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) lds[j * 64 + lane] = v[j];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // same wavefront writes and reads: program order
+        const int nvalid = min(t1 - pg * 16, 16);                // tokens of this page inside the partition
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint4 u = lds[ch * 16 + 4 * tq + i];
+          if (4 * tq + i < nvalid) {
+            const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float lo = __uint_as_float(w[e] << 16), hi = __uint_as_float(w[e] & 0xffff0000u);
+              mn[2 * e] = fminf(mn[2 * e], lo); mx[2 * e] = fmaxf(mx[2 * e], lo);
+              mn[2 * e + 1] = fminf(mn[2 * e + 1], hi); mx[2 * e + 1] = fmaxf(mx[2 * e + 1], hi);
+            }
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        any = true;
+      }
+    }
+    // fold the four token quads (lanes 4ch .. 4ch+3)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      mn[i] = fminf(mn[i], spin_dpp<SPIN_DPP_XOR1>(mn[i])); mn[i] = fminf(mn[i], spin_dpp<SPIN_DPP_XOR2>(mn[i]));
+      mx[i] = fmaxf(mx[i], spin_dpp<SPIN_DPP_XOR1>(mx[i])); mx[i] = fmaxf(mx[i], spin_dpp<SPIN_DPP_XOR2>(mx[i]));
+    }
+    if (tq == 0) {
+      uint32_t omx[4], omn[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        omx[i] = any ? ((__float_as_uint(mx[2 * i]) >> 16) | (__float_as_uint(mx[2 * i + 1]) & 0xffff0000u)) : 0u;
+        omn[i] = any ? ((__float_as_uint(mn[2 * i]) >> 16) | (__float_as_uint(mn[2 * i + 1]) & 0xffff0000u)) : 0u;
+      }
+      const size_t R = base + p;
+      const size_t tbase = (R >> 4) * (size_t)(16 * 256 / 8);
+      o[tbase + (size_t)ch * 16 + (R & 15)] = make_uint4(omx[0], omx[1], omx[2], omx[3]);
+      o[tbase + (size_t)(16 + ch) * 16 + (R & 15)] = make_uint4(omn[0], omn[1], omn[2], omn[3]);
+    }
+  }
+}
+
 // fp64 -> bf16 with a single rounding: truncate to fp32 with a sticky low bit
 // (round to odd), then round the 16 dropped bits to nearest even.
 __device__ inline uint16_t spin_f64_to_bf16(double x) {
@@ -177,6 +261,12 @@ extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv
   int32_t *status = (int32_t *)workspace;
   if (c.score_kind == SPIN_SCORE_MINMAX) {
     const int max_tiles = max_pp / 16;
+    if (c.partition_tokens >= 16)
+      spin_launch(ctx, SPIN_K_INDEX, spin_index_minmax_pages_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
+                  (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
+                  c.num_kv_heads, c.partition_tokens, ctx->dir_stride, c.leaf_entries, max_tiles,
+                  (uint16_t *)summaries, status);
+    else
     hipLaunchKernelGGL(spin_index_minmax_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
                        (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
                        c.num_kv_heads, c.partition_tokens, ctx->dir_stride, c.leaf_entries, max_tiles,
