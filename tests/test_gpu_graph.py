@@ -1,0 +1,47 @@
+"""The stage calls allocate nothing and record no memset, so a decode step can
+be captured in a HIP graph.  The graph is replayed several times, with eager
+work and synchronisations between replays, and every replay must reproduce the
+eager result bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_26837_amd import runner, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def test_step_replays_from_a_graph():
+    w = synth.config0().with_(seq_lens=(4096, 1000, 2049), num_q_heads=8, num_kv_heads=2, topk=24, sink_pages=2,
+                              recent_pages=3, name="graph")
+    data = synth.generate(w)
+    natural = torch.from_numpy(data.pool_bits.view(np.int16).copy()).to("cuda:0").view(torch.bfloat16)
+    layer = runner.LayerState.from_natural_pool(w, data.slot_of, natural, decode_splits=2)
+    layer.build_summaries()
+    qs = [torch.from_numpy(synth.make_queries(w, 100 + i).view(np.int16)).to("cuda:0").view(torch.bfloat16)
+          for i in range(3)]
+    q_static = qs[0].clone()
+    eager = []
+    for q in qs:
+        layer.step3(q)
+        torch.cuda.synchronize()
+        eager.append((layer.out.clone(), layer.sel.clone(), layer.slots.clone()))
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        layer.step3(q_static)                      # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(s)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        layer.step3(q_static)
+    for rep in range(6):
+        i = rep % 3
+        q_static.copy_(qs[i])
+        layer.out.fill_(9.0)                       # eager work between replays
+        layer.sel.fill_(-3)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert layer.status() == 0
+        assert torch.equal(layer.out.view(torch.int16), eager[i][0].view(torch.int16)), f"replay {rep}"
+        assert torch.equal(layer.sel, eager[i][1]) and torch.equal(layer.slots, eager[i][2])
