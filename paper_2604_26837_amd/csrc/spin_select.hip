@@ -157,13 +157,15 @@ extern "C" int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *score
 #define SPIN_SELECT_ARGS                                                                                      \
   0, (hipStream_t)stream, scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk,         \
       c.topk_includes_forced, c.sink_pages, c.recent_pages, ctx->sel_stride, sel, nsel
-  // counts are packed in 16-bit halves in the register variants: rows of at most 16384 partitions
   if (ctx->max_parts <= 2048)
     spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<256, 8>, dim3((unsigned)rows), dim3(256), SPIN_SELECT_ARGS);
   else if (ctx->max_parts <= 4096)
     spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<512, 8>, dim3((unsigned)rows), dim3(512), SPIN_SELECT_ARGS);
   else if (ctx->max_parts <= 16384)
     spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<1024, 16>, dim3((unsigned)rows), dim3(1024),
+                SPIN_SELECT_ARGS);
+  else if (ctx->max_parts <= 65536)
+    spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<1024, 64>, dim3((unsigned)rows), dim3(1024),
                 SPIN_SELECT_ARGS);
   else
     spin_launch(ctx, SPIN_K_SELECT, spin_select_kernel, dim3((unsigned)rows), dim3(SEL_BLOCK), SPIN_SELECT_ARGS);

@@ -23,7 +23,7 @@ __device__ inline int select_reg_row(
     int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel, int row) {
   constexpr int NW = BLOCK / 64;
   __shared__ int s_hist[2][256];
-  __shared__ unsigned s_wtot[NW];
+  __shared__ unsigned long long s_wtot[NW];
   __shared__ int s_digit, s_remaining;
 
   const int b = row / Hkv, h = row - b * Hkv;
@@ -117,29 +117,29 @@ __device__ inline int select_reg_row(
   const unsigned need_eq = kprime > 0 ? (unsigned)remaining : 0u;
 
   // counts of this thread: low half = forced or above threshold, high half = equal to it
-  unsigned mine = 0;
+  unsigned long long mine = 0;
 #pragma unroll
   for (int k = 0; k < KPT; ++k) {
     const int p = c0 + k;
     if (p >= P) continue;
-    if (p < nf_lo || p >= first_hi) { mine += 1u; continue; }
+    if (p < nf_lo || p >= first_hi) { mine += 1ull; continue; }
     if (kprime == 0) continue;
-    mine += (key[k] > T) ? 1u : 0u;
-    mine += (key[k] == T) ? 0x10000u : 0u;
+    mine += (key[k] > T) ? 1ull : 0ull;
+    mine += (key[k] == T) ? (1ull << 32) : 0ull;
   }
-  unsigned inc = mine;
+  unsigned long long inc = mine;
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
-    const unsigned o = __shfl_up(inc, d);
+    const unsigned long long o = __shfl_up(inc, d);
     if (lane >= d) inc += o;
   }
   if (lane == 63) s_wtot[wave] = inc;
   __syncthreads();
-  unsigned before = inc - mine;
+  unsigned long long before = inc - mine;
 #pragma unroll
   for (int w = 0; w < NW; ++w)
     if (w < wave) before += s_wtot[w];
-  const unsigned gt_before = before & 0xffffu, eq_before = before >> 16;
+  const unsigned gt_before = (unsigned)(before & 0xffffffffull), eq_before = (unsigned)(before >> 32);
   unsigned eq_quota = need_eq > eq_before ? need_eq - eq_before : 0u;
   int pos = (int)(gt_before + min(eq_before, need_eq));
 #pragma unroll
