@@ -109,6 +109,8 @@ typedef struct spin_config {
   int32_t decode_depth;         /* page buffers per decode wavefront (pages in flight + 1): 2, 3 or 4; 0 = choose */
   int32_t score_tiles_per_wg;   /* 16-row summary tiles per stage-1 workgroup; 0 = choose */
   int32_t score_waves;          /* wavefronts per stage-1 workgroup: 4 or 8; 0 = 4 */
+  int32_t variable_partitions;  /* 1: strides are sized for spin_set_partition_tables (partitions of 1 page up to
+                                   partition_tokens tokens) */
   float softmax_scale;          /* 0 = 1/sqrt(head_dim) */
 } spin_config;
 
@@ -148,6 +150,27 @@ enum spin_kernel_id {
 };
 int spin_profile_enable(spin_ctx *ctx, int32_t capacity);
 int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_us, float *min_us);
+
+/* Variable-length partitions (Section 5.2: the Meta-partition table keeps each
+ * partition's token count, the Partition Offset table where its page list
+ * starts; Section 4.1: a partition may be a block or a cluster of any size).
+ * Registers three DEVICE tables, all indexed like `scores` (entry
+ * num_kv_heads*part_offsets[b] + h*PP_b + p for partition p of row (b,h)):
+ *   part_count      int32 [rows]  partitions of the row
+ *   part_first_page int32         first logical page of the partition; partitions own
+ *                                 whole pages, ascend, and follow one another without gaps
+ *   part_tokens     int32         tokens in the partition (1 .. cfg.partition_tokens); only
+ *                                 its last page may be partly filled
+ * From then on Index, stage 2 and stage 3 (and spin_select_resolve) take a row's
+ * partitions from these tables instead of cutting the context every
+ * cfg.partition_tokens tokens: cfg.partition_tokens is then the LARGEST partition
+ * (it sizes the strides) and seq_lens is not consulted by stages 2 and 3.  Sink and
+ * recent pages are the first / last pages of the row's page list.  Supported for
+ * MINMAX scores, all-resident mode, rows of at most 65536 partitions.  Passing
+ * NULL for the three tables returns to uniform partitions.  The pointers are kept,
+ * not copied: the tables must outlive the calls that use them. */
+int spin_set_partition_tables(spin_ctx *ctx, const int32_t *part_offsets, const int32_t *part_count,
+                              const int32_t *part_first_page, const int32_t *part_tokens);
 
 /* Offload, layout half: write `n_pages` pages given in plain token-major order
  * (src_k, src_v: DEVICE bf16 [n_pages][16][128]) into pool slots `slots[i]`

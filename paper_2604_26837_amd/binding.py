@@ -23,6 +23,7 @@ EXPORTS = [
     "spin_workspace_init", "spin_poll_status", "spin_profile_enable", "spin_profile_read", "spin_pack_kv_pages", "spin_build_summaries",
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
     "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv", "spin_reclaim_tail", "spin_alloc_leaves", "spin_free_leaves",
+    "spin_set_partition_tables",
 ]
 
 
@@ -32,7 +33,7 @@ class SpinConfig(C.Structure):
         "score_kind", "sketch_channels", "reps_per_partition", "topk", "topk_includes_forced",
         "sink_pages", "recent_pages", "max_context", "leaf_entries", "lru_timestamps",
         "lru_evict_exact", "decode_splits", "decode_waves", "decode_depth", "score_tiles_per_wg",
-        "score_waves")] + [("softmax_scale", C.c_float)]
+        "score_waves", "variable_partitions")] + [("softmax_scale", C.c_float)]
 
 
 class SpinError(RuntimeError):
@@ -73,6 +74,7 @@ def load_library() -> C.CDLL:
     lib.spin_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
+    lib.spin_set_partition_tables.argtypes = [vp, vp, vp, vp, vp]
     lib.spin_reclaim_tail.argtypes = [vp, i32, vp, vp, vp, vp, i64, vp, vp, vp]
     lib.spin_alloc_leaves.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, vp, vp, vp]
     lib.spin_free_leaves.argtypes = [vp, i32, vp, i64, vp, vp, vp]
@@ -108,7 +110,7 @@ class Spin:
         c = SpinConfig()
         defaults = dict(head_dim=128, page_tokens=16, partition_tokens=16, score_kind=0, sketch_channels=16,
                         reps_per_partition=4, topk_includes_forced=1, sink_pages=0, recent_pages=0,
-                        leaf_entries=512, lru_timestamps=0, lru_evict_exact=0, decode_splits=0, decode_waves=0, decode_depth=0, score_tiles_per_wg=0, score_waves=0,
+                        leaf_entries=512, lru_timestamps=0, lru_evict_exact=0, decode_splits=0, decode_waves=0, decode_depth=0, score_tiles_per_wg=0, score_waves=0, variable_partitions=0,
                         softmax_scale=0.0)
         defaults.update(cfg)
         for k, v in defaults.items():
@@ -205,6 +207,15 @@ class Spin:
             _ptr(leaf_pool, torch.int32, "leaf_pool"), leaf_pool.shape[0],
             _ptr(part_offsets, torch.int32, "part_offsets"), _ptr(chan_idx, torch.int32, "chan_idx"),
             _ptr(summaries), _ptr(ws), _stream()), "spin_append_kv")
+
+    def set_partition_tables(self, part_offsets=None, part_count=None, part_first_page=None, part_tokens=None):
+        """Registers (or, with no arguments, clears) the variable-length partition tables.  The
+        tensors are kept alive by this object because the library stores their addresses."""
+        self._var_tables = (part_offsets, part_count, part_first_page, part_tokens)
+        self._check(self.lib.spin_set_partition_tables(
+            self.h, _ptr(part_offsets, torch.int32, "part_offsets"), _ptr(part_count, torch.int32, "part_count"),
+            _ptr(part_first_page, torch.int32, "part_first_page"), _ptr(part_tokens, torch.int32, "part_tokens")),
+            "spin_set_partition_tables")
 
     def reclaim_tail(self, batch, slot_range, new_count, dir_, leaf_pool, rev_table, ws):
         self._check(self.lib.spin_reclaim_tail(

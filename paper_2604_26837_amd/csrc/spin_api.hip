@@ -22,6 +22,7 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   if (!((tp < 16 && 16 % tp == 0) || (tp >= 16 && tp % 16 == 0))) return SPIN_ERR_UNSUPPORTED;
   if (c->lru_timestamps > 256) return SPIN_ERR_UNSUPPORTED;
   if (c->decode_depth != 0 && (c->decode_depth < 2 || c->decode_depth > 4)) return SPIN_ERR_INVALID;
+  if (c->variable_partitions && (tp < 16 || c->lru_timestamps > 0)) return SPIN_ERR_UNSUPPORTED;
   if (c->score_tiles_per_wg < 0 || (c->score_waves != 0 && c->score_waves != 4 && c->score_waves != 8))
     return SPIN_ERR_INVALID;
 
@@ -32,7 +33,9 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   x->group = group;
   x->max_rows = c->max_batch * c->num_kv_heads;
   x->max_pages = cdiv32(c->max_context, SPIN_PAGE_TOKENS);
-  x->max_parts = cdiv32(c->max_context, tp);
+  // with variable-length partitions max_context/16 bounds a row's pages and, since a
+  // partition owns at least one page, its partitions too
+  x->max_parts = c->variable_partitions ? cdiv32(c->max_context, SPIN_PAGE_TOKENS) : cdiv32(c->max_context, tp);
   x->pages_per_part = tp >= 16 ? tp / 16 : 0;
   x->parts_per_page = tp < 16 ? 16 / tp : 0;
 
@@ -49,7 +52,9 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
 
   // upper bound of the partitions all of whose pages are forced
   int64_t forced_max;
-  if (tp >= 16) {
+  if (c->variable_partitions) {
+    forced_max = c->sink_pages + c->recent_pages;   // partitions may be as small as one page
+  } else if (tp >= 16) {
     const int32_t m = x->pages_per_part;
     forced_max = cdiv32(c->sink_pages, m) + cdiv32(c->recent_pages, m) + 1;
     if (c->sink_pages + c->recent_pages == 0) forced_max = 0;
@@ -62,7 +67,7 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   if (sel < 1) sel = 1;
   x->sel_stride = (int32_t)sel;
   // forced pages outside every selected partition exist only when a partition spans several pages
-  int64_t pg = tp > 16 ? sel * x->pages_per_part + c->sink_pages + c->recent_pages : sel;
+  int64_t pg = (tp > 16 || c->variable_partitions) ? sel * x->pages_per_part + c->sink_pages + c->recent_pages : sel;
   if (pg > x->max_pages) pg = x->max_pages;
   if (pg < 1) pg = 1;
   x->page_stride = (int32_t)pg;
@@ -168,6 +173,20 @@ extern "C" const char *spin_status_string(int s) {
     case SPIN_ERR_LEAF_POOL: return "leaf segment pool exhausted";
     default: return "unknown status";
   }
+}
+
+extern "C" int spin_set_partition_tables(spin_ctx *ctx, const int32_t *part_offsets, const int32_t *part_count,
+                                         const int32_t *part_first_page, const int32_t *part_tokens) {
+  if (!ctx) return SPIN_ERR_INVALID;
+  if (!part_count && !part_first_page && !part_tokens) {   // back to uniform partitions
+    ctx->var = spin_var{nullptr, nullptr, nullptr, nullptr};
+    return SPIN_OK;
+  }
+  if (!part_offsets || !part_count || !part_first_page || !part_tokens) return SPIN_ERR_INVALID;
+  const spin_config &c = ctx->cfg;
+  if (c.partition_tokens < 16 || c.score_kind != SPIN_SCORE_MINMAX || c.lru_timestamps > 0) return SPIN_ERR_UNSUPPORTED;
+  ctx->var = spin_var{part_offsets, part_count, part_first_page, part_tokens};
+  return SPIN_OK;
 }
 
 extern "C" size_t spin_workspace_bytes(const spin_ctx *c) { return c ? c->ws_bytes : 0; }

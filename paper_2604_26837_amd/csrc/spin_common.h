@@ -15,6 +15,17 @@
 
 #define SPIN_KERNEL_IDS 8
 
+// Variable-length partitions (Section 5.2: the Meta-partition table holds each
+// partition's token count, the Partition Offset table where its page list
+// starts).  All three arrays are indexed like `scores`: entry base(row) + p.
+// count == NULL means uniform partitions of cfg.partition_tokens tokens.
+struct spin_var {
+  const int32_t *part_offsets;  // [batch+1] the padded partition offsets the tables are indexed with
+  const int32_t *count;       // [rows] partitions of the row
+  const int32_t *first_page;  // first logical page of partition p
+  const int32_t *tokens;      // tokens of partition p (its last page may be partly filled)
+};
+
 struct spin_ctx {
   spin_config cfg;
   int32_t group;          // query heads per KV head
@@ -35,6 +46,7 @@ struct spin_ctx {
   size_t ws_bytes;
   size_t ws_ticket_off, ws_ml_off, ws_acc_off;
   size_t ws_zero_bytes;   // leading part of the workspace that spin_workspace_init clears
+  spin_var var;           // registered partition tables (all NULL: uniform partitions)
   // optional per-kernel timing: pairs of HIP events handed to the launches
   int32_t prof_cap;
   int32_t prof_n[SPIN_KERNEL_IDS];
@@ -107,6 +119,36 @@ __device__ inline int32_t spin_walk(const int32_t *__restrict__ dir, const int32
   const int32_t chunk = dir[(size_t)row * dir_stride + ci];
   if (chunk < 0 || (int64_t)chunk >= leaf_chunks) return -1;
   return leaf_pool[(size_t)chunk * leaf_entries + (page - ci * leaf_entries)];
+}
+
+// variable-length partitions: first table entry of a row
+__device__ inline size_t spin_var_base(const spin_var &v, int row, int Hkv) {
+  const int b = row / Hkv, h = row - b * Hkv;
+  const int off = v.part_offsets[b];
+  return (size_t)Hkv * off + (size_t)h * (v.part_offsets[b + 1] - off);
+}
+// variable-length partitions: pages of partition p, and the row's page count
+__device__ inline int spin_var_npages(const spin_var &v, size_t base, int p) { return (v.tokens[base + p] + 15) >> 4; }
+__device__ inline int spin_var_row_pages(const spin_var &v, size_t base, int P) {
+  return P > 0 ? v.first_page[base + P - 1] + spin_var_npages(v, base, P - 1) : 0;
+}
+// first p in [0, P) whose first page is >= page (P if none); first pages ascend
+__device__ inline int spin_var_lower_bound_start(const spin_var &v, size_t base, int P, int page) {
+  int lo = 0, hi = P;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (v.first_page[base + mid] >= page) hi = mid; else lo = mid + 1;
+  }
+  return lo;
+}
+// number of leading partitions that end at or before `page`
+__device__ inline int spin_var_count_end_le(const spin_var &v, size_t base, int P, int page) {
+  int lo = 0, hi = P;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (v.first_page[base + mid] + spin_var_npages(v, base, mid) <= page) lo = mid + 1; else hi = mid;
+  }
+  return lo;
 }
 
 // DPP lane exchanges inside a row of 16 lanes

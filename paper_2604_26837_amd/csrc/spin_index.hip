@@ -77,15 +77,16 @@ __global__ __launch_bounds__(256) void spin_index_minmax_pages_kernel(
     const uint4 *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
     const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int dir_stride, int leaf_entries, int max_tiles,
-    uint16_t *__restrict__ summ, int32_t *status) {
+    uint16_t *__restrict__ summ, int32_t *status, spin_var var) {
   __shared__ uint4 s_tile[4][SPIN_KTILE_U4];
   const int row = blockIdx.x / max_tiles, tile = blockIdx.x - row * max_tiles;
   const int b = row / Hkv, h = row - b * Hkv;
   const int PP = part_offsets[b + 1] - part_offsets[b];
   if (tile * 16 >= PP) return;
   const int N = seq_lens[b];
-  const int P = (N + tp - 1) / tp;
   const size_t base = (size_t)Hkv * part_offsets[b] + (size_t)h * PP;
+  int P = var.count ? var.count[row] : (N + tp - 1) / tp;
+  P = P < 0 ? 0 : (P > PP ? PP : P);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ch = lane >> 2, tq = lane & 3;      // after regrouping: chunk of 8 channels, tokens 4tq..4tq+3
   uint4 *lds = s_tile[wave];
@@ -98,8 +99,16 @@ __global__ __launch_bounds__(256) void spin_index_minmax_pages_kernel(
     for (int i = 0; i < 8; ++i) { mn[i] = __builtin_inff(); mx[i] = -__builtin_inff(); }
     bool any = false;
     if (p < P) {
-      const int t0 = p * tp, t1 = min(t0 + tp, N);
-      for (int pg = t0 >> 4; pg <= (t1 - 1) >> 4; ++pg) {
+      // the partition's pages and the token position (in page units of 16) where it ends
+      int pg0, t1;
+      if (var.count) {
+        pg0 = var.first_page[base + p];
+        t1 = pg0 * 16 + var.tokens[base + p];
+      } else {
+        pg0 = (p * tp) >> 4;
+        t1 = min(p * tp + tp, N);
+      }
+      for (int pg = pg0; pg <= (t1 - 1) >> 4; ++pg) {
         const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
         if (slot < 0 || (int64_t)slot >= pool_slots) {
           if (lane == 0) spin_raise(status, SPIN_ERR_NOT_RESIDENT);
@@ -255,6 +264,7 @@ extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv
   if (!kv_pool || !dir || !leaf_pool || !part_offsets || !seq_lens || !summaries) return SPIN_ERR_INVALID;
   if (!workspace) return SPIN_ERR_WORKSPACE;
   const spin_config &c = ctx->cfg;
+  if (ctx->var.count && !(c.score_kind == SPIN_SCORE_MINMAX && c.partition_tokens >= 16)) return SPIN_ERR_UNSUPPORTED;
   const int rows = batch * c.num_kv_heads;
   const int max_pp = ((ctx->max_parts + 15) / 16) * 16;
   hipStream_t st = (hipStream_t)stream;
@@ -265,7 +275,7 @@ extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv
       spin_launch(ctx, SPIN_K_INDEX, spin_index_minmax_pages_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
                   (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
                   c.num_kv_heads, c.partition_tokens, ctx->dir_stride, c.leaf_entries, max_tiles,
-                  (uint16_t *)summaries, status);
+                  (uint16_t *)summaries, status, ctx->var);
     else
     hipLaunchKernelGGL(spin_index_minmax_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
                        (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,

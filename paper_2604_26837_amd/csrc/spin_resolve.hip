@@ -16,10 +16,11 @@ __global__ __launch_bounds__(RES_BLOCK) void spin_resolve_kernel(
     const int32_t *dir, const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, int Hkv, int tp,
     int sink_pages, int recent_pages, int sel_stride, int page_stride, int dir_stride, int leaf_entries,
     int32_t *__restrict__ slots, int32_t *__restrict__ page_ids, uint16_t *__restrict__ valid_mask,
-    int32_t *__restrict__ npages, int32_t *status) {
+    int32_t *__restrict__ npages, int32_t *status, spin_var var) {
   const int row = blockIdx.x;
   resolve_row<RES_BLOCK>(row, nsel[row], sel, seq_lens, dir, leaf_pool, leaf_chunks, Hkv, tp, sink_pages, recent_pages,
-                         sel_stride, page_stride, dir_stride, leaf_entries, slots, page_ids, valid_mask, npages, status);
+                         sel_stride, page_stride, dir_stride, leaf_entries, slots, page_ids, valid_mask, npages, status,
+                         var);
 }
 
 // ---------------------------------------------------------------------------
@@ -268,7 +269,7 @@ extern "C" int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, co
   const int rows = batch * c.num_kv_heads;
   if (c.lru_timestamps > 0) {
     if (!rev_table || !slot_base || !miss_pages || !miss_slots || !nmiss) return SPIN_ERR_INVALID;
-    if (c.partition_tokens != 16 || c.lru_timestamps > LRU_MAX_TS) return SPIN_ERR_UNSUPPORTED;
+    if (c.partition_tokens != 16 || c.lru_timestamps > LRU_MAX_TS || ctx->var.count) return SPIN_ERR_UNSUPPORTED;
     // LDS: two int32 per output entry plus one flag byte per slot of the row
     const int max_slots_lds = 48 * 1024;
     const size_t lds = (size_t)ctx->page_stride * 8 + max_slots_lds;
@@ -283,6 +284,6 @@ extern "C" int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, co
   spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_kernel, dim3((unsigned)rows), dim3(RES_BLOCK), 0, (hipStream_t)stream, sel, nsel,
                      seq_lens, dir, leaf_pool, leaf_chunks, c.num_kv_heads, c.partition_tokens, c.sink_pages,
                      c.recent_pages, ctx->sel_stride, ctx->page_stride, ctx->dir_stride, c.leaf_entries, slots,
-                     page_ids, valid_mask, npages, (int32_t *)workspace);
+                     page_ids, valid_mask, npages, (int32_t *)workspace, ctx->var);
   return spin_launch_status();
 }

@@ -64,7 +64,7 @@ __device__ inline void resolve_row(
     const int32_t *dir, const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, int Hkv, int tp,
     int sink_pages, int recent_pages, int sel_stride, int page_stride, int dir_stride, int leaf_entries,
     int32_t *__restrict__ slots, int32_t *__restrict__ page_ids, uint16_t *__restrict__ valid_mask,
-    int32_t *__restrict__ npages, int32_t *status) {
+    int32_t *__restrict__ npages, int32_t *status, spin_var var) {
   constexpr int RES_WAVES = RES_BLOCK / 64;
   __shared__ int s_wave[RES_WAVES];
   __shared__ int s_flagA, s_flagB, s_cntB;
@@ -87,7 +87,82 @@ __device__ inline void resolve_row(
 
   if (dir_in_lds) __syncthreads();
 
-  if (tp == 16) {
+  if (var.count) {
+    // Variable-length partitions: the page list of partition p starts at
+    // first_page[p] and holds ceil(tokens[p]/16) pages (Partition Offset and
+    // Meta-partition tables).  Output positions come from a prefix sum of the
+    // selected partitions' page counts.
+    __shared__ int s_sumA, s_sumB;
+    const size_t vb = spin_var_base(var, row, Hkv);
+    int P = var.count[row];
+    const int cap = var.part_offsets[b + 1] - var.part_offsets[b];
+    P = P < 0 ? 0 : (P > cap ? cap : P);
+    const int vpages = spin_var_row_pages(var, vb, P);
+    int sink_end = min(sink_pages, vpages);
+    int recent_begin = max(vpages - recent_pages, 0);
+    if (sink_end >= recent_begin) { sink_end = vpages; recent_begin = vpages; }
+    int A = -1, B = -1, a0 = 0, a1 = 0, b0 = 0, b1 = 0;
+    if (sink_end > 0) {
+      const int pa = spin_var_lower_bound_start(var, vb, P, sink_end) - 1;   // last partition starting before sink_end
+      if (pa >= 0 && var.first_page[vb + pa] + spin_var_npages(var, vb, pa) > sink_end) {
+        A = pa; a0 = var.first_page[vb + pa]; a1 = sink_end;
+      }
+    }
+    if (recent_begin < vpages) {
+      const int pb = spin_var_lower_bound_start(var, vb, P, recent_begin + 1) - 1;   // partition holding recent_begin
+      if (pb >= 0 && var.first_page[vb + pb] < recent_begin) {
+        B = pb; b0 = recent_begin; b1 = var.first_page[vb + pb] + spin_var_npages(var, vb, pb);
+      }
+    }
+    if (tid == 0) { s_flagA = 0; s_flagB = 0; s_sumA = 0; s_sumB = 0; }
+    __syncthreads();
+    for (int i = tid; i < ns; i += RES_BLOCK) {
+      const int s = rsel[i];
+      if (s < 0 || s >= P) continue;
+      const int n = spin_var_npages(var, vb, s);
+      if (s == A) s_flagA = 1;
+      if (s == B) s_flagB = 1;
+      if (A >= 0 && s < A) atomicAdd(&s_sumA, n);
+      if (B >= 0 && s < B) atomicAdd(&s_sumB, n);
+    }
+    __syncthreads();
+    const int extraA = (A >= 0 && !s_flagA) ? (a1 - a0) : 0;
+    const int extraB = (B >= 0 && !s_flagB) ? (b1 - b0) : 0;
+    int carry = 0;
+    for (int i0 = 0; i0 < ns; i0 += RES_BLOCK) {
+      const int i = i0 + tid;
+      int s = -1, n = 0;
+      if (i < ns) {
+        s = rsel[i];
+        if (s >= 0 && s < P) n = spin_var_npages(var, vb, s); else s = -1;
+      }
+      int tot;
+      const int before = res_block_exclusive_scan<RES_BLOCK>(n, s_wave, tot);
+      if (s >= 0) {
+        int pos = carry + before + ((extraA && s > A) ? extraA : 0) + ((extraB && s > B) ? extraB : 0);
+        const int fp = var.first_page[vb + s], tk = var.tokens[vb + s];
+        for (int k = 0; k < n; ++k) {
+          const int nv = min(max(tk - 16 * k, 0), 16);
+          emit_page(o, pos + k, page_stride, fp + k, (1u << nv) - 1u, dir, leaf_pool, leaf_chunks, row, dir_stride,
+                    leaf_entries, status);
+        }
+      }
+      carry += tot;
+    }
+    for (int k = tid; k < extraA; k += RES_BLOCK) {
+      const int nv = min(max(var.tokens[vb + A] - 16 * (a0 + k - var.first_page[vb + A]), 0), 16);
+      emit_page(o, s_sumA + k, page_stride, a0 + k, (1u << nv) - 1u, dir, leaf_pool, leaf_chunks, row, dir_stride,
+                leaf_entries, status);
+    }
+    for (int k = tid; k < extraB; k += RES_BLOCK) {
+      const int nv = min(max(var.tokens[vb + B] - 16 * (b0 + k - var.first_page[vb + B]), 0), 16);
+      emit_page(o, s_sumB + ((A >= 0 && A <= B) ? extraA : 0) + k, page_stride, b0 + k, (1u << nv) - 1u, dir, leaf_pool,
+                leaf_chunks, row, dir_stride, leaf_entries, status);
+    }
+    const int total = min(carry + extraA + extraB, page_stride);
+    for (int i = total + tid; i < page_stride; i += RES_BLOCK) { o.slots[i] = -1; o.page_ids[i] = -1; o.mask[i] = 0; }
+    if (tid == 0) npages[row] = total;
+  } else if (tp == 16) {
     // partition == page: the selection is the page list.  The entry is loaded
     // before the row's counts are known (the buffer is sel_stride wide), so the
     // leaf lookup is the only dependent round trip.

@@ -140,9 +140,9 @@ template <int BLOCK, int KPT>
 __global__ __launch_bounds__(BLOCK) void spin_select_reg_kernel(
     const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
-    int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel) {
+    int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel, spin_var var) {
   (void)select_reg_row<BLOCK, KPT, false>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced, sink_pages,
-                                          recent_pages, sel_stride, sel, nsel, (int)blockIdx.x);
+                                          recent_pages, sel_stride, sel, nsel, (int)blockIdx.x, var);
 }
 
 extern "C" int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
@@ -158,15 +158,17 @@ extern "C" int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *score
   0, (hipStream_t)stream, scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk,         \
       c.topk_includes_forced, c.sink_pages, c.recent_pages, ctx->sel_stride, sel, nsel
   if (ctx->max_parts <= 2048)
-    spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<256, 8>, dim3((unsigned)rows), dim3(256), SPIN_SELECT_ARGS);
+    spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<256, 8>, dim3((unsigned)rows), dim3(256), SPIN_SELECT_ARGS, ctx->var);
   else if (ctx->max_parts <= 4096)
-    spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<512, 8>, dim3((unsigned)rows), dim3(512), SPIN_SELECT_ARGS);
+    spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<512, 8>, dim3((unsigned)rows), dim3(512), SPIN_SELECT_ARGS, ctx->var);
   else if (ctx->max_parts <= 16384)
     spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<1024, 16>, dim3((unsigned)rows), dim3(1024),
-                SPIN_SELECT_ARGS);
+                SPIN_SELECT_ARGS, ctx->var);
   else if (ctx->max_parts <= 65536)
     spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<1024, 64>, dim3((unsigned)rows), dim3(1024),
-                SPIN_SELECT_ARGS);
+                SPIN_SELECT_ARGS, ctx->var);
+  else if (ctx->var.count)
+    return SPIN_ERR_UNSUPPORTED;   // variable-length partitions: rows of at most 65536 partitions
   else
     spin_launch(ctx, SPIN_K_SELECT, spin_select_kernel, dim3((unsigned)rows), dim3(SEL_BLOCK), SPIN_SELECT_ARGS);
 #undef SPIN_SELECT_ARGS

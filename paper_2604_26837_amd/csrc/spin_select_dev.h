@@ -20,7 +20,8 @@ template <int BLOCK, int KPT, bool COH>
 __device__ inline int select_reg_row(
     const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
-    int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel, int row) {
+    int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel, int row,
+    spin_var var) {
   constexpr int NW = BLOCK / 64;
   __shared__ int s_hist[2][256];
   __shared__ unsigned long long s_wtot[NW];
@@ -33,7 +34,9 @@ __device__ inline int select_reg_row(
   const float *rs = scores + (size_t)Hkv * off_b + (size_t)h * PP;
   int32_t *rsel = sel + (size_t)row * sel_stride;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int P = N > 0 ? (N + tp - 1) / tp : 0;
+  const size_t vbase = (size_t)Hkv * off_b + (size_t)h * PP;
+  int P = var.count ? var.count[row] : (N > 0 ? (N + tp - 1) / tp : 0);
+  if (P < 0) P = 0;
   if (P > PP) P = PP;
   if (P > BLOCK * KPT) P = BLOCK * KPT;   // the host picks a variant that fits; keep indexing in range
 
@@ -52,12 +55,18 @@ __device__ inline int select_reg_row(
   }
 
   // forced partitions: a prefix [0, nf_lo) and a suffix [first_hi, P)
-  const int pages = (N + 15) >> 4;
+  const int pages = var.count ? spin_var_row_pages(var, vbase, P) : ((N + 15) >> 4);
   int sink_end = min(sink_pages, pages);
   int recent_begin = max(pages - recent_pages, 0);
   if (sink_end >= recent_begin) { sink_end = pages; recent_begin = pages; }
-  int nf_lo = (N <= sink_end * 16) ? P : min((sink_end * 16) / tp, P);
-  int first_hi = min((recent_begin * 16 + tp - 1) / tp, P);
+  int nf_lo, first_hi;
+  if (var.count) {
+    nf_lo = spin_var_count_end_le(var, vbase, P, sink_end);
+    first_hi = spin_var_lower_bound_start(var, vbase, P, recent_begin);
+  } else {
+    nf_lo = (N <= sink_end * 16) ? P : min((sink_end * 16) / tp, P);
+    first_hi = min((recent_begin * 16 + tp - 1) / tp, P);
+  }
   if (first_hi <= nf_lo) { nf_lo = P; first_hi = P; }
   const int nforced = nf_lo + (P - first_hi);
   const int ncand = P - nforced;

@@ -13,13 +13,13 @@ __global__ __launch_bounds__(BLOCK) void spin_select_resolve_kernel(
     int recent_pages, int sel_stride, int32_t *sel, int32_t *nsel, const int32_t *dir,
     const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, int page_stride, int dir_stride, int leaf_entries,
     int32_t *__restrict__ slots, int32_t *__restrict__ page_ids, uint16_t *__restrict__ valid_mask,
-    int32_t *__restrict__ npages, int32_t *status) {
+    int32_t *__restrict__ npages, int32_t *status, spin_var var) {
   const int row = blockIdx.x;
   const int take = select_reg_row<BLOCK, KPT, false>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced,
-                                                     sink_pages, recent_pages, sel_stride, sel, nsel, row);
+                                                     sink_pages, recent_pages, sel_stride, sel, nsel, row, var);
   __syncthreads();   // the selection was written by this workgroup: visible to all its threads from here
   resolve_row<BLOCK>(row, take, sel, seq_lens, dir, leaf_pool, leaf_chunks, Hkv, tp, sink_pages, recent_pages,
-                     sel_stride, page_stride, dir_stride, leaf_entries, slots, page_ids, valid_mask, npages, status);
+                     sel_stride, page_stride, dir_stride, leaf_entries, slots, page_ids, valid_mask, npages, status, var);
 }
 
 extern "C" int spin_select_resolve(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
@@ -40,7 +40,7 @@ extern "C" int spin_select_resolve(spin_ctx *ctx, int32_t batch, const float *sc
   0, (hipStream_t)stream, scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk,         \
       c.topk_includes_forced, c.sink_pages, c.recent_pages, ctx->sel_stride, sel, nsel, dir, leaf_pool,       \
       leaf_chunks, ctx->page_stride, ctx->dir_stride, c.leaf_entries, slots, page_ids, valid_mask, npages,    \
-      (int32_t *)workspace
+      (int32_t *)workspace, ctx->var
   if (ctx->max_parts <= 2048)
     spin_launch(ctx, SPIN_K_SELECT, spin_select_resolve_kernel<256, 8>, dim3((unsigned)rows), dim3(256), SPIN_SR_ARGS);
   else if (ctx->max_parts <= 4096)

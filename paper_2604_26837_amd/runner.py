@@ -17,9 +17,14 @@ from . import binding, synth, tables
 
 class LayerState:
     def __init__(self, w: synth.Workload, slot_of: List[np.ndarray], kv_pool: torch.Tensor,
-                 device: str = "cuda:0", **cfg_over):
+                 device: str = "cuda:0", layouts=None, **cfg_over):
+        """``layouts`` (optional): per request, per KV head, a pair of lists
+        ``(first_page, tokens)`` describing variable-length partitions; the
+        workload's ``partition_tokens`` is then the largest partition allowed."""
         self.w = w
         self.device = device
+        if layouts is not None:
+            cfg_over = dict(cfg_over, variable_partitions=1)
         self.spin = binding.Spin.for_workload(w, **cfg_over)
         self.ws = self.spin.new_workspace(device)
         self.kv_pool = kv_pool
@@ -28,8 +33,19 @@ class LayerState:
         sp = self.spin
         rows = w.rows
         self.seq_lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=device)
-        self.part_offsets_np = tables.part_offsets(w.seq_lens, w.partition_tokens)
+        if layouts is None:
+            self.part_offsets_np = tables.part_offsets(w.seq_lens, w.partition_tokens)
+        else:
+            self.part_offsets_np = tables.part_offsets_from_counts(
+                [max(len(fp) for fp, _ in layouts[b]) for b in range(w.batch)])
         self.part_offsets = torch.from_numpy(self.part_offsets_np).to(device)
+        if layouts is not None:
+            cnt, first, toks = tables.partition_tables(layouts, self.part_offsets_np, w.num_kv_heads)
+            self.part_count = torch.from_numpy(cnt).to(device)
+            self.part_first_page = torch.from_numpy(first).to(device)
+            self.part_tokens = torch.from_numpy(toks).to(device)
+            self.spin.set_partition_tables(self.part_offsets, self.part_count, self.part_first_page,
+                                           self.part_tokens)
         d, l = tables.build_two_level(slot_of, sp.dir_stride, w.leaf_entries)
         self.dir = torch.from_numpy(d).to(device)
         self.leaf_pool = torch.from_numpy(l).to(device)
@@ -49,12 +65,12 @@ class LayerState:
 
     # ------------------------------------------------------------------
     @classmethod
-    def from_natural_pool(cls, w, slot_of, natural_pool: torch.Tensor, device="cuda:0", **cfg_over):
+    def from_natural_pool(cls, w, slot_of, natural_pool: torch.Tensor, device="cuda:0", layouts=None, **cfg_over):
         """``natural_pool``: bf16 ``[slots][2][16][128]`` in plain token-major
         order; it is re-written into the library's slot layout by the pack kernel."""
         nslots = natural_pool.shape[0]
         kv_pool = torch.empty((nslots, 4096), dtype=torch.bfloat16, device=device)
-        self = cls(w, slot_of, kv_pool, device=device, **cfg_over)
+        self = cls(w, slot_of, kv_pool, device=device, layouts=layouts, **cfg_over)
         chunk = 32768
         for s0 in range(0, nslots, chunk):
             s1 = min(nslots, s0 + chunk)

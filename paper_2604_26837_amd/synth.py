@@ -259,6 +259,29 @@ def generate(w: Workload, seed: Optional[int] = None, spare_slots: int = 0) -> S
     return SynthData(workload=w, q_bits=q_bits, pool_bits=pool, slot_of=slot_of, planted=planted)
 
 
+def variable_layouts(w: Workload, seed: int, min_tokens: int = 1):
+    """Seeded variable-length partition layouts: for every (request, KV head) row,
+    partition sizes drawn uniformly from [min_tokens, partition_tokens] until the
+    row's pages are used up (the last one is cut to fit).  Returns, per request,
+    per head, ``(first_page, tokens)`` lists.  Partitions own whole pages."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for b in range(w.batch):
+        pages = w.pages(b)
+        per_head = []
+        for _ in range(w.num_kv_heads):
+            first, toks, pg = [], [], 0
+            while pg < pages:
+                t = int(rng.integers(min_tokens, w.partition_tokens + 1))
+                t = min(t, (pages - pg) * w.page_tokens)
+                first.append(pg)
+                toks.append(t)
+                pg += -(-t // w.page_tokens)
+            per_head.append((first, toks))
+        out.append(per_head)
+    return out
+
+
 def sketch_channels(data: SynthData) -> np.ndarray:
     """Per KV head, the ``sketch_channels`` channels with the largest mean |K|
     over all requests and valid tokens (ties -> lowest channel), ascending.

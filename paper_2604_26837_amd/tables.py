@@ -29,6 +29,32 @@ def part_offsets(seq_lens: Sequence[int], partition_tokens: int) -> np.ndarray:
     return out
 
 
+def part_offsets_from_counts(max_parts_per_request: Sequence[int]) -> np.ndarray:
+    """Padded offsets when every request brings its own partition count (the
+    largest over its KV heads)."""
+    out = np.zeros(len(max_parts_per_request) + 1, dtype=np.int32)
+    for b, p in enumerate(max_parts_per_request):
+        out[b + 1] = out[b] + cdiv(p, PART_ALIGN) * PART_ALIGN
+    return out
+
+
+def partition_tables(layouts, offsets: np.ndarray, num_kv_heads: int):
+    """Flattens per-row ``(first_page, tokens)`` lists into the three device
+    tables of variable-length partitions, indexed like the score array."""
+    rows = len(layouts) * num_kv_heads
+    total = int(offsets[-1]) * num_kv_heads
+    count = np.zeros(rows, dtype=np.int32)
+    first = np.zeros(total, dtype=np.int32)
+    toks = np.zeros(total, dtype=np.int32)
+    for b, per_head in enumerate(layouts):
+        for h, (fp, tk) in enumerate(per_head):
+            base = row_base(offsets, b, h, num_kv_heads)
+            count[b * num_kv_heads + h] = len(fp)
+            first[base: base + len(fp)] = fp
+            toks[base: base + len(tk)] = tk
+    return count, first, toks
+
+
 def row_base(offsets: np.ndarray, b: int, h: int, num_kv_heads: int) -> int:
     """First entry of row (b, h) in the scores / summary-row arrays."""
     pp = int(offsets[b + 1] - offsets[b])
