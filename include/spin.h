@@ -9,9 +9,12 @@
  *                                                   Section 5.4 two-level tables)
  *   spin_sparse_decode      Attention              (Section 4.1 "Attention")
  *
- * plus two set-up calls that materialise the layouts the stages read
- * (spin_pack_kv_pages: Offload's "materialise the partitioned layout";
- *  spin_build_summaries: Index's per-partition summaries, Section 4.1 / Table 1).
+ * Around them:
+ *   spin_pack_kv_pages, spin_build_summaries, spin_append_kv   Offload's layout and Index (Section 4.1)
+ *   spin_gather_misses, spin_copy_misses_host                  Retrieve steps 3-4 (Sections 5.2, 5.5)
+ *   spin_select_resolve                                        stages 2+3 in one launch, same results
+ *   spin_set_partition_tables                                  variable-length partitions (Section 5.2)
+ *   spin_alloc_leaves, spin_free_leaves, spin_reclaim_tail     on-demand metadata, budget resizing (5.3, 5.4)
  *
  * Conventions
  * -----------
