@@ -260,6 +260,22 @@ def main():
         sp.profile_enable(0)
         assert layer.status() == 0, "device fault during the event-bracketed pass"
 
+    # --- yardstick: a plain streaming read of 128 MiB per launch from the same pool (cold: the
+    # launches walk through 2 GiB), timed with the same kernel events
+    stream_gbps = None
+    if not args.no_kernel_events:
+        sp.profile_enable(32)
+        pool_u8 = layer.kv_pool.view(torch.uint8).reshape(-1)
+        chunk = 128 << 20
+        nchunks = pool_u8.numel() // chunk
+        for i in range(32):
+            sp.probe_stream_read(pool_u8[(i % nchunks) * chunk:], chunk, layer.ws)
+        torch.cuda.synchronize()
+        n, mean, mn = sp.profile_read("probe")
+        sp.profile_enable(0)
+        if n:
+            stream_gbps = round(chunk / mean / 1e3, 1)
+
     # --- byte accounting (Eq. 1 / Eq. 2 of the paper's envelope for this workload)
     attended_tokens = int(layer.npages.sum().item()) * w.page_tokens
     kv_bytes = attended_tokens * 2 * w.head_dim * 2                    # 512 B per attended token
@@ -319,6 +335,7 @@ def main():
         "kernel_us_sum": round(sum(k["mean_us"] for k in kernels.values()), 2) if kernels else None,
         "kernels": kernels,
         "score_gbps": round(score_bytes / sc_us / 1e3, 1) if sc_us else None,
+        "stream_read_128MiB_gbps": stream_gbps,
         "ideal_us_at_peak": round((kv_bytes + score_bytes) / PEAK_HBM_GBPS / 1e3, 2),
         "roofline": roofline, "cpu_baseline": cpu, "parity": parity,
         "paper_context": "end-to-end on A100/B200 (not this metric): 1.66-5.66x throughput, 7-9x lower TTFT "

@@ -149,7 +149,7 @@ int spin_poll_status(spin_ctx *ctx, const void *workspace, void *stream);
  * releases the events.  Not for concurrent use with stage calls. */
 enum spin_kernel_id {
   SPIN_K_SCORE = 0, SPIN_K_SELECT = 1, SPIN_K_RESOLVE = 2, SPIN_K_DECODE = 3, SPIN_K_MERGE = 4,
-  SPIN_K_INDEX = 5, SPIN_K_PACK = 6, SPIN_K_GATHER = 7
+  SPIN_K_INDEX = 5, SPIN_K_PACK = 6, SPIN_K_GATHER = 7, SPIN_K_PROBE = 8
 };
 int spin_profile_enable(spin_ctx *ctx, int32_t capacity);
 int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_us, float *min_us);
@@ -174,6 +174,12 @@ int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_
  * not copied: the tables must outlive the calls that use them. */
 int spin_set_partition_tables(spin_ctx *ctx, const int32_t *part_offsets, const int32_t *part_count,
                               const int32_t *part_first_page, const int32_t *part_tokens);
+
+/* Measurement aid: streams `bytes` (a multiple of 16) from the DEVICE buffer `buf`
+ * with a plain read-only kernel, timed as SPIN_K_PROBE when profiling is enabled.
+ * Gives the bandwidth a single launch of that size can reach on the box at hand,
+ * the yardstick the stage kernels are compared with. */
+int spin_probe_stream_read(spin_ctx *ctx, const void *buf, size_t bytes, void *workspace, void *stream);
 
 /* Offload, layout half: write `n_pages` pages given in plain token-major order
  * (src_k, src_v: DEVICE bf16 [n_pages][16][128]) into pool slots `slots[i]`

@@ -23,7 +23,7 @@ EXPORTS = [
     "spin_workspace_init", "spin_poll_status", "spin_profile_enable", "spin_profile_read", "spin_pack_kv_pages", "spin_build_summaries",
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
     "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv", "spin_reclaim_tail", "spin_alloc_leaves", "spin_free_leaves",
-    "spin_set_partition_tables",
+    "spin_set_partition_tables", "spin_probe_stream_read",
 ]
 
 
@@ -74,6 +74,7 @@ def load_library() -> C.CDLL:
     lib.spin_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
+    lib.spin_probe_stream_read.argtypes = [vp, vp, C.c_size_t, vp, vp]
     lib.spin_set_partition_tables.argtypes = [vp, vp, vp, vp, vp]
     lib.spin_reclaim_tail.argtypes = [vp, i32, vp, vp, vp, vp, i64, vp, vp, vp]
     lib.spin_alloc_leaves.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, vp, vp, vp]
@@ -168,7 +169,7 @@ class Spin:
     def summary_bytes(self, padded_partitions: int) -> int:
         return self.lib.spin_summary_bytes(self.h, padded_partitions)
 
-    KERNEL_IDS = dict(score=0, select=1, resolve=2, decode=3, merge=4, index=5, pack=6, gather=7)
+    KERNEL_IDS = dict(score=0, select=1, resolve=2, decode=3, merge=4, index=5, pack=6, gather=7, probe=8)
 
     def profile_enable(self, capacity: int):
         self._check(self.lib.spin_profile_enable(self.h, capacity), "spin_profile_enable")
@@ -207,6 +208,10 @@ class Spin:
             _ptr(leaf_pool, torch.int32, "leaf_pool"), leaf_pool.shape[0],
             _ptr(part_offsets, torch.int32, "part_offsets"), _ptr(chan_idx, torch.int32, "chan_idx"),
             _ptr(summaries), _ptr(ws), _stream()), "spin_append_kv")
+
+    def probe_stream_read(self, buf, nbytes, ws):
+        self._check(self.lib.spin_probe_stream_read(self.h, _ptr(buf), nbytes, _ptr(ws), _stream()),
+                    "spin_probe_stream_read")
 
     def set_partition_tables(self, part_offsets=None, part_count=None, part_first_page=None, part_tokens=None):
         """Registers (or, with no arguments, clears) the variable-length partition tables.  The

@@ -206,6 +206,31 @@ __global__ void spin_fill_i32_kernel(int32_t *p, int32_t v, int n) {
   if (i < n) p[i] = v;
 }
 
+// Plain streaming read used as the bandwidth yardstick of a box: every lane
+// fetches 16-byte units with a grid stride and folds them into one word.
+__global__ __launch_bounds__(256) void spin_stream_read_kernel(const uint4 *__restrict__ p, size_t n_u4,
+                                                               uint32_t *__restrict__ sink) {
+  size_t i = (size_t)blockIdx.x * 256 * 8 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256 * 8;
+  uint32_t acc = 0;
+  for (; i < n_u4; i += stride) {
+    uint4 v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = (i + 256 * k < n_u4) ? spin_nt_load(p + i + 256 * k) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+  }
+  if (acc == 0x9e3779b9u) *sink = acc;   // keeps the loads alive; practically never taken
+}
+
+extern "C" int spin_probe_stream_read(spin_ctx *ctx, const void *buf, size_t bytes, void *workspace, void *stream) {
+  if (!ctx || !buf || bytes < 16) return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  spin_launch(ctx, SPIN_K_PROBE, spin_stream_read_kernel, dim3(2048), dim3(256), 0, (hipStream_t)stream,
+              (const uint4 *)buf, bytes / 16, (uint32_t *)workspace + 8);
+  return spin_launch_status();
+}
+
 extern "C" int spin_workspace_init(spin_ctx *ctx, void *workspace, void *stream) {
   if (!ctx) return SPIN_ERR_INVALID;
   if (!workspace) return SPIN_ERR_WORKSPACE;

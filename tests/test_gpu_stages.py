@@ -244,6 +244,16 @@ def test_select_large_rows_token_partitions():
     _check_select(w2, [rng.standard_normal(16384).astype(np.float32)])
 
 
+def test_select_rows_beyond_the_register_variants():
+    """Rows of more than 65536 partitions take the kernel that re-reads the scores per pass."""
+    base = synth.config0().with_(num_q_heads=4, num_kv_heads=1)
+    rng = np.random.default_rng(12)
+    w = base.with_(seq_lens=(100000, 70001), partition_tokens=1, topk=500, sink_pages=1, recent_pages=2,
+                   score_kind=synth.SCORE_SKETCH, name="huge_tokens")
+    rows = [np.round(rng.standard_normal(n) * 20).astype(np.float32) / 20 for n in w.seq_lens]
+    _check_select(w, rows)
+
+
 def test_resolve_reports_missing_leaf_and_missing_slot():
     from gpu_harness import DEV, DeviceWorkload, build_summaries, run_step
     w = synth.config0().with_(seq_lens=(4096,), name="holes")
