@@ -169,3 +169,84 @@ def belady_min_misses(trace: List[List[int]], num_slots: int) -> int:
                 del resident[far]
             resident[p] = next_use[i][p]
     return misses
+
+
+# ---------------------------------------------------------------------------
+# Second policy: set-associative placement (the "8-way buckets hashed on
+# (request, page)" of the budget workload's description; the paper's own policy
+# is lru_step above, Section 5.3).  Conventions of this build, stated in full:
+# the row's S slots form S // ways sets of `ways` consecutive slots; a page's
+# home set is mix32(row, page) mod sets; lookups go through the forward table,
+# only placement is constrained.  Misses are handled one at a time in ascending
+# page id: starting at the home set, skip (circularly) every set whose ways all
+# hold pages selected in this step; in the first other set take the lowest empty
+# way, else evict the non-selected way with the smallest timestamp (lowest way
+# on ties).  Timestamps follow step 2 of the bucketed policy.
+# ---------------------------------------------------------------------------
+def mix32(row: int, page: int) -> int:
+    """32-bit finaliser (xor-shift / multiply rounds of the MurmurHash3
+    finaliser) of row * 0x9E3779B1 + page."""
+    x = (row * 0x9E3779B1 + page) & 0xFFFFFFFF
+    x ^= x >> 16
+    x = (x * 0x85EBCA6B) & 0xFFFFFFFF
+    x ^= x >> 13
+    x = (x * 0xC2B2AE35) & 0xFFFFFFFF
+    x ^= x >> 16
+    return x
+
+
+def setassoc_step(cache: RowCache, pages: List[int], step: int, n: int, row: int,
+                  ways: int = 8) -> Tuple[List[int], List[Tuple[int, int]], int]:
+    """One decode step of the set-associative policy; same interface as
+    ``lru_step`` (slots beyond ``(S // ways) * ways`` are never used)."""
+    S = len(cache.page)
+    sets = S // ways
+    selected = set(pages)
+    assert len(selected) == len(pages)
+    if sets < 1 or len(pages) > sets * ways:
+        raise BudgetExceeded((len(pages), S))
+
+    misses = [p for p in pages if p not in cache.where]
+    hits = len(pages) - len(misses)
+
+    ts_star = min(step, n - 1)
+    for s in range(S):
+        p = cache.page[s]
+        if p < 0:
+            continue
+        if p in selected:
+            cache.ts[s] = ts_star
+        elif step > n - 1:
+            cache.ts[s] = max(cache.ts[s] - 1, 0)
+
+    miss_list = []
+    for p in misses:
+        st = mix32(row, p) % sets
+        for _ in range(sets):
+            base = st * ways
+            if any(cache.page[base + w] not in selected for w in range(ways)):
+                break
+            st = (st + 1) % sets
+        else:
+            raise BudgetExceeded((len(pages), S))
+        base = st * ways
+        victim = None
+        for w in range(ways):                          # lowest empty way
+            if cache.page[base + w] < 0:
+                victim = base + w
+                break
+        if victim is None:                             # oldest non-selected way, lowest way on ties
+            best = None
+            for w in range(ways):
+                q = cache.page[base + w]
+                if q in selected:
+                    continue
+                if best is None or cache.ts[base + w] < best:
+                    best, victim = cache.ts[base + w], base + w
+            del cache.where[cache.page[victim]]
+        cache.page[victim] = p
+        cache.ts[victim] = ts_star
+        cache.where[p] = victim
+        miss_list.append((p, victim))
+    slots = [cache.where[p] for p in pages]
+    return slots, miss_list, hits
