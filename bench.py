@@ -108,15 +108,17 @@ def run_cfg4(args):
     steps = 64
     results = {}
     modes = ["memcpy", "gather"] if args.copy_mode == "both" else [args.copy_mode]
-    for exact in (False, True):
+    # the paper's bucketed policy (whole buckets, then exact), then the 8-way set-associative variant
+    for exact, policy in ((False, 0), (True, 0), (False, 1)):
         for mode in modes:
-            if exact and mode != modes[-1]:
+            if (exact or policy) and mode != modes[-1]:
                 continue
-            layer = hier.HierLayer(w, budget_frac=args.budget_frac, n_ts=64, evict_exact=exact, copy_mode=mode)
+            layer = hier.HierLayer(w, budget_frac=args.budget_frac, n_ts=64, evict_exact=exact, copy_mode=mode,
+                                   lru_policy=policy)
             q = layer.q0
             lat, persist, prev = [], [], None
             layer.spin.profile_enable(steps)          # kernels bracketed by HIP events on the launch stream
-            trace = [[] for _ in range(w.rows)] if (mode == modes[-1] and not exact and not args.no_cpu) else None
+            trace = [[] for _ in range(w.rows)] if (mode == modes[-1] and not exact and not policy and not args.no_cpu) else None
             for s in range(steps):
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
@@ -143,7 +145,7 @@ def run_cfg4(args):
             layer.spin.profile_enable(0)
             overall, warm = layer.hit_rates()
             lat_w = sorted(lat[1:])
-            key = f"{mode}{'_evict_exact' if exact else ''}"
+            key = f"{mode}{'_evict_exact' if exact else ''}{'_set_assoc8' if policy else ''}"
             results[key] = dict(hit_rate=round(overall, 4), hit_rate_after_step0=round(warm, 4),
                                 misses_per_step=round(layer.stats["misses_after_first"] / (steps - 1), 1),
                                 selected_per_step=round(layer.stats["selected"] / steps, 1),

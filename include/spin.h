@@ -107,6 +107,8 @@ typedef struct spin_config {
   int32_t leaf_entries;         /* entries per second-level table chunk (512) */
   int32_t lru_timestamps;       /* 0 = all-resident mode; n > 0 = bucketed LRU with n timestamp values */
   int32_t lru_evict_exact;      /* 0 = evict whole buckets <= x; 1 = only as many pages of bucket x as needed */
+  int32_t lru_policy;           /* budget mode: 0 = bucketed LRU (Section 5.3); 1 = 8-way set-associative placement:
+                                   home set = mix32(row, page) mod (slots / 8), see spin_resolve_slots */
   int32_t decode_splits;        /* split-K factor of spin_sparse_decode; 0 = choose from the shape */
   int32_t decode_waves;         /* wavefronts per decode workgroup: 2, 4 or 8; 0 = 8 */
   int32_t decode_depth;         /* page buffers per decode wavefront (pages in flight + 1): 2, 3 or 4; 0 = choose */
@@ -250,7 +252,19 @@ int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const in
  * admitted to freed slots (ascending page id -> ascending free slot) and
  * listed in miss_pages / miss_slots (DEVICE int32 [rows][page_stride]) with
  * nmiss (DEVICE int32 [rows]) for the copy that must complete before stage 4.
- * Leaves must exist for every page range a row can select. */
+ * Leaves must exist for every page range a row can select.
+ * Budget mode with lru_policy == 1 (the budget workload's "8-way buckets hashed
+ * on (request, page)"; a convention of this library, not the paper's policy):
+ * the row's slots form slot_range[r][1] / 8 sets of 8 consecutive slots (slots
+ * past the last whole set are not used for placement); the home set of page p
+ * is mix32(r, p) mod sets with mix32(r, p) = f(r * 0x9E3779B1 + p) in 32-bit
+ * arithmetic, f(x): x ^= x >> 16; x *= 0x85EBCA6B; x ^= x >> 13; x *= 0xC2B2AE35;
+ * x ^= x >> 16.  Misses are placed as if one at a time in ascending page id:
+ * from the home set on, sets whose 8 ways all hold pages selected in this step
+ * are skipped circularly; in the set reached the lowest empty way is taken,
+ * else the way not selected in this step with the smallest timestamp (lowest
+ * way on ties) is evicted.  Timestamps and every output are as above; at most
+ * 32768 slots per row. */
 int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, const int32_t *sel,
                        const int32_t *nsel, const int32_t *seq_lens, const int32_t *dir,
                        int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev_table,

@@ -32,7 +32,7 @@ class SpinConfig(C.Structure):
         "max_batch", "num_q_heads", "num_kv_heads", "head_dim", "page_tokens", "partition_tokens",
         "score_kind", "sketch_channels", "reps_per_partition", "topk", "topk_includes_forced",
         "sink_pages", "recent_pages", "max_context", "leaf_entries", "lru_timestamps",
-        "lru_evict_exact", "decode_splits", "decode_waves", "decode_depth", "score_tiles_per_wg",
+        "lru_evict_exact", "lru_policy", "decode_splits", "decode_waves", "decode_depth", "score_tiles_per_wg",
         "score_waves", "variable_partitions")] + [("softmax_scale", C.c_float)]
 
 
@@ -111,7 +111,7 @@ class Spin:
         c = SpinConfig()
         defaults = dict(head_dim=128, page_tokens=16, partition_tokens=16, score_kind=0, sketch_channels=16,
                         reps_per_partition=4, topk_includes_forced=1, sink_pages=0, recent_pages=0,
-                        leaf_entries=512, lru_timestamps=0, lru_evict_exact=0, decode_splits=0, decode_waves=0, decode_depth=0, score_tiles_per_wg=0, score_waves=0, variable_partitions=0,
+                        leaf_entries=512, lru_timestamps=0, lru_evict_exact=0, lru_policy=0, decode_splits=0, decode_waves=0, decode_depth=0, score_tiles_per_wg=0, score_waves=0, variable_partitions=0,
                         softmax_scale=0.0)
         defaults.update(cfg)
         for k, v in defaults.items():

@@ -21,6 +21,7 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   if (tp <= 0) return SPIN_ERR_INVALID;
   if (!((tp < 16 && 16 % tp == 0) || (tp >= 16 && tp % 16 == 0))) return SPIN_ERR_UNSUPPORTED;
   if (c->lru_timestamps > 256) return SPIN_ERR_UNSUPPORTED;
+  if (c->lru_policy != 0 && c->lru_policy != 1) return SPIN_ERR_INVALID;
   if (c->decode_depth != 0 && (c->decode_depth < 2 || c->decode_depth > 4)) return SPIN_ERR_INVALID;
   if (c->variable_partitions && (tp < 16 || c->lru_timestamps > 0)) return SPIN_ERR_UNSUPPORTED;
   if (c->score_tiles_per_wg < 0 || (c->score_waves != 0 && c->score_waves != 4 && c->score_waves != 8))

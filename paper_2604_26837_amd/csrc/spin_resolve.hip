@@ -254,6 +254,233 @@ __global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_lru_kernel(
   if (tid == 0) { npages[row] = ns; nmiss[row] = tot_miss; }
 }
 
+// ---------------------------------------------------------------------------
+// Budget mode, second policy: set-associative placement (lru_policy = 1).
+//
+// The row's S slots form S / 8 sets of 8 consecutive slots; the home set of a
+// page is mix32(row, page) mod sets.  Lookups still go through the leaf entries,
+// only placement is constrained.  Misses are placed as if one at a time in
+// ascending page id: from the home set on, sets whose 8 ways all hold pages
+// selected in this step are skipped (circularly); in the set reached the lowest
+// empty way is taken, else the not-selected way with the smallest timestamp
+// (lowest way on ties).  Because an admitted page counts as selected, the i-th
+// miss to reach a set takes the i-th way of that set's order (empty ways by
+// index, then not-selected ways by timestamp and index), whatever the other
+// sets do: the kernel ranks the misses per set in parallel and falls back to
+// one lane walking the miss list only when some set receives more misses than
+// it has ways left.  Timestamps follow step 2 of the bucketed policy.
+__device__ inline uint32_t sa_mix32(uint32_t row, uint32_t page) {
+  uint32_t x = row * 0x9E3779B1u + page;
+  x ^= x >> 16;
+  x *= 0x85EBCA6Bu;
+  x ^= x >> 13;
+  x *= 0xC2B2AE35u;
+  x ^= x >> 16;
+  return x;
+}
+
+#define SA_WAYS 8
+
+__global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_sa_kernel(
+    const int32_t *__restrict__ sel, const int32_t *__restrict__ nsel, const int32_t *__restrict__ seq_lens,
+    const int32_t *__restrict__ dir, int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev,
+    const int32_t *__restrict__ slot_base, int Hkv, int sel_stride, int page_stride, int dir_stride,
+    int leaf_entries, int step, int n_ts, int max_slots_lds, int32_t *__restrict__ slots,
+    int32_t *__restrict__ page_ids, uint16_t *__restrict__ valid_mask, int32_t *__restrict__ npages,
+    int32_t *__restrict__ miss_pages, int32_t *__restrict__ miss_slots, int32_t *__restrict__ nmiss,
+    int32_t *status) {
+  extern __shared__ int32_t lds[];
+  int32_t *s_loc = lds;                                   // [page_stride] leaf entry address per selected page
+  int32_t *s_mi = lds + page_stride;                      // [page_stride] selection index of the m-th miss
+  int32_t *s_set = lds + 2 * page_stride;                 // [page_stride] home set, then set reached, then victim slot
+  int32_t *s_rank = lds + 3 * page_stride;                // [page_stride] arrival rank of the miss in its set
+  int32_t *s_cnt = lds + 4 * page_stride;                 // [max_sets] misses homed in the set / ways handed out
+  uint8_t *s_cap = (uint8_t *)(s_cnt + max_slots_lds / SA_WAYS);   // [max_sets] ways not holding a selected page
+  uint8_t *s_flag = s_cap + max_slots_lds / SA_WAYS;      // [S] 1 = holds a page selected in this step
+  __shared__ int s_wave[LRU_WAVES];
+  __shared__ int s_err;
+
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int b = row / Hkv;
+  const int N = seq_lens[b];
+  const int pages = (N + 15) >> 4;
+  int ns = nsel[row];
+  ns = ns < 0 ? 0 : (ns > sel_stride ? sel_stride : ns);
+  if (ns > page_stride) ns = page_stride;
+  const int32_t *rsel = sel + (size_t)row * sel_stride;
+  int32_t *o_slots = slots + (size_t)row * page_stride;
+  int32_t *o_pages = page_ids + (size_t)row * page_stride;
+  uint16_t *o_mask = valid_mask + (size_t)row * page_stride;
+  int32_t *o_mpages = miss_pages + (size_t)row * page_stride;
+  int32_t *o_mslots = miss_slots + (size_t)row * page_stride;
+  const int sb = slot_base[2 * row];
+  const int S = slot_base[2 * row + 1];
+  const int sets = S > 0 ? S / SA_WAYS : 0;
+  const int SU = sets * SA_WAYS;                          // slots in whole sets; the rest is never used
+  const int32_t *gdir = dir + (size_t)row * dir_stride;
+
+  if (tid == 0) s_err = 0;
+  if (S <= max_slots_lds) {
+    for (int j = tid; j < SU; j += LRU_BLOCK) s_flag[j] = 0;
+    for (int j = tid; j < sets; j += LRU_BLOCK) s_cnt[j] = 0;
+  }
+  __syncthreads();
+  if (S > max_slots_lds || sets < 1 || ns > SU) {
+    if (tid == 0) { spin_raise(status, SPIN_ERR_BUDGET); npages[row] = 0; nmiss[row] = 0; }
+    for (int i = tid; i < page_stride; i += LRU_BLOCK) { o_slots[i] = -1; o_pages[i] = -1; o_mask[i] = 0; }
+    return;
+  }
+  const int ts_star = min(step, n_ts - 1);
+
+  // (1) classification: hit when the leaf holds a slot of this row
+  for (int i = tid; i < ns; i += LRU_BLOCK) {
+    const int pg = rsel[i];
+    int loc = -1, slot = -1;
+    if (pg >= 0 && pg < pages) {
+      const int ci = pg / leaf_entries;
+      const int32_t chunk = ci < dir_stride ? gdir[ci] : -1;
+      if (chunk >= 0 && (int64_t)chunk < leaf_chunks) {
+        loc = chunk * leaf_entries + (pg - ci * leaf_entries);
+        slot = leaf_pool[loc];
+      }
+    }
+    if (loc < 0) s_err = 1;
+    if (slot >= sb && slot < sb + S) {            // resident (a slot past the last whole set can only hold a
+      if (slot < sb + SU) s_flag[slot - sb] = 1;  // page admitted before the row's slot count changed)
+    } else slot = -1;
+    s_loc[i] = loc;
+    o_slots[i] = slot;
+    o_pages[i] = pg;
+    o_mask[i] = (uint16_t)page_mask(pg, N);
+  }
+  __syncthreads();
+  if (s_err) {
+    if (tid == 0) { spin_raise(status, SPIN_ERR_NOT_RESIDENT); npages[row] = 0; nmiss[row] = 0; }
+    for (int i = tid; i < page_stride; i += LRU_BLOCK) { o_slots[i] = -1; o_pages[i] = -1; o_mask[i] = 0; }
+    return;
+  }
+
+  // (2) timestamps of the resident pages; ways left per set
+  for (int j = tid; j < SU; j += LRU_BLOCK) {
+    const int2 e = *(const int2 *)(rev + 2 * (size_t)(sb + j));
+    if (e.x < 0) continue;
+    int ts = e.y;
+    if (s_flag[j]) ts = ts_star;
+    else {
+      if (step > n_ts - 1) ts = max(ts - 1, 0);
+      ts = min(max(ts, 0), n_ts - 1);
+    }
+    if (ts != e.y) rev[2 * (size_t)(sb + j) + 1] = ts;
+  }
+  for (int st = tid; st < sets; st += LRU_BLOCK) {
+    int c = 0;
+#pragma unroll
+    for (int w = 0; w < SA_WAYS; ++w) c += s_flag[st * SA_WAYS + w];
+    s_cap[st] = (uint8_t)(SA_WAYS - c);
+  }
+
+  // (3) the misses in ascending page order (= selection order) and their home sets
+  const int pchunk = (ns + LRU_BLOCK - 1) / LRU_BLOCK;
+  const int i0 = min(tid * pchunk, ns), i1 = min(i0 + pchunk, ns);
+  int cnt = 0;
+  for (int i = i0; i < i1; ++i) cnt += (o_slots[i] < 0);
+  int tot_miss;
+  int mrank = lru_scan(cnt, s_wave, tot_miss);
+  for (int i = i0; i < i1; ++i) {
+    if (o_slots[i] >= 0) continue;
+    const int home = (int)(sa_mix32((uint32_t)row, (uint32_t)o_pages[i]) % (uint32_t)sets);
+    s_mi[mrank] = i;
+    s_set[mrank] = home;
+    atomicAdd(&s_cnt[home], 1);
+    ++mrank;
+  }
+  __syncthreads();
+  int over = 0;
+  for (int st = tid; st < sets; st += LRU_BLOCK) over |= (s_cnt[st] > (int)s_cap[st]);
+  over = __syncthreads_or(over);
+
+  if (!over) {
+    // every miss stays in its home set; rank = earlier misses with the same home
+    for (int m = tid; m < tot_miss; m += LRU_BLOCK) {
+      const int home = s_set[m];
+      int r = 0;
+      for (int k = 0; k < m; ++k) r += (s_set[k] == home);
+      s_rank[m] = r;
+    }
+  } else {
+    for (int st = tid; st < sets; st += LRU_BLOCK) s_cnt[st] = 0;
+    __syncthreads();
+    if (tid == 0) {
+      for (int m = 0; m < tot_miss; ++m) {
+        int st = s_set[m], hops = 0;
+        while (s_cnt[st] >= (int)s_cap[st] && hops < sets) { st = st + 1 == sets ? 0 : st + 1; ++hops; }
+        if (hops >= sets) { s_err = 1; st = -1; }     // cannot happen when ns <= 8 * sets
+        else s_rank[m] = s_cnt[st]++;
+        s_set[m] = st;
+      }
+    }
+  }
+  __syncthreads();
+  if (s_err) {   // keep the tables as they are
+    if (tid == 0) { spin_raise(status, SPIN_ERR_BUDGET); npages[row] = 0; nmiss[row] = 0; }
+    return;
+  }
+
+  // (4a) victim of every miss: the way whose position in its set's order equals the rank
+  for (int m = tid; m < tot_miss; m += LRU_BLOCK) {
+    const int st = s_set[m], r = s_rank[m];
+    int key[SA_WAYS], page[SA_WAYS];
+#pragma unroll
+    for (int w = 0; w < SA_WAYS; ++w) {
+      const int j = st * SA_WAYS + w;
+      const int2 e = *(const int2 *)(rev + 2 * (size_t)(sb + j));
+      page[w] = e.x;
+      key[w] = s_flag[j] ? 0x7fffffff : (e.x < 0 ? w : SA_WAYS * (1 + e.y) + w);
+    }
+    int vw = -1;
+#pragma unroll
+    for (int w = 0; w < SA_WAYS; ++w) {
+      int before = 0;
+#pragma unroll
+      for (int v = 0; v < SA_WAYS; ++v) before += (key[v] < key[w]);
+      if (key[w] != 0x7fffffff && before == r) vw = w;
+    }
+    int evicted = -1;
+#pragma unroll
+    for (int w = 0; w < SA_WAYS; ++w)
+      if (w == vw) evicted = page[w];
+    s_rank[m] = evicted;
+    s_set[m] = vw < 0 ? -1 : st * SA_WAYS + vw;
+  }
+  __syncthreads();
+
+  // (4b) eviction and admission
+  for (int m = tid; m < tot_miss; m += LRU_BLOCK) {
+    const int i = s_mi[m], j = s_set[m], old = s_rank[m];
+    if (j < 0) {                                        // cannot happen: rank < ways left in the set
+      spin_raise(status, SPIN_ERR_BUDGET);
+      o_mask[i] = 0;
+      o_mpages[m] = -1;
+      o_mslots[m] = -1;
+      continue;
+    }
+    if (old >= 0) {
+      const int ci = old / leaf_entries;
+      const int32_t ch = ci < dir_stride ? gdir[ci] : -1;
+      if (ch >= 0 && (int64_t)ch < leaf_chunks) leaf_pool[(size_t)ch * leaf_entries + (old - ci * leaf_entries)] = -1;
+    }
+    const int pg = o_pages[i];
+    *(int2 *)(rev + 2 * (size_t)(sb + j)) = make_int2(pg, ts_star);
+    leaf_pool[s_loc[i]] = sb + j;
+    o_slots[i] = sb + j;
+    o_mpages[m] = pg;
+    o_mslots[m] = sb + j;
+  }
+  for (int i = ns + tid; i < page_stride; i += LRU_BLOCK) { o_slots[i] = -1; o_pages[i] = -1; o_mask[i] = 0; }
+  for (int i = tot_miss + tid; i < page_stride; i += LRU_BLOCK) { o_mpages[i] = -1; o_mslots[i] = -1; }
+  if (tid == 0) { npages[row] = ns; nmiss[row] = tot_miss; }
+}
+
 extern "C" int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, const int32_t *sel,
                                   const int32_t *nsel, const int32_t *seq_lens, const int32_t *dir,
                                   int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev_table,
@@ -270,6 +497,18 @@ extern "C" int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, co
   if (c.lru_timestamps > 0) {
     if (!rev_table || !slot_base || !miss_pages || !miss_slots || !nmiss) return SPIN_ERR_INVALID;
     if (c.partition_tokens != 16 || c.lru_timestamps > LRU_MAX_TS || ctx->var.count) return SPIN_ERR_UNSUPPORTED;
+    if (c.lru_policy == 1) {
+      // LDS: four int32 per output entry; per set a counter and a byte; one flag byte per slot of the row
+      const int max_slots_lds = 32 * 1024;
+      const size_t lds = (size_t)ctx->page_stride * 16 + (size_t)(max_slots_lds / SA_WAYS) * 5 + max_slots_lds;
+      if (lds > 64 * 1024) return SPIN_ERR_UNSUPPORTED;
+      spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_sa_kernel, dim3((unsigned)rows), dim3(LRU_BLOCK), lds,
+                  (hipStream_t)stream, sel, nsel, seq_lens, dir, leaf_pool, leaf_chunks, rev_table, slot_base,
+                  c.num_kv_heads, ctx->sel_stride, ctx->page_stride, ctx->dir_stride, c.leaf_entries, step,
+                  c.lru_timestamps, max_slots_lds, slots, page_ids, valid_mask, npages, miss_pages, miss_slots, nmiss,
+                  (int32_t *)workspace);
+      return spin_launch_status();
+    }
     // LDS: two int32 per output entry plus one flag byte per slot of the row
     const int max_slots_lds = 48 * 1024;
     const size_t lds = (size_t)ctx->page_stride * 8 + max_slots_lds;

@@ -1,5 +1,5 @@
 """End-to-end budget mode on a small hierarchical workload: full KV in pinned
-host memory, bucketed LRU on the device, misses copied in (both copiers), then
+host memory, bucketed LRU (or the set-associative variant) on the device, misses copied in (both copiers), then
 attention.  Every step is checked against the oracle: selection on the device's
 fp32 scores, slots and miss list against the step-by-step LRU, and attention
 against fp64 attention over the LOGICAL pages -- which only holds if every
@@ -20,11 +20,13 @@ def _small():
                                  sink_pages=2, recent_pages=3, name="hier_small")
 
 
-@pytest.mark.parametrize("copy_mode,exact", [("memcpy", False), ("gather", False), ("gather", True)])
-def test_steps_match_oracle(copy_mode, exact):
+@pytest.mark.parametrize("copy_mode,exact,policy", [("memcpy", False, 0), ("gather", False, 0), ("gather", True, 0),
+                                                    ("gather", False, 1)])
+def test_steps_match_oracle(copy_mode, exact, policy):
     w = _small()
     n_ts = 6                      # small range: demotion kicks in within the trace
-    layer = hier.HierLayer(w, budget_frac=0.06, n_ts=n_ts, evict_exact=exact, copy_mode=copy_mode, keep_natural=True)
+    layer = hier.HierLayer(w, budget_frac=0.06, n_ts=n_ts, evict_exact=exact, copy_mode=copy_mode, keep_natural=True,
+                           lru_policy=policy)
     rows, g = w.rows, w.group
     caches = [lru.RowCache(layer.budgets[r]) for r in range(rows)]
     nat = [n.view(torch.int16).numpy().view(np.uint16) for n in layer.natural]      # per request [slots][2][16][D]
@@ -47,7 +49,10 @@ def test_steps_match_oracle(copy_mode, exact):
             want_sel = select.select_topk(scores[base:base + P], n, 16, 16, w.topk, True, w.sink_pages, w.recent_pages)
             assert sel[r, :nsel[r]].tolist() == want_sel
             trace[r].append(want_sel)
-            want_slots, want_miss, _ = lru.lru_step(caches[r], want_sel, step, n_ts, evict_exact=exact)
+            if policy == 1:
+                want_slots, want_miss, _ = lru.setassoc_step(caches[r], want_sel, step, n_ts, row=r)
+            else:
+                want_slots, want_miss, _ = lru.lru_step(caches[r], want_sel, step, n_ts, evict_exact=exact)
             sb = int(layer.slot_base_np[r])
             assert slots[r, :npages[r]].tolist() == [sb + s for s in want_slots], f"step {step} row {r}"
             assert mp[r, :nm[r]].tolist() == [p for p, _ in want_miss]

@@ -1,5 +1,5 @@
-"""GPU parity of budget-mode resolve (bucketed LRU) against the step-by-step
-oracle: slots of every selected page, the miss list, timestamps and the
+"""GPU parity of budget-mode resolve (bucketed LRU and the set-associative
+variant) against the step-by-step oracle: slots of every selected page, the miss list, timestamps and the
 forward/reverse tables, bit-exact, over multi-step traces."""
 import numpy as np
 import pytest
@@ -16,9 +16,10 @@ class Budget:
     """Device state of budget mode for a workload with page partitions; the
     selection of each step is fed in directly (stage 3b takes `sel` as input)."""
 
-    def __init__(self, w, budgets, n_ts, evict_exact=False):
+    def __init__(self, w, budgets, n_ts, evict_exact=False, policy=0):
         self.w = w
-        self.sp = binding.Spin.for_workload(w, lru_timestamps=n_ts, lru_evict_exact=int(evict_exact))
+        self.sp = binding.Spin.for_workload(w, lru_timestamps=n_ts, lru_evict_exact=int(evict_exact),
+                                            lru_policy=policy)
         sp = self.sp
         self.ws = sp.new_workspace(DEV)
         rows = w.rows
@@ -148,3 +149,79 @@ def test_large_row_many_slots():
         assert slots[0, :npg[0]].tolist() == want_slots
         assert mslots[0, :nmiss[0]].tolist() == [s for _, s in want_miss]
     assert bd.sp.poll_status(bd.ws) == 0
+
+
+def _check_step(bd, caches, budgets, selections, step, n_ts, out):
+    slots, npg, mpages, mslots, nmiss = out
+    rev = bd.rev.cpu().numpy()
+    hops = 0
+    for r in range(bd.w.rows):
+        want_slots, want_miss, hits = lru.setassoc_step(caches[r], selections[r], step, n_ts, row=r)
+        base = int(bd.slot_base_np[r])
+        sets = budgets[r] // 8
+        hops += sum(1 for p, s in want_miss if s // 8 != lru.mix32(r, p) % sets)
+        assert npg[r] == len(selections[r])
+        assert slots[r, :npg[r]].tolist() == [base + s for s in want_slots], f"step {step} row {r}"
+        assert nmiss[r] == len(want_miss)
+        assert mpages[r, :nmiss[r]].tolist() == [p for p, _ in want_miss]
+        assert mslots[r, :nmiss[r]].tolist() == [base + s for _, s in want_miss], f"step {step} row {r}"
+        got_pages = rev[base:base + budgets[r], 0].tolist()
+        assert got_pages == caches[r].page, f"step {step} row {r}"
+        got_ts = [t if p >= 0 else 0 for p, t in zip(got_pages, rev[base:base + budgets[r], 1].tolist())]
+        assert got_ts == [t if p >= 0 else 0 for p, t in zip(caches[r].page, caches[r].ts)]
+    return hops
+
+
+@pytest.mark.parametrize("n_ts,budget_mult,k", [(64, 3.0, 12), (4, 2.0, 12), (3, 1.0, 16), (64, 1.15, 28)])
+def test_set_associative_traces_match_oracle(n_ts, budget_mult, k):
+    w = synth.config0().with_(seq_lens=(1600, 700, 16 * 600 + 3), num_q_heads=4, num_kv_heads=2, topk=k,
+                              sink_pages=0, recent_pages=0, name="lru_sa")
+    rows = w.rows
+    pages_per_row = [w.pages(r // w.num_kv_heads) for r in range(rows)]
+    rng = np.random.default_rng(n_ts * 11 + k)
+    # budgets that are not multiples of 8 leave up to 7 slots unused
+    budgets = [max(8 * -(-k // 8), int(budget_mult * k) + r) for r in range(rows)]
+    bd = Budget(w, budgets, n_ts, policy=1)
+    caches = [lru.RowCache(budgets[r]) for r in range(rows)]
+    trace = _trace(rng, rows, pages_per_row, k, 24)
+    hops = 0
+    for step, selections in enumerate(trace):
+        out = bd.step(step, selections)
+        assert bd.sp.poll_status(bd.ws) == 0
+        hops += _check_step(bd, caches, budgets, selections, step, n_ts, out)
+        leaf = bd.leaf.cpu().numpy()
+        d = bd.dir.cpu().numpy()
+        for r in range(rows):
+            base = int(bd.slot_base_np[r])
+            fwd = {}
+            for ci in range(d.shape[1]):
+                if d[r, ci] >= 0:
+                    for i, s in enumerate(leaf[d[r, ci]]):
+                        if s >= 0:
+                            fwd[ci * w.leaf_entries + i] = int(s) - base
+            assert fwd == caches[r].where
+    if budget_mult < 1.5:
+        assert hops > 0          # tight budgets reach the probing path (one lane walks the miss list)
+
+
+def test_set_associative_large_row_and_errors():
+    w = synth.config0().with_(seq_lens=(262144,), num_q_heads=4, num_kv_heads=1, topk=128, sink_pages=4,
+                              recent_pages=8, name="lru_sa_big")
+    bd = Budget(w, [4096], 64, policy=1)
+    caches = [lru.RowCache(4096)]
+    rng = np.random.default_rng(5)
+    trace = _trace(rng, 1, [16384], 128, 30, hot_frac=0.8)
+    for step, selections in enumerate(trace):
+        out = bd.step(step, selections)
+        _check_step(bd, caches, [4096], selections, step, 64, out)
+    assert bd.sp.poll_status(bd.ws) == 0
+    # fewer whole sets than the selection needs: reported, row emptied, tables untouched
+    w2 = synth.config0().with_(seq_lens=(1600,), num_q_heads=4, num_kv_heads=2, topk=12, sink_pages=0,
+                               recent_pages=0, name="lru_sa_small")
+    bd2 = Budget(w2, [16, 15], 64, policy=1)
+    sel = [list(range(0, 24, 2)), list(range(1, 25, 2))]
+    slots, npg, _, _, nmiss = bd2.step(0, sel)
+    assert bd2.sp.poll_status(bd2.ws) == -5
+    assert npg[0] == 12 and npg[1] == 0 and nmiss[1] == 0
+    assert (slots[1] == -1).all()
+    assert (bd2.rev.cpu().numpy()[16:, 0] == -1).all()
