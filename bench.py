@@ -34,8 +34,10 @@ def parse_args():
     ap.add_argument("--cpu-rows", type=int, default=32, help="rows of the workload timed on the CPU oracle")
     ap.add_argument("--cpu-reps", type=int, default=8)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg4"],
-                    help="cfg1: the headline all-resident layer; cfg4: hierarchical HBM budget, 64 decode steps")
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "cfg3", "cfg4"],
+                    help="cfg1: the headline all-resident layer (the metric's workload); cfg2: token partitions scored "
+                         "on a key sketch; cfg3: 128-token blocks with representative keys; cfg4: hierarchical HBM "
+                         "budget, 64 decode steps")
     ap.add_argument("--copy-mode", default="both", choices=["memcpy", "gather", "both"])
     ap.add_argument("--budget-frac", type=float, default=0.25)
     ap.add_argument("--four-calls", action="store_true",
@@ -71,23 +73,31 @@ def cpu_oracle_leg(layer, natural, q_bits, rows, reps):
     g = w.group
     stride = max(1, w.rows // rows)
     picked = list(range(0, w.rows, stride))[:rows]
+    chan_all = layer.chan.cpu().numpy() if layer.chan is not None else None
     prepared = []
     for r in picked:
         b, h = divmod(r, w.num_kv_heads)
         slots = torch.from_numpy(layer.slot_of[b][h].astype(np.int64)).to(natural.device)
         pages = natural[slots].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)  # [pages][2][16][128]
         K = bf16.decode(pages[:, 0].reshape(-1, w.head_dim))
-        summ = index.minmax_summaries(K, w.seq_lens[b], w.partition_tokens)
+        chan = None
+        if w.score_kind == ostep.SCORE_MINMAX:
+            summ = index.minmax_summaries(K, w.seq_lens[b], w.partition_tokens)
+        elif w.score_kind == ostep.SCORE_REPMAX:
+            summ = index.block_representatives(K, w.seq_lens[b], w.partition_tokens, w.reps_per_partition)
+        else:
+            chan = chan_all[h]
+            summ = index.key_sketch(K, w.seq_lens[b], chan)
         page_map = {(r, pg): pg for pg in range(pages.shape[0])}      # local pool: slot == logical page
         q = bf16.decode(q_bits[b, h * g:(h + 1) * g])
-        prepared.append((r, b, h, q, summ, page_map, pages))
+        prepared.append((r, b, h, q, summ, page_map, pages, chan))
     t0 = time.perf_counter()
     results = None
     for _ in range(reps):
-        results = [ostep.decode_row(q, summ, ostep.SCORE_MINMAX, w.seq_lens[b], w.page_tokens,
+        results = [ostep.decode_row(q, summ, w.score_kind, w.seq_lens[b], w.page_tokens,
                                     w.partition_tokens, w.topk, w.topk_includes_forced, w.sink_pages,
-                                    w.recent_pages, page_map, r, pages, layer.scale)
-                   for (r, b, h, q, summ, page_map, pages) in prepared]
+                                    w.recent_pages, page_map, r, pages, layer.scale, channels=chan)
+                   for (r, b, h, q, summ, page_map, pages, chan) in prepared]
     dt = (time.perf_counter() - t0) / reps
     if limiter is not None:
         limiter.restore_original_limits() if hasattr(limiter, "restore_original_limits") else None
@@ -196,8 +206,12 @@ def main():
     if args.workload == "cfg4":
         run_cfg4(args)
         return
-    w = synth.config1()
+    w = {"cfg1": synth.config1, "cfg2": synth.config2, "cfg3": synth.config3}[args.workload]()
     layer, natural = runner.build_device_layer(w, device=dev, keep_natural=not args.no_cpu)
+    # stages 2+3 share a launch only for rows the one-launch kernel takes (at most 16384 partitions)
+    one_launch_23 = max(w.partitions(b) for b in range(w.batch)) <= 16384
+    if not one_launch_23:
+        args.four_calls = True
     sp = layer.spin
 
     # distinct query sets (seeds base+1000+i) and distinct summary copies
@@ -232,14 +246,16 @@ def main():
 
     # --- the other launch shape of the same step, for reference
     other = run_three if args.four_calls else run_four
-    for i in range(5):
-        other(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        other(i)
-    torch.cuda.synchronize()
-    us_per_step_other = (time.perf_counter() - t0) * 1e6 / args.steps
+    us_per_step_other = None
+    if one_launch_23:
+        for i in range(5):
+            other(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            other(i)
+        torch.cuda.synchronize()
+        us_per_step_other = (time.perf_counter() - t0) * 1e6 / args.steps
 
     # --- the same K steps again with every kernel bracketed by HIP events on the
     # launch stream (start/stop timestamps of the kernel itself); the bracketing
@@ -279,18 +295,22 @@ def main():
             stream_gbps = round(chunk / mean / 1e3, 1)
 
     # --- byte accounting (Eq. 1 / Eq. 2 of the paper's envelope for this workload)
-    attended_tokens = int(layer.npages.sum().item()) * w.page_tokens
+    # attended tokens = set bits of the page masks (whole pages unless partitions are smaller than a page)
+    mask_bits = layer.valid_mask.to(torch.int32) & 0xFFFF
+    in_list = torch.arange(mask_bits.shape[1], device=dev)[None, :] < layer.npages[:, None]
+    attended_tokens = int(sum(((mask_bits >> t) & 1)[in_list].sum().item() for t in range(16)))
     kv_bytes = attended_tokens * 2 * w.head_dim * 2                    # 512 B per attended token
-    score_bytes = int(layer.part_offsets_np[-1]) * w.num_kv_heads * 512
+    page_bytes = int(layer.npages.sum().item()) * 8192                 # what page-granular gathering reads
+    score_bytes = int(layer.summaries.numel())                         # summary bytes of the (padded) rows
     dec_us = kernels.get("decode", {}).get("mean_us") or None
     sc_us = kernels.get("score", {}).get("mean_us") or None
     roofline = None
     if dec_us:
         ach = kv_bytes / dec_us / 1e3                                  # GB/s
-        traffic = read_traffic(os.path.join(ROOT, "profiles", "cfg1_stage_kernels_pmc.txt"))
+        traffic = read_traffic(os.path.join(ROOT, "profiles", f"{args.workload}_stage_kernels_pmc.txt"))
         roofline = dict(bound="hbm", kernel="spin_decode_kernel", achieved=round(ach, 1), peak=PEAK_HBM_GBPS,
                         unit="GB/s", frac=round(ach / PEAK_HBM_GBPS, 4), traffic=traffic,
-                        algorithmic_bytes=kv_bytes, mean_us=dec_us)
+                        algorithmic_bytes=kv_bytes, whole_page_bytes=page_bytes, mean_us=dec_us)
 
     # --- CPU oracle on a bounded sample of the same workload, same run
     cpu = None
@@ -305,11 +325,13 @@ def main():
         page_ids = layer.page_ids.cpu().numpy()
         npages = layer.npages.cpu().numpy()
         worst, same_sel = 0.0, 0
-        for (r, b, h, q, summ, page_map, pages), res in zip(prepared, results):
+        vmask = layer.valid_mask.cpu().numpy().view(np.uint16)
+        for (r, b, h, q, summ, page_map, pages, chan), res in zip(prepared, results):
             gp = page_ids[r, :npages[r]].tolist()
-            same_sel += int(gp == res["page_ids"])
+            gm = [int(m) for m in vmask[r, :npages[r]]]
+            same_sel += int(gp == res["page_ids"] and gm == [int(m) for m in res["masks"]])
             pg = obf16.decode(pages[np.asarray(gp, dtype=np.int64)])
-            ks, vs = pg[:, 0].reshape(-1, w.head_dim), pg[:, 1].reshape(-1, w.head_dim)
+            ks, vs = oattend.gather_tokens(pg[:, 0], pg[:, 1], gm)   # the GPU's own page list and masks
             ref, _ = oattend.attend(q, ks, vs, layer.scale)
             g = w.group
             err = np.abs(out[b, h * g:(h + 1) * g] - ref) - (2e-2 + 1e-2 * np.abs(ref))
@@ -321,18 +343,20 @@ def main():
                           f"scaled by {w.rows / len(picked):.0f}; host has {os.cpu_count()} logical CPUs")
 
     line = {
-        "metric": METRIC, "value": round(us_per_step, 2), "unit": "us/layer", "n_gpus": 1,
+        "metric": METRIC if args.workload == "cfg1" else f"sparse decode µs/layer + attended-KV HBM GB/s (% peak), {w.name}",
+        "value": round(us_per_step, 2), "unit": "us/layer", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us_per_step / 1e3, 5),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "context": w.seq_lens[0], "q_heads": w.num_q_heads,
                    "kv_heads": w.num_kv_heads, "head_dim": w.head_dim, "page_tokens": w.page_tokens,
-                   "topk_pages": w.topk, "decode_splits": sp.decode_splits, "query_sets": len(qsets),
+                   "partition_tokens": w.partition_tokens, "score": ["minmax", "sketch", "repmax"][w.score_kind],
+                   "topk_partitions": w.topk, "decode_splits": sp.decode_splits, "query_sets": len(qsets),
                    "summary_copies": len(summ_copies)},
         "attended_kv_gbps": roofline["achieved"] if roofline else None,
         "attended_kv_pct_peak": round(100 * roofline["frac"], 2) if roofline else None,
         "step_launches": "four stage calls" if args.four_calls else "score, select+resolve, attention (3 launches)",
-        ("us_per_layer_three_launches" if args.four_calls else "us_per_layer_four_calls"): round(us_per_step_other, 2),
+        ("us_per_layer_three_launches" if args.four_calls else "us_per_layer_four_calls"): round(us_per_step_other, 2) if us_per_step_other else None,
         "us_per_layer_with_kernel_events": round(us_per_step_events, 2) if us_per_step_events else None,
         "kernel_us_sum": round(sum(k["mean_us"] for k in kernels.values()), 2) if kernels else None,
         "kernels": kernels,

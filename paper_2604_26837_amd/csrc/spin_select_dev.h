@@ -82,21 +82,39 @@ __device__ inline int select_reg_row(
 
   uint32_t prefix = 0;
   int remaining = kprime;
+  // Rows with many keys per thread: scores share a few exponents, so the atomics of the first
+  // digit would pile onto a handful of bins.  Instead every thread counts, in one packed
+  // register, its keys in the 8 highest digits at or below the row's largest one; the full
+  // histogram is only built when the k'-th candidate lies below them.
+  constexpr bool TOP8 = KPT >= 16 && KPT <= 255;
+  __shared__ uint32_t s_wmax[NW];
   if (kprime > 0) {
     if (tid < 256) s_hist[0][tid] = 0;
-    __syncthreads();
-#pragma unroll
-    for (int pass = 0; pass < 4; ++pass) {
-      const int shift = 24 - 8 * pass, cur = pass & 1;
+    uint32_t top_digit = 0;
+    if (TOP8) {
+      uint32_t m = 0;
 #pragma unroll
       for (int k = 0; k < KPT; ++k) {
         const int p = c0 + k;
-        if (p >= ca && p < cb && (pass == 0 || (key[k] >> (shift + 8)) == prefix))
-          atomicAdd(&s_hist[cur][(key[k] >> shift) & 255u], 1);
+        if (p >= ca && p < cb) m = max(m, key[k]);
       }
-      if (tid < 256) s_hist[cur ^ 1][tid] = 0;
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, d));
+      if (lane == 0) s_wmax[wave] = m;
+    }
+    __syncthreads();
+    if (TOP8) {
+      uint32_t m = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) m = max(m, s_wmax[w]);
+      top_digit = m >> 24;
+    }
+    // suffix scan of the 256-bin histogram `cur` by the first wavefront: digit of the
+    // remaining-th largest candidate, or -1 when the histogram holds fewer
+    auto find_digit = [&](int cur) {
       __syncthreads();
       if (wave == 0) {
+        if (lane == 0) s_digit = -1;   // after the barrier: every thread has read the previous digit
         // lane handles digits 255-4*lane .. 252-4*lane, in descending order
         int hv[4], local = 0;
 #pragma unroll
@@ -118,6 +136,48 @@ __device__ inline int select_reg_row(
         }
       }
       __syncthreads();
+    };
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass, cur = pass & 1;
+      if (TOP8 && pass == 0) {
+        unsigned long long acc = 0;                  // 8 counters of 8 bits: digit top_digit - j in byte j
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+          const int p = c0 + k;
+          const uint32_t o = top_digit - (key[k] >> 24);
+          if (p >= ca && p < cb && o < 8u) acc += 1ull << (8u * o);
+        }
+        // widen to 16-bit fields (a wavefront holds at most 64 * 255 keys of one digit) and add up
+        unsigned long long even = acc & 0x00ff00ff00ff00ffull, odd = (acc >> 8) & 0x00ff00ff00ff00ffull;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+          even += __shfl_xor(even, d);
+          odd += __shfl_xor(odd, d);
+        }
+        if (lane < 8) {
+          const unsigned long long v = (lane & 1) ? odd : even;
+          const int c = (int)((v >> (16 * (lane >> 1))) & 0xffffull);
+          if (c && (uint32_t)lane <= top_digit) atomicAdd(&s_hist[0][top_digit - lane], c);
+        }
+      } else {
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+          const int p = c0 + k;
+          if (p >= ca && p < cb && (pass == 0 || (key[k] >> (shift + 8)) == prefix))
+            atomicAdd(&s_hist[cur][(key[k] >> shift) & 255u], 1);
+        }
+      }
+      if (tid < 256) s_hist[cur ^ 1][tid] = 0;
+      find_digit(cur);
+      if (TOP8 && pass == 0 && s_digit < 0) {        // block-uniform: add the digits not counted yet
+#pragma unroll
+        for (int k = 0; k < KPT; ++k) {
+          const int p = c0 + k;
+          if (p >= ca && p < cb && top_digit - (key[k] >> 24) >= 8u) atomicAdd(&s_hist[0][key[k] >> 24], 1);
+        }
+        find_digit(0);
+      }
       prefix = (prefix << 8) | (uint32_t)s_digit;
       remaining = s_remaining;
     }

@@ -140,3 +140,65 @@ def test_config3_block_repmax_sampled_rows():
     npages = layer.npages.cpu().numpy()
     assert (npages <= 32 * 8 + 64 + 4).all() and (npages >= 32 * 8 + 64).all()
     print("cfg3 rows in the rounding band:", band)
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+def test_config4_budget_sampled_rows(policy):
+    """The hierarchical-budget workload at full size (32 ragged requests, 7.85 GiB of KV in
+    pinned host memory, 25 % of the pages as slots), as `bench.py --workload cfg4` runs it with
+    the copy kernel: over the first steps, sampled rows are checked against the oracle
+    (selection on the device's fp32 scores, replacement state and miss list bit-exact,
+    attention over the logical pages); tables of all rows stay consistent."""
+    from oracle import lru
+    from paper_2604_26837_amd import hier
+    w = synth.config4()
+    n_ts = 64
+    layer = hier.HierLayer(w, budget_frac=0.25, n_ts=n_ts, copy_mode="gather", keep_natural=True, lru_policy=policy)
+    g, hkv = w.group, w.num_kv_heads
+    longest = int(np.argmax(w.seq_lens)) * hkv
+    shortest = int(np.argmin(w.seq_lens)) * hkv + hkv - 1
+    sample = sorted({0, 13, 100, 255, longest, shortest})
+    caches = {r: lru.RowCache(layer.budgets[r]) for r in sample}
+    q = layer.q0
+    for step in range(4):
+        layer.step(q, step)
+        torch.cuda.synchronize()
+        assert layer.status() == 0
+        scores = layer.scores.cpu().numpy()
+        sel, nsel = layer.sel.cpu().numpy(), layer.nsel.cpu().numpy()
+        slots, npages = layer.slots.cpu().numpy(), layer.npages.cpu().numpy()
+        mp, ms, nm = layer.miss_pages.cpu().numpy(), layer.miss_slots.cpu().numpy(), layer.nmiss.cpu().numpy()
+        out = bf16.decode(layer.out.view(torch.int16).cpu().numpy().view(np.uint16))
+        q_bits = q.view(torch.int16).cpu().numpy().view(np.uint16)
+        assert (npages == w.topk).all() and (nm <= npages).all()
+        if step == 0:
+            assert (nm == npages).all()                   # cold start: everything misses
+        for r in sample:
+            b, h = divmod(r, hkv)
+            n, P = w.seq_lens[b], w.partitions(b)
+            base = layer.part_offsets_np[b] * hkv + h * int(layer.part_offsets_np[b + 1] - layer.part_offsets_np[b])
+            want_sel = select.select_topk(scores[base:base + P], n, 16, 16, w.topk, True, w.sink_pages, w.recent_pages)
+            assert sel[r, :nsel[r]].tolist() == want_sel, f"step {step} row {r}"
+            if policy == 1:
+                want_slots, want_miss, _ = lru.setassoc_step(caches[r], want_sel, step, n_ts, row=r)
+            else:
+                want_slots, want_miss, _ = lru.lru_step(caches[r], want_sel, step, n_ts)
+            sb = int(layer.slot_base_np[r])
+            assert slots[r, :npages[r]].tolist() == [sb + s for s in want_slots], f"step {step} row {r}"
+            assert mp[r, :nm[r]].tolist() == [p for p, _ in want_miss]
+            assert ms[r, :nm[r]].tolist() == [sb + s for _, s in want_miss]
+            nat = layer.natural[b].view(torch.int16).numpy().view(np.uint16)
+            pages = bf16.decode(nat[layer.natural_slot_of[b][h][np.asarray(want_sel, dtype=np.int64)]])
+            masks = [(1 << min(16, n - 16 * p)) - 1 for p in want_sel]
+            ks, vs = attend.gather_tokens(pages[:, 0], pages[:, 1], masks)
+            ref, _ = attend.attend(bf16.decode(q_bits[b, h * g:(h + 1) * g]), ks, vs, layer.scale)
+            o = out[b, h * g:(h + 1) * g]
+            assert np.all(np.abs(o - ref) <= ATOL + RTOL * np.abs(ref)), f"step {step} row {r}"
+        q = torch.from_numpy(synth.next_query_ar1(q_bits, 0.9, w.seed + 7000 + step).view(np.int16)).to(q.device).view(torch.bfloat16)
+    # every row: the reverse table holds each page at most once, inside the row's own slot range
+    rev = layer.rev.cpu().numpy()
+    for r in range(0, w.rows, 7):
+        sb, cnt = int(layer.slot_base_np[r]), layer.budgets[r]
+        held = rev[sb:sb + cnt, 0]
+        held = held[held >= 0]
+        assert len(np.unique(held)) == len(held) and (held < w.pages(r // hkv)).all()

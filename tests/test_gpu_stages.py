@@ -244,6 +244,25 @@ def test_select_large_rows_token_partitions():
     _check_select(w2, [rng.standard_normal(16384).astype(np.float32)])
 
 
+def test_select_wide_dynamic_range_rows():
+    """Rows whose k'-th candidate lies many exponents below the largest score (the first radix
+    digit cannot be settled from the highest few digits), on every register variant's row size."""
+    base = synth.config0().with_(num_q_heads=4, num_kv_heads=1)
+    rng = np.random.default_rng(21)
+    for n, tp, topk in [(65536, 1, 1024), (12000, 1, 900), (3000 * 16, 16, 200), (300 * 16, 16, 64)]:
+        w = base.with_(seq_lens=(n,) * 5, partition_tokens=tp, topk=topk, sink_pages=1, recent_pages=1,
+                       score_kind=synth.SCORE_SKETCH if tp == 1 else synth.SCORE_MINMAX, name="wide")
+        P = w.partitions(0)
+        spread = (rng.choice([-1.0, 1.0], size=P) * np.exp2(rng.uniform(-100, 100, size=P))).astype(np.float32)
+        few_huge = rng.standard_normal(P).astype(np.float32)
+        few_huge[rng.choice(P, size=topk // 3, replace=False)] = 1e30      # k' reaches far below the top digit
+        negative = -np.exp2(rng.uniform(-20, 60, size=P)).astype(np.float32)
+        one_spike = np.full(P, 1e-20, dtype=np.float32)
+        one_spike[P // 2] = 3e38
+        exact_top8 = np.exp2(rng.integers(0, 16, size=P).astype(np.float64) * 2.0).astype(np.float32)  # 8 digits
+        _check_select(w, [spread, few_huge, negative, one_spike, exact_top8])
+
+
 def test_select_rows_beyond_the_register_variants():
     """Rows of more than 65536 partitions take the kernel that re-reads the scores per pass."""
     base = synth.config0().with_(num_q_heads=4, num_kv_heads=1)
