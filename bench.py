@@ -270,7 +270,7 @@ def main():
             run(i)
         torch.cuda.synchronize()
         us_per_step_events = (time.perf_counter() - t0) * 1e6 / args.steps
-        for name in ("score", "select", "resolve", "decode"):
+        for name in ("score", "select_hist", "select", "resolve", "decode"):
             n, mean, mn = sp.profile_read(name)
             if n:
                 label = "select+resolve" if (name == "select" and not args.four_calls) else name

@@ -151,7 +151,8 @@ int spin_poll_status(spin_ctx *ctx, const void *workspace, void *stream);
  * releases the events.  Not for concurrent use with stage calls. */
 enum spin_kernel_id {
   SPIN_K_SCORE = 0, SPIN_K_SELECT = 1, SPIN_K_RESOLVE = 2, SPIN_K_DECODE = 3, SPIN_K_MERGE = 4,
-  SPIN_K_INDEX = 5, SPIN_K_PACK = 6, SPIN_K_GATHER = 7, SPIN_K_PROBE = 8
+  SPIN_K_INDEX = 5, SPIN_K_PACK = 6, SPIN_K_GATHER = 7, SPIN_K_PROBE = 8,
+  SPIN_K_SELECT_HIST = 9 /* first launch of stage 2 for rows of more than 16384 partitions */
 };
 int spin_profile_enable(spin_ctx *ctx, int32_t capacity);
 int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_us, float *min_us);
@@ -232,7 +233,10 @@ int spin_score_partitions(spin_ctx *ctx, int32_t batch, const void *q, const voi
  * recent pages) plus the k' best-scoring other partitions, k' = topk - forced
  * (topk_includes_forced) or topk; ties go to the lower id, +0 and -0 tie, NaN
  * ranks lowest.  sel (DEVICE int32 [rows][sel_stride]) ascending, padded with
- * -1; nsel (DEVICE int32 [rows]). */
+ * -1; nsel (DEVICE int32 [rows]).  Contexts configured for rows of 16385 to
+ * 131072 partitions run two launches (a histogram of the leading key bits kept
+ * in `workspace`, then the selection); the workspace must have been cleared by
+ * spin_workspace_init once and is left cleared. */
 int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
                      const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace,
                      void *stream);

@@ -97,6 +97,11 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   x->ws_ticket_off = off;                       // one arrival counter per row, zero between launches
   off += (size_t)x->max_rows * sizeof(int32_t);
   off = (off + 255) & ~(size_t)255;
+  // stage 2 of long rows: 4096 counters per row, zero between launches
+  if (x->max_parts > 16384 && x->max_parts <= 131072 && !c->variable_partitions) {
+    x->ws_hist_off = off;
+    off += (size_t)x->max_rows * 4096 * sizeof(int32_t);
+  }
   x->ws_zero_bytes = off;
   x->ws_ml_off = off;
   off += (size_t)x->max_rows * splits * group * 2 * sizeof(float);

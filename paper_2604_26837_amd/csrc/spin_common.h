@@ -13,7 +13,7 @@
 #define SPIN_KTILE_U4 256     // 4096-byte K tile in 16-byte units
 #define SPIN_WS_HEADER 256    // bytes reserved in front of the workspace (status word)
 
-#define SPIN_KERNEL_IDS 9
+#define SPIN_KERNEL_IDS 10
 
 // Variable-length partitions (Section 5.2: the Meta-partition table holds each
 // partition's token count, the Partition Offset table where its page list
@@ -45,6 +45,7 @@ struct spin_ctx {
   float scale;
   size_t ws_bytes;
   size_t ws_ticket_off, ws_ml_off, ws_acc_off;
+  size_t ws_hist_off;     // per-row first-digit histograms of stage 2 for long rows; 0 = not used
   size_t ws_zero_bytes;   // leading part of the workspace that spin_workspace_init clears
   spin_var var;           // registered partition tables (all NULL: uniform partitions)
   // optional per-kernel timing: pairs of HIP events handed to the launches

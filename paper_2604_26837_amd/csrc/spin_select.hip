@@ -12,9 +12,9 @@
 #include "spin_select_dev.h"
 
 #define SEL_BLOCK 512
-#define SEL_WAVES (SEL_BLOCK / 64)
 
 // exclusive prefix sum of one int per thread over the workgroup, plus the total
+template <int BLOCK>
 __device__ inline int block_exclusive_scan(int v, int *s_wave, int &total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int inc = v;
@@ -28,7 +28,7 @@ __device__ inline int block_exclusive_scan(int v, int *s_wave, int &total) {
   __syncthreads();
   int off = 0, tot = 0;
 #pragma unroll
-  for (int w = 0; w < SEL_WAVES; ++w) {
+  for (int w = 0; w < BLOCK / 64; ++w) {
     const int x = s_wave[w];
     if (w < wave) off += x;
     tot += x;
@@ -37,15 +37,16 @@ __device__ inline int block_exclusive_scan(int v, int *s_wave, int &total) {
   return off + inc - v;
 }
 
-__global__ __launch_bounds__(SEL_BLOCK) void spin_select_kernel(
+// Rows of any length: every pass re-reads the row's scores.
+template <int BLOCK>
+__device__ inline void select_generic_row(
     const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
-    int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel) {
+    int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel, int row) {
   __shared__ int s_hist[256];
-  __shared__ int s_wave[SEL_WAVES];
+  __shared__ int s_wave[BLOCK / 64];
   __shared__ int s_digit, s_remaining;
 
-  const int row = blockIdx.x;
   const int b = row / Hkv, h = row - b * Hkv;
   const int N = seq_lens[b];
   const int PP = part_offsets[b + 1] - part_offsets[b];
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(SEL_BLOCK) void spin_select_kernel(
   }
 
   // contiguous chunk of partitions per thread
-  int chunk = (P + SEL_BLOCK - 1) / SEL_BLOCK;
+  int chunk = (P + BLOCK - 1) / BLOCK;
   chunk = (chunk + 3) & ~3;
   const int c0 = min(tid * chunk, P), c1 = min(c0 + chunk, P);
 
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(SEL_BLOCK) void spin_select_kernel(
       __syncthreads();
       // suffix sums over digits: thread t looks at digit 255 - t
       int cnt = tid < 256 ? s_hist[255 - tid] : 0, total;
-      const int excl = block_exclusive_scan(cnt, s_wave, total);
+      const int excl = block_exclusive_scan<BLOCK>(cnt, s_wave, total);
       if (tid < 256 && excl < remaining && excl + cnt >= remaining) {
         s_digit = 255 - tid;
         s_remaining = remaining - excl;
@@ -117,9 +118,9 @@ __global__ __launch_bounds__(SEL_BLOCK) void spin_select_kernel(
     my_eq += k == T;
   }
   int total_eq, total_sel;
-  const int eq_before = block_exclusive_scan(my_eq, s_wave, total_eq);
+  const int eq_before = block_exclusive_scan<BLOCK>(my_eq, s_wave, total_eq);
   int eq_quota = min(max(need_eq - eq_before, 0), my_eq);
-  const int pos0 = block_exclusive_scan(my_gt + eq_quota, s_wave, total_sel);
+  const int pos0 = block_exclusive_scan<BLOCK>(my_gt + eq_quota, s_wave, total_sel);
   int pos = pos0;
   for (int p = c0; p < c1; ++p) {
     bool pick;
@@ -132,8 +133,16 @@ __global__ __launch_bounds__(SEL_BLOCK) void spin_select_kernel(
     }
     if (pick && pos < sel_stride) rsel[pos++] = p;
   }
-  for (int i = take + tid; i < sel_stride; i += SEL_BLOCK) rsel[i] = -1;
+  for (int i = take + tid; i < sel_stride; i += BLOCK) rsel[i] = -1;
   if (tid == 0) nsel[row] = min(total_sel, sel_stride);
+}
+
+__global__ __launch_bounds__(SEL_BLOCK) void spin_select_kernel(
+    const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
+    const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
+    int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel) {
+  select_generic_row<SEL_BLOCK>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced, sink_pages,
+                                recent_pages, sel_stride, sel, nsel, (int)blockIdx.x);
 }
 
 template <int BLOCK, int KPT>
@@ -145,13 +154,279 @@ __global__ __launch_bounds__(BLOCK) void spin_select_reg_kernel(
                                           recent_pages, sel_stride, sel, nsel, (int)blockIdx.x, var);
 }
 
+// ---------------------------------------------------------------------------
+// Long rows (more than 16384 partitions, e.g. token partitions of a 64K context).
+//
+// A single workgroup spends most of its time walking a long row several times,
+// so the first digit is settled by the whole chip instead: a first launch, many
+// workgroups per row, histograms the top 12 key bits of the candidates into the
+// workspace.  The second launch, one workgroup per row, finds the bin D of the
+// k'-th candidate from it, walks the row ONCE (coalesced, order does not
+// matter): partitions above bin D and forced partitions set their bit in an LDS
+// bitmap, the few keys inside bin D go to an LDS list, where three short radix
+// passes over the remaining 20 bits find the threshold key T.  List entries
+// above T join the bitmap, entries equal to T a second bitmap; one ordered walk
+// over both emits the indices ascending, taking the lowest-index ties first.
+// A row whose bin D does not fit the list (heavy ties) falls back, inside the
+// same launch, to the multi-pass algorithms above; the results are the same.
+#define BIG_BINS 4096
+#define BIG_CHUNK 8192
+#define BIG_BLOCK 1024
+#define BIG_CAP 3072
+
+struct sel_plan {
+  int P, nf_lo, first_hi, kprime, take;
+};
+
+// forced prefix / suffix and k' of a row of uniform partitions (same rules as select_reg_row)
+__device__ inline sel_plan select_plan(int N, int PP, int tp, int topk, int includes_forced, int sink_pages,
+                                       int recent_pages, int sel_stride) {
+  sel_plan pl;
+  int P = N > 0 ? (N + tp - 1) / tp : 0;
+  if (P > PP) P = PP;
+  const int pages = (N + 15) >> 4;
+  int sink_end = min(sink_pages, pages);
+  int recent_begin = max(pages - recent_pages, 0);
+  if (sink_end >= recent_begin) { sink_end = pages; recent_begin = pages; }
+  int nf_lo = (N <= sink_end * 16) ? P : min((sink_end * 16) / tp, P);
+  int first_hi = min((recent_begin * 16 + tp - 1) / tp, P);
+  if (first_hi <= nf_lo) { nf_lo = P; first_hi = P; }
+  const int nforced = nf_lo + (P - first_hi);
+  int kprime = includes_forced ? max(topk - nforced, 0) : topk;
+  kprime = min(kprime, P - nforced);
+  int take = nforced + kprime;
+  if (take > sel_stride) {
+    kprime = max(sel_stride - nforced, 0);
+    take = min(nforced + kprime, sel_stride);
+  }
+  pl.P = P; pl.nf_lo = nf_lo; pl.first_hi = first_hi; pl.kprime = kprime; pl.take = take;
+  return pl;
+}
+
+__global__ __launch_bounds__(256) void spin_select_hist_kernel(
+    const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
+    const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
+    int recent_pages, int sel_stride, int32_t *__restrict__ hist) {
+  __shared__ int s_h[BIG_BINS];
+  const int row = blockIdx.y, tid = threadIdx.x;
+  const int b = row / Hkv, h = row - b * Hkv;
+  const int PP = part_offsets[b + 1] - part_offsets[b];
+  const float *rs = scores + (size_t)Hkv * part_offsets[b] + (size_t)h * PP;
+  const sel_plan pl = select_plan(seq_lens[b], PP, tp, topk, includes_forced, sink_pages, recent_pages, sel_stride);
+  const int lo = max((int)blockIdx.x * BIG_CHUNK, pl.nf_lo);
+  const int hi = min(((int)blockIdx.x + 1) * BIG_CHUNK, pl.first_hi);
+  if (lo >= hi || pl.kprime == 0) return;
+  for (int i = tid; i < BIG_BINS; i += 256) s_h[i] = 0;
+  __syncthreads();
+  // the chunk's 8192 scores as 8 aligned 16-byte loads per thread, all issued before the first use
+  // (rows are padded to a multiple of 16 partitions, so a load never leaves the row)
+  float4 f[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int p4 = (int)blockIdx.x * BIG_CHUNK + (i * 256 + tid) * 4;
+    f[i] = p4 < PP ? *(const float4 *)(rs + p4) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int p4 = (int)blockIdx.x * BIG_CHUNK + (i * 256 + tid) * 4;
+    const float v[4] = {f[i].x, f[i].y, f[i].z, f[i].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (p4 + e >= lo && p4 + e < hi) atomicAdd(&s_h[score_key(v[e]) >> 20], 1);
+  }
+  __syncthreads();
+  for (int i = tid; i < BIG_BINS; i += 256) {
+    const int c = s_h[i];
+    if (c) atomicAdd(&hist[(size_t)row * BIG_BINS + i], c);
+  }
+}
+
+__global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
+    const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
+    const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
+    int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel, int32_t *hist,
+    int words_max) {
+  extern __shared__ uint32_t s_dyn[];
+  uint32_t *s_main = s_dyn;                              // [words_max] bit p: partition p is selected
+  uint32_t *s_eq = s_dyn + words_max;                    // [words_max] bit p: candidate p has the threshold key
+  uint2 *s_list = (uint2 *)(s_dyn + 2 * words_max);      // [BIG_CAP] {key, partition} of the keys in bin D
+  __shared__ int s_wave[BIG_BLOCK / 64];
+  __shared__ unsigned long long s_wtot[BIG_BLOCK / 64];
+  __shared__ int s_h[256];
+  __shared__ int s_D, s_r, s_cntD, s_n, s_digit, s_remaining;
+
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = row / Hkv, h = row - b * Hkv;
+  const int PP = part_offsets[b + 1] - part_offsets[b];
+  const float *rs = scores + (size_t)Hkv * part_offsets[b] + (size_t)h * PP;
+  int32_t *rsel = sel + (size_t)row * sel_stride;
+  const sel_plan pl = select_plan(seq_lens[b], PP, tp, topk, includes_forced, sink_pages, recent_pages, sel_stride);
+  const int P = pl.P, kprime = pl.kprime;
+  const int W = (P + 31) >> 5;
+
+  // bin of the k'-th candidate: thread t owns bins 4095-4t .. 4092-4t, highest first
+  int hv[4], local = 0;
+  int32_t *rh = hist + (size_t)row * BIG_BINS;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    hv[j] = rh[BIG_BINS - 1 - 4 * tid - j];
+    rh[BIG_BINS - 1 - 4 * tid - j] = 0;                  // ready for the next launch
+    local += hv[j];
+  }
+  if (tid == 0) { s_D = BIG_BINS; s_r = 0; s_cntD = 0; s_n = 0; }
+  int total;
+  int running = block_exclusive_scan<BIG_BLOCK>(local, s_wave, total);   // its barriers order the lines above
+  if (kprime > 0) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (running < kprime && running + hv[j] >= kprime) {
+        s_D = BIG_BINS - 1 - 4 * tid - j;
+        s_r = kprime - running;
+        s_cntD = hv[j];
+      }
+      running += hv[j];
+    }
+  }
+  __syncthreads();
+  const int D = s_D;
+  if (kprime > 0 && (D == BIG_BINS || s_cntD > BIG_CAP || W > words_max)) {
+    // heavy ties in the threshold bin (or a histogram that does not cover the row): multi-pass algorithms
+    if (P <= BIG_BLOCK * 64) {
+      spin_var none = {};
+      (void)select_reg_row<BIG_BLOCK, 64, false>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced, sink_pages,
+                                                 recent_pages, sel_stride, sel, nsel, row, none);
+    } else {
+      select_generic_row<BIG_BLOCK>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced, sink_pages,
+                                    recent_pages, sel_stride, sel, nsel, row);
+    }
+    return;
+  }
+
+  for (int i = tid; i < W; i += BIG_BLOCK) { s_main[i] = 0; s_eq[i] = 0; }
+  __syncthreads();
+
+  // one walk over the row: 16-byte loads, eight per thread in flight
+  for (int base = 0; base < P; base += BIG_BLOCK * 32) {
+    float4 f[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int p4 = base + (i * BIG_BLOCK + tid) * 4;
+      f[i] = p4 < PP ? *(const float4 *)(rs + p4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int p4 = base + (i * BIG_BLOCK + tid) * 4;
+      const float v[4] = {f[i].x, f[i].y, f[i].z, f[i].w};
+      uint32_t bits = 0;                                 // this thread's four partitions: selected so far
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int p = p4 + e;
+        if (p >= P) continue;
+        if (p < pl.nf_lo || p >= pl.first_hi) bits |= 1u << e;
+        else if (kprime > 0) {
+          const uint32_t key = score_key(v[e]);
+          const int bin = (int)(key >> 20);
+          if (bin > D) bits |= 1u << e;
+          else if (bin == D) {
+            const int pos = atomicAdd(&s_n, 1);
+            if (pos < BIG_CAP) s_list[pos] = make_uint2(key, (uint32_t)p);
+          }
+        }
+      }
+      if (bits) atomicOr(&s_main[p4 >> 5], bits << (p4 & 31));   // p4 is a multiple of 4: the bits stay in one word
+    }
+  }
+  __syncthreads();
+  const int n = min(s_n, BIG_CAP);
+
+  // threshold key among the list: digits of 8, 8 and 4 bits below the 12 settled ones
+  uint32_t low = 0;                 // settled bits below bit 20, right-aligned
+  int remaining = s_r;
+  if (kprime > 0) {
+#pragma unroll
+    for (int pass = 0; pass < 3; ++pass) {
+      const int shift = pass == 0 ? 12 : (pass == 1 ? 4 : 0);
+      const int width = pass == 2 ? 4 : 8;
+      if (tid < 256) s_h[tid] = 0;
+      __syncthreads();
+      for (int i = tid; i < n; i += BIG_BLOCK) {
+        const uint32_t k20 = s_list[i].x & 0xfffffu;
+        if (pass == 0 || (k20 >> (shift + width)) == low) atomicAdd(&s_h[(k20 >> shift) & ((1u << width) - 1u)], 1);
+      }
+      __syncthreads();
+      if (wave == 0) {
+        int v4[4], loc = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { v4[j] = s_h[255 - 4 * lane - j]; loc += v4[j]; }
+        int inc = loc;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+          const int o = __shfl_up(inc, d);
+          if (lane >= d) inc += o;
+        }
+        int run = inc - loc;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (run < remaining && run + v4[j] >= remaining) {
+            s_digit = 255 - 4 * lane - j;
+            s_remaining = remaining - run;
+          }
+          run += v4[j];
+        }
+      }
+      __syncthreads();
+      low = (low << width) | (uint32_t)s_digit;
+      remaining = s_remaining;
+    }
+  }
+  const uint32_t T = ((uint32_t)D << 20) | low;
+  const unsigned need_eq = kprime > 0 ? (unsigned)remaining : 0u;
+  for (int i = tid; i < n; i += BIG_BLOCK) {
+    const uint2 e = s_list[i];
+    if (e.x > T) atomicOr(&s_main[e.y >> 5], 1u << (e.y & 31));
+    else if (e.x == T) atomicOr(&s_eq[e.y >> 5], 1u << (e.y & 31));
+  }
+  __syncthreads();
+
+  // ordered emission: thread t owns the words [t * wpt, (t + 1) * wpt)
+  const int wpt = (W + BIG_BLOCK - 1) / BIG_BLOCK;
+  const int w0 = min(tid * wpt, W), w1 = min(w0 + wpt, W);
+  unsigned long long mine = 0;
+  for (int w = w0; w < w1; ++w) mine += (unsigned long long)__popc(s_main[w]) + ((unsigned long long)__popc(s_eq[w]) << 32);
+  unsigned long long inc = mine;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const unsigned long long o = __shfl_up(inc, d);
+    if (lane >= d) inc += o;
+  }
+  if (lane == 63) s_wtot[wave] = inc;
+  __syncthreads();
+  unsigned long long before = inc - mine;
+  for (int w = 0; w < wave; ++w) before += s_wtot[w];
+  const unsigned main_before = (unsigned)(before & 0xffffffffull), eq_before = (unsigned)(before >> 32);
+  unsigned eq_quota = need_eq > eq_before ? need_eq - eq_before : 0u;
+  int pos = (int)(main_before + min(eq_before, need_eq));
+  for (int w = w0; w < w1; ++w) {
+    const uint32_t m = s_main[w], e = s_eq[w];
+    uint32_t both = m | e;
+    while (both) {
+      const int bit = __ffs(both) - 1;
+      both &= both - 1;
+      bool pick = (m >> bit) & 1u;
+      if (!pick && eq_quota > 0) { pick = true; --eq_quota; }
+      if (pick && pos < sel_stride) rsel[pos++] = w * 32 + bit;
+    }
+  }
+  for (int i = pl.take + tid; i < sel_stride; i += BIG_BLOCK) rsel[i] = -1;
+  if (tid == 0) nsel[row] = pl.take;
+}
+
 extern "C" int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
                                 const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace,
                                 void *stream) {
   if (!ctx || batch < 0 || batch > ctx->cfg.max_batch) return SPIN_ERR_INVALID;
   if (batch == 0) return SPIN_OK;
   if (!scores || !part_offsets || !seq_lens || !sel || !nsel) return SPIN_ERR_INVALID;
-  (void)workspace;
   const spin_config &c = ctx->cfg;
   const int rows = batch * c.num_kv_heads;
 #define SPIN_SELECT_ARGS                                                                                      \
@@ -164,7 +439,19 @@ extern "C" int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *score
   else if (ctx->max_parts <= 16384)
     spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<1024, 16>, dim3((unsigned)rows), dim3(1024),
                 SPIN_SELECT_ARGS, ctx->var);
-  else if (ctx->max_parts <= 65536)
+  else if (ctx->ws_hist_off && workspace) {
+    // two launches: histogram of the first 12 key bits by many workgroups per row, then one workgroup per row
+    int32_t *hist = (int32_t *)((char *)workspace + ctx->ws_hist_off);
+    const int words_max = ((ctx->max_parts + 63) / 64) * 2;
+    const size_t lds = (size_t)words_max * 8 + (size_t)BIG_CAP * 8;
+    spin_launch(ctx, SPIN_K_SELECT_HIST, spin_select_hist_kernel,
+                dim3((unsigned)((ctx->max_parts + BIG_CHUNK - 1) / BIG_CHUNK), (unsigned)rows), dim3(256), 0,
+                (hipStream_t)stream, scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk,
+                c.topk_includes_forced, c.sink_pages, c.recent_pages, ctx->sel_stride, hist);
+    spin_launch(ctx, SPIN_K_SELECT, spin_select_big_kernel, dim3((unsigned)rows), dim3(BIG_BLOCK), lds, (hipStream_t)stream,
+                scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk, c.topk_includes_forced,
+                c.sink_pages, c.recent_pages, ctx->sel_stride, sel, nsel, hist, words_max);
+  } else if (ctx->max_parts <= 65536)
     spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<1024, 64>, dim3((unsigned)rows), dim3(1024),
                 SPIN_SELECT_ARGS, ctx->var);
   else if (ctx->var.count)

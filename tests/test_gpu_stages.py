@@ -261,16 +261,29 @@ def test_select_wide_dynamic_range_rows():
         one_spike[P // 2] = 3e38
         exact_top8 = np.exp2(rng.integers(0, 16, size=P).astype(np.float64) * 2.0).astype(np.float32)  # 8 digits
         _check_select(w, [spread, few_huge, negative, one_spike, exact_top8])
+        # several candidates share the threshold key while its leading-bits bin stays small
+        tied = (np.round(rng.standard_normal(P) * 4 * 64) / 64).astype(np.float32)
+        tied_neg = (-np.abs(tied) - 1.0).astype(np.float32)
+        smooth = (rng.standard_normal(P) * 4).astype(np.float32)
+        _check_select(w, [tied, tied_neg, smooth, -smooth, tied])
 
 
 def test_select_rows_beyond_the_register_variants():
-    """Rows of more than 65536 partitions take the kernel that re-reads the scores per pass."""
+    """Rows of more than 65536 partitions: the long-row kernels, their fall-back that re-reads the
+    scores per pass, and that kernel on its own for rows beyond 131072 partitions."""
     base = synth.config0().with_(num_q_heads=4, num_kv_heads=1)
     rng = np.random.default_rng(12)
     w = base.with_(seq_lens=(100000, 70001), partition_tokens=1, topk=500, sink_pages=1, recent_pages=2,
                    score_kind=synth.SCORE_SKETCH, name="huge_tokens")
     rows = [np.round(rng.standard_normal(n) * 20).astype(np.float32) / 20 for n in w.seq_lens]
     _check_select(w, rows)
+    # smooth scores: the threshold bin is small, so the long-row kernels do not fall back
+    _check_select(w, [(rng.standard_normal(n) * 3).astype(np.float32) for n in w.seq_lens])
+    _check_select(w, [(np.round(rng.standard_normal(n) * 3 * 128) / 128).astype(np.float32) for n in w.seq_lens])
+    # past the long-row kernels' range (131072 partitions): every pass re-reads the scores
+    w3 = base.with_(seq_lens=(140000,), partition_tokens=1, topk=700, sink_pages=2, recent_pages=1,
+                    score_kind=synth.SCORE_SKETCH, name="huge_tokens2")
+    _check_select(w3, [rng.standard_normal(140000).astype(np.float32)])
 
 
 def test_resolve_reports_missing_leaf_and_missing_slot():
