@@ -3,7 +3,7 @@
 //
 // Each score kind is a contraction of a summary row with a query-derived
 // vector, so a tile of 16 summary rows is one matrix-core tile
-// S[row][head] = sum_k A[row][k] * B[k][head]:
+// S[head][row] = sum_k Q[head][k] * A[row][k]:
 //   MINMAX  sum_d max(q*min, q*max) = sum_d ( max(q,0)*max_d + min(q,0)*min_d ),
 //           i.e. the row [max | min] (256 elements) against [q+ | q-]; one of the
 //           two products per channel is exactly zero, so nothing is added that
@@ -12,9 +12,10 @@
 //           maximum over the partition's 4 rows.
 //   SKETCH  16 sketched channels, 1 x (16x16x16).
 // bf16 x bf16 products are exact in fp32; accumulation is fp32 inside the
-// matrix core.  The group's heads (columns) are reduced by a maximum with two
-// to four DPP exchanges.  Summary tiles are stored chunk-major so each load is
-// a contiguous wavefront transaction.
+// matrix core.  The queries are the first operand, so a lane holds one summary
+// row's values for four heads and the maximum over the group's heads needs no
+// exchange for groups of up to four heads (two otherwise).  Summary tiles are
+// stored chunk-major so each load is a contiguous wavefront transaction.
 #include "spin_score_dev.h"
 
 #define SCORE_WAVES 4
@@ -44,7 +45,7 @@ __global__ __launch_bounds__(SCORE_WAVES * 64) void spin_score_sketch_kernel(
   const int n = lane & 15, c = lane >> 4;
   const size_t base = (size_t)Hkv * part_offsets[b] + (size_t)h * PP;
 
-  // B operand: column n = head, k = sketched channels 4c..4c+3
+  // A operand: row n = head, k = sketched channels 4c..4c+3
   spin_s16x4 qf;
   {
     const uint16_t *qrow = q + ((size_t)(b * Hq + h * G + (n < G ? n : 0))) * SPIN_HEAD_DIM;
@@ -64,12 +65,9 @@ __global__ __launch_bounds__(SCORE_WAVES * 64) void spin_score_sketch_kernel(
     for (int u = 0; u < U; ++u) {
       if (t0 + u >= t_end) break;
       spin_f32x4 s = {0.f, 0.f, 0.f, 0.f};
-      s = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(spin_s16x4, a[u]), qf, s, 0, 0, 0);
-      float v[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) v[i] = spin_row16_max(n < G ? s[i] : -__builtin_inff());
-      if (n == 0)
-        *(float4 *)(scores + base + (size_t)(t0 + u) * 16 + 4 * c) = make_float4(v[0], v[1], v[2], v[3]);
+      s = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(qf, __builtin_bit_cast(spin_s16x4, a[u]), s, 0, 0, 0);
+      const float m = spin_head_max(s, c, G);   // lane (n, c): heads 4c+i of token n
+      if (c == 0) scores[base + (size_t)(t0 + u) * 16 + n] = m;
     }
   }
 }

@@ -24,33 +24,44 @@ __device__ inline void load_tile(score_tile<NJ> &r, const uint4 *__restrict__ tp
   for (int j = 0; j < NJ; ++j) r.a[j] = spin_nt_load(tp + j * 64 + lane);
 }
 
+// maximum over the heads of the group of a 16 x 16 tile S[head][column] held as lane (n, c):
+// S[4c+i][n]; the result is valid in every lane
+__device__ inline float spin_head_max(const spin_f32x4 &s, int c, int G) {
+  float m = -__builtin_inff();
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (4 * c + i < G) m = fmaxf(m, s[i]);
+  if (G > 4) {
+    m = fmaxf(m, __shfl_xor(m, 16));
+    m = fmaxf(m, __shfl_xor(m, 32));
+  }
+  return m;
+}
+
 template <int NJ, bool MINMAX, bool COH>
 __device__ inline void consume_tile(const score_tile<NJ> &r, const spin_bf16x8 (&qf)[NJ], int n, int c, int G,
                                     float *__restrict__ scores, size_t base, int t) {
+  // the queries are the A operand, the summary rows the B operand: lane (n, c) ends up with
+  // S[head 4c+i][summary row n], so the maximum over the group's heads stays inside the lane
+  // (plus two exchanges between the lane quarters when the group has more than 4 heads)
   spin_f32x4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int j = 0; j < NJ; ++j)
-    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(spin_bf16x8, r.a[j]), qf[j], s, 0, 0, 0);
-  // s[i] = value of summary row 4c+i for head n
-  float v[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) v[i] = spin_row16_max(n < G ? s[i] : -__builtin_inff());
+    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[j], __builtin_bit_cast(spin_bf16x8, r.a[j]), s, 0, 0, 0);
+  float m = spin_head_max(s, c, G);
   if (MINMAX) {
-    if (n == 0) {
-      float *o = scores + base + (size_t)t * 16 + 4 * c;
-      if (COH) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) spin_dev_store(o + i, v[i]);
-      } else {
-        *(float4 *)o = make_float4(v[0], v[1], v[2], v[3]);
-      }
+    if (c == 0) {
+      float *o = scores + base + (size_t)t * 16 + n;
+      if (COH) spin_dev_store(o, m);
+      else *o = m;
     }
   } else {
-    // rows 4c..4c+3 are the four representatives of partition 4t + c
-    const float m = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
-    if (n == 0) {
-      if (COH) spin_dev_store(&scores[base + (size_t)t * 4 + c], m);
-      else scores[base + (size_t)t * 4 + c] = m;
+    // rows 4p..4p+3 are the four representatives of partition 4t + p: lanes n = 4p .. 4p+3
+    m = fmaxf(m, spin_dpp<SPIN_DPP_XOR1>(m));
+    m = fmaxf(m, spin_dpp<SPIN_DPP_XOR2>(m));
+    if (c == 0 && (n & 3) == 0) {
+      if (COH) spin_dev_store(&scores[base + (size_t)t * 4 + (n >> 2)], m);
+      else scores[base + (size_t)t * 4 + (n >> 2)] = m;
     }
   }
 }
@@ -73,7 +84,7 @@ __device__ inline void score_row_tiles(
   const int n = lane & 15, c = lane >> 4;
   const size_t base = (size_t)Hkv * off_b + (size_t)h * PP;   // in partitions
 
-  // B operand: column n = query head, k = elements 32j + 8c .. +8 of the query-side vector
+  // A operand: row n = query head, k = elements 32j + 8c .. +8 of the query-side vector
   spin_bf16x8 qf[NJ];
   {
     const uint4 *qrow = (const uint4 *)(q + ((size_t)(b * Hq + h * G + (n < G ? n : 0))) * SPIN_HEAD_DIM);
