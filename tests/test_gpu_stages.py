@@ -37,6 +37,17 @@ def _workloads():
                                   topk_includes_forced=True, sink_pages=3, recent_pages=6, name="mm_blocks"),
         "minmax_quarter": c0.with_(seq_lens=(500,), partition_tokens=4, topk=50, sink_pages=1,
                                    recent_pages=1, name="mm_quarter"),
+        # group sizes other than 4: one head, a group that is no power of two, more than one lane quarter
+        "g1_pages": c0.with_(seq_lens=(900, 333), num_q_heads=2, num_kv_heads=2, topk=12, sink_pages=1,
+                             recent_pages=1, name="g1_pages"),
+        "g3_pages": c0.with_(seq_lens=(900,), num_q_heads=6, num_kv_heads=2, topk=12, name="g3_pages"),
+        "g8_blocks": c0.with_(seq_lens=(40 * 128 + 77,), num_q_heads=16, num_kv_heads=2, partition_tokens=128,
+                              score_kind=synth.SCORE_REPMAX, topk=5, topk_includes_forced=False, sink_pages=2,
+                              recent_pages=4, block_mean_std=0.5, name="g8_blocks"),
+        "g16_tokens": c0.with_(seq_lens=(2500,), num_q_heads=32, num_kv_heads=2, partition_tokens=1,
+                               score_kind=synth.SCORE_SKETCH, topk=150, planted_frac=0.01, name="g16_tokens"),
+        "g12_pages": c0.with_(seq_lens=(1500,), num_q_heads=24, num_kv_heads=2, topk=20, sink_pages=1,
+                              recent_pages=2, name="g12_pages"),
     }
 
 
