@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--budget-frac", type=float, default=0.25)
     ap.add_argument("--four-calls", action="store_true",
                     help="time the four separate stage calls as the step (default: stages 2+3 share one launch)")
+    ap.add_argument("--decode-splits", type=int, default=0, help="split-K factor of the attention kernel (0: library default)")
+    ap.add_argument("--decode-waves", type=int, default=0, help="wavefronts per attention workgroup (0: library default)")
+    ap.add_argument("--decode-depth", type=int, default=0, help="page buffers per attention wavefront (0: library default)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events during the timed region")
     return ap.parse_args()
@@ -124,7 +127,8 @@ def run_cfg4(args):
             if (exact or policy) and mode != modes[-1]:
                 continue
             layer = hier.HierLayer(w, budget_frac=args.budget_frac, n_ts=64, evict_exact=exact, copy_mode=mode,
-                                   lru_policy=policy)
+                                   lru_policy=policy, decode_splits=args.decode_splits,
+                                   decode_waves=args.decode_waves, decode_depth=args.decode_depth)
             q = layer.q0
             lat, persist, prev = [], [], None
             layer.spin.profile_enable(steps)          # kernels bracketed by HIP events on the launch stream
@@ -207,7 +211,9 @@ def main():
         run_cfg4(args)
         return
     w = {"cfg1": synth.config1, "cfg2": synth.config2, "cfg3": synth.config3}[args.workload]()
-    layer, natural = runner.build_device_layer(w, device=dev, keep_natural=not args.no_cpu)
+    layer, natural = runner.build_device_layer(w, device=dev, keep_natural=not args.no_cpu,
+                                               decode_splits=args.decode_splits, decode_waves=args.decode_waves,
+                                               decode_depth=args.decode_depth)
     # stages 2+3 share a launch only for rows the one-launch kernel takes (at most 16384 partitions)
     one_launch_23 = max(w.partitions(b) for b in range(w.batch)) <= 16384
     if not one_launch_23:
@@ -351,7 +357,7 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "context": w.seq_lens[0], "q_heads": w.num_q_heads,
                    "kv_heads": w.num_kv_heads, "head_dim": w.head_dim, "page_tokens": w.page_tokens,
                    "partition_tokens": w.partition_tokens, "score": ["minmax", "sketch", "repmax"][w.score_kind],
-                   "topk_partitions": w.topk, "decode_splits": sp.decode_splits, "query_sets": len(qsets),
+                   "topk_partitions": w.topk, "decode_splits": sp.decode_splits, "decode_waves": args.decode_waves or 8, "query_sets": len(qsets),
                    "summary_copies": len(summ_copies)},
         "attended_kv_gbps": roofline["achieved"] if roofline else None,
         "attended_kv_pct_peak": round(100 * roofline["frac"], 2) if roofline else None,

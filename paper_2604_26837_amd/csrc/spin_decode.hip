@@ -33,12 +33,34 @@ struct page_regs {
   uint4 k[4], v[4];
 };
 
-__device__ inline void load_page(page_regs &r, const uint4 *__restrict__ pool, int slot, int lane) {
+// Loads of a page.  A page whose mask is not full (token partitions, the ragged last page) only
+// fetches what its attended tokens need: in the K tile a lane holds 16 bytes of ONE token, in
+// the V tile 16 bytes of ONE token quad, so lanes of unattended tokens / quads issue no load
+// and hold zeros (their logits are masked and their probabilities are exactly zero, so the
+// result has the same bits as with the whole page loaded).
+__device__ inline void load_page(page_regs &r, const uint4 *__restrict__ pool, int slot, int lane, unsigned mask) {
   const uint4 *kp = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
+  if (mask == 0xffffu) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j) r.k[j] = spin_nt_load(kp + j * 64);
+    for (int j = 0; j < 4; ++j) r.k[j] = spin_nt_load(kp + j * 64);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) r.v[j] = spin_nt_load(kp + SPIN_KTILE_U4 + j * 64);
+    for (int j = 0; j < 4; ++j) r.v[j] = spin_nt_load(kp + SPIN_KTILE_U4 + j * 64);
+  } else {
+    const bool kneed = (mask >> (lane & 15)) & 1u;
+    const bool vneed = ((mask >> (4 * (lane >> 4))) & 0xfu) != 0u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r.k[j] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r.v[j] = make_uint4(0, 0, 0, 0);
+    if (kneed) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) r.k[j] = spin_nt_load(kp + j * 64);
+    }
+    if (vneed) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) r.v[j] = spin_nt_load(kp + SPIN_KTILE_U4 + j * 64);
+    }
+  }
 }
 
 struct softmax_state {
@@ -177,12 +199,14 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
     page_regs r[DEPTH];
 #pragma unroll
     for (int d = 0; d < DEPTH - 1; ++d)
-      if (d < cnt) load_page(r[d], pool, __builtin_amdgcn_readlane(myslot, d), lane);
+      if (d < cnt) load_page(r[d], pool, __builtin_amdgcn_readlane(myslot, d), lane,
+                             (unsigned)__builtin_amdgcn_readlane((int)mymask, d));
     for (int i = 0; i < cnt; i += DEPTH) {
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
         const int ahead = i + d + DEPTH - 1;
-        if (ahead < cnt) load_page(r[(d + DEPTH - 1) % DEPTH], pool, __builtin_amdgcn_readlane(myslot, ahead), lane);
+        if (ahead < cnt) load_page(r[(d + DEPTH - 1) % DEPTH], pool, __builtin_amdgcn_readlane(myslot, ahead), lane,
+                                   (unsigned)__builtin_amdgcn_readlane((int)mymask, ahead));
         if (i + d < cnt)
           consume_page(st, r[d], qf, (unsigned)__builtin_amdgcn_readlane((int)mymask, i + d), c, scale_log2e);
       }
