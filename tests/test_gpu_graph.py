@@ -11,13 +11,30 @@ from paper_2604_26837_amd import runner, synth
 pytestmark = pytest.mark.gpu
 
 
-def test_step_replays_from_a_graph():
-    w = synth.config0().with_(seq_lens=(4096, 1000, 2049), num_q_heads=8, num_kv_heads=2, topk=24, sink_pages=2,
-                              recent_pages=3, name="graph")
+def _workloads():
+    c0 = synth.config0()
+    return {
+        # stages 2+3 in one launch
+        "pages": (c0.with_(seq_lens=(4096, 1000, 2049), num_q_heads=8, num_kv_heads=2, topk=24, sink_pages=2,
+                           recent_pages=3, name="graph"), "step3"),
+        # token partitions, rows long enough for the two-launch selection (its histogram lives in the
+        # workspace and must be left cleared by every replay), partial page masks in the attention
+        "long_token_rows": (c0.with_(seq_lens=(20000, 17001), num_q_heads=8, num_kv_heads=2, partition_tokens=1,
+                                     score_kind=synth.SCORE_SKETCH, topk=300, sink_pages=1, recent_pages=1,
+                                     name="graph_tokens"), "step"),
+    }
+
+
+@pytest.mark.parametrize("name", list(_workloads()))
+def test_step_replays_from_a_graph(name):
+    w, how = _workloads()[name]
     data = synth.generate(w)
     natural = torch.from_numpy(data.pool_bits.view(np.int16).copy()).to("cuda:0").view(torch.bfloat16)
     layer = runner.LayerState.from_natural_pool(w, data.slot_of, natural, decode_splits=2)
+    if w.score_kind == synth.SCORE_SKETCH:
+        layer.set_channels(synth.sketch_channels(data))
     layer.build_summaries()
+    layer.step3 = getattr(layer, how)              # the step as this workload runs it
     qs = [torch.from_numpy(synth.make_queries(w, 100 + i).view(np.int16)).to("cuda:0").view(torch.bfloat16)
           for i in range(3)]
     q_static = qs[0].clone()
