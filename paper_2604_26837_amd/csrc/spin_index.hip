@@ -220,6 +220,86 @@ __global__ __launch_bounds__(256) void spin_index_repmean_kernel(
   o[tbase + (size_t)ch * 16 + (R & 15)] = make_uint4(outw[0], outw[1], outw[2], outw[3]);
 }
 
+// REPMAX when every representative covers whole pages (partition_tokens / reps a multiple of 16),
+// the hot shape: one workgroup per tile of 16 summary rows, each of its four wavefronts builds
+// four of them.  As in the MINMAX kernel above a page's K tile is fetched with four contiguous
+// 1 KiB loads and regrouped through the wavefront's own 4 KiB of LDS (lane = 8-channel chunk x
+// token quad); the lane adds its four tokens in fp64 (exact for bf16 addends), the four token
+// quads are added with two exchanges, and the mean is rounded once.
+__global__ __launch_bounds__(256) void spin_index_repmean_pages_kernel(
+    const uint4 *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
+    const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
+    const int32_t *__restrict__ seq_lens, int Hkv, int tp, int reps, int dir_stride, int leaf_entries,
+    int max_tiles, uint16_t *__restrict__ summ, int32_t *status) {
+  __shared__ uint4 s_tile[4][SPIN_KTILE_U4];
+  const int row = blockIdx.x / max_tiles, tile = blockIdx.x - row * max_tiles;
+  const int b = row / Hkv, h = row - b * Hkv;
+  const int PP = part_offsets[b + 1] - part_offsets[b];
+  if (tile * 16 >= PP * reps) return;
+  const int N = seq_lens[b];
+  const int P = (N + tp - 1) / tp;
+  const size_t base = ((size_t)Hkv * part_offsets[b] + (size_t)h * PP) * reps;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ch = lane >> 2, tq = lane & 3;      // after regrouping: chunk of 8 channels, tokens 4tq..4tq+3
+  const int sub = tp / reps;
+  uint4 *lds = s_tile[wave];
+  uint4 *o = (uint4 *)summ;
+  for (int k = 0; k < 4; ++k) {
+    const int sr = tile * 16 + wave * 4 + k;     // summary row inside this KV row
+    const int p = sr / reps, rep = sr - p * reps;
+    uint32_t outw[4] = {0, 0, 0, 0};
+    if (p < P) {
+      // an empty sub-range repeats representative 0 of the partition
+      int t0 = p * tp + rep * sub, t1 = min(t0 + sub, N);
+      if (t1 <= t0) { t0 = p * tp; t1 = min(t0 + sub, N); }
+      double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      for (int pg = t0 >> 4; pg <= (t1 - 1) >> 4; ++pg) {
+        const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
+        if (slot < 0 || (int64_t)slot >= pool_slots) {
+          if (lane == 0) spin_raise(status, SPIN_ERR_NOT_RESIDENT);
+          continue;
+        }
+        const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
+        uint4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = spin_nt_load(kt + j * 64);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) lds[j * 64 + lane] = v[j];
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // same wavefront writes and reads: program order
+        const int nvalid = min(t1 - pg * 16, 16);                // the sub-range starts on a page boundary
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint4 u = lds[ch * 16 + 4 * tq + i];
+          if (4 * tq + i < nvalid) {
+            const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              acc[2 * e] += (double)__uint_as_float(w[e] << 16);
+              acc[2 * e + 1] += (double)__uint_as_float(w[e] & 0xffff0000u);
+            }
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      }
+      // add the four token quads (lanes 4ch .. 4ch+3); exact sums, so the order does not matter
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        acc[i] += __shfl_xor(acc[i], 1);
+        acc[i] += __shfl_xor(acc[i], 2);
+      }
+      const double cnt = (double)(t1 - t0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        outw[i] = (uint32_t)spin_f64_to_bf16(acc[2 * i] / cnt) | ((uint32_t)spin_f64_to_bf16(acc[2 * i + 1] / cnt) << 16);
+    }
+    if (tq == 0) {
+      const size_t R = base + sr;
+      const size_t tbase = (R >> 4) * (size_t)(16 * 128 / 8);
+      o[tbase + (size_t)ch * 16 + (R & 15)] = make_uint4(outw[0], outw[1], outw[2], outw[3]);
+    }
+  }
+}
+
 // One thread per (token, channel quad): gathers the sketched channels of a key.
 __global__ __launch_bounds__(256) void spin_index_sketch_kernel(
     const uint16_t *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
@@ -283,10 +363,16 @@ extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv
                        (uint16_t *)summaries, status);
   } else if (c.score_kind == SPIN_SCORE_REPMAX) {
     const int max_tiles = max_pp * c.reps_per_partition / 16;
-    hipLaunchKernelGGL(spin_index_repmean_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
-                       (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
-                       c.num_kv_heads, c.partition_tokens, c.reps_per_partition, ctx->dir_stride, c.leaf_entries,
-                       max_tiles, (uint16_t *)summaries, status);
+    if ((c.partition_tokens / c.reps_per_partition) % 16 == 0)
+      spin_launch(ctx, SPIN_K_INDEX, spin_index_repmean_pages_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
+                  (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
+                  c.num_kv_heads, c.partition_tokens, c.reps_per_partition, ctx->dir_stride, c.leaf_entries,
+                  max_tiles, (uint16_t *)summaries, status);
+    else
+      spin_launch(ctx, SPIN_K_INDEX, spin_index_repmean_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
+                  (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
+                  c.num_kv_heads, c.partition_tokens, c.reps_per_partition, ctx->dir_stride, c.leaf_entries,
+                  max_tiles, (uint16_t *)summaries, status);
   } else {
     if (!chan_idx) return SPIN_ERR_INVALID;
     if (c.partition_tokens != 1) return SPIN_ERR_UNSUPPORTED;

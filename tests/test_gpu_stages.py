@@ -37,6 +37,10 @@ def _workloads():
                                   topk_includes_forced=True, sink_pages=3, recent_pages=6, name="mm_blocks"),
         "minmax_quarter": c0.with_(seq_lens=(500,), partition_tokens=4, topk=50, sink_pages=1,
                                    recent_pages=1, name="mm_quarter"),
+        # representatives that cover half a page each (the Index kernel for whole-page sub-ranges does not apply)
+        "blocks_small": c0.with_(seq_lens=(70 * 32 + 9, 32 * 16), partition_tokens=32, score_kind=synth.SCORE_REPMAX,
+                                 topk=7, topk_includes_forced=False, sink_pages=2, recent_pages=3, block_mean_std=0.5,
+                                 name="blocks_small"),
         # group sizes other than 4: one head, a group that is no power of two, more than one lane quarter
         "g1_pages": c0.with_(seq_lens=(900, 333), num_q_heads=2, num_kv_heads=2, topk=12, sink_pages=1,
                              recent_pages=1, name="g1_pages"),
