@@ -12,6 +12,7 @@
  * Around them:
  *   spin_pack_kv_pages, spin_build_summaries, spin_append_kv   Offload's layout and Index (Section 4.1)
  *   spin_gather_misses, spin_copy_misses_host                  Retrieve steps 3-4 (Sections 5.2, 5.5)
+ *   spin_offload_pages                                         Offload's copy, slot -> host page (Table 1)
  *   spin_select_resolve                                        stages 2+3 in one launch, same results
  *   spin_set_partition_tables                                  variable-length partitions (Section 5.2)
  *   spin_alloc_leaves, spin_free_leaves, spin_reclaim_tail     on-demand metadata, budget resizing (5.3, 5.4)
@@ -152,7 +153,8 @@ int spin_poll_status(spin_ctx *ctx, const void *workspace, void *stream);
 enum spin_kernel_id {
   SPIN_K_SCORE = 0, SPIN_K_SELECT = 1, SPIN_K_RESOLVE = 2, SPIN_K_DECODE = 3, SPIN_K_MERGE = 4,
   SPIN_K_INDEX = 5, SPIN_K_PACK = 6, SPIN_K_GATHER = 7, SPIN_K_PROBE = 8,
-  SPIN_K_SELECT_HIST = 9 /* first launch of stage 2 for rows of more than 16384 partitions */
+  SPIN_K_SELECT_HIST = 9, /* first launch of stage 2 for rows of more than 16384 partitions */
+  SPIN_K_OFFLOAD = 10
 };
 int spin_profile_enable(spin_ctx *ctx, int32_t capacity);
 int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_us, float *min_us);
@@ -333,6 +335,19 @@ int spin_copy_misses_host(spin_ctx *ctx, int32_t batch, const void *host_kv, con
 int spin_gather_misses(spin_ctx *ctx, int32_t batch, const void *host_kv, const int64_t *row_base,
                        const int32_t *nmiss, const int32_t *miss_pages, const int32_t *miss_slots,
                        void *kv_pool, int64_t pool_slots, void *workspace, void *stream);
+
+/* Offload's copy (Table 1: copy(gpu_kv, cpu_kv, map); Section 4.1 Offload), the
+ * copy kernel run the other way: for every row r write the pages listed in
+ * pages[r][0 .. count[r]) from the slots slots[r][...] to the pinned host copy
+ * (page p of row r is host page row_base[r] + p).  count (DEVICE int32 [rows]),
+ * pages / slots (DEVICE int32 [rows][page_stride]) have the shape of stage 3's
+ * page or miss lists, so those can be passed as they are; host_kv is the
+ * device-visible address of the pinned buffer.  Used at decode time to write a
+ * page back once its last token has been appended, before it can be evicted.
+ * Tables are not touched. */
+int spin_offload_pages(spin_ctx *ctx, int32_t batch, const void *kv_pool, int64_t pool_slots, void *host_kv,
+                       const int64_t *row_base, const int32_t *count, const int32_t *pages,
+                       const int32_t *slots, void *workspace, void *stream);
 
 /* Stage 4.  out[b][hq] (DEVICE bf16 [batch][num_q_heads][128]) =
  * softmax(scale * q K_S^T) V_S over the tokens whose mask bit is set in the

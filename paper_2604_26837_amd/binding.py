@@ -23,7 +23,7 @@ EXPORTS = [
     "spin_workspace_init", "spin_poll_status", "spin_profile_enable", "spin_profile_read", "spin_pack_kv_pages", "spin_build_summaries",
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
     "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv", "spin_reclaim_tail", "spin_alloc_leaves", "spin_free_leaves",
-    "spin_set_partition_tables", "spin_probe_stream_read",
+    "spin_set_partition_tables", "spin_probe_stream_read", "spin_offload_pages",
 ]
 
 
@@ -83,6 +83,7 @@ def load_library() -> C.CDLL:
     lib.spin_select_resolve.argtypes = [vp, i32] + [vp] * 7 + [i64] + [vp] * 6
     lib.spin_copy_misses_host.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i64, vp, C.POINTER(i64)]
     lib.spin_gather_misses.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i64, vp, vp]
+    lib.spin_offload_pages.argtypes = [vp, i32, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     _LIB = lib
     return lib
 
@@ -169,7 +170,7 @@ class Spin:
     def summary_bytes(self, padded_partitions: int) -> int:
         return self.lib.spin_summary_bytes(self.h, padded_partitions)
 
-    KERNEL_IDS = dict(score=0, select=1, resolve=2, decode=3, merge=4, index=5, pack=6, gather=7, probe=8, select_hist=9)
+    KERNEL_IDS = dict(score=0, select=1, resolve=2, decode=3, merge=4, index=5, pack=6, gather=7, probe=8, select_hist=9, offload=10)
 
     def profile_enable(self, capacity: int):
         self._check(self.lib.spin_profile_enable(self.h, capacity), "spin_profile_enable")
@@ -300,6 +301,16 @@ class Spin:
             _ptr(nmiss, torch.int32, "nmiss"), _ptr(miss_pages, torch.int32, "miss_pages"),
             _ptr(miss_slots, torch.int32, "miss_slots"), _ptr(kv_pool), pool_slots, _ptr(ws), _stream()),
             "spin_gather_misses")
+
+    def offload_pages(self, batch, kv_pool, host_kv, row_base, count, pages, slots, ws):
+        """host_kv: pinned CPU tensor (written by the kernel); the lists are DEVICE tensors."""
+        pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192
+        if not host_kv.is_pinned():
+            raise ValueError("host_kv must be pinned host memory")
+        self._check(self.lib.spin_offload_pages(
+            self.h, batch, _ptr(kv_pool), pool_slots, host_kv.data_ptr(), _ptr(row_base, torch.int64, "row_base"),
+            _ptr(count, torch.int32, "count"), _ptr(pages, torch.int32, "pages"),
+            _ptr(slots, torch.int32, "slots"), _ptr(ws), _stream()), "spin_offload_pages")
 
     def sparse_decode(self, batch, q, kv_pool, slots, valid_mask, npages, out, lse, ws):
         pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192

@@ -6,7 +6,8 @@
 // the paper's copy kernel (Section 5.5): one wavefront copies one page with
 // 16-byte lane transactions straight out of pinned host memory; workgroups are
 // dealt (row, chunk of misses) pairs so pages spread over the whole chip
-// whatever row owns them, and the miss list never leaves the device.
+// whatever row owns them, and the miss list never leaves the device.  The same
+// kernel run the other way is Offload's copy (slot -> host page).
 #include "spin_common.h"
 
 extern "C" int spin_copy_misses_host(spin_ctx *ctx, int32_t batch, const void *host_kv,
@@ -39,8 +40,11 @@ extern "C" int spin_copy_misses_host(spin_ctx *ctx, int32_t batch, const void *h
 #define GATHER_WAVES 4
 #define GATHER_PAGES_PER_WG 16
 
+// TO_HOST = false: host page -> slot (Retrieve).  TO_HOST = true: slot -> host page (Offload's copy,
+// Table 1: copy(gpu_kv, cpu_kv, map)); the lists have the same shape in both directions.
+template <bool TO_HOST>
 __global__ __launch_bounds__(GATHER_WAVES * 64) void spin_gather_kernel(
-    const uint4 *__restrict__ host_kv, const int64_t *__restrict__ row_base, const int32_t *__restrict__ nmiss,
+    uint4 *__restrict__ host_kv, const int64_t *__restrict__ row_base, const int32_t *__restrict__ nmiss,
     const int32_t *__restrict__ miss_pages, const int32_t *__restrict__ miss_slots, uint4 *__restrict__ pool,
     int64_t pool_slots, int page_stride, int chunks_per_row, int32_t *status) {
   const int row = blockIdx.x / chunks_per_row, chunk = blockIdx.x - row * chunks_per_row;
@@ -57,8 +61,10 @@ __global__ __launch_bounds__(GATHER_WAVES * 64) void spin_gather_kernel(
       if (lane == 0) spin_raise(status, SPIN_ERR_SLOT_RANGE);
       continue;
     }
-    const uint4 *src = host_kv + (size_t)(rb + pg) * SPIN_SLOT_U4 + lane;
-    uint4 *dst = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
+    uint4 *hp = host_kv + (size_t)(rb + pg) * SPIN_SLOT_U4 + lane;
+    uint4 *dp = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
+    const uint4 *src = TO_HOST ? dp : hp;
+    uint4 *dst = TO_HOST ? hp : dp;
     uint4 v[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) v[k] = src[k * 64];
@@ -76,8 +82,23 @@ extern "C" int spin_gather_misses(spin_ctx *ctx, int32_t batch, const void *host
   if (!workspace) return SPIN_ERR_WORKSPACE;
   const int rows = batch * ctx->cfg.num_kv_heads;
   const int chunks = (ctx->page_stride + GATHER_PAGES_PER_WG - 1) / GATHER_PAGES_PER_WG;
-  spin_launch(ctx, SPIN_K_GATHER, spin_gather_kernel, dim3((unsigned)(rows * chunks)), dim3(GATHER_WAVES * 64), 0,
-              (hipStream_t)stream, (const uint4 *)host_kv, row_base, nmiss, miss_pages, miss_slots,
+  spin_launch(ctx, SPIN_K_GATHER, spin_gather_kernel<false>, dim3((unsigned)(rows * chunks)), dim3(GATHER_WAVES * 64), 0,
+              (hipStream_t)stream, (uint4 *)const_cast<void *>(host_kv), row_base, nmiss, miss_pages, miss_slots,
               (uint4 *)kv_pool, pool_slots, ctx->page_stride, chunks, (int32_t *)workspace);
+  return spin_launch_status();
+}
+
+extern "C" int spin_offload_pages(spin_ctx *ctx, int32_t batch, const void *kv_pool, int64_t pool_slots, void *host_kv,
+                                  const int64_t *row_base, const int32_t *count, const int32_t *pages,
+                                  const int32_t *slots, void *workspace, void *stream) {
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || pool_slots <= 0) return SPIN_ERR_INVALID;
+  if (batch == 0) return SPIN_OK;
+  if (!host_kv || !row_base || !count || !pages || !slots || !kv_pool) return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  const int rows = batch * ctx->cfg.num_kv_heads;
+  const int chunks = (ctx->page_stride + GATHER_PAGES_PER_WG - 1) / GATHER_PAGES_PER_WG;
+  spin_launch(ctx, SPIN_K_OFFLOAD, spin_gather_kernel<true>, dim3((unsigned)(rows * chunks)), dim3(GATHER_WAVES * 64), 0,
+              (hipStream_t)stream, (uint4 *)host_kv, row_base, count, pages, slots,
+              (uint4 *)const_cast<void *>(kv_pool), pool_slots, ctx->page_stride, chunks, (int32_t *)workspace);
   return spin_launch_status();
 }

@@ -140,6 +140,79 @@ class HierLayer:
                 st["misses_after_first"] += copied
         return copied
 
+    # ------------------------------------------------------------------
+    def rebuild_summaries_from_host(self):
+        """Index over the host copy for the current ``seq_lens`` (shorter than the
+        lengths the layer was sized for): each request's pages are staged in a
+        temporary all-resident pool and summarised there."""
+        sp, w, hkv = self.spin, self.w, self.w.num_kv_heads
+        lens = self.seq_lens.cpu().tolist()
+        self.summaries.zero_()
+        for b in range(w.batch):
+            pages_b = w.pages(b)
+            tmp = torch.empty((hkv * pages_b, 4096), dtype=torch.bfloat16, device=self.device)
+            slot_of = np.empty((hkv, pages_b), dtype=np.int32)
+            for h in range(hkv):
+                r = b * hkv + h
+                lo = int(self.host_row_base_np[r])
+                tmp[h * pages_b:(h + 1) * pages_b].copy_(self.host_kv[lo:lo + pages_b])
+                slot_of[h] = np.arange(h * pages_b, (h + 1) * pages_b, dtype=np.int32)
+            d, l = tables.build_two_level([slot_of], sp.dir_stride, w.leaf_entries)
+            pp = int(self.part_offsets_np[b + 1] - self.part_offsets_np[b])
+            po = torch.tensor([0, pp], dtype=torch.int32, device=self.device)
+            sl = torch.tensor([lens[b]], dtype=torch.int32, device=self.device)
+            off = hkv * int(self.part_offsets_np[b]) * 512
+            part = self.summaries[off: off + hkv * pp * 512]
+            sp.build_summaries(1, tmp, torch.from_numpy(d).to(self.device), torch.from_numpy(l).to(self.device), po, sl,
+                               None, part, self.ws)
+            torch.cuda.synchronize()
+            del tmp
+
+    def step_append(self, q: torch.Tensor, step: int, k_new: torch.Tensor, v_new: torch.Tensor) -> int:
+        """One decode step in which every request grows by one token: the stages run for
+        the new lengths (the tail partition is forced, so its summary need not hold the
+        new token yet), misses are fetched, the token is appended to its now resident page
+        (decode-time Index), attention runs, and a page that the token completed is copied
+        back to the host (Offload's copy) so that a later eviction loses nothing.
+        ``seq_lens`` holds the lengths before the call and is incremented.  Returns the
+        number of pages written back.  Needs recent_pages >= 1."""
+        sp, w, hkv = self.spin, self.w, self.w.num_kv_heads
+        assert w.recent_pages >= 1 and self.copy_mode == "gather"
+        before = self.seq_lens.clone()
+        after = before + 1
+        sp.score_partitions(w.batch, q, self.summaries, None, self.part_offsets, after, self.scores, self.ws)
+        sp.select_topk(w.batch, self.scores, self.part_offsets, after, self.sel, self.nsel, self.ws)
+        sp.resolve_slots(w.batch, step, self.sel, self.nsel, after, self.dir, self.leaf_pool, self.slots,
+                         self.page_ids, self.valid_mask, self.npages, self.ws, rev_table=self.rev,
+                         slot_base=self.slot_base, miss_pages=self.miss_pages, miss_slots=self.miss_slots,
+                         nmiss=self.nmiss)
+        sp.gather_misses(w.batch, self.host_kv, self.host_row_base_dev, self.nmiss, self.miss_pages,
+                         self.miss_slots, self.kv_pool, self.ws)
+        sp.append_kv(w.batch, k_new, v_new, before, self.kv_pool, self.dir, self.leaf_pool, self.part_offsets, None,
+                     self.summaries, self.ws)
+        sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
+                         self.ws)
+        # the tail page is the last entry of every row's ascending page list
+        last = (self.npages - 1).clamp(min=0).long().unsqueeze(1)
+        off_pages = torch.full_like(self.page_ids, -1)
+        off_slots = torch.full_like(self.slots, -1)
+        off_pages[:, 0:1] = torch.gather(self.page_ids, 1, last)
+        off_slots[:, 0:1] = torch.gather(self.slots, 1, last)
+        complete = ((after % 16) == 0).to(torch.int32).repeat_interleave(hkv)
+        sp.offload_pages(w.batch, self.kv_pool, self.host_kv, self.host_row_base_dev, complete, off_pages, off_slots,
+                         self.ws)
+        self.seq_lens.copy_(after)
+        copied = int(self.nmiss.sum().item())
+        selected = int(self.npages.sum().item())
+        st = self.stats
+        st["steps"] += 1
+        st["selected"] += selected
+        st["misses"] += copied
+        if step > 0:
+            st["selected_after_first"] += selected
+            st["misses_after_first"] += copied
+        return int(complete.sum().item())
+
     def hit_rates(self):
         st = self.stats
         overall = 1.0 - st["misses"] / max(st["selected"], 1)
