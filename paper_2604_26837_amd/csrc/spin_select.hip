@@ -241,6 +241,15 @@ __global__ __launch_bounds__(256) void spin_select_hist_kernel(
   }
 }
 
+// The smallest score whose key is at least K (keys as in score_key).  Bit patterns that are no
+// ordered number: below -inf every real key of the bin is at least key(-inf), so `low_end` asks
+// for -inf there; above +inf no key exists and the NaN returned fails every comparison.
+__device__ inline float key_floor_score(uint32_t K, bool low_end) {
+  const uint32_t u = (K & 0x80000000u) ? (K ^ 0x80000000u) : ~K;
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (low_end && (u & 0x80000000u)) ? -__builtin_inff() : __builtin_nanf("");
+  return __uint_as_float(u);
+}
+
 __global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
     const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
@@ -289,7 +298,9 @@ __global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
   }
   __syncthreads();
   const int D = s_D;
-  if (kprime > 0 && (D == BIG_BINS || s_cntD > BIG_CAP || W > words_max)) {
+  // (bin 7 holds -inf and the NaN scores, which rank as -inf: the walk below compares scores as
+  // floats and would not see the NaNs, so that bin goes the multi-pass way as well)
+  if (kprime > 0 && (D == BIG_BINS || D == 7 || s_cntD > BIG_CAP || W > words_max)) {
     // heavy ties in the threshold bin (or a histogram that does not cover the row): multi-pass algorithms
     if (P <= BIG_BLOCK * 64) {
       spin_var none = {};
@@ -302,38 +313,94 @@ __global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
     return;
   }
 
-  for (int i = tid; i < W; i += BIG_BLOCK) { s_main[i] = 0; s_eq[i] = 0; }
+  // the bitmaps start with the forced partitions [0, nf_lo) and [first_hi, P) set
+  for (int i = tid; i < W; i += BIG_BLOCK) {
+    const int p0 = i * 32;
+    uint32_t m = 0;
+    if (p0 < pl.nf_lo) m |= pl.nf_lo - p0 >= 32 ? 0xffffffffu : (1u << (pl.nf_lo - p0)) - 1u;
+    if (p0 + 32 > pl.first_hi) {
+      const uint32_t from = p0 >= pl.first_hi ? 0xffffffffu : ~((1u << (pl.first_hi - p0)) - 1u);
+      const uint32_t upto = P - p0 >= 32 ? 0xffffffffu : (1u << (P - p0)) - 1u;   // P > p0: i < W
+      m |= from & upto;
+    }
+    s_main[i] = m;
+    s_eq[i] = 0;
+  }
   __syncthreads();
 
-  // one walk over the row: 16-byte loads, eight per thread in flight
-  for (int base = 0; base < P; base += BIG_BLOCK * 32) {
+  // One walk over the row, 16-byte loads, eight per thread in flight.  Membership of a score in
+  // bin D or above is decided on the float itself: the key is monotone in the score, so
+  // key >= K  <=>  score >= (the score whose key is K); a NaN score fails every comparison, which is
+  // right above the bin of -inf (the rank NaN has as a key).  The exact key is only formed for the
+  // few scores that join the list.
+  const float f_lo = key_floor_score((uint32_t)D << 20, true);
+  const float f_hi = D + 1 < BIG_BINS ? key_floor_score(((uint32_t)D + 1u) << 20, false) : __builtin_nanf("");
+  for (int base = 0; base < P && kprime > 0; base += BIG_BLOCK * 32) {
     float4 f[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int p4 = base + (i * BIG_BLOCK + tid) * 4;
       f[i] = p4 < PP ? *(const float4 *)(rs + p4) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+    // non-candidates (forced partitions, the padding past P) become NaN, which fails every comparison;
+    // only the loads that straddle an end of the candidate range have any
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int p4 = base + (i * BIG_BLOCK + tid) * 4;
+      if (!(p4 >= pl.nf_lo && p4 + 4 <= pl.first_hi)) {
+        if (p4 + 0 < pl.nf_lo || p4 + 0 >= pl.first_hi) f[i].x = __builtin_nanf("");
+        if (p4 + 1 < pl.nf_lo || p4 + 1 >= pl.first_hi) f[i].y = __builtin_nanf("");
+        if (p4 + 2 < pl.nf_lo || p4 + 2 >= pl.first_hi) f[i].z = __builtin_nanf("");
+        if (p4 + 3 < pl.nf_lo || p4 + 3 >= pl.first_hi) f[i].w = __builtin_nanf("");
+      }
+    }
+    // classify the thread's 32 scores: bit 4i+e of `above` / `in_d` = score e of load i lies above bin D /
+    // in it.  One comparison per score; the rest only runs when some lane of the wavefront passes it.
+    uint32_t above = 0, in_d = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
       const float v[4] = {f[i].x, f[i].y, f[i].z, f[i].w};
-      uint32_t bits = 0;                                 // this thread's four partitions: selected so far
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int p = p4 + e;
-        if (p >= P) continue;
-        if (p < pl.nf_lo || p >= pl.first_hi) bits |= 1u << e;
-        else if (kprime > 0) {
-          const uint32_t key = score_key(v[e]);
-          const int bin = (int)(key >> 20);
-          if (bin > D) bits |= 1u << e;
-          else if (bin == D) {
-            const int pos = atomicAdd(&s_n, 1);
-            if (pos < BIG_CAP) s_list[pos] = make_uint2(key, (uint32_t)p);
-          }
+        const bool ge_lo = v[e] >= f_lo;
+        if (__ballot(ge_lo) == 0ull) continue;
+        const bool ge_hi = v[e] >= f_hi;
+        above |= (ge_lo && ge_hi) ? 1u << (4 * i + e) : 0u;
+        in_d |= (ge_lo && !ge_hi) ? 1u << (4 * i + e) : 0u;
+      }
+    }
+    if (above) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int p4 = base + (i * BIG_BLOCK + tid) * 4;
+        const uint32_t bits = (above >> (4 * i)) & 0xfu;
+        if (bits) atomicOr(&s_main[p4 >> 5], bits << (p4 & 31));   // p4 is a multiple of 4: the bits stay in one word
+      }
+    }
+    // the scores in bin D join the list: one counter update per wavefront and batch
+    if (__ballot(in_d != 0u)) {
+      const int mine = __popc(in_d);
+      int inc = mine;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(inc, d);
+        if (lane >= d) inc += o;
+      }
+      int first = 0;
+      if (lane == 63) first = atomicAdd(&s_n, inc);
+      int pos = __shfl(first, 63) + inc - mine;
+      if (in_d) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float v[4] = {f[i].x, f[i].y, f[i].z, f[i].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if ((in_d >> (4 * i + e)) & 1u) {
+              if (pos < BIG_CAP) s_list[pos] = make_uint2(score_key(v[e]), (uint32_t)(base + (i * BIG_BLOCK + tid) * 4 + e));
+              ++pos;
+            }
         }
       }
-      if (bits) atomicOr(&s_main[p4 >> 5], bits << (p4 & 31));   // p4 is a multiple of 4: the bits stay in one word
     }
   }
   __syncthreads();

@@ -281,6 +281,14 @@ def test_select_wide_dynamic_range_rows():
         tied_neg = (-np.abs(tied) - 1.0).astype(np.float32)
         smooth = (rng.standard_normal(P) * 4).astype(np.float32)
         _check_select(w, [tied, tied_neg, smooth, -smooth, tied])
+        # subnormals, signed zeros, infinities and NaN among smooth scores
+        specials = (rng.standard_normal(P) * 1e-39).astype(np.float32)
+        mixed = smooth.copy()
+        idx = rng.choice(P, size=P // 8, replace=False)
+        mixed[idx] = rng.choice(np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-40, -1e-40], dtype=np.float32),
+                                size=idx.size)
+        mostly_minus_inf = np.where(rng.random(P) < 0.995, -np.inf, smooth).astype(np.float32)
+        _check_select(w, [specials, mixed, mostly_minus_inf, np.abs(specials), mixed])
 
 
 def test_select_rows_beyond_the_register_variants():
