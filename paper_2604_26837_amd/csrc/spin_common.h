@@ -161,6 +161,32 @@ template <int CTRL>
 __device__ inline float spin_dpp(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
 }
+template <int CTRL>
+__device__ inline int spin_dpp_i(int v) {   // lanes whose source lies outside the row read 0
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+// inclusive prefix sum over the 64 lanes of a wavefront: four row shifts inside each row of 16
+// lanes, then the totals of the rows before (three lane reads); no trip through LDS
+__device__ inline int spin_wave_inclusive_scan(int v) {
+  v += spin_dpp_i<0x111>(v);   // row_shr:1
+  v += spin_dpp_i<0x112>(v);   // row_shr:2
+  v += spin_dpp_i<0x114>(v);   // row_shr:4
+  v += spin_dpp_i<0x118>(v);   // row_shr:8
+  const int t0 = __builtin_amdgcn_readlane(v, 15), t1 = __builtin_amdgcn_readlane(v, 31),
+            t2 = __builtin_amdgcn_readlane(v, 47);
+  const int row = (threadIdx.x & 63) >> 4;
+  return v + (row >= 1 ? t0 : 0) + (row >= 2 ? t1 : 0) + (row >= 3 ? t2 : 0);
+}
+// maximum / minimum of an unsigned word over the wavefront, result uniform
+__device__ inline uint32_t spin_wave_max_u32(uint32_t v) {
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, SPIN_DPP_XOR1, 0xf, 0xf, false));
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, SPIN_DPP_XOR2, 0xf, 0xf, false));
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, SPIN_DPP_HALF_MIRROR, 0xf, 0xf, false));
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, SPIN_DPP_MIRROR, 0xf, 0xf, false));
+  return max(max((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 16)),
+             max((uint32_t)__builtin_amdgcn_readlane((int)v, 32), (uint32_t)__builtin_amdgcn_readlane((int)v, 48)));
+}
+__device__ inline uint32_t spin_wave_min_u32(uint32_t v) { return ~spin_wave_max_u32(~v); }
 // maximum over the 16 lanes of a row, result in every lane
 __device__ inline float spin_row16_max(float v) {
   v = fmaxf(v, spin_dpp<SPIN_DPP_XOR1>(v));

@@ -82,33 +82,32 @@ __device__ inline int select_reg_row(
 
   uint32_t prefix = 0;
   int remaining = kprime;
-  // Rows with many keys per thread: scores share a few exponents, so the atomics of the first
-  // digit would pile onto a handful of bins.  Instead every thread counts, in one packed
-  // register, its keys in the 8 highest digits at or below the row's largest one; the full
+  // Radix select of the k'-th largest candidate key, most significant digit first.  The digits
+  // start at the highest bit in which the row's candidate keys differ at all (one min/max
+  // reduction): scores of one row usually share sign, exponent and leading mantissa bits, so
+  // this saves a pass or two and, above all, spreads the first histogram over many bins
+  // instead of piling every key onto one LDS counter.
+  // Rows with many keys per thread: for the first digit every thread counts, in one packed
+  // register, its keys in the 8 highest digit values at or below the row's largest one; the full
   // histogram is only built when the k'-th candidate lies below them.
   constexpr bool TOP8 = KPT >= 16 && KPT <= 255;
-  __shared__ uint32_t s_wmax[NW];
+  __shared__ uint32_t s_wmax[NW], s_wmin[NW];
   if (kprime > 0) {
     if (tid < 256) s_hist[0][tid] = 0;
-    uint32_t top_digit = 0;
-    if (TOP8) {
-      uint32_t m = 0;
+    uint32_t kmx = 0u, kmn = 0xffffffffu;
 #pragma unroll
-      for (int k = 0; k < KPT; ++k) {
-        const int p = c0 + k;
-        if (p >= ca && p < cb) m = max(m, key[k]);
-      }
-#pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, d));
-      if (lane == 0) s_wmax[wave] = m;
+    for (int k = 0; k < KPT; ++k) {
+      const int p = c0 + k;
+      if (p >= ca && p < cb) { kmx = max(kmx, key[k]); kmn = min(kmn, key[k]); }
     }
+    kmx = spin_wave_max_u32(kmx);
+    kmn = spin_wave_min_u32(kmn);
+    if (lane == 0) { s_wmax[wave] = kmx; s_wmin[wave] = kmn; }
     __syncthreads();
-    if (TOP8) {
-      uint32_t m = 0;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) m = max(m, s_wmax[w]);
-      top_digit = m >> 24;
-    }
+    for (int w = 0; w < NW; ++w) { kmx = max(kmx, s_wmax[w]); kmn = min(kmn, s_wmin[w]); }
+    int hi = kmx == kmn ? 0 : 32 - __clz((int)(kmx ^ kmn));   // the low `hi` bits are the ones that vary
+    prefix = hi < 32 ? kmx >> hi : 0u;
     // suffix scan of the 256-bin histogram `cur` by the first wavefront: digit of the
     // remaining-th largest candidate, or -1 when the histogram holds fewer
     auto find_digit = [&](int cur) {
@@ -119,12 +118,7 @@ __device__ inline int select_reg_row(
         int hv[4], local = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) { hv[j] = s_hist[cur][255 - 4 * lane - j]; local += hv[j]; }
-        int inc = local;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-          const int o = __shfl_up(inc, d);
-          if (lane >= d) inc += o;
-        }
+        const int inc = spin_wave_inclusive_scan(local);
         int running = inc - local;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -139,13 +133,16 @@ __device__ inline int select_reg_row(
     };
 #pragma unroll
     for (int pass = 0; pass < 4; ++pass) {
-      const int shift = 24 - 8 * pass, cur = pass & 1;
+      if (hi <= 0) break;                                  // block-uniform
+      const int lo = max(hi - 8, 0), width = hi - lo, cur = pass & 1;
+      const uint32_t dmask = (1u << width) - 1u;
+      const uint32_t top_digit = (kmx >> lo) & dmask;      // pass 0: the largest digit present
       if (TOP8 && pass == 0) {
         unsigned long long acc = 0;                  // 8 counters of 8 bits: digit top_digit - j in byte j
 #pragma unroll
         for (int k = 0; k < KPT; ++k) {
           const int p = c0 + k;
-          const uint32_t o = top_digit - (key[k] >> 24);
+          const uint32_t o = top_digit - ((key[k] >> lo) & dmask);
           if (p >= ca && p < cb && o < 8u) acc += 1ull << (8u * o);
         }
         // widen to 16-bit fields (a wavefront holds at most 64 * 255 keys of one digit) and add up
@@ -164,8 +161,8 @@ __device__ inline int select_reg_row(
 #pragma unroll
         for (int k = 0; k < KPT; ++k) {
           const int p = c0 + k;
-          if (p >= ca && p < cb && (pass == 0 || (key[k] >> (shift + 8)) == prefix))
-            atomicAdd(&s_hist[cur][(key[k] >> shift) & 255u], 1);
+          if (p >= ca && p < cb && (pass == 0 || (key[k] >> hi) == prefix))
+            atomicAdd(&s_hist[cur][(key[k] >> lo) & dmask], 1);
         }
       }
       if (tid < 256) s_hist[cur ^ 1][tid] = 0;
@@ -174,12 +171,14 @@ __device__ inline int select_reg_row(
 #pragma unroll
         for (int k = 0; k < KPT; ++k) {
           const int p = c0 + k;
-          if (p >= ca && p < cb && top_digit - (key[k] >> 24) >= 8u) atomicAdd(&s_hist[0][key[k] >> 24], 1);
+          const uint32_t dg = (key[k] >> lo) & dmask;
+          if (p >= ca && p < cb && top_digit - dg >= 8u) atomicAdd(&s_hist[0][dg], 1);
         }
         find_digit(0);
       }
-      prefix = (prefix << 8) | (uint32_t)s_digit;
+      prefix = (prefix << width) | (uint32_t)s_digit;
       remaining = s_remaining;
+      hi = lo;
     }
   }
   const uint32_t T = prefix;
@@ -196,12 +195,9 @@ __device__ inline int select_reg_row(
     mine += (key[k] > T) ? 1ull : 0ull;
     mine += (key[k] == T) ? (1ull << 32) : 0ull;
   }
-  unsigned long long inc = mine;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const unsigned long long o = __shfl_up(inc, d);
-    if (lane >= d) inc += o;
-  }
+  // the two counts never carry into one another: scan the halves separately
+  const unsigned long long inc = (unsigned long long)(uint32_t)spin_wave_inclusive_scan((int)(uint32_t)mine) |
+                                 ((unsigned long long)(uint32_t)spin_wave_inclusive_scan((int)(mine >> 32)) << 32);
   if (lane == 63) s_wtot[wave] = inc;
   __syncthreads();
   unsigned long long before = inc - mine;
