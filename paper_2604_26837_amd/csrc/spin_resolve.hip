@@ -41,12 +41,7 @@ __global__ __launch_bounds__(RES_BLOCK) void spin_resolve_kernel(
 
 __device__ inline int lru_scan(int v, int *s_wave, int &total) {   // exclusive prefix sum over the workgroup
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const int o = __shfl_up(inc, d);
-    if (lane >= d) inc += o;
-  }
+  const int inc = spin_wave_inclusive_scan(v);
   __syncthreads();
   if (lane == 63) s_wave[wave] = inc;
   __syncthreads();
@@ -167,12 +162,7 @@ __global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_lru_kernel(
     const int t0 = min(tid * per, n_ts), t1 = min(t0 + per, n_ts);
     int local = 0;
     for (int t = t0; t < t1; ++t) local += s_hist[t];
-    int inc = local;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const int o = __shfl_up(inc, d);
-      if (tid >= d) inc += o;
-    }
+    const int inc = spin_wave_inclusive_scan(local);
     int running = inc - local;
     for (int t = t0; t < t1; ++t) {
       if (running < net && running + s_hist[t] >= net) { s_x = t; s_need_x = net - running; }

@@ -7,12 +7,7 @@ template <int RES_BLOCK>
 __device__ inline int res_block_exclusive_scan(int v, int *s_wave, int &total) {
   constexpr int RES_WAVES = RES_BLOCK / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const int o = __shfl_up(inc, d);
-    if (lane >= d) inc += o;
-  }
+  const int inc = spin_wave_inclusive_scan(v);
   __syncthreads();
   if (lane == 63) s_wave[wave] = inc;
   __syncthreads();

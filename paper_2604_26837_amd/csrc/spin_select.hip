@@ -17,12 +17,7 @@
 template <int BLOCK>
 __device__ inline int block_exclusive_scan(int v, int *s_wave, int &total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const int o = __shfl_up(inc, d);
-    if (lane >= d) inc += o;
-  }
+  const int inc = spin_wave_inclusive_scan(v);
   __syncthreads();  // s_wave may still be read from a previous scan
   if (lane == 63) s_wave[wave] = inc;
   __syncthreads();
@@ -380,15 +375,10 @@ __global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
     // the scores in bin D join the list: one counter update per wavefront and batch
     if (__ballot(in_d != 0u)) {
       const int mine = __popc(in_d);
-      int inc = mine;
-#pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
-        const int o = __shfl_up(inc, d);
-        if (lane >= d) inc += o;
-      }
+      const int inc = spin_wave_inclusive_scan(mine);
       int first = 0;
       if (lane == 63) first = atomicAdd(&s_n, inc);
-      int pos = __shfl(first, 63) + inc - mine;
+      int pos = __builtin_amdgcn_readlane(first, 63) + inc - mine;
       if (in_d) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -425,12 +415,7 @@ __global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
         int v4[4], loc = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) { v4[j] = s_h[255 - 4 * lane - j]; loc += v4[j]; }
-        int inc = loc;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-          const int o = __shfl_up(inc, d);
-          if (lane >= d) inc += o;
-        }
+        const int inc = spin_wave_inclusive_scan(loc);
         int run = inc - loc;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -460,12 +445,8 @@ __global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
   const int w0 = min(tid * wpt, W), w1 = min(w0 + wpt, W);
   unsigned long long mine = 0;
   for (int w = w0; w < w1; ++w) mine += (unsigned long long)__popc(s_main[w]) + ((unsigned long long)__popc(s_eq[w]) << 32);
-  unsigned long long inc = mine;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const unsigned long long o = __shfl_up(inc, d);
-    if (lane >= d) inc += o;
-  }
+  const unsigned long long inc = (unsigned long long)(uint32_t)spin_wave_inclusive_scan((int)(uint32_t)mine) |
+                                 ((unsigned long long)(uint32_t)spin_wave_inclusive_scan((int)(mine >> 32)) << 32);
   if (lane == 63) s_wtot[wave] = inc;
   __syncthreads();
   unsigned long long before = inc - mine;
