@@ -11,9 +11,10 @@ __device__ inline uint32_t score_key(float f) {
 }
 
 // Register-resident variant for rows of at most BLOCK * KPT partitions: every
-// thread keeps KPT consecutive keys in registers, so scores are read once; the
-// digit histograms alternate between two LDS buffers, the 256-bin suffix scan
-// is done by one wavefront, and the two compaction prefix sums share one scan.
+// thread keeps KPT consecutive keys in registers, so scores are read once; each
+// digit has its own LDS histogram, every wavefront does the 256-bin suffix scan
+// for itself (one barrier per digit), and the two compaction prefix sums share
+// one scan.
 // COH: read the scores with device-scope loads (they were produced by other
 // workgroups of the same launch).  Returns the number of selected partitions.
 template <int BLOCK, int KPT, bool COH>
@@ -23,9 +24,8 @@ __device__ inline int select_reg_row(
     int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel, int row,
     spin_var var) {
   constexpr int NW = BLOCK / 64;
-  __shared__ int s_hist[2][256];
+  __shared__ int s_hist[4][256];   // one histogram per digit: no buffer is cleared while others read it
   __shared__ unsigned long long s_wtot[NW];
-  __shared__ int s_digit, s_remaining;
 
   const int b = row / Hkv, h = row - b * Hkv;
   const int N = seq_lens[b];
@@ -93,7 +93,7 @@ __device__ inline int select_reg_row(
   constexpr bool TOP8 = KPT >= 16 && KPT <= 255;
   __shared__ uint32_t s_wmax[NW], s_wmin[NW];
   if (kprime > 0) {
-    if (tid < 256) s_hist[0][tid] = 0;
+    for (int i = tid; i < 4 * 256; i += BLOCK) (&s_hist[0][0])[i] = 0;
     uint32_t kmx = 0u, kmn = 0xffffffffu;
 #pragma unroll
     for (int k = 0; k < KPT; ++k) {
@@ -108,33 +108,37 @@ __device__ inline int select_reg_row(
     for (int w = 0; w < NW; ++w) { kmx = max(kmx, s_wmax[w]); kmn = min(kmn, s_wmin[w]); }
     int hi = kmx == kmn ? 0 : 32 - __clz((int)(kmx ^ kmn));   // the low `hi` bits are the ones that vary
     prefix = hi < 32 ? kmx >> hi : 0u;
-    // suffix scan of the 256-bin histogram `cur` by the first wavefront: digit of the
-    // remaining-th largest candidate, or -1 when the histogram holds fewer
-    auto find_digit = [&](int cur) {
+    // Suffix scan of the 256-bin histogram `buf`, done by every wavefront for itself: digit of the
+    // remaining-th largest candidate (and how many are still wanted inside it), or -1 when the
+    // histogram holds fewer.  The result is uniform over the workgroup.
+    auto find_digit = [&](int buf, int &digit) {
       __syncthreads();
-      if (wave == 0) {
-        if (lane == 0) s_digit = -1;   // after the barrier: every thread has read the previous digit
-        // lane handles digits 255-4*lane .. 252-4*lane, in descending order
-        int hv[4], local = 0;
+      // lane handles digits 255-4*lane .. 252-4*lane, in descending order
+      int hv[4], local = 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { hv[j] = s_hist[cur][255 - 4 * lane - j]; local += hv[j]; }
-        const int inc = spin_wave_inclusive_scan(local);
-        int running = inc - local;
+      for (int j = 0; j < 4; ++j) { hv[j] = s_hist[buf][255 - 4 * lane - j]; local += hv[j]; }
+      int running = spin_wave_inclusive_scan(local) - local;
+      int my_digit = -1, my_rem = 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          if (running < remaining && running + hv[j] >= remaining) {
-            s_digit = 255 - 4 * lane - j;
-            s_remaining = remaining - running;
-          }
-          running += hv[j];
+      for (int j = 0; j < 4; ++j) {
+        if (running < remaining && running + hv[j] >= remaining) {
+          my_digit = 255 - 4 * lane - j;
+          my_rem = remaining - running;
         }
+        running += hv[j];
       }
-      __syncthreads();
+      const unsigned long long found = __ballot(my_digit >= 0);
+      digit = -1;
+      if (found) {
+        const int src = __ffsll((long long)found) - 1;
+        digit = __builtin_amdgcn_readlane(my_digit, src);
+        remaining = __builtin_amdgcn_readlane(my_rem, src);
+      }
     };
 #pragma unroll
     for (int pass = 0; pass < 4; ++pass) {
       if (hi <= 0) break;                                  // block-uniform
-      const int lo = max(hi - 8, 0), width = hi - lo, cur = pass & 1;
+      const int lo = max(hi - 8, 0), width = hi - lo;
       const uint32_t dmask = (1u << width) - 1u;
       const uint32_t top_digit = (kmx >> lo) & dmask;      // pass 0: the largest digit present
       if (TOP8 && pass == 0) {
@@ -162,22 +166,22 @@ __device__ inline int select_reg_row(
         for (int k = 0; k < KPT; ++k) {
           const int p = c0 + k;
           if (p >= ca && p < cb && (pass == 0 || (key[k] >> hi) == prefix))
-            atomicAdd(&s_hist[cur][(key[k] >> lo) & dmask], 1);
+            atomicAdd(&s_hist[pass][(key[k] >> lo) & dmask], 1);
         }
       }
-      if (tid < 256) s_hist[cur ^ 1][tid] = 0;
-      find_digit(cur);
-      if (TOP8 && pass == 0 && s_digit < 0) {        // block-uniform: add the digits not counted yet
+      int digit;
+      find_digit(pass, digit);
+      if (TOP8 && pass == 0 && digit < 0) {          // block-uniform: add the digits not counted yet
+        __syncthreads();                             // every wavefront has scanned the partial histogram
 #pragma unroll
         for (int k = 0; k < KPT; ++k) {
           const int p = c0 + k;
           const uint32_t dg = (key[k] >> lo) & dmask;
           if (p >= ca && p < cb && top_digit - dg >= 8u) atomicAdd(&s_hist[0][dg], 1);
         }
-        find_digit(0);
+        find_digit(0, digit);
       }
-      prefix = (prefix << width) | (uint32_t)s_digit;
-      remaining = s_remaining;
+      prefix = (prefix << width) | (uint32_t)digit;
       hi = lo;
     }
   }
