@@ -314,7 +314,7 @@ def main():
     if dec_us:
         ach = kv_bytes / dec_us / 1e3                                  # GB/s
         traffic = read_traffic(os.path.join(ROOT, "profiles", f"{args.workload}_stage_kernels_pmc.txt"))
-        roofline = dict(bound="hbm", kernel="spin_decode_kernel", achieved=round(ach, 1), peak=PEAK_HBM_GBPS,
+        roofline = dict(bound="hbm", kernel="spin_decode_tokens_kernel" if w.partition_tokens < 16 else "spin_decode_kernel", achieved=round(ach, 1), peak=PEAK_HBM_GBPS,
                         unit="GB/s", frac=round(ach / PEAK_HBM_GBPS, 4), traffic=traffic,
                         algorithmic_bytes=kv_bytes, whole_page_bytes=page_bytes, mean_us=dec_us)
 

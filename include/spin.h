@@ -45,6 +45,9 @@
  *              wavefront load is one contiguous 1 KiB transaction:
  *                K[t][d] at element ((d/32)*64 + ((d%32)/8)*16 + t)*8 + d%8
  *                V[t][d] at element ((((d/32)*64 + (t/4)*16 + d%16)*2 + (d/16)%2)*4) + t%4
+ *              With partition_tokens < 16 both tiles are token-major instead, K[t][d]
+ *              and V[t][d] at element t*128 + d of their tile, so that the key and the
+ *              value of one attended token are 256 contiguous bytes each.
  *              Use spin_pack_kv_pages to write pages in this layout.
  * part_offsets int32 [batch+1], prefix sum over requests of their partition
  *              count rounded up to a multiple of 16 (SPIN_PART_ALIGN).  Row

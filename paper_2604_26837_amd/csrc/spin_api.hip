@@ -37,6 +37,7 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   // with variable-length partitions max_context/16 bounds a row's pages and, since a
   // partition owns at least one page, its partitions too
   x->max_parts = c->variable_partitions ? cdiv32(c->max_context, SPIN_PAGE_TOKENS) : cdiv32(c->max_context, tp);
+  x->k_token_major = tp < 16 ? 1 : 0;
   x->pages_per_part = tp >= 16 ? tp / 16 : 0;
   x->parts_per_page = tp < 16 ? 16 / tp : 0;
 

@@ -9,8 +9,9 @@
 // same exact fp64 sum and single rounding as the bulk builder.
 #include "spin_common.h"
 
-__device__ inline size_t k_elem(int t, int d) { return ((size_t)((d >> 5) * 64 + ((d & 31) >> 3) * 16 + t) << 3) + (d & 7); }
-__device__ inline size_t v_elem(int t, int d) {
+__device__ inline size_t k_elem(int token_major, int t, int d) { return ((size_t)spin_k_unit(token_major, t, d >> 3) << 3) + (d & 7); }
+__device__ inline size_t v_elem(int token_major, int t, int d) {
+  if (token_major) return (size_t)t * SPIN_HEAD_DIM + d;
   return (((size_t)((d >> 5) * 64 + (t >> 2) * 16 + (d & 15)) * 2 + ((d >> 4) & 1)) << 2) + (t & 3);
 }
 __device__ inline size_t summ_elem(size_t R, int e, int kd, int kc) {
@@ -27,7 +28,8 @@ __global__ __launch_bounds__(128) void spin_append_kernel(
     const uint16_t *__restrict__ k_new, const uint16_t *__restrict__ v_new, const int32_t *__restrict__ seq_lens,
     uint16_t *pool, int64_t pool_slots, const int32_t *__restrict__ dir, const int32_t *__restrict__ leaf_pool,
     int64_t leaf_chunks, const int32_t *__restrict__ part_offsets, const int32_t *__restrict__ chan,
-    uint16_t *summ, int Hkv, int tp, int kind, int reps, int dir_stride, int leaf_entries, int32_t *status) {
+    uint16_t *summ, int Hkv, int tp, int kind, int reps, int dir_stride, int leaf_entries, int k_token_major,
+    int32_t *status) {
   const int row = blockIdx.x, d = threadIdx.x;
   const int b = row / Hkv, h = row - b * Hkv;
   const int t = seq_lens[b];                 // position of the new token
@@ -45,8 +47,8 @@ __global__ __launch_bounds__(128) void spin_append_kernel(
   uint16_t *page = pool + (size_t)slot * (SPIN_SLOT_U4 * 8);
   const uint16_t kb = k_new[(size_t)row * SPIN_HEAD_DIM + d];
   const uint16_t vb = v_new[(size_t)row * SPIN_HEAD_DIM + d];
-  page[k_elem(t & 15, d)] = kb;
-  page[SPIN_KTILE_U4 * 8 + v_elem(t & 15, d)] = vb;
+  page[k_elem(k_token_major, t & 15, d)] = kb;
+  page[SPIN_KTILE_U4 * 8 + v_elem(k_token_major, t & 15, d)] = vb;
 
   const size_t base = (size_t)Hkv * part_offsets[b] + (size_t)h * PP;
   const bool first_in_part = (t == p * tp);
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(128) void spin_append_kernel(
     for (int u = t0; u < t; ++u) {
       const int32_t s2 = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, u >> 4);
       if (s2 < 0 || (int64_t)s2 >= pool_slots) { spin_raise(status, SPIN_ERR_NOT_RESIDENT); continue; }
-      acc += (double)spin_bf16_to_f32(pool[(size_t)s2 * (SPIN_SLOT_U4 * 8) + k_elem(u & 15, d)]);
+      acc += (double)spin_bf16_to_f32(pool[(size_t)s2 * (SPIN_SLOT_U4 * 8) + k_elem(k_token_major, u & 15, d)]);
     }
     const uint16_t m = f64_to_bf16(acc / (double)(t - t0 + 1));
     const size_t R = (base + p) * reps;
@@ -97,6 +99,6 @@ extern "C" int spin_append_kv(spin_ctx *ctx, int32_t batch, const void *k_new, c
               (const uint16_t *)k_new, (const uint16_t *)v_new, seq_lens, (uint16_t *)kv_pool, pool_slots, dir,
               leaf_pool, leaf_chunks, part_offsets, chan_idx, (uint16_t *)summaries, c.num_kv_heads,
               c.partition_tokens, c.score_kind, c.reps_per_partition, ctx->dir_stride, c.leaf_entries,
-              (int32_t *)workspace);
+              ctx->k_token_major, (int32_t *)workspace);
   return spin_launch_status();
 }

@@ -48,6 +48,7 @@ struct spin_ctx {
   size_t ws_hist_off;     // per-row first-digit histograms of stage 2 for long rows; 0 = not used
   size_t ws_zero_bytes;   // leading part of the workspace that spin_workspace_init clears
   spin_var var;           // registered partition tables (all NULL: uniform partitions)
+  int32_t k_token_major;  // layout of a slot's K tile, see spin_k_unit(): 1 for partitions smaller than a page
   // optional per-kernel timing: pairs of HIP events handed to the launches
   int32_t prof_cap;
   int32_t prof_n[SPIN_KERNEL_IDS];
@@ -161,6 +162,12 @@ template <int CTRL>
 __device__ inline float spin_dpp(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
 }
+// 16-byte unit of (token t, 8-channel chunk ch) inside a slot's K tile.  Partitions of whole pages:
+// chunk-major [chunk][token], the matrix operand's register image (a wavefront load is one
+// contiguous KiB).  Partitions smaller than a page: token-major [token][chunk], a token's key is
+// 256 contiguous bytes, so attending to one token of a page touches two cache lines, not sixteen
+// (the V tile of such a slot is token-major too: the slot is simply K[16][128] then V[16][128]).
+__device__ inline int spin_k_unit(int token_major, int t, int ch) { return token_major ? t * 16 + ch : ch * 16 + t; }
 template <int CTRL>
 __device__ inline int spin_dpp_i(int v) {   // lanes whose source lies outside the row read 0
   return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);

@@ -125,94 +125,17 @@ __device__ inline void write_out(uint16_t *__restrict__ out, float *__restrict__
   if (lse && d == 0) lse[qhead] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f : NEG_INF;
 }
 
-template <int WAVES, int DEPTH>
-__global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
-    const uint16_t *__restrict__ q, const uint4 *__restrict__ pool, int64_t pool_slots,
-    const int32_t *__restrict__ slots, const uint16_t *__restrict__ masks,
-    const int32_t *__restrict__ npages, int page_stride, int G, int Hq, int Hkv, int nsplit,
-    float scale_log2e, float *part_ml, float *part_acc, int32_t *tickets, uint16_t *__restrict__ out,
-    float *__restrict__ lse, int32_t *status) {
+// After a workgroup's wavefronts have consumed their tiles: merge the wavefront partials through
+// LDS and, with several splits, the workgroup partials through the workspace (see the header).
+template <int WAVES>
+__device__ __forceinline__ void decode_finish(softmax_state &st, int row, int split, int b, int h, int lane, int wave,
+                                              int n, int c, int G, int Hq, int nsplit, float *part_ml, float *part_acc,
+                                              int32_t *tickets, uint16_t *__restrict__ out, float *__restrict__ lse) {
   extern __shared__ float smem[];
   float *s_acc = smem;                                  // [WAVES][G][128]
   float *s_m = smem + WAVES * G * SPIN_HEAD_DIM;        // [WAVES][G]
   float *s_l = s_m + WAVES * G;                         // [WAVES][G]
   __shared__ int s_last;
-
-  const int row = blockIdx.x / nsplit;
-  const int split = blockIdx.x - row * nsplit;
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const int n = lane & 15;   // column: query head of the group (logits), channel-in-block (output)
-  const int c = lane >> 4;   // token quad (logits) / head quad (output)
-  const int b = row / Hkv;
-  const int h = row - b * Hkv;
-
-  // Pages are dealt round-robin: page p belongs to split p % nsplit and, inside
-  // it, to wavefront (p / nsplit) % WAVES.  The addresses of this wavefront's
-  // slot entries therefore do not depend on the row's page count, and their
-  // load is issued together with it.
-  const int32_t *rslots = slots + (size_t)row * page_stride;
-  const uint16_t *rmask = masks + (size_t)row * page_stride;
-  const int first = wave * nsplit + split, stride = WAVES * nsplit;
-  int np = npages[row];
-  np = np < 0 ? 0 : (np > page_stride ? page_stride : np);
-
-  // the group's queries as the B operand: column n = head, k = channels 32j+8c..+8
-  spin_bf16x8 qf[4];
-  {
-    const uint4 *qrow = (const uint4 *)(q + ((size_t)(b * Hq + h * G + (n < G ? n : 0))) * SPIN_HEAD_DIM);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      uint4 v = qrow[j * 4 + c];
-      if (n >= G) v = make_uint4(0, 0, 0, 0);
-      qf[j] = __builtin_bit_cast(spin_bf16x8, v);
-    }
-  }
-
-  softmax_state st;
-  st.m = NEG_INF;
-  st.l = 0.f;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) st.acc[i] = (spin_f32x4){0.f, 0.f, 0.f, 0.f};
-
-  // this wavefront's pages: first + i * stride, i < nw
-  const int nw_max = (page_stride - first + stride - 1) / stride;   // entries that exist in the buffer
-  for (int base = 0; base < nw_max; base += 64) {
-    int myslot = 0;
-    unsigned mymask = 0;
-    const int p = first + (base + lane) * stride;
-    if (p < page_stride) {
-      myslot = rslots[p];
-      mymask = rmask[p];
-    }
-    const int nw = np > first ? (np - first + stride - 1) / stride : 0;
-    if (base >= nw) break;
-    const int cnt = (nw - base) < 64 ? (nw - base) : 64;
-    if (lane < cnt) {
-      if (myslot < 0 || (int64_t)myslot >= pool_slots) {
-        spin_raise(status, SPIN_ERR_SLOT_RANGE);
-        myslot = 0;   // read a valid slot, attend to none of it
-        mymask = 0;
-      }
-    }
-    // ring of DEPTH register buffers: DEPTH-1 pages are in flight while one is consumed
-    page_regs r[DEPTH];
-#pragma unroll
-    for (int d = 0; d < DEPTH - 1; ++d)
-      if (d < cnt) load_page(r[d], pool, __builtin_amdgcn_readlane(myslot, d), lane,
-                             (unsigned)__builtin_amdgcn_readlane((int)mymask, d));
-    for (int i = 0; i < cnt; i += DEPTH) {
-#pragma unroll
-      for (int d = 0; d < DEPTH; ++d) {
-        const int ahead = i + d + DEPTH - 1;
-        if (ahead < cnt) load_page(r[(d + DEPTH - 1) % DEPTH], pool, __builtin_amdgcn_readlane(myslot, ahead), lane,
-                                   (unsigned)__builtin_amdgcn_readlane((int)mymask, ahead));
-        if (i + d < cnt)
-          consume_page(st, r[d], qf, (unsigned)__builtin_amdgcn_readlane((int)mymask, i + d), c, scale_log2e);
-      }
-    }
-  }
-
   // denominators: sum the four token-quad lanes of each head
   float l = st.l;
   l += __shfl_xor(l, 16);
@@ -319,6 +242,235 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
     __hip_atomic_store(&tickets[row], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+template <int WAVES, int DEPTH>
+__global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
+    const uint16_t *__restrict__ q, const uint4 *__restrict__ pool, int64_t pool_slots,
+    const int32_t *__restrict__ slots, const uint16_t *__restrict__ masks,
+    const int32_t *__restrict__ npages, int page_stride, int G, int Hq, int Hkv, int nsplit,
+    float scale_log2e, float *part_ml, float *part_acc, int32_t *tickets, uint16_t *__restrict__ out,
+    float *__restrict__ lse, int32_t *status) {
+  const int row = blockIdx.x / nsplit;
+  const int split = blockIdx.x - row * nsplit;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int n = lane & 15;   // column: query head of the group (logits), channel-in-block (output)
+  const int c = lane >> 4;   // token quad (logits) / head quad (output)
+  const int b = row / Hkv;
+  const int h = row - b * Hkv;
+
+  // Pages are dealt round-robin: page p belongs to split p % nsplit and, inside
+  // it, to wavefront (p / nsplit) % WAVES.  The addresses of this wavefront's
+  // slot entries therefore do not depend on the row's page count, and their
+  // load is issued together with it.
+  const int32_t *rslots = slots + (size_t)row * page_stride;
+  const uint16_t *rmask = masks + (size_t)row * page_stride;
+  const int first = wave * nsplit + split, stride = WAVES * nsplit;
+  int np = npages[row];
+  np = np < 0 ? 0 : (np > page_stride ? page_stride : np);
+
+  // the group's queries as the B operand: column n = head, k = channels 32j+8c..+8
+  spin_bf16x8 qf[4];
+  {
+    const uint4 *qrow = (const uint4 *)(q + ((size_t)(b * Hq + h * G + (n < G ? n : 0))) * SPIN_HEAD_DIM);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint4 v = qrow[j * 4 + c];
+      if (n >= G) v = make_uint4(0, 0, 0, 0);
+      qf[j] = __builtin_bit_cast(spin_bf16x8, v);
+    }
+  }
+
+  softmax_state st;
+  st.m = NEG_INF;
+  st.l = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) st.acc[i] = (spin_f32x4){0.f, 0.f, 0.f, 0.f};
+
+  // this wavefront's pages: first + i * stride, i < nw
+  const int nw_max = (page_stride - first + stride - 1) / stride;   // entries that exist in the buffer
+  for (int base = 0; base < nw_max; base += 64) {
+    int myslot = 0;
+    unsigned mymask = 0;
+    const int p = first + (base + lane) * stride;
+    if (p < page_stride) {
+      myslot = rslots[p];
+      mymask = rmask[p];
+    }
+    const int nw = np > first ? (np - first + stride - 1) / stride : 0;
+    if (base >= nw) break;
+    const int cnt = (nw - base) < 64 ? (nw - base) : 64;
+    if (lane < cnt) {
+      if (myslot < 0 || (int64_t)myslot >= pool_slots) {
+        spin_raise(status, SPIN_ERR_SLOT_RANGE);
+        myslot = 0;   // read a valid slot, attend to none of it
+        mymask = 0;
+      }
+    }
+    // ring of DEPTH register buffers: DEPTH-1 pages are in flight while one is consumed
+    page_regs r[DEPTH];
+#pragma unroll
+    for (int d = 0; d < DEPTH - 1; ++d)
+      if (d < cnt) load_page(r[d], pool, __builtin_amdgcn_readlane(myslot, d), lane,
+                             (unsigned)__builtin_amdgcn_readlane((int)mymask, d));
+    for (int i = 0; i < cnt; i += DEPTH) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        const int ahead = i + d + DEPTH - 1;
+        if (ahead < cnt) load_page(r[(d + DEPTH - 1) % DEPTH], pool, __builtin_amdgcn_readlane(myslot, ahead), lane,
+                                   (unsigned)__builtin_amdgcn_readlane((int)mymask, ahead));
+        if (i + d < cnt)
+          consume_page(st, r[d], qf, (unsigned)__builtin_amdgcn_readlane((int)mymask, i + d), c, scale_log2e);
+      }
+    }
+  }
+
+  decode_finish<WAVES>(st, row, split, b, h, lane, wave, n, c, G, Hq, nsplit, part_ml, part_acc, tickets, out, lse);
+}
+
+// ---------------------------------------------------------------------------
+// Partitions smaller than a page (token-major slots): most attended pages hold one or two
+// attended tokens, so a tile is not a physical page but 16 ATTENDED tokens gathered from
+// wherever they live.  A wavefront expands the masks of its pages (dealt round-robin exactly as
+// above) into a token list in LDS -- page order, then token order, so the accumulation order is
+// fixed -- and then treats every 16 list entries as one tile: lane (n, c) fetches 64 contiguous
+// bytes of the key of tile row n per load, and the values of tile rows 4c .. 4c+3 for its 8
+// output channels with 2-byte loads that land in the operand layout of P V directly.  Per
+// attended token that is the algorithmic 512 bytes (two cache lines of K, two of V) instead of
+// the page's 8 KiB, and sixteen times fewer matrix tiles.  Logits, softmax and merge are the
+// code of the page kernel.
+#define TOK_LIST 1024   // list entries per wavefront and batch of 64 pages
+
+struct tile_src {
+  const uint4 *k;           // key row of tile row n (lane % 16), chunk c (lane / 16): + 4 j
+  const uint16_t *v[4];     // value rows of tile rows 4c .. 4c+3 at channel n: + 16 jn
+};
+
+// Rows past the end of the list repeat its last entry: their loads stay inside attended data, their
+// logits are masked and their probabilities are exactly zero.
+__device__ inline tile_src tile_source(const uint4 *__restrict__ pool, const uint32_t *tok, int first, int count, int lane) {
+  tile_src s;
+  const int n = lane & 15, c = lane >> 4;
+  const int last = count - 1 - first;                    // >= 0: the tile exists
+  const uint32_t e = tok[first + min(n, last)];          // slot * 16 + token
+  s.k = pool + (size_t)(e >> 4) * SPIN_SLOT_U4 + (e & 15u) * 16 + c;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t ev = tok[first + min(4 * c + i, last)];
+    s.v[i] = (const uint16_t *)(pool + (size_t)(ev >> 4) * SPIN_SLOT_U4 + SPIN_KTILE_U4) + (ev & 15u) * SPIN_HEAD_DIM + n;
+  }
+  return s;
+}
+
+__device__ inline void load_tile(page_regs &r, const tile_src &s) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) r.k[j] = spin_nt_load(s.k + 4 * j);
+  // operand layout of P V: r.v[jv] = {rows 4c,4c+1 | rows 4c+2,4c+3} for channel block 2jv, then 2jv+1.
+  // Each 16-bit load lands in its half of an operand register, so nothing waits for the data
+  // before the tile is consumed.
+  typedef unsigned short us8 __attribute__((ext_vector_type(8)));
+#pragma unroll
+  for (int jv = 0; jv < 4; ++jv) {
+    us8 w;
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) w[4 * blk + i] = s.v[i][16 * (2 * jv + blk)];
+    r.v[jv] = __builtin_bit_cast(uint4, w);
+  }
+}
+
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void spin_decode_tokens_kernel(
+    const uint16_t *__restrict__ q, const uint4 *__restrict__ pool, int64_t pool_slots,
+    const int32_t *__restrict__ slots, const uint16_t *__restrict__ masks,
+    const int32_t *__restrict__ npages, int page_stride, int G, int Hq, int Hkv, int nsplit,
+    float scale_log2e, float *part_ml, float *part_acc, int32_t *tickets, uint16_t *__restrict__ out,
+    float *__restrict__ lse, int32_t *status) {
+  extern __shared__ float smem[];
+  // the token lists live behind the merge buffers of decode_finish
+  uint32_t *tok = (uint32_t *)(smem + WAVES * G * (SPIN_HEAD_DIM + 2)) + (threadIdx.x >> 6) * TOK_LIST;
+
+  const int row = blockIdx.x / nsplit;
+  const int split = blockIdx.x - row * nsplit;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int n = lane & 15, c = lane >> 4;
+  const int b = row / Hkv;
+  const int h = row - b * Hkv;
+  const int32_t *rslots = slots + (size_t)row * page_stride;
+  const uint16_t *rmask = masks + (size_t)row * page_stride;
+  const int first = wave * nsplit + split, stride = WAVES * nsplit;
+  int np = npages[row];
+  np = np < 0 ? 0 : (np > page_stride ? page_stride : np);
+
+  spin_bf16x8 qf[4];
+  {
+    const uint4 *qrow = (const uint4 *)(q + ((size_t)(b * Hq + h * G + (n < G ? n : 0))) * SPIN_HEAD_DIM);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint4 v = qrow[j * 4 + c];
+      if (n >= G) v = make_uint4(0, 0, 0, 0);
+      qf[j] = __builtin_bit_cast(spin_bf16x8, v);
+    }
+  }
+  softmax_state st;
+  st.m = NEG_INF;
+  st.l = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) st.acc[i] = (spin_f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const int nw_max = (page_stride - first + stride - 1) / stride;
+  for (int base = 0; base < nw_max; base += 64) {
+    int myslot = 0;
+    unsigned mymask = 0;
+    const int p = first + (base + lane) * stride;
+    if (p < page_stride) {
+      myslot = rslots[p];
+      mymask = rmask[p];
+    }
+    const int nw = np > first ? (np - first + stride - 1) / stride : 0;
+    if (base >= nw) break;
+    const int cnt = (nw - base) < 64 ? (nw - base) : 64;
+    if (lane >= cnt) mymask = 0;
+    else if (myslot < 0 || (int64_t)myslot >= pool_slots) {
+      spin_raise(status, SPIN_ERR_SLOT_RANGE);
+      myslot = 0;
+      mymask = 0;
+    }
+    // token list of this batch of pages: page order, then token order
+    const int mine = __popc(mymask);
+    const int incl = spin_wave_inclusive_scan(mine);
+    const int total = __builtin_amdgcn_readlane(incl, 63);
+    {
+      int pos = incl - mine;
+      unsigned m = mymask;
+      while (m) {
+        const int t = __ffs(m) - 1;
+        m &= m - 1;
+        tok[pos++] = ((uint32_t)myslot << 4) | (uint32_t)t;
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the wavefront reads its own list: program order
+    // two register buffers: the next tile's loads are issued before the current one is consumed
+    page_regs r[2];
+    const int ntiles = (total + 15) >> 4;
+    if (ntiles > 0) load_tile(r[0], tile_source(pool, tok, 0, total, lane));
+    for (int k = 0; k < ntiles; k += 2) {
+      if (k + 1 < ntiles) load_tile(r[1], tile_source(pool, tok, 16 * (k + 1), total, lane));
+      const int left0 = total - 16 * k;
+      consume_page(st, r[0], qf, left0 >= 16 ? 0xffffu : ((1u << left0) - 1u), c, scale_log2e);
+      if (k + 2 < ntiles) load_tile(r[0], tile_source(pool, tok, 16 * (k + 2), total, lane));
+      if (k + 1 < ntiles) {
+        const int left1 = total - 16 * (k + 1);
+        consume_page(st, r[1], qf, left1 >= 16 ? 0xffffu : ((1u << left1) - 1u), c, scale_log2e);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // before the next batch overwrites the list
+  }
+  __syncthreads();   // the merge buffers are separate from the lists, but keep the phases apart
+  decode_finish<WAVES>(st, row, split, b, h, lane, wave, n, c, G, Hq, nsplit, part_ml, part_acc, tickets, out, lse);
+}
+
 extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool,
                                   int64_t pool_slots, const int32_t *slots, const uint16_t *valid_mask,
                                   const int32_t *npages, void *out, float *lse, void *workspace,
@@ -336,6 +488,15 @@ extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, c
   const float scale_log2e = ctx->scale * 1.4426950408889634f;
   const int W = ctx->waves;
   const size_t lds = (size_t)W * G * (SPIN_HEAD_DIM + 2) * sizeof(float);
+  if (ctx->k_token_major) {
+    // token-major slots: tiles of gathered tokens (8 wavefronts; the depth knob does not apply)
+    const size_t lds_tok = lds + (size_t)8 * TOK_LIST * sizeof(uint32_t);
+    spin_launch(ctx, SPIN_K_DECODE, spin_decode_tokens_kernel<8>, dim3((unsigned)(rows * nsplit)), dim3(512), lds_tok,
+                (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, slots, valid_mask, npages,
+                ctx->page_stride, G, ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, scale_log2e, part_ml,
+                part_acc, tickets, (uint16_t *)out, lse, (int32_t *)workspace);
+    return spin_launch_status();
+  }
 #define SPIN_DECODE_LAUNCH2(WV, DP)                                                                              \
   spin_launch(ctx, SPIN_K_DECODE, spin_decode_kernel<WV, DP>, dim3((unsigned)(rows * nsplit)), dim3(WV * 64), lds, \
               (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, slots, valid_mask,   \

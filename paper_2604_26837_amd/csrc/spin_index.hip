@@ -18,7 +18,7 @@ __global__ __launch_bounds__(256) void spin_index_minmax_kernel(
     const uint4 *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
     const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int dir_stride, int leaf_entries, int max_tiles,
-    uint16_t *__restrict__ summ, int32_t *status) {
+    uint16_t *__restrict__ summ, int32_t *status, int k_token_major) {
   const int row = blockIdx.x / max_tiles, tile = blockIdx.x - row * max_tiles;
   const int b = row / Hkv, h = row - b * Hkv;
   const int PP = part_offsets[b + 1] - part_offsets[b];
@@ -37,10 +37,10 @@ __global__ __launch_bounds__(256) void spin_index_minmax_kernel(
     for (int pg = t0 >> 4; pg <= (t1 - 1) >> 4; ++pg) {
       const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
       if (slot < 0 || (int64_t)slot >= pool_slots) { spin_raise(status, SPIN_ERR_NOT_RESIDENT); continue; }
-      const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + ch * 16;
+      const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4;
       const int a = max(t0 - pg * 16, 0), e = min(t1 - pg * 16, 16);
       for (int t = a; t < e; ++t) {
-        const uint4 v = kt[t];
+        const uint4 v = kt[spin_k_unit(k_token_major, t, ch)];
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256) void spin_index_repmean_kernel(
     const uint4 *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
     const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int reps, int dir_stride, int leaf_entries,
-    int max_tiles, uint16_t *__restrict__ summ, int32_t *status) {
+    int max_tiles, uint16_t *__restrict__ summ, int32_t *status, int k_token_major) {
   const int row = blockIdx.x / max_tiles, tile = blockIdx.x - row * max_tiles;
   const int b = row / Hkv, h = row - b * Hkv;
   const int PP = part_offsets[b + 1] - part_offsets[b];
@@ -197,10 +197,10 @@ __global__ __launch_bounds__(256) void spin_index_repmean_kernel(
     for (int pg = t0 >> 4; pg <= (t1 - 1) >> 4; ++pg) {
       const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
       if (slot < 0 || (int64_t)slot >= pool_slots) { spin_raise(status, SPIN_ERR_NOT_RESIDENT); continue; }
-      const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + ch * 16;
+      const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4;
       const int a = max(t0 - pg * 16, 0), e = min(t1 - pg * 16, 16);
       for (int t = a; t < e; ++t) {
-        const uint4 v = kt[t];
+        const uint4 v = kt[spin_k_unit(k_token_major, t, ch)];
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -305,7 +305,7 @@ __global__ __launch_bounds__(256) void spin_index_sketch_kernel(
     const uint16_t *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
     const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ chan, int Hkv, int dir_stride,
-    int leaf_entries, int max_blocks, uint16_t *__restrict__ summ, int32_t *status) {
+    int leaf_entries, int max_blocks, uint16_t *__restrict__ summ, int32_t *status, int k_token_major) {
   const int row = blockIdx.x / max_blocks, blk = blockIdx.x - row * max_blocks;
   const int b = row / Hkv, h = row - b * Hkv;
   const int PP = part_offsets[b + 1] - part_offsets[b];
@@ -324,7 +324,7 @@ __global__ __launch_bounds__(256) void spin_index_sketch_kernel(
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int d = chan[h * 16 + cq * 4 + i];
-        e[i] = kt[(((d >> 5) * 64 + ((d & 31) >> 3) * 16 + (t & 15)) << 3) + (d & 7)];
+        e[i] = kt[(spin_k_unit(k_token_major, t & 15, d >> 3) << 3) + (d & 7)];
       }
     }
   }
@@ -360,7 +360,7 @@ extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv
     hipLaunchKernelGGL(spin_index_minmax_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
                        (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
                        c.num_kv_heads, c.partition_tokens, ctx->dir_stride, c.leaf_entries, max_tiles,
-                       (uint16_t *)summaries, status);
+                       (uint16_t *)summaries, status, ctx->k_token_major);
   } else if (c.score_kind == SPIN_SCORE_REPMAX) {
     const int max_tiles = max_pp * c.reps_per_partition / 16;
     if ((c.partition_tokens / c.reps_per_partition) % 16 == 0)
@@ -372,7 +372,7 @@ extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv
       spin_launch(ctx, SPIN_K_INDEX, spin_index_repmean_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
                   (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
                   c.num_kv_heads, c.partition_tokens, c.reps_per_partition, ctx->dir_stride, c.leaf_entries,
-                  max_tiles, (uint16_t *)summaries, status);
+                  max_tiles, (uint16_t *)summaries, status, ctx->k_token_major);
   } else {
     if (!chan_idx) return SPIN_ERR_INVALID;
     if (c.partition_tokens != 1) return SPIN_ERR_UNSUPPORTED;
@@ -380,7 +380,7 @@ extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv
     hipLaunchKernelGGL(spin_index_sketch_kernel, dim3((unsigned)rows * max_blocks), dim3(256), 0, st,
                        (const uint16_t *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
                        chan_idx, c.num_kv_heads, ctx->dir_stride, c.leaf_entries, max_blocks,
-                       (uint16_t *)summaries, status);
+                       (uint16_t *)summaries, status, ctx->k_token_major);
   }
   return spin_launch_status();
 }
