@@ -356,7 +356,11 @@ int spin_offload_pages(spin_ctx *ctx, int32_t batch, const void *kv_pool, int64_
  * softmax(scale * q K_S^T) V_S over the tokens whose mask bit is set in the
  * row's resolved pages; fp32 online softmax, split over the page list and
  * merged in a fixed order.  lse (DEVICE fp32 [batch][num_q_heads], natural log;
- * may be NULL).  A row with no valid token gives out = 0, lse = -inf. */
+ * may be NULL).  A row with no valid token gives out = 0, lse = -inf.
+ * Only the bytes of attended tokens are fetched: a page with a partial mask
+ * loads the K rows and V quads its mask names; with partition_tokens < 16
+ * (token-major slots) the attended tokens of all pages are gathered 16 at a
+ * time into one matrix tile, 512 bytes per token. */
 int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool,
                        int64_t pool_slots, const int32_t *slots, const uint16_t *valid_mask,
                        const int32_t *npages, void *out, float *lse, void *workspace,
