@@ -9,8 +9,7 @@
 // pages owns the output entry and ORs the run's token ranges.
 #include "spin_resolve_dev.h"
 
-#define RES_BLOCK 256
-
+template <int RES_BLOCK>
 __global__ __launch_bounds__(RES_BLOCK) void spin_resolve_kernel(
     const int32_t *__restrict__ sel, const int32_t *__restrict__ nsel, const int32_t *__restrict__ seq_lens,
     const int32_t *dir, const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, int Hkv, int tp,
@@ -510,9 +509,15 @@ extern "C" int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, co
                 miss_slots, nmiss, (int32_t *)workspace);
     return spin_launch_status();
   }
-  spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_kernel, dim3((unsigned)rows), dim3(RES_BLOCK), 0, (hipStream_t)stream, sel, nsel,
-                     seq_lens, dir, leaf_pool, leaf_chunks, c.num_kv_heads, c.partition_tokens, c.sink_pages,
-                     c.recent_pages, ctx->sel_stride, ctx->page_stride, ctx->dir_stride, c.leaf_entries, slots,
-                     page_ids, valid_mask, npages, (int32_t *)workspace, ctx->var);
+  // long selections (token partitions) get a workgroup that covers them in one sweep
+#define SPIN_RESOLVE_ARGS                                                                                       \
+  0, (hipStream_t)stream, sel, nsel, seq_lens, dir, leaf_pool, leaf_chunks, c.num_kv_heads, c.partition_tokens, \
+      c.sink_pages, c.recent_pages, ctx->sel_stride, ctx->page_stride, ctx->dir_stride, c.leaf_entries, slots,  \
+      page_ids, valid_mask, npages, (int32_t *)workspace, ctx->var
+  if (ctx->sel_stride > 512)
+    spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_kernel<1024>, dim3((unsigned)rows), dim3(1024), SPIN_RESOLVE_ARGS);
+  else
+    spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_kernel<256>, dim3((unsigned)rows), dim3(256), SPIN_RESOLVE_ARGS);
+#undef SPIN_RESOLVE_ARGS
   return spin_launch_status();
 }
