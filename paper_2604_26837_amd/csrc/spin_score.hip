@@ -45,6 +45,15 @@ __global__ __launch_bounds__(SCORE_WAVES * 64) void spin_score_sketch_kernel(
   const int n = lane & 15, c = lane >> 4;
   const size_t base = (size_t)Hkv * part_offsets[b] + (size_t)h * PP;
 
+  const uint2 *tiles = summ + base * 4;   // 16 elements = 4 units of 8 bytes per row
+  constexpr int U = 8;
+  // the first batch of tiles is requested before the query gather below (two dependent loads)
+  // has to be waited for
+  int t0 = t_begin + wave * U;
+  uint2 a[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) a[u] = (t0 + u < t_end) ? tiles[(size_t)(t0 + u) * 64 + lane] : make_uint2(0, 0);
+
   // A operand: row n = head, k = sketched channels 4c..4c+3
   spin_s16x4 qf;
   {
@@ -55,12 +64,12 @@ __global__ __launch_bounds__(SCORE_WAVES * 64) void spin_score_sketch_kernel(
     uint2 pk = make_uint2(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16));
     qf = __builtin_bit_cast(spin_s16x4, pk);
   }
-  const uint2 *tiles = summ + base * 4;   // 16 elements = 4 units of 8 bytes per row
-  constexpr int U = 8;
-  for (int t0 = t_begin + wave * U; t0 < t_end; t0 += SCORE_WAVES * U) {
-    uint2 a[U];
+  for (; t0 < t_end; t0 += SCORE_WAVES * U) {
+    // the next batch is in flight while this one is consumed
+    uint2 nx[U];
+    const int t1 = t0 + SCORE_WAVES * U;
 #pragma unroll
-    for (int u = 0; u < U; ++u) a[u] = (t0 + u < t_end) ? tiles[(size_t)(t0 + u) * 64 + lane] : make_uint2(0, 0);
+    for (int u = 0; u < U; ++u) nx[u] = (t1 + u < t_end) ? tiles[(size_t)(t1 + u) * 64 + lane] : make_uint2(0, 0);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (t0 + u >= t_end) break;
@@ -69,6 +78,8 @@ __global__ __launch_bounds__(SCORE_WAVES * 64) void spin_score_sketch_kernel(
       const float m = spin_head_max(s, c, G);   // lane (n, c): heads 4c+i of token n
       if (c == 0) scores[base + (size_t)(t0 + u) * 16 + n] = m;
     }
+#pragma unroll
+    for (int u = 0; u < U; ++u) a[u] = nx[u];
   }
 }
 
