@@ -194,12 +194,4 @@ __device__ inline uint32_t spin_wave_max_u32(uint32_t v) {
              max((uint32_t)__builtin_amdgcn_readlane((int)v, 32), (uint32_t)__builtin_amdgcn_readlane((int)v, 48)));
 }
 __device__ inline uint32_t spin_wave_min_u32(uint32_t v) { return ~spin_wave_max_u32(~v); }
-// maximum over the 16 lanes of a row, result in every lane
-__device__ inline float spin_row16_max(float v) {
-  v = fmaxf(v, spin_dpp<SPIN_DPP_XOR1>(v));
-  v = fmaxf(v, spin_dpp<SPIN_DPP_XOR2>(v));
-  v = fmaxf(v, spin_dpp<SPIN_DPP_HALF_MIRROR>(v));
-  v = fmaxf(v, spin_dpp<SPIN_DPP_MIRROR>(v));
-  return v;
-}
 #endif

@@ -22,13 +22,6 @@
 
 #define NEG_INF (-__builtin_inff())
 
-__device__ inline void dev_store(float *p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline float dev_load(const float *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 struct page_regs {
   uint4 k[4], v[4];
 };
@@ -174,10 +167,10 @@ __device__ __forceinline__ void decode_finish(softmax_state &st, int row, int sp
     } else {
       // device-scope stores: written through to where every compute die sees them
       const size_t pi = ((size_t)row * nsplit + split) * G + g;
-      dev_store(&part_acc[pi * SPIN_HEAD_DIM + d], O);
+      spin_dev_store(&part_acc[pi * SPIN_HEAD_DIM + d], O);
       if (d == 0) {
-        dev_store(&part_ml[pi * 2 + 0], M);
-        dev_store(&part_ml[pi * 2 + 1], L);
+        spin_dev_store(&part_ml[pi * 2 + 0], M);
+        spin_dev_store(&part_ml[pi * 2 + 1], L);
       }
     }
   }
@@ -207,11 +200,11 @@ __device__ __forceinline__ void decode_finish(softmax_state &st, int row, int sp
 #pragma unroll
     for (int s = 0; s < CH; ++s)
       a0[s] = (threadIdx.x < G * SPIN_HEAD_DIM && s < nsplit)
-                  ? dev_load(&part_acc[(pbase + (size_t)s * G + g) * SPIN_HEAD_DIM + d]) : 0.f;
+                  ? spin_dev_load(&part_acc[(pbase + (size_t)s * G + g) * SPIN_HEAD_DIM + d]) : 0.f;
   }
   for (int i = threadIdx.x; i < nsplit * G; i += WAVES * 64) {
-    t_m[i] = dev_load(&part_ml[(pbase + i) * 2]);
-    t_l[i] = dev_load(&part_ml[(pbase + i) * 2 + 1]);
+    t_m[i] = spin_dev_load(&part_ml[(pbase + i) * 2]);
+    t_l[i] = spin_dev_load(&part_ml[(pbase + i) * 2 + 1]);
   }
   __syncthreads();
   for (int idx = threadIdx.x; idx < G * SPIN_HEAD_DIM; idx += WAVES * 64) {
@@ -225,7 +218,7 @@ __device__ __forceinline__ void decode_finish(softmax_state &st, int row, int sp
 #pragma unroll
       for (int s = 0; s < CH; ++s) {
         if (idx == (int)threadIdx.x && s0 == 0) a[s] = a0[s];
-        else a[s] = (s0 + s < nsplit) ? dev_load(&part_acc[(pbase + (size_t)(s0 + s) * G + g) * SPIN_HEAD_DIM + d]) : 0.f;
+        else a[s] = (s0 + s < nsplit) ? spin_dev_load(&part_acc[(pbase + (size_t)(s0 + s) * G + g) * SPIN_HEAD_DIM + d]) : 0.f;
       }
 #pragma unroll
       for (int s = 0; s < CH; ++s) {

@@ -25,7 +25,7 @@ __global__ __launch_bounds__(WAVES * 64) void spin_score_k32_kernel(
     const uint16_t *__restrict__ q, const uint4 *__restrict__ summ, const int32_t *__restrict__ part_offsets,
     int Hq, int Hkv, int G, int rows_per_part, int tiles_per_wg, int wgs_per_row, float *__restrict__ scores) {
   const int row = blockIdx.x / wgs_per_row, chunk = blockIdx.x - row * wgs_per_row;
-  score_row_tiles<NJ, MINMAX, WAVES, false>(q, summ, part_offsets, Hq, Hkv, G, rows_per_part, tiles_per_wg, row, chunk,
+  score_row_tiles<NJ, MINMAX, WAVES>(q, summ, part_offsets, Hq, Hkv, G, rows_per_part, tiles_per_wg, row, chunk,
                                             scores);
 }
 

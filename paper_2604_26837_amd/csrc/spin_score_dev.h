@@ -38,7 +38,7 @@ __device__ inline float spin_head_max(const spin_f32x4 &s, int c, int G) {
   return m;
 }
 
-template <int NJ, bool MINMAX, bool COH>
+template <int NJ, bool MINMAX>
 __device__ inline void consume_tile(const score_tile<NJ> &r, const spin_bf16x8 (&qf)[NJ], int n, int c, int G,
                                     float *__restrict__ scores, size_t base, int t) {
   // the queries are the A operand, the summary rows the B operand: lane (n, c) ends up with
@@ -51,25 +51,21 @@ __device__ inline void consume_tile(const score_tile<NJ> &r, const spin_bf16x8 (
   float m = spin_head_max(s, c, G);
   if (MINMAX) {
     if (c == 0) {
-      float *o = scores + base + (size_t)t * 16 + n;
-      if (COH) spin_dev_store(o, m);
-      else *o = m;
+      scores[base + (size_t)t * 16 + n] = m;
     }
   } else {
     // rows 4p..4p+3 are the four representatives of partition 4t + p: lanes n = 4p .. 4p+3
     m = fmaxf(m, spin_dpp<SPIN_DPP_XOR1>(m));
     m = fmaxf(m, spin_dpp<SPIN_DPP_XOR2>(m));
     if (c == 0 && (n & 3) == 0) {
-      if (COH) spin_dev_store(&scores[base + (size_t)t * 4 + (n >> 2)], m);
-      else scores[base + (size_t)t * 4 + (n >> 2)] = m;
+      scores[base + (size_t)t * 4 + (n >> 2)] = m;
     }
   }
 }
 
 // Scores the tiles [chunk*tiles_per_wg, +tiles_per_wg) of one row with the calling
-// workgroup (WAVES wavefronts).  COH: store scores with device-scope stores so a
-// workgroup on another compute die can read them within the same launch.
-template <int NJ, bool MINMAX, int WAVES, bool COH>
+// workgroup (WAVES wavefronts).
+template <int NJ, bool MINMAX, int WAVES>
 __device__ inline void score_row_tiles(
     const uint16_t *__restrict__ q, const uint4 *__restrict__ summ, const int32_t *__restrict__ part_offsets,
     int Hq, int Hkv, int G, int rows_per_part, int tiles_per_wg, int row, int chunk, float *__restrict__ scores) {
@@ -108,9 +104,9 @@ __device__ inline void score_row_tiles(
   for (; t < t_end; t += 2 * WAVES) {
     const int t1 = t + WAVES, t2 = t + 2 * WAVES;
     if (t1 < t_end) load_tile<NJ>(rb, tiles + (size_t)t1 * (NJ * 64), lane);
-    consume_tile<NJ, MINMAX, COH>(ra, qf, n, c, G, scores, base, t);
+    consume_tile<NJ, MINMAX>(ra, qf, n, c, G, scores, base, t);
     if (t2 < t_end) load_tile<NJ>(ra, tiles + (size_t)t2 * (NJ * 64), lane);
-    if (t1 < t_end) consume_tile<NJ, MINMAX, COH>(rb, qf, n, c, G, scores, base, t1);
+    if (t1 < t_end) consume_tile<NJ, MINMAX>(rb, qf, n, c, G, scores, base, t1);
   }
 }
 

@@ -145,7 +145,7 @@ __global__ __launch_bounds__(BLOCK) void spin_select_reg_kernel(
     const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
     int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel, spin_var var) {
-  (void)select_reg_row<BLOCK, KPT, false>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced, sink_pages,
+  (void)select_reg_row<BLOCK, KPT>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced, sink_pages,
                                           recent_pages, sel_stride, sel, nsel, (int)blockIdx.x, var);
 }
 
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
     // heavy ties in the threshold bin (or a histogram that does not cover the row): multi-pass algorithms
     if (P <= BIG_BLOCK * 64) {
       spin_var none = {};
-      (void)select_reg_row<BIG_BLOCK, 64, false>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced, sink_pages,
+      (void)select_reg_row<BIG_BLOCK, 64>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced, sink_pages,
                                                  recent_pages, sel_stride, sel, nsel, row, none);
     } else {
       select_generic_row<BIG_BLOCK>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced, sink_pages,

@@ -15,9 +15,8 @@ __device__ inline uint32_t score_key(float f) {
 // digit has its own LDS histogram, every wavefront does the 256-bin suffix scan
 // for itself (one barrier per digit), and the two compaction prefix sums share
 // one scan.
-// COH: read the scores with device-scope loads (they were produced by other
-// workgroups of the same launch).  Returns the number of selected partitions.
-template <int BLOCK, int KPT, bool COH>
+// Returns the number of selected partitions.
+template <int BLOCK, int KPT>
 __device__ inline int select_reg_row(
     const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
@@ -46,11 +45,7 @@ __device__ inline int select_reg_row(
 #pragma unroll
   for (int k4 = 0; k4 < KPT; k4 += 4) {
     float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (c0 + k4 < PP) {
-      if (COH) f = make_float4(spin_dev_load(rs + c0 + k4), spin_dev_load(rs + c0 + k4 + 1),
-                               spin_dev_load(rs + c0 + k4 + 2), spin_dev_load(rs + c0 + k4 + 3));
-      else f = *(const float4 *)(rs + c0 + k4);
-    }
+    if (c0 + k4 < PP) f = *(const float4 *)(rs + c0 + k4);
     key[k4] = score_key(f.x); key[k4 + 1] = score_key(f.y); key[k4 + 2] = score_key(f.z); key[k4 + 3] = score_key(f.w);
   }
 

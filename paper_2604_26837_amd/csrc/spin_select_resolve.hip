@@ -15,7 +15,7 @@ __global__ __launch_bounds__(BLOCK) void spin_select_resolve_kernel(
     int32_t *__restrict__ slots, int32_t *__restrict__ page_ids, uint16_t *__restrict__ valid_mask,
     int32_t *__restrict__ npages, int32_t *status, spin_var var) {
   const int row = blockIdx.x;
-  const int take = select_reg_row<BLOCK, KPT, false>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced,
+  const int take = select_reg_row<BLOCK, KPT>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced,
                                                      sink_pages, recent_pages, sel_stride, sel, nsel, row, var);
   __syncthreads();   // the selection was written by this workgroup: visible to all its threads from here
   resolve_row<BLOCK>(row, take, sel, seq_lens, dir, leaf_pool, leaf_chunks, Hkv, tp, sink_pages, recent_pages,
