@@ -263,6 +263,19 @@ def main():
         torch.cuda.synchronize()
         us_per_step_other = (time.perf_counter() - t0) * 1e6 / args.steps
 
+    # --- spread of the step time: the same K steps with a stream event between consecutive steps
+    # (no host synchronisation inside; the event records cost a little, so `value` stays the
+    # figure of the plain run above)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    evs[0].record()
+    for i in range(args.steps):
+        run(i)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(args.steps))
+    pct = lambda f: round(per_step[min(int(f * len(per_step)), len(per_step) - 1)], 2)
+    step_spread = dict(p10=pct(0.10), median=pct(0.50), p90=pct(0.90), note="stream events between steps")
+
     # --- the same K steps again with every kernel bracketed by HIP events on the
     # launch stream (start/stop timestamps of the kernel itself); the bracketing
     # slows the step down, so it is kept out of `value`
@@ -364,6 +377,7 @@ def main():
         "step_launches": "four stage calls" if args.four_calls else "score, select+resolve, attention (3 launches)",
         ("us_per_layer_three_launches" if args.four_calls else "us_per_layer_four_calls"): round(us_per_step_other, 2) if us_per_step_other else None,
         "us_per_layer_with_kernel_events": round(us_per_step_events, 2) if us_per_step_events else None,
+        "us_per_layer_spread": step_spread,
         "kernel_us_sum": round(sum(k["mean_us"] for k in kernels.values()), 2) if kernels else None,
         "kernels": kernels,
         "score_gbps": round(score_bytes / sc_us / 1e3, 1) if sc_us else None,
