@@ -45,6 +45,8 @@ def parse_args():
     ap.add_argument("--decode-splits", type=int, default=0, help="split-K factor of the attention kernel (0: library default)")
     ap.add_argument("--decode-waves", type=int, default=0, help="wavefronts per attention workgroup (0: library default)")
     ap.add_argument("--decode-depth", type=int, default=0, help="page buffers per attention wavefront (0: library default)")
+    ap.add_argument("--score-waves", type=int, default=0, help="wavefronts per stage-1 workgroup (0: library default)")
+    ap.add_argument("--score-tiles", type=int, default=0, help="summary tiles per stage-1 workgroup (0: library default)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events during the timed region")
     return ap.parse_args()
@@ -213,7 +215,8 @@ def main():
     w = {"cfg1": synth.config1, "cfg2": synth.config2, "cfg3": synth.config3}[args.workload]()
     layer, natural = runner.build_device_layer(w, device=dev, keep_natural=not args.no_cpu,
                                                decode_splits=args.decode_splits, decode_waves=args.decode_waves,
-                                               decode_depth=args.decode_depth)
+                                               decode_depth=args.decode_depth, score_waves=args.score_waves,
+                                               score_tiles_per_wg=args.score_tiles)
     # stages 2+3 share a launch only for rows the one-launch kernel takes (at most 16384 partitions)
     one_launch_23 = max(w.partitions(b) for b in range(w.batch)) <= 16384
     if not one_launch_23:
