@@ -170,3 +170,37 @@ def test_run_to_run_bits_identical():
     a, _ = _run_decode(dw, pl, ml)
     b, _ = _run_decode(dw, pl, ml)
     assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("splits,npages,sparse", [(1, 600, True), (1, 600, False), (2, 200, True), (4, 37, True)])
+def test_token_partitions_gathered_tiles(splits, npages, sparse):
+    """Slots of token partitions are token-major and attention gathers attended tokens into
+    tiles of 16: page lists long enough that a wavefront walks more than 64 pages, masks with
+    one or two tokens, empty masks in between, and full pages."""
+    from gpu_harness import DeviceWorkload
+    w = synth.config0().with_(seq_lens=(16 * 640 + 5, 4000), num_q_heads=8, num_kv_heads=2, partition_tokens=1,
+                              score_kind=synth.SCORE_SKETCH, topk=16 * 640, sink_pages=0, recent_pages=0,
+                              name="tok_tiles")
+    dw = DeviceWorkload(synth.generate(w), decode_splits=splits)
+    rng = np.random.default_rng(17 + splits)
+    pl, ml = _random_selection(w, rng, npages, ragged_masks=True)
+    if sparse:
+        for r in range(w.rows):
+            for i in range(len(ml[r])):
+                kind = rng.integers(0, 4)
+                full = ml[r][i]
+                if kind == 0:
+                    ml[r][i] = 0                                    # page listed, nothing attended
+                elif kind in (1, 2):
+                    bits = [t for t in range(16) if (full >> t) & 1]
+                    keep = rng.choice(bits, size=min(len(bits), int(kind)), replace=False) if bits else []
+                    ml[r][i] = int(sum(1 << int(t) for t in keep))
+    ref, lref = _oracle_rows(dw, pl, ml)
+    got, lgot = _run_decode(dw, pl, ml)
+    _compare(got, ref, lgot, lref)
+    got2, lgot2 = _run_decode(dw, pl, ml)
+    assert np.array_equal(got, got2) and np.array_equal(lgot, lgot2)      # same bits run to run
+    # no attended token at all in a row: zeros and -inf
+    ml0 = [[0] * len(m) for m in ml]
+    got0, lgot0 = _run_decode(dw, pl, ml0)
+    assert (got0 == 0).all() and np.isneginf(lgot0).all()
