@@ -177,7 +177,7 @@ int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_
  * cfg.partition_tokens tokens: cfg.partition_tokens is then the LARGEST partition
  * (it sizes the strides) and seq_lens is not consulted by stages 2 and 3.  Sink and
  * recent pages are the first / last pages of the row's page list.  Supported for
- * MINMAX scores, all-resident mode, rows of at most 65536 partitions.  Passing
+ * MINMAX scores, in all-resident and in budget mode, rows of at most 65536 partitions.  Passing
  * NULL for the three tables returns to uniform partitions.  The pointers are kept,
  * not copied: the tables must outlive the calls that use them. */
 int spin_set_partition_tables(spin_ctx *ctx, const int32_t *part_offsets, const int32_t *part_count,
@@ -261,7 +261,10 @@ int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const in
  * admitted to freed slots (ascending page id -> ascending free slot) and
  * listed in miss_pages / miss_slots (DEVICE int32 [rows][page_stride]) with
  * nmiss (DEVICE int32 [rows]) for the copy that must complete before stage 4.
- * Leaves must exist for every page range a row can select.
+ * Leaves must exist for every page range a row can select.  The policies work
+ * on pages: with partitions other than one page each (blocks, tokens,
+ * variable-length) the selection is first expanded to its page list and masks
+ * as in all-resident mode, then replacement runs on that list.
  * Budget mode with lru_policy == 1 (the budget workload's "8-way buckets hashed
  * on (request, page)"; a convention of this library, not the paper's policy):
  * the row's slots form slot_range[r][1] / 8 sets of 8 consecutive slots (slots

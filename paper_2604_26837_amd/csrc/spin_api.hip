@@ -23,7 +23,7 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   if (c->lru_timestamps > 256) return SPIN_ERR_UNSUPPORTED;
   if (c->lru_policy != 0 && c->lru_policy != 1) return SPIN_ERR_INVALID;
   if (c->decode_depth != 0 && (c->decode_depth < 2 || c->decode_depth > 4)) return SPIN_ERR_INVALID;
-  if (c->variable_partitions && (tp < 16 || c->lru_timestamps > 0)) return SPIN_ERR_UNSUPPORTED;
+  if (c->variable_partitions && tp < 16) return SPIN_ERR_UNSUPPORTED;
   if (c->score_tiles_per_wg < 0 || (c->score_waves != 0 && c->score_waves != 4 && c->score_waves != 8))
     return SPIN_ERR_INVALID;
 
@@ -193,7 +193,7 @@ extern "C" int spin_set_partition_tables(spin_ctx *ctx, const int32_t *part_offs
   }
   if (!part_offsets || !part_count || !part_first_page || !part_tokens) return SPIN_ERR_INVALID;
   const spin_config &c = ctx->cfg;
-  if (c.partition_tokens < 16 || c.score_kind != SPIN_SCORE_MINMAX || c.lru_timestamps > 0) return SPIN_ERR_UNSUPPORTED;
+  if (c.partition_tokens < 16 || c.score_kind != SPIN_SCORE_MINMAX) return SPIN_ERR_UNSUPPORTED;
   ctx->var = spin_var{part_offsets, part_count, part_first_page, part_tokens};
   return SPIN_OK;
 }

@@ -55,14 +55,54 @@ __device__ inline int lru_scan(int v, int *s_wave, int &total) {   // exclusive 
   return off + inc - v;
 }
 
+// Partitions other than one page each (blocks, tokens, variable-length): the replacement policies
+// work on pages, so the workgroup first expands the row's selection to its ascending page list
+// with masks -- stage 3's own code, without the slot lookup -- and then runs the policy on that
+// list (EXPAND).
+struct lru_expand {
+  int tp, sink_pages, recent_pages;
+  spin_var var;
+};
+
+// the page list of the row as the policy's input; returns its length
+template <bool EXPAND>
+__device__ inline int lru_input(int row, const int32_t *__restrict__ sel, const int32_t *__restrict__ nsel,
+                                const int32_t *__restrict__ seq_lens, const int32_t *dir, const int32_t *leaf_pool,
+                                int64_t leaf_chunks, int Hkv, int sel_stride, int page_stride, int dir_stride,
+                                int leaf_entries, int32_t *slots, int32_t *page_ids, uint16_t *valid_mask,
+                                int32_t *npages, int32_t *status, const lru_expand &ex, const int32_t *&list) {
+  if (!EXPAND) {
+    list = sel + (size_t)row * sel_stride;
+    return nsel[row];
+  }
+  resolve_row<LRU_BLOCK, false>(row, nsel[row], sel, seq_lens, dir, leaf_pool, leaf_chunks, Hkv, ex.tp, ex.sink_pages,
+                                ex.recent_pages, sel_stride, page_stride, dir_stride, leaf_entries, slots, page_ids,
+                                valid_mask, npages, status, ex.var);
+  __syncthreads();   // the list was written by this workgroup: visible to all its threads from here
+  list = page_ids + (size_t)row * page_stride;
+  return npages[row];
+}
+
+// pages of the row's context (bound of a valid page id)
+__device__ inline int lru_row_pages(const lru_expand &ex, int row, int Hkv, int N) {
+  if (!ex.var.count) return (N + 15) >> 4;
+  const size_t vb = spin_var_base(ex.var, row, Hkv);
+  const int b = row / Hkv;
+  const int cap = ex.var.part_offsets[b + 1] - ex.var.part_offsets[b];
+  int P = ex.var.count[row];
+  P = P < 0 ? 0 : (P > cap ? cap : P);
+  return spin_var_row_pages(ex.var, vb, P);
+}
+
+template <bool EXPAND>
 __global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_lru_kernel(
     const int32_t *__restrict__ sel, const int32_t *__restrict__ nsel, const int32_t *__restrict__ seq_lens,
     const int32_t *__restrict__ dir, int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev,
     const int32_t *__restrict__ slot_base, int Hkv, int sel_stride, int page_stride, int dir_stride,
-    int leaf_entries, int step, int n_ts, int evict_exact, int max_slots_lds, int32_t *__restrict__ slots,
-    int32_t *__restrict__ page_ids, uint16_t *__restrict__ valid_mask, int32_t *__restrict__ npages,
+    int leaf_entries, int step, int n_ts, int evict_exact, int max_slots_lds, int32_t *slots,
+    int32_t *page_ids, uint16_t *valid_mask, int32_t *npages,
     int32_t *__restrict__ miss_pages, int32_t *__restrict__ miss_slots, int32_t *__restrict__ nmiss,
-    int32_t *status) {
+    int32_t *status, lru_expand ex) {
   extern __shared__ int32_t lds[];
   int32_t *s_loc = lds;                                  // [page_stride]  leaf entry address (as chunk*LE+idx) per selected page
   int32_t *s_free = lds + page_stride;                   // [page_stride]  free slot (local) by rank
@@ -74,11 +114,12 @@ __global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_lru_kernel(
   const int row = blockIdx.x, tid = threadIdx.x;
   const int b = row / Hkv;
   const int N = seq_lens[b];
-  const int pages = (N + 15) >> 4;
-  int ns = nsel[row];
-  ns = ns < 0 ? 0 : (ns > sel_stride ? sel_stride : ns);
+  const int pages = lru_row_pages(ex, row, Hkv, N);
+  const int32_t *rsel;
+  int ns = lru_input<EXPAND>(row, sel, nsel, seq_lens, dir, leaf_pool, leaf_chunks, Hkv, sel_stride, page_stride,
+                             dir_stride, leaf_entries, slots, page_ids, valid_mask, npages, status, ex, rsel);
+  ns = ns < 0 ? 0 : ((!EXPAND && ns > sel_stride) ? sel_stride : ns);
   if (ns > page_stride) ns = page_stride;
-  const int32_t *rsel = sel + (size_t)row * sel_stride;
   int32_t *o_slots = slots + (size_t)row * page_stride;
   int32_t *o_pages = page_ids + (size_t)row * page_stride;
   uint16_t *o_mask = valid_mask + (size_t)row * page_stride;
@@ -117,8 +158,10 @@ __global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_lru_kernel(
     else slot = -1;
     s_loc[i] = loc;
     o_slots[i] = slot;                            // hits are final, misses are filled in step (4)
-    o_pages[i] = pg;
-    o_mask[i] = (uint16_t)page_mask(pg, N);
+    if (!EXPAND) {                                // (the expanded list already holds ids and masks)
+      o_pages[i] = pg;
+      o_mask[i] = (uint16_t)page_mask(pg, N);
+    }
   }
   __syncthreads();
   if (s_err) {
@@ -270,14 +313,15 @@ __device__ inline uint32_t sa_mix32(uint32_t row, uint32_t page) {
 
 #define SA_WAYS 8
 
+template <bool EXPAND>
 __global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_sa_kernel(
     const int32_t *__restrict__ sel, const int32_t *__restrict__ nsel, const int32_t *__restrict__ seq_lens,
     const int32_t *__restrict__ dir, int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev,
     const int32_t *__restrict__ slot_base, int Hkv, int sel_stride, int page_stride, int dir_stride,
-    int leaf_entries, int step, int n_ts, int max_slots_lds, int32_t *__restrict__ slots,
-    int32_t *__restrict__ page_ids, uint16_t *__restrict__ valid_mask, int32_t *__restrict__ npages,
+    int leaf_entries, int step, int n_ts, int max_slots_lds, int32_t *slots,
+    int32_t *page_ids, uint16_t *valid_mask, int32_t *npages,
     int32_t *__restrict__ miss_pages, int32_t *__restrict__ miss_slots, int32_t *__restrict__ nmiss,
-    int32_t *status) {
+    int32_t *status, lru_expand ex) {
   extern __shared__ int32_t lds[];
   int32_t *s_loc = lds;                                   // [page_stride] leaf entry address per selected page
   int32_t *s_mi = lds + page_stride;                      // [page_stride] selection index of the m-th miss
@@ -292,11 +336,12 @@ __global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_sa_kernel(
   const int row = blockIdx.x, tid = threadIdx.x;
   const int b = row / Hkv;
   const int N = seq_lens[b];
-  const int pages = (N + 15) >> 4;
-  int ns = nsel[row];
-  ns = ns < 0 ? 0 : (ns > sel_stride ? sel_stride : ns);
+  const int pages = lru_row_pages(ex, row, Hkv, N);
+  const int32_t *rsel;
+  int ns = lru_input<EXPAND>(row, sel, nsel, seq_lens, dir, leaf_pool, leaf_chunks, Hkv, sel_stride, page_stride,
+                             dir_stride, leaf_entries, slots, page_ids, valid_mask, npages, status, ex, rsel);
+  ns = ns < 0 ? 0 : ((!EXPAND && ns > sel_stride) ? sel_stride : ns);
   if (ns > page_stride) ns = page_stride;
-  const int32_t *rsel = sel + (size_t)row * sel_stride;
   int32_t *o_slots = slots + (size_t)row * page_stride;
   int32_t *o_pages = page_ids + (size_t)row * page_stride;
   uint16_t *o_mask = valid_mask + (size_t)row * page_stride;
@@ -339,8 +384,10 @@ __global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_sa_kernel(
     } else slot = -1;
     s_loc[i] = loc;
     o_slots[i] = slot;
-    o_pages[i] = pg;
-    o_mask[i] = (uint16_t)page_mask(pg, N);
+    if (!EXPAND) {
+      o_pages[i] = pg;
+      o_mask[i] = (uint16_t)page_mask(pg, N);
+    }
   }
   __syncthreads();
   if (s_err) {
@@ -485,28 +532,36 @@ extern "C" int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, co
   const int rows = batch * c.num_kv_heads;
   if (c.lru_timestamps > 0) {
     if (!rev_table || !slot_base || !miss_pages || !miss_slots || !nmiss) return SPIN_ERR_INVALID;
-    if (c.partition_tokens != 16 || c.lru_timestamps > LRU_MAX_TS || ctx->var.count) return SPIN_ERR_UNSUPPORTED;
+    if (c.lru_timestamps > LRU_MAX_TS) return SPIN_ERR_UNSUPPORTED;
+    const bool expand = c.partition_tokens != 16 || ctx->var.count;
+    const lru_expand ex = {c.partition_tokens, c.sink_pages, c.recent_pages, ctx->var};
     if (c.lru_policy == 1) {
       // LDS: four int32 per output entry; per set a counter and a byte; one flag byte per slot of the row
       const int max_slots_lds = 32 * 1024;
       const size_t lds = (size_t)ctx->page_stride * 16 + (size_t)(max_slots_lds / SA_WAYS) * 5 + max_slots_lds;
       if (lds > 64 * 1024) return SPIN_ERR_UNSUPPORTED;
-      spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_sa_kernel, dim3((unsigned)rows), dim3(LRU_BLOCK), lds,
-                  (hipStream_t)stream, sel, nsel, seq_lens, dir, leaf_pool, leaf_chunks, rev_table, slot_base,
-                  c.num_kv_heads, ctx->sel_stride, ctx->page_stride, ctx->dir_stride, c.leaf_entries, step,
-                  c.lru_timestamps, max_slots_lds, slots, page_ids, valid_mask, npages, miss_pages, miss_slots, nmiss,
-                  (int32_t *)workspace);
+#define SPIN_SA_ARGS                                                                                            \
+  dim3((unsigned)rows), dim3(LRU_BLOCK), lds, (hipStream_t)stream, sel, nsel, seq_lens, dir, leaf_pool, leaf_chunks, \
+      rev_table, slot_base, c.num_kv_heads, ctx->sel_stride, ctx->page_stride, ctx->dir_stride, c.leaf_entries,   \
+      step, c.lru_timestamps, max_slots_lds, slots, page_ids, valid_mask, npages, miss_pages, miss_slots, nmiss,  \
+      (int32_t *)workspace, ex
+      if (expand) spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_sa_kernel<true>, SPIN_SA_ARGS);
+      else spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_sa_kernel<false>, SPIN_SA_ARGS);
+#undef SPIN_SA_ARGS
       return spin_launch_status();
     }
     // LDS: two int32 per output entry plus one flag byte per slot of the row
     const int max_slots_lds = 48 * 1024;
     const size_t lds = (size_t)ctx->page_stride * 8 + max_slots_lds;
     if (lds > 64 * 1024) return SPIN_ERR_UNSUPPORTED;
-    spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_lru_kernel, dim3((unsigned)rows), dim3(LRU_BLOCK), lds,
-                (hipStream_t)stream, sel, nsel, seq_lens, dir, leaf_pool, leaf_chunks, rev_table, slot_base,
-                c.num_kv_heads, ctx->sel_stride, ctx->page_stride, ctx->dir_stride, c.leaf_entries, step,
-                c.lru_timestamps, c.lru_evict_exact, max_slots_lds, slots, page_ids, valid_mask, npages, miss_pages,
-                miss_slots, nmiss, (int32_t *)workspace);
+#define SPIN_LRU_ARGS                                                                                           \
+  dim3((unsigned)rows), dim3(LRU_BLOCK), lds, (hipStream_t)stream, sel, nsel, seq_lens, dir, leaf_pool, leaf_chunks, \
+      rev_table, slot_base, c.num_kv_heads, ctx->sel_stride, ctx->page_stride, ctx->dir_stride, c.leaf_entries,   \
+      step, c.lru_timestamps, c.lru_evict_exact, max_slots_lds, slots, page_ids, valid_mask, npages, miss_pages,  \
+      miss_slots, nmiss, (int32_t *)workspace, ex
+    if (expand) spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_lru_kernel<true>, SPIN_LRU_ARGS);
+    else spin_launch(ctx, SPIN_K_RESOLVE, spin_resolve_lru_kernel<false>, SPIN_LRU_ARGS);
+#undef SPIN_LRU_ARGS
     return spin_launch_status();
   }
   // long selections (token partitions) get a workgroup that covers them in one sweep

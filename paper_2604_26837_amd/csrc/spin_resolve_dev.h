@@ -35,16 +35,21 @@ struct res_out {
 #define RES_DIR_LDS 256
 
 // `dir` points at the row's directory entries (a copy in LDS when it fits)
+// LOOKUP = false: only the page list and the masks are wanted (budget mode decides the slots)
+template <bool LOOKUP>
 __device__ inline void emit_page(const res_out &o, int pos, int page_stride, int page, uint32_t mask,
                                  const int32_t *dir, const int32_t *leaf_pool, int64_t leaf_chunks, int row,
                                  int dir_stride, int leaf_entries, int32_t *status) {
   if (pos < 0 || pos >= page_stride) return;
   (void)row;
-  int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, 0, dir_stride, leaf_entries, page);
-  if (slot < 0) {
-    spin_raise(status, SPIN_ERR_NOT_RESIDENT);
-    slot = -1;
-    mask = 0;
+  int32_t slot = -1;
+  if (LOOKUP) {
+    slot = spin_walk(dir, leaf_pool, leaf_chunks, 0, dir_stride, leaf_entries, page);
+    if (slot < 0) {
+      spin_raise(status, SPIN_ERR_NOT_RESIDENT);
+      slot = -1;
+      mask = 0;
+    }
   }
   o.slots[pos] = slot;
   o.page_ids[pos] = page;
@@ -53,7 +58,7 @@ __device__ inline void emit_page(const res_out &o, int pos, int page_stride, int
 
 // Resolves one row with the calling workgroup of RES_BLOCK threads; `ns` = the
 // row's selection count.
-template <int RES_BLOCK>
+template <int RES_BLOCK, bool LOOKUP = true>
 __device__ inline void resolve_row(
     int row, int ns, const int32_t *__restrict__ sel, const int32_t *__restrict__ seq_lens,
     const int32_t *dir, const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, int Hkv, int tp,
@@ -138,7 +143,7 @@ __device__ inline void resolve_row(
         const int fp = var.first_page[vb + s], tk = var.tokens[vb + s];
         for (int k = 0; k < n; ++k) {
           const int nv = min(max(tk - 16 * k, 0), 16);
-          emit_page(o, pos + k, page_stride, fp + k, (1u << nv) - 1u, dir, leaf_pool, leaf_chunks, row, dir_stride,
+          emit_page<LOOKUP>(o, pos + k, page_stride, fp + k, (1u << nv) - 1u, dir, leaf_pool, leaf_chunks, row, dir_stride,
                     leaf_entries, status);
         }
       }
@@ -146,12 +151,12 @@ __device__ inline void resolve_row(
     }
     for (int k = tid; k < extraA; k += RES_BLOCK) {
       const int nv = min(max(var.tokens[vb + A] - 16 * (a0 + k - var.first_page[vb + A]), 0), 16);
-      emit_page(o, s_sumA + k, page_stride, a0 + k, (1u << nv) - 1u, dir, leaf_pool, leaf_chunks, row, dir_stride,
+      emit_page<LOOKUP>(o, s_sumA + k, page_stride, a0 + k, (1u << nv) - 1u, dir, leaf_pool, leaf_chunks, row, dir_stride,
                 leaf_entries, status);
     }
     for (int k = tid; k < extraB; k += RES_BLOCK) {
       const int nv = min(max(var.tokens[vb + B] - 16 * (b0 + k - var.first_page[vb + B]), 0), 16);
-      emit_page(o, s_sumB + ((A >= 0 && A <= B) ? extraA : 0) + k, page_stride, b0 + k, (1u << nv) - 1u, dir, leaf_pool,
+      emit_page<LOOKUP>(o, s_sumB + ((A >= 0 && A <= B) ? extraA : 0) + k, page_stride, b0 + k, (1u << nv) - 1u, dir, leaf_pool,
                 leaf_chunks, row, dir_stride, leaf_entries, status);
     }
     const int total = min(carry + extraA + extraB, page_stride);
@@ -165,7 +170,7 @@ __device__ inline void resolve_row(
       const int i = i0 + tid;
       const int s = i < sel_stride ? rsel[i] : -1;
       if (i < ns && s >= 0 && s < pages)
-        emit_page(o, i, page_stride, s, page_mask(s, N), dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries,
+        emit_page<LOOKUP>(o, i, page_stride, s, page_mask(s, N), dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries,
                   status);
       if (i0 + RES_BLOCK >= ns) break;
     }
@@ -210,15 +215,15 @@ __device__ inline void resolve_row(
       int pos = i * m + k;
       if (extraA && s > A) pos += extraA;
       if (extraB && s > B) pos += extraB;
-      emit_page(o, pos, page_stride, pg, page_mask(pg, N), dir, leaf_pool, leaf_chunks, row, dir_stride,
+      emit_page<LOOKUP>(o, pos, page_stride, pg, page_mask(pg, N), dir, leaf_pool, leaf_chunks, row, dir_stride,
                 leaf_entries, status);
     }
     // standalone forced pages: partitions 0..A-1 are wholly forced, hence selected
     for (int k = tid; k < extraA; k += RES_BLOCK)
-      emit_page(o, A * m + k, page_stride, a0 + k, page_mask(a0 + k, N), dir, leaf_pool, leaf_chunks, row,
+      emit_page<LOOKUP>(o, A * m + k, page_stride, a0 + k, page_mask(a0 + k, N), dir, leaf_pool, leaf_chunks, row,
                 dir_stride, leaf_entries, status);
     for (int k = tid; k < extraB; k += RES_BLOCK)
-      emit_page(o, sel_below_b * m + ((A >= 0 && A <= B) ? extraA : 0) + k, page_stride, b0 + k,
+      emit_page<LOOKUP>(o, sel_below_b * m + ((A >= 0 && A <= B) ? extraA : 0) + k, page_stride, b0 + k,
                 page_mask(b0 + k, N), dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, status);
     // total: only the context's last partition can be short
     int total = ns * m + extraA + extraB;
@@ -249,7 +254,7 @@ __device__ inline void resolve_row(
           const int t0 = s * tp, cnt = min(tp, N - t0);
           if (cnt > 0) mk |= ((1u << cnt) - 1u) << (t0 & 15);
         }
-        emit_page(o, carry + before, page_stride, pg, mk, dir, leaf_pool, leaf_chunks, row, dir_stride,
+        emit_page<LOOKUP>(o, carry + before, page_stride, pg, mk, dir, leaf_pool, leaf_chunks, row, dir_stride,
                   leaf_entries, status);
       }
       carry += tot;

@@ -16,10 +16,10 @@ class Budget:
     """Device state of budget mode for a workload with page partitions; the
     selection of each step is fed in directly (stage 3b takes `sel` as input)."""
 
-    def __init__(self, w, budgets, n_ts, evict_exact=False, policy=0):
+    def __init__(self, w, budgets, n_ts, evict_exact=False, policy=0, **cfg_over):
         self.w = w
         self.sp = binding.Spin.for_workload(w, lru_timestamps=n_ts, lru_evict_exact=int(evict_exact),
-                                            lru_policy=policy)
+                                            lru_policy=policy, **cfg_over)
         sp = self.sp
         self.ws = sp.new_workspace(DEV)
         rows = w.rows
@@ -225,3 +225,109 @@ def test_set_associative_large_row_and_errors():
     assert npg[0] == 12 and npg[1] == 0 and nmiss[1] == 0
     assert (slots[1] == -1).all()
     assert (bd2.rev.cpu().numpy()[16:, 0] == -1).all()
+
+
+# ---------------------------------------------------------------------------
+# Budget mode for partitions other than one page each: the selection is first
+# expanded to its page list (with masks), the replacement policy runs on pages.
+# Oracle = the oracle's own expansion followed by the oracle's own policy.
+# ---------------------------------------------------------------------------
+def _granularity_workloads():
+    c0 = synth.config0().with_(num_q_heads=4, num_kv_heads=2)
+    return {
+        "blocks128": c0.with_(seq_lens=(131 * 16 + 5, 40 * 128), partition_tokens=128, score_kind=synth.SCORE_REPMAX,
+                              topk=4, topk_includes_forced=False, sink_pages=2, recent_pages=5, name="lru_blocks"),
+        "blocks64": c0.with_(seq_lens=(3000, 1500), partition_tokens=64, topk=6, topk_includes_forced=True,
+                             sink_pages=3, recent_pages=3, name="lru_b64"),
+        "tokens": c0.with_(seq_lens=(2500, 900), partition_tokens=1, score_kind=synth.SCORE_SKETCH, topk=40,
+                           sink_pages=1, recent_pages=2, name="lru_tokens"),
+        "quarter_pages": c0.with_(seq_lens=(1000,), partition_tokens=4, topk=30, sink_pages=1, recent_pages=1,
+                                  name="lru_q"),
+    }
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+@pytest.mark.parametrize("name", list(_granularity_workloads()))
+def test_budget_mode_any_uniform_granularity(name, policy):
+    from oracle import resolve as oresolve, select as oselect
+    w = _granularity_workloads()[name]
+    rows, n_ts = w.rows, 5
+    probe = binding.Spin.for_workload(w, lru_timestamps=n_ts, lru_policy=policy)
+    budgets = [probe.page_stride + 8 * (r % 3) + (0 if policy else r) for r in range(rows)]
+    if policy:
+        budgets = [8 * -(-b // 8) for b in budgets]
+    bd = Budget(w, budgets, n_ts, policy=policy)
+    caches = [lru.RowCache(budgets[r]) for r in range(rows)]
+    rng = np.random.default_rng(31 + policy)
+    for step in range(16):
+        selections, want_pages = [], []
+        for r in range(rows):
+            b = r // w.num_kv_heads
+            n = w.seq_lens[b]
+            P = w.partitions(b)
+            scores = rng.standard_normal(P) + (np.arange(P) % 7 == step % 7) * 2.0   # drifting favourites
+            sel = oselect.select_topk(scores, n, 16, w.partition_tokens, w.topk, w.topk_includes_forced,
+                                      w.sink_pages, w.recent_pages)
+            selections.append(sel)
+            want_pages.append(oresolve.selected_pages(sel, n, 16, w.partition_tokens, w.sink_pages, w.recent_pages))
+        slots, npg, mpages, mslots, nmiss = bd.step(step, selections)
+        assert bd.sp.poll_status(bd.ws) == 0, f"step {step}"
+        page_ids = bd.page_ids.cpu().numpy()
+        masks = bd.mask.cpu().numpy().view(np.uint16)
+        rev = bd.rev.cpu().numpy()
+        for r in range(rows):
+            pages = sorted(want_pages[r])
+            if policy:
+                want_slots, want_miss, _ = lru.setassoc_step(caches[r], pages, step, n_ts, row=r)
+            else:
+                want_slots, want_miss, _ = lru.lru_step(caches[r], pages, step, n_ts)
+            base = int(bd.slot_base_np[r])
+            assert npg[r] == len(pages), f"step {step} row {r}"
+            assert page_ids[r, :npg[r]].tolist() == pages
+            assert masks[r, :npg[r]].tolist() == [want_pages[r][p] for p in pages]
+            assert slots[r, :npg[r]].tolist() == [base + s for s in want_slots], f"step {step} row {r}"
+            assert mpages[r, :nmiss[r]].tolist() == [p for p, _ in want_miss]
+            assert mslots[r, :nmiss[r]].tolist() == [base + s for _, s in want_miss]
+            assert rev[base:base + budgets[r], 0].tolist() == caches[r].page
+
+
+def test_budget_mode_variable_length_partitions():
+    from oracle import varpart
+    w = synth.config0().with_(seq_lens=(4000, 2300), num_q_heads=4, num_kv_heads=2, partition_tokens=96, topk=7,
+                              topk_includes_forced=True, sink_pages=2, recent_pages=3, name="lru_var")
+    layouts = synth.variable_layouts(w, seed=77, min_tokens=5)
+    rows, n_ts = w.rows, 4
+    sp = binding.Spin.for_workload(w, lru_timestamps=n_ts, variable_partitions=1)
+    budgets = [sp.page_stride + 3 * r for r in range(rows)]
+    bd = Budget(w, budgets, n_ts, variable_partitions=1)
+    offs = tables.part_offsets_from_counts([max(len(layouts[b][h][0]) for h in range(w.num_kv_heads))
+                                            for b in range(w.batch)])
+    count, first, toks = tables.partition_tables(layouts, offs, w.num_kv_heads)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+    keep = [dev(offs), dev(count), dev(first), dev(toks)]
+    bd.sp.set_partition_tables(*keep)
+    caches = [lru.RowCache(budgets[r]) for r in range(rows)]
+    rng = np.random.default_rng(9)
+    for step in range(14):
+        selections, wants = [], []
+        for r in range(rows):
+            b, h = divmod(r, w.num_kv_heads)
+            fp, tk = layouts[b][h]
+            scores = rng.standard_normal(len(fp))
+            sel = varpart.select_topk(scores, fp, tk, 16, w.topk, True, w.sink_pages, w.recent_pages)
+            selections.append(sel)
+            pg, _, mk = varpart.resolve_slots(sel, fp, tk, 16, w.sink_pages, w.recent_pages,
+                                              {(r, p): p for p in range(w.pages(b))}, r)
+            wants.append((pg, mk))
+        slots, npg, mpages, mslots, nmiss = bd.step(step, selections)
+        assert bd.sp.poll_status(bd.ws) == 0, f"step {step}"
+        page_ids = bd.page_ids.cpu().numpy()
+        masks = bd.mask.cpu().numpy().view(np.uint16)
+        for r in range(rows):
+            pages, mk = wants[r]
+            want_slots, want_miss, _ = lru.lru_step(caches[r], pages, step, n_ts)
+            base = int(bd.slot_base_np[r])
+            assert page_ids[r, :npg[r]].tolist() == pages, f"step {step} row {r}"
+            assert masks[r, :npg[r]].tolist() == mk
+            assert slots[r, :npg[r]].tolist() == [base + s for s in want_slots]
+            assert mslots[r, :nmiss[r]].tolist() == [base + s for _, s in want_miss]
