@@ -22,7 +22,8 @@ def request_workload(w: synth.Workload, b: int) -> synth.Workload:
 class HierLayer:
     def __init__(self, w: synth.Workload, budget_frac: float = 0.25, n_ts: int = 64, evict_exact: bool = False,
                  device: str = "cuda:0", copy_mode: str = "memcpy", keep_natural: bool = False, **cfg_over):
-        assert w.partition_tokens == 16 and w.score_kind == synth.SCORE_MINMAX
+        # any uniform partition size; scores that need no per-head channel table
+        assert w.score_kind in (synth.SCORE_MINMAX, synth.SCORE_REPMAX)
         assert copy_mode in ("memcpy", "gather")
         self.w, self.device, self.copy_mode = w, device, copy_mode
         self.spin = binding.Spin.for_workload(w, lru_timestamps=n_ts, lru_evict_exact=int(evict_exact), **cfg_over)
@@ -31,6 +32,8 @@ class HierLayer:
         rows, hkv = w.rows, w.num_kv_heads
         # slot budget per row: a fraction of the request's pages, never below one step's selection
         self.budgets = [max(int(math.ceil(budget_frac * w.pages(r // hkv))), sp.page_stride) for r in range(rows)]
+        if cfg_over.get("lru_policy", 0) == 1:       # whole 8-way sets
+            self.budgets = [8 * -(-x // 8) for x in self.budgets]
         base = np.zeros(rows + 1, dtype=np.int64)
         base[1:] = np.cumsum(self.budgets)
         self.pool_slots = int(base[-1])
@@ -54,10 +57,11 @@ class HierLayer:
         rev[:, 0] = -1
         self.rev = torch.from_numpy(rev).to(device)
         self.seq_lens = torch.tensor(w.seq_lens, dtype=torch.int32, device=device)
-        self.part_offsets_np = tables.part_offsets(w.seq_lens, 16)
+        self.part_offsets_np = tables.part_offsets(w.seq_lens, w.partition_tokens)
         self.part_offsets = torch.from_numpy(self.part_offsets_np).to(device)
         padded = int(self.part_offsets_np[-1])
         self.summaries = torch.zeros(sp.summary_bytes(padded), dtype=torch.uint8, device=device)
+        self.summary_bytes_per_partition = sp.summary_bytes(16) // (16 * hkv)   # per KV head
         self.scores = torch.zeros(padded * hkv, dtype=torch.float32, device=device)
         z = lambda *s, dt=torch.int32: torch.zeros(s, dtype=dt, device=device)
         self.sel, self.nsel = z(rows, sp.sel_stride), z(rows)
@@ -86,8 +90,9 @@ class HierLayer:
             tmp, natural = runner.build_device_layer(wb, device=self.device, keep_natural=True)
             qs.append(tmp.q0)
             pp = int(self.part_offsets_np[b + 1] - self.part_offsets_np[b])
-            off = hkv * int(self.part_offsets_np[b]) * 512
-            self.summaries[off: off + hkv * pp * 512] = tmp.summaries[: hkv * pp * 512]
+            spb = self.summary_bytes_per_partition
+            off = hkv * int(self.part_offsets_np[b]) * spb
+            self.summaries[off: off + hkv * pp * spb] = tmp.summaries[: hkv * pp * spb]
             for h in range(hkv):
                 r = b * hkv + h
                 slots = torch.from_numpy(tmp.slot_of[0][h].astype(np.int64)).to(self.device)
@@ -161,8 +166,9 @@ class HierLayer:
             pp = int(self.part_offsets_np[b + 1] - self.part_offsets_np[b])
             po = torch.tensor([0, pp], dtype=torch.int32, device=self.device)
             sl = torch.tensor([lens[b]], dtype=torch.int32, device=self.device)
-            off = hkv * int(self.part_offsets_np[b]) * 512
-            part = self.summaries[off: off + hkv * pp * 512]
+            spb = self.summary_bytes_per_partition
+            off = hkv * int(self.part_offsets_np[b]) * spb
+            part = self.summaries[off: off + hkv * pp * spb]
             sp.build_summaries(1, tmp, torch.from_numpy(d).to(self.device), torch.from_numpy(l).to(self.device), po, sl,
                                None, part, self.ws)
             torch.cuda.synchronize()
@@ -177,7 +183,7 @@ class HierLayer:
         ``seq_lens`` holds the lengths before the call and is incremented.  Returns the
         number of pages written back.  Needs recent_pages >= 1."""
         sp, w, hkv = self.spin, self.w, self.w.num_kv_heads
-        assert w.recent_pages >= 1 and self.copy_mode == "gather"
+        assert w.recent_pages >= 1 and self.copy_mode == "gather" and w.partition_tokens == 16
         before = self.seq_lens.clone()
         after = before + 1
         sp.score_partitions(w.batch, q, self.summaries, None, self.part_offsets, after, self.scores, self.ws)

@@ -73,3 +73,72 @@ def test_steps_match_oracle(copy_mode, exact, policy):
     assert compulsory <= belady <= layer.stats["misses"]
     assert 0.0 < warm < 1.0
     print(f"{copy_mode} exact={exact}: hit rate overall {overall:.3f}, after step 0 {warm:.3f}")
+
+
+def _other_granularities():
+    base = synth.config4().with_(num_q_heads=8, num_kv_heads=2)
+    return {
+        "blocks64": base.with_(seq_lens=(2048, 5000, 9001), partition_tokens=64, topk=5, sink_pages=2, recent_pages=3,
+                               name="hier_b64"),
+        "repmax128": base.with_(seq_lens=(6000, 128 * 40 + 9), partition_tokens=128, score_kind=synth.SCORE_REPMAX,
+                                topk=3, topk_includes_forced=False, sink_pages=1, recent_pages=4, block_mean_std=0.5,
+                                name="hier_rep"),
+        "quarter_pages": base.with_(seq_lens=(3000, 1234), partition_tokens=4, topk=60, sink_pages=1, recent_pages=1,
+                                    name="hier_q"),
+    }
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+@pytest.mark.parametrize("name", list(_other_granularities()))
+def test_other_granularities_under_a_budget(name, policy):
+    """Blocks, blocks with representative keys and sub-page partitions with the full KV on the
+    host: selection on the device's scores, page list, masks, replacement state and miss list
+    against the oracle, attention over the logical tokens (which needs every missed page copied
+    into the slot the policy assigned, and for sub-page partitions the token-major slot layout
+    to survive the trip through host memory)."""
+    from oracle import resolve as oresolve
+    w = _other_granularities()[name]
+    n_ts = 5
+    layer = hier.HierLayer(w, budget_frac=0.05, n_ts=n_ts, copy_mode="gather", keep_natural=True, lru_policy=policy)
+    rows, g, tp = w.rows, w.group, w.partition_tokens
+    caches = [lru.RowCache(layer.budgets[r]) for r in range(rows)]
+    nat = [n.view(torch.int16).numpy().view(np.uint16) for n in layer.natural]
+    q = layer.q0
+    for step in range(10):
+        layer.step(q, step)
+        torch.cuda.synchronize()
+        assert layer.status() == 0, f"step {step}"
+        scores = layer.scores.cpu().numpy()
+        sel, nsel = layer.sel.cpu().numpy(), layer.nsel.cpu().numpy()
+        slots, npages = layer.slots.cpu().numpy(), layer.npages.cpu().numpy()
+        page_ids = layer.page_ids.cpu().numpy()
+        masks = layer.valid_mask.cpu().numpy().view(np.uint16)
+        ms, nm = layer.miss_slots.cpu().numpy(), layer.nmiss.cpu().numpy()
+        out = bf16.decode(layer.out.view(torch.int16).cpu().numpy().view(np.uint16))
+        q_bits = q.view(torch.int16).cpu().numpy().view(np.uint16)
+        for r in range(rows):
+            b, h = divmod(r, w.num_kv_heads)
+            n, P = w.seq_lens[b], w.partitions(b)
+            base = w.num_kv_heads * int(layer.part_offsets_np[b]) + h * int(layer.part_offsets_np[b + 1] - layer.part_offsets_np[b])
+            want_sel = select.select_topk(scores[base:base + P], n, 16, tp, w.topk, w.topk_includes_forced,
+                                          w.sink_pages, w.recent_pages)
+            assert sel[r, :nsel[r]].tolist() == want_sel, f"step {step} row {r}"
+            pm = oresolve.selected_pages(want_sel, n, 16, tp, w.sink_pages, w.recent_pages)
+            pages = sorted(pm)
+            if policy:
+                want_slots, want_miss, _ = lru.setassoc_step(caches[r], pages, step, n_ts, row=r)
+            else:
+                want_slots, want_miss, _ = lru.lru_step(caches[r], pages, step, n_ts)
+            sb = int(layer.slot_base_np[r])
+            assert page_ids[r, :npages[r]].tolist() == pages
+            assert masks[r, :npages[r]].tolist() == [pm[p] for p in pages]
+            assert slots[r, :npages[r]].tolist() == [sb + s for s in want_slots], f"step {step} row {r}"
+            assert ms[r, :nm[r]].tolist() == [sb + s for _, s in want_miss]
+            pg = bf16.decode(nat[b][layer.natural_slot_of[b][h][np.asarray(pages, dtype=np.int64)]])
+            ks, vs = attend.gather_tokens(pg[:, 0], pg[:, 1], [pm[p] for p in pages])
+            ref, _ = attend.attend(bf16.decode(q_bits[b, h * g:(h + 1) * g]), ks, vs, layer.scale)
+            o = out[b, h * g:(h + 1) * g]
+            assert np.all(np.abs(o - ref) <= ATOL + RTOL * np.abs(ref)), f"step {step} row {r}: {np.abs(o - ref).max()}"
+        q = torch.from_numpy(synth.next_query_ar1(q_bits, 0.9, w.seed + 6000 + step).view(np.int16)).to(q.device).view(torch.bfloat16)
+    overall, warm = layer.hit_rates()
+    assert 0.0 < warm < 1.0
