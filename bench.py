@@ -34,10 +34,11 @@ def parse_args():
     ap.add_argument("--cpu-rows", type=int, default=32, help="rows of the workload timed on the CPU oracle")
     ap.add_argument("--cpu-reps", type=int, default=8)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "cfg3", "cfg4"],
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "cfg3", "cfg4", "setup"],
                     help="cfg1: the headline all-resident layer (the metric's workload); cfg2: token partitions scored "
                          "on a key sketch; cfg3: 128-token blocks with representative keys; cfg4: hierarchical HBM "
-                         "budget, 64 decode steps")
+                         "budget, 64 decode steps; setup: the layout, Index, append, copy and metadata kernels at "
+                         "cfg1's shape")
     ap.add_argument("--copy-mode", default="both", choices=["memcpy", "gather", "both"])
     ap.add_argument("--budget-frac", type=float, default=0.25)
     ap.add_argument("--four-calls", action="store_true",
@@ -190,6 +191,162 @@ def run_cfg4(args):
     print(json.dumps(line))
 
 
+def run_setup(args):
+    """The kernels around the decode step at the headline workload's shape: the
+    layout and Index passes of set-up, the decode-time append, the copy kernel in
+    both directions over the host link, and the metadata mechanisms.  Every figure
+    is the kernel's own duration (HIP events on the launch stream)."""
+    import numpy as np
+    import torch
+    from paper_2604_26837_amd import binding, runner, synth, tables
+
+    dev = "cuda:0"
+    w = synth.config1()
+    dd = synth.generate_on_device(w, device=dev)
+    layer = runner.LayerState.from_natural_pool(w, dd.slot_of, dd.pool, device=dev)
+    sp, rows, hkv = layer.spin, w.rows, w.num_kv_heads
+    out = {}
+
+    def timed(spx, kid, n, fn):
+        spx.profile_enable(n)
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        cnt, mean, mn = spx.profile_read(kid)
+        spx.profile_enable(0)
+        assert cnt == n, (kid, cnt, n)
+        return mean, mn
+
+    def entry(mean, mn, nbytes=None, what=None):
+        e = dict(mean_us=round(mean, 2), min_us=round(mn, 2))
+        if nbytes:
+            e.update(bytes=int(nbytes), gbps=round(nbytes / mean / 1e3, 1), counts=what)
+        return e
+
+    # --- layout pass: token-major pages -> slot layout, 32768 pages per launch
+    k_all, v_all = dd.pool[:, 0].contiguous(), dd.pool[:, 1].contiguous()
+    ids = torch.arange(layer.pool_slots, dtype=torch.int32, device=dev)
+    chunk = 32768
+    nchunk = layer.pool_slots // chunk
+    def pack(i):
+        s0 = (i % nchunk) * chunk
+        sp.pack_kv_pages(k_all[s0:s0 + chunk], v_all[s0:s0 + chunk], ids[s0:s0 + chunk], layer.kv_pool)
+    mean, mn = timed(sp, "pack", 16, pack)
+    out["pack_32768_pages"] = entry(mean, mn, chunk * 8192 * 2, "bytes read + written")
+    del k_all, v_all
+
+    # --- Index: min/max summaries of every page from the keys in the pool
+    mean, mn = timed(sp, "index", 8, lambda i: layer.build_summaries())
+    index_bytes = layer.pool_slots * 4096 + layer.summaries.numel()      # K tiles read + summaries written
+    out["index_minmax_all_pages"] = entry(mean, mn, index_bytes, "K tiles read + summaries written")
+    index_us = mean
+
+    # --- copy kernel over the host link, both directions: 64 pages of every row (64 MiB)
+    per_row = 64
+    host = torch.empty((rows * per_row, 4096), dtype=torch.bfloat16, pin_memory=True)
+    row_base = (torch.arange(rows, dtype=torch.int64) * per_row).to(dev)
+    count = torch.full((rows,), per_row, dtype=torch.int32, device=dev)
+    pages = torch.zeros((rows, sp.page_stride), dtype=torch.int32, device=dev)
+    pages[:, :per_row] = torch.arange(per_row, dtype=torch.int32, device=dev)[None, :]
+    slots = torch.zeros((rows, sp.page_stride), dtype=torch.int32, device=dev)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(w.seed)
+    slots[:, :per_row] = torch.randperm(layer.pool_slots, generator=g)[:rows * per_row].to(torch.int32).reshape(rows, per_row).to(dev)
+    before = layer.kv_pool[slots[:, :per_row].reshape(-1).long()].clone()
+    mean, mn = timed(sp, "offload", 8, lambda i: sp.offload_pages(w.batch, layer.kv_pool, host, row_base, count, pages,
+                                                                  slots, layer.ws))
+    out["offload_8192_pages_to_host"] = entry(mean, mn, rows * per_row * 8192, "page bytes over the host link")
+    mean, mn = timed(sp, "gather", 8, lambda i: sp.gather_misses(w.batch, host, row_base, count, pages, slots,
+                                                                 layer.kv_pool, layer.ws))
+    out["gather_8192_pages_from_host"] = entry(mean, mn, rows * per_row * 8192, "page bytes over the host link")
+    assert torch.equal(layer.kv_pool[slots[:, :per_row].reshape(-1).long()], before), "offload + gather round trip"
+    del before
+
+    # --- a real selection for the metadata kernels
+    layer.step(dd.q)
+    torch.cuda.synchronize()
+    assert layer.status() == 0
+
+    # --- budget mode at 512 slots per row: resolve under the budget, shrink to half, grow back
+    cfg = dict(lru_timestamps=64)
+    spb, spb_untimed = binding.Spin.for_workload(w, **cfg), binding.Spin.for_workload(w, **cfg)
+    wsb = spb.new_workspace(dev)
+    S = 512
+    rng_np = np.stack([np.arange(rows, dtype=np.int32) * S, np.full(rows, S, dtype=np.int32)], axis=1)
+    slot_range = torch.from_numpy(np.ascontiguousarray(rng_np)).to(dev)
+    empty = [np.full((hkv, w.pages(b)), -1, dtype=np.int32) for b in range(w.batch)]
+    d, l = tables.build_two_level(empty, spb.dir_stride, w.leaf_entries, allocate_all=True)
+    dir_b, leaf_b = torch.from_numpy(d).to(dev), torch.from_numpy(l).to(dev)
+    rev = torch.zeros((rows * S, 2), dtype=torch.int32, device=dev)
+    rev[:, 0] = -1
+    z = lambda *sh, dt=torch.int32: torch.zeros(sh, dtype=dt, device=dev)
+    b_slots, b_pages, b_mask, b_np = z(rows, spb.page_stride), z(rows, spb.page_stride), z(rows, spb.page_stride, dt=torch.int16), z(rows)
+    m_pages, m_slots, m_n = z(rows, spb.page_stride), z(rows, spb.page_stride), z(rows)
+    qsets = [dd.q] + [synth.make_queries_on_device(w, w.seed + 1000 + i, dev) for i in range(1, 8)]
+    sels = []
+    for q in qsets:
+        layer.step(q)
+        sels.append((layer.sel.clone(), layer.nsel.clone()))
+    half, full = torch.full((rows,), S // 2, dtype=torch.int32, device=dev), torch.full((rows,), S, dtype=torch.int32, device=dev)
+    def budget_step(i, spx):
+        sel, nsel = sels[i % len(sels)]
+        spx.resolve_slots(w.batch, i, sel, nsel, layer.seq_lens, dir_b, leaf_b, b_slots, b_pages, b_mask, b_np, wsb,
+                          rev_table=rev, slot_base=slot_range, miss_pages=m_pages, miss_slots=m_slots, nmiss=m_n)
+    def shrink_cycle(i):
+        budget_step(i, spb_untimed)
+        spb.reclaim_tail(w.batch, slot_range, half, dir_b, leaf_b, rev, wsb)          # timed: evicts the tail's pages
+        spb_untimed.reclaim_tail(w.batch, slot_range, full, dir_b, leaf_b, rev, wsb)  # grow back
+    mean, mn = timed(spb, "meta", 16, shrink_cycle)
+    out["reclaim_tail_512_to_256_slots_per_row"] = entry(mean, mn)
+    mean, mn = timed(spb, "resolve", 16, lambda i: budget_step(100 + i, spb))
+    out["resolve_under_budget_512_slots_per_row"] = entry(mean, mn)
+    assert spb.poll_status(wsb) == 0
+
+    # --- leaf chunks on demand: every row's selection touches up to 4 page ranges; a pool with
+    # twice the chunks needed, and the worst case of a pool that ends exactly full
+    sel0, nsel0 = sels[0]
+    for label, chunks in (("pool_2x", rows * 8), ("pool_exact", rows * 4)):
+        dir_d = torch.full_like(dir_b, -1)
+        leaf_d = torch.zeros((chunks, w.leaf_entries), dtype=torch.int32, device=dev)
+        bitmap = torch.zeros((chunks + 31) // 32, dtype=torch.int32, device=dev)
+        def alloc_cycle(i):
+            spb.alloc_leaves(w.batch, sel0, nsel0, layer.seq_lens, dir_d, leaf_d, bitmap, wsb)       # timed
+            spb_untimed.free_leaves(w.batch, dir_d, chunks, bitmap, wsb)
+        mean, mn = timed(spb, "meta", 16, alloc_cycle)
+        out[f"alloc_leaves_from_empty_directory_{label}"] = entry(mean, mn)
+        def free_cycle(i):
+            spb_untimed.alloc_leaves(w.batch, sel0, nsel0, layer.seq_lens, dir_d, leaf_d, bitmap, wsb)
+            spb.free_leaves(w.batch, dir_d, chunks, bitmap, wsb)                                     # timed
+        mean, mn = timed(spb, "meta", 16, free_cycle)
+        out[f"free_leaves_{label}"] = entry(mean, mn)
+        assert spb.poll_status(wsb) == 0 and int(bitmap.abs().sum().item()) == 0
+
+    # --- decode-time Index: one token per request appended to its slot and its page's summary
+    k_new = torch.randn((w.batch, hkv, w.head_dim), device=dev).to(torch.bfloat16)
+    v_new = torch.randn((w.batch, hkv, w.head_dim), device=dev).to(torch.bfloat16)
+    n_app = 32
+    lens = [torch.full((w.batch,), w.seq_lens[0] - 40 + i, dtype=torch.int32, device=dev) for i in range(n_app)]
+    mean, mn = timed(sp, "append", n_app, lambda i: sp.append_kv(w.batch, k_new, v_new, lens[i], layer.kv_pool, layer.dir,
+                                                                  layer.leaf_pool, layer.part_offsets, None,
+                                                                  layer.summaries, layer.ws))
+    out["append_one_token_per_request"] = entry(mean, mn)
+    assert layer.status() == 0
+
+    ach = index_bytes / index_us / 1e3
+    line = {"metric": "set-up and maintenance kernels at the headline workload's shape (kernel us per launch)",
+            "value": round(index_us, 2), "unit": "us (Index over all pages)", "n_gpus": 1, "steps": 8, "warmup": 0,
+            "ms_per_step": round(index_us / 1e3, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": w.name + "_setup", "batch": w.batch, "context": w.seq_lens[0], "kv_heads": hkv,
+                       "pool_slots": layer.pool_slots},
+            "kernels": out,
+            "roofline": dict(bound="hbm", kernel="spin_index_minmax_pages_kernel", achieved=round(ach, 1),
+                             peak=PEAK_HBM_GBPS, unit="GB/s", frac=round(ach / PEAK_HBM_GBPS, 4), traffic=None,
+                             algorithmic_bytes=int(index_bytes), mean_us=round(index_us, 2)),
+            "cpu_baseline": None}
+    print(json.dumps(line))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -211,6 +368,9 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "cfg4":
         run_cfg4(args)
+        return
+    if args.workload == "setup":
+        run_setup(args)
         return
     w = {"cfg1": synth.config1, "cfg2": synth.config2, "cfg3": synth.config3}[args.workload]()
     layer, natural = runner.build_device_layer(w, device=dev, keep_natural=not args.no_cpu,

@@ -157,7 +157,8 @@ enum spin_kernel_id {
   SPIN_K_SCORE = 0, SPIN_K_SELECT = 1, SPIN_K_RESOLVE = 2, SPIN_K_DECODE = 3, SPIN_K_MERGE = 4,
   SPIN_K_INDEX = 5, SPIN_K_PACK = 6, SPIN_K_GATHER = 7, SPIN_K_PROBE = 8,
   SPIN_K_SELECT_HIST = 9, /* first launch of stage 2 for rows of more than 16384 partitions */
-  SPIN_K_OFFLOAD = 10
+  SPIN_K_OFFLOAD = 10, SPIN_K_APPEND = 11,
+  SPIN_K_META = 12 /* spin_reclaim_tail, spin_alloc_leaves, spin_free_leaves */
 };
 int spin_profile_enable(spin_ctx *ctx, int32_t capacity);
 int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_us, float *min_us);

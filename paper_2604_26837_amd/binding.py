@@ -170,7 +170,8 @@ class Spin:
     def summary_bytes(self, padded_partitions: int) -> int:
         return self.lib.spin_summary_bytes(self.h, padded_partitions)
 
-    KERNEL_IDS = dict(score=0, select=1, resolve=2, decode=3, merge=4, index=5, pack=6, gather=7, probe=8, select_hist=9, offload=10)
+    KERNEL_IDS = dict(score=0, select=1, resolve=2, decode=3, merge=4, index=5, pack=6, gather=7, probe=8, select_hist=9, offload=10, append=11,
+                      meta=12)
 
     def profile_enable(self, capacity: int):
         self._check(self.lib.spin_profile_enable(self.h, capacity), "spin_profile_enable")

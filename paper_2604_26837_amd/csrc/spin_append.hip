@@ -95,7 +95,7 @@ extern "C" int spin_append_kv(spin_ctx *ctx, int32_t batch, const void *k_new, c
   const spin_config &c = ctx->cfg;
   if (c.score_kind == SPIN_SCORE_SKETCH && (!chan_idx || c.partition_tokens != 1)) return SPIN_ERR_INVALID;
   const int rows = batch * c.num_kv_heads;
-  spin_launch(ctx, SPIN_K_INDEX, spin_append_kernel, dim3((unsigned)rows), dim3(128), 0, (hipStream_t)stream,
+  spin_launch(ctx, SPIN_K_APPEND, spin_append_kernel, dim3((unsigned)rows), dim3(128), 0, (hipStream_t)stream,
               (const uint16_t *)k_new, (const uint16_t *)v_new, seq_lens, (uint16_t *)kv_pool, pool_slots, dir,
               leaf_pool, leaf_chunks, part_offsets, chan_idx, (uint16_t *)summaries, c.num_kv_heads,
               c.partition_tokens, c.score_kind, c.reps_per_partition, ctx->dir_stride, c.leaf_entries,

@@ -13,7 +13,7 @@
 #define SPIN_KTILE_U4 256     // 4096-byte K tile in 16-byte units
 #define SPIN_WS_HEADER 256    // bytes reserved in front of the workspace (status word)
 
-#define SPIN_KERNEL_IDS 11
+#define SPIN_KERNEL_IDS 13
 
 // Variable-length partitions (Section 5.2: the Meta-partition table holds each
 // partition's token count, the Partition Offset table where its page list

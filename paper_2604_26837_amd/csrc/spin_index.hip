@@ -357,7 +357,7 @@ extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv
                   c.num_kv_heads, c.partition_tokens, ctx->dir_stride, c.leaf_entries, max_tiles,
                   (uint16_t *)summaries, status, ctx->var);
     else
-    hipLaunchKernelGGL(spin_index_minmax_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
+      spin_launch(ctx, SPIN_K_INDEX, spin_index_minmax_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
                        (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
                        c.num_kv_heads, c.partition_tokens, ctx->dir_stride, c.leaf_entries, max_tiles,
                        (uint16_t *)summaries, status, ctx->k_token_major);
@@ -377,7 +377,7 @@ extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv
     if (!chan_idx) return SPIN_ERR_INVALID;
     if (c.partition_tokens != 1) return SPIN_ERR_UNSUPPORTED;
     const int max_blocks = (max_pp + 63) / 64;
-    hipLaunchKernelGGL(spin_index_sketch_kernel, dim3((unsigned)rows * max_blocks), dim3(256), 0, st,
+    spin_launch(ctx, SPIN_K_INDEX, spin_index_sketch_kernel, dim3((unsigned)rows * max_blocks), dim3(256), 0, st,
                        (const uint16_t *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
                        chan_idx, c.num_kv_heads, ctx->dir_stride, c.leaf_entries, max_blocks,
                        (uint16_t *)summaries, status, ctx->k_token_major);

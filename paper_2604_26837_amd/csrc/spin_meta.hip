@@ -27,18 +27,23 @@ __global__ __launch_bounds__(META_BLOCK) void spin_reclaim_kernel(int32_t *slot_
   if (threadIdx.x == 0) slot_range[2 * row + 1] = keep;
 }
 
-// take one free chunk: set the first clear bit found, scanning from `start`
-__device__ inline int32_t bitmap_take(uint32_t *bitmap, int64_t chunks, int start_word) {
+// take one free chunk: set a clear bit, looking from bit `start` of the bitmap onwards (circularly).
+// Requests that start at different bits do not meet as long as the pool has room near them.
+__device__ inline int32_t bitmap_take(uint32_t *bitmap, int64_t chunks, int64_t start) {
   const int nwords = (int)((chunks + 31) / 32);
+  const int w0 = (int)(start >> 5) % nwords, sb = (int)(start & 31);
   for (int k = 0; k < nwords; ++k) {
-    const int w = (start_word + k) % nwords;
+    const int w = (w0 + k) % nwords;
+    const int rot = k == 0 ? sb : 0;                 // the first word is searched from the start bit, circularly
     uint32_t word = __hip_atomic_load(&bitmap[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    while (~word != 0u) {
-      const int bit = __builtin_ctz(~word);
-      const int64_t id = (int64_t)w * 32 + bit;
-      if (id >= chunks) break;                      // only padding bits are left in this word
+    for (;;) {
+      uint32_t freeb = ~word;
+      if ((int64_t)w * 32 + 32 > chunks) freeb &= (1u << (int)(chunks - (int64_t)w * 32)) - 1u;   // padding bits
+      if (!freeb) break;
+      const uint32_t r = rot ? ((freeb >> rot) | (freeb << (32 - rot))) : freeb;
+      const int bit = (__builtin_ctz(r) + rot) & 31;
       const uint32_t old = atomicOr(&bitmap[w], 1u << bit);
-      if (!(old & (1u << bit))) return (int32_t)id;
+      if (!(old & (1u << bit))) return (int32_t)((int64_t)w * 32 + bit);
       word = old | (1u << bit);
     }
   }
@@ -74,7 +79,9 @@ __global__ __launch_bounds__(META_BLOCK) void spin_alloc_leaves_kernel(
   __syncthreads();
   for (int ci = tid; ci < dir_stride; ci += META_BLOCK) {
     if (!s_need[ci] || rdir[ci] >= 0) continue;
-    const int32_t ch = bitmap_take(bitmap, leaf_chunks, (row * 7 + ci) & 0x7fffffff);
+    // requests spread over the pool in proportion to (row, range): no two meet while the pool has room
+    const int64_t want = (int64_t)row * dir_stride + ci, all = (int64_t)gridDim.x * dir_stride;
+    const int32_t ch = bitmap_take(bitmap, leaf_chunks, want * leaf_chunks / all);
     if (ch < 0) { spin_raise(status, SPIN_ERR_LEAF_POOL); continue; }
     s_new[ci] = ch;
   }
@@ -109,7 +116,7 @@ extern "C" int spin_reclaim_tail(spin_ctx *ctx, int32_t batch, int32_t *slot_ran
   if (!slot_range || !new_count || !dir || !leaf_pool || !rev_table) return SPIN_ERR_INVALID;
   if (!workspace) return SPIN_ERR_WORKSPACE;
   const int rows = batch * ctx->cfg.num_kv_heads;
-  hipLaunchKernelGGL(spin_reclaim_kernel, dim3((unsigned)rows), dim3(META_BLOCK), 0, (hipStream_t)stream, slot_range,
+  spin_launch(ctx, SPIN_K_META, spin_reclaim_kernel, dim3((unsigned)rows), dim3(META_BLOCK), 0, (hipStream_t)stream, slot_range,
                      new_count, dir, leaf_pool, leaf_chunks, rev_table, ctx->dir_stride, ctx->cfg.leaf_entries,
                      (int32_t *)workspace);
   return spin_launch_status();
@@ -125,7 +132,7 @@ extern "C" int spin_alloc_leaves(spin_ctx *ctx, int32_t batch, const int32_t *se
   if (ctx->dir_stride > META_DIR_LDS) return SPIN_ERR_UNSUPPORTED;
   const spin_config &c = ctx->cfg;
   const int rows = batch * c.num_kv_heads;
-  hipLaunchKernelGGL(spin_alloc_leaves_kernel, dim3((unsigned)rows), dim3(META_BLOCK), 0, (hipStream_t)stream, sel, nsel,
+  spin_launch(ctx, SPIN_K_META, spin_alloc_leaves_kernel, dim3((unsigned)rows), dim3(META_BLOCK), 0, (hipStream_t)stream, sel, nsel,
                      seq_lens, dir, leaf_pool, leaf_chunks, leaf_bitmap, c.num_kv_heads, c.partition_tokens,
                      c.sink_pages, c.recent_pages, ctx->sel_stride, ctx->dir_stride, c.leaf_entries,
                      (int32_t *)workspace);
@@ -139,7 +146,7 @@ extern "C" int spin_free_leaves(spin_ctx *ctx, int32_t batch, int32_t *dir, int6
   if (!dir || !leaf_bitmap) return SPIN_ERR_INVALID;
   (void)workspace;
   const int rows = batch * ctx->cfg.num_kv_heads;
-  hipLaunchKernelGGL(spin_free_leaves_kernel, dim3((unsigned)rows), dim3(META_BLOCK), 0, (hipStream_t)stream, dir,
+  spin_launch(ctx, SPIN_K_META, spin_free_leaves_kernel, dim3((unsigned)rows), dim3(META_BLOCK), 0, (hipStream_t)stream, dir,
                      leaf_chunks, leaf_bitmap, ctx->dir_stride);
   return spin_launch_status();
 }

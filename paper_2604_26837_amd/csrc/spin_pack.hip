@@ -49,8 +49,8 @@ extern "C" int spin_pack_kv_pages(spin_ctx *ctx, int64_t n_pages, const void *sr
   if (n_pages == 0) return SPIN_OK;
   if (!src_k || !src_v || !slots || !kv_pool) return SPIN_ERR_INVALID;
   if (n_pages > 0x7fffffffLL) return SPIN_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(spin_pack_kernel, dim3((unsigned)n_pages), dim3(256), 0, (hipStream_t)stream,
-                     (const uint16_t *)src_k, (const uint16_t *)src_v, slots, (uint4 *)kv_pool, pool_slots,
-                     n_pages, ctx->k_token_major);
+  spin_launch(ctx, SPIN_K_PACK, spin_pack_kernel, dim3((unsigned)n_pages), dim3(256), 0, (hipStream_t)stream,
+              (const uint16_t *)src_k, (const uint16_t *)src_v, slots, (uint4 *)kv_pool, pool_slots,
+              n_pages, ctx->k_token_major);
   return spin_launch_status();
 }
