@@ -379,8 +379,8 @@ def main():
                                                score_tiles_per_wg=args.score_tiles)
     # stages 2+3 share a launch only for rows the one-launch kernel takes (at most 16384 partitions)
     one_launch_23 = max(w.partitions(b) for b in range(w.batch)) <= 16384
-    if not one_launch_23:
-        args.four_calls = True
+    # longer rows: stages 1+2 share a call instead (stage 1 takes stage 2's histogram along)
+    fused_12 = not one_launch_23 and not args.four_calls
     sp = layer.spin
 
     # distinct query sets (seeds base+1000+i) and distinct summary copies
@@ -396,7 +396,10 @@ def main():
 
     # the step as timed: score, select+resolve in one launch, attention (three
     # launches, same results bit for bit); the four separate calls are timed beside it
-    run = run_four if args.four_calls else run_three
+    def run_12(i):
+        layer.step12(qsets[i % len(qsets)], summ_copies[i % len(summ_copies)])
+
+    run = run_four if args.four_calls else (run_12 if fused_12 else run_three)
 
     for i in range(args.warmup):
         run(i)
@@ -414,9 +417,9 @@ def main():
     assert layer.status() == 0, "device fault during the timed region"
 
     # --- the other launch shape of the same step, for reference
-    other = run_three if args.four_calls else run_four
+    other = (run_three if one_launch_23 else run_12) if args.four_calls else run_four
     us_per_step_other = None
-    if one_launch_23:
+    if True:
         for i in range(5):
             other(i)
         torch.cuda.synchronize()
@@ -455,7 +458,7 @@ def main():
         for name in ("score", "select_hist", "select", "resolve", "decode"):
             n, mean, mn = sp.profile_read(name)
             if n:
-                label = "select+resolve" if (name == "select" and not args.four_calls) else name
+                label = "select+resolve" if (name == "select" and not args.four_calls and one_launch_23) else name
                 kernels[label] = dict(launches=n, mean_us=round(mean, 3), min_us=round(mn, 3))
         sp.profile_enable(0)
         assert layer.status() == 0, "device fault during the event-bracketed pass"
@@ -537,8 +540,10 @@ def main():
                    "summary_copies": len(summ_copies)},
         "attended_kv_gbps": roofline["achieved"] if roofline else None,
         "attended_kv_pct_peak": round(100 * roofline["frac"], 2) if roofline else None,
-        "step_launches": "four stage calls" if args.four_calls else "score, select+resolve, attention (3 launches)",
-        ("us_per_layer_three_launches" if args.four_calls else "us_per_layer_four_calls"): round(us_per_step_other, 2) if us_per_step_other else None,
+        "step_launches": "four stage calls" if args.four_calls else (
+            "score+select in one call (stage 1 counts stage 2's histogram), resolve, attention (4 launches)" if fused_12
+            else "score, select+resolve, attention (3 launches)"),
+        ("us_per_layer_fused_calls" if args.four_calls else "us_per_layer_four_calls"): round(us_per_step_other, 2) if us_per_step_other else None,
         "us_per_layer_with_kernel_events": round(us_per_step_events, 2) if us_per_step_events else None,
         "us_per_layer_spread": step_spread,
         "kernel_us_sum": round(sum(k["mean_us"] for k in kernels.values()), 2) if kernels else None,

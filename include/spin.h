@@ -247,6 +247,17 @@ int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const in
                      const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace,
                      void *stream);
 
+/* Stages 1 and 2 in ONE call: arguments and results are exactly those of
+ * spin_score_partitions followed by spin_select_topk, bit for bit (the scores
+ * are still written).  With SKETCH scores and contexts whose stage 2 takes two
+ * launches (rows of 16385 to 131072 partitions) stage 1 counts the leading key
+ * bits of its scores while it still holds them, so the histogram launch over
+ * the score array is saved; every other configuration simply runs the two
+ * stages one after the other.  The workspace is needed as for the two calls. */
+int spin_score_select_topk(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries,
+                           const int32_t *chan_idx, const int32_t *part_offsets, const int32_t *seq_lens,
+                           float *scores, int32_t *sel, int32_t *nsel, void *workspace, void *stream);
+
 /* Stage 3.  Expand each row's selection (plus forced pages that lie in no
  * selected partition) to logical pages, walk dir -> leaf -> slot, and emit, in
  * ascending page order, slots / page_ids (DEVICE int32 [rows][page_stride]),

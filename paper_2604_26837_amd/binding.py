@@ -23,7 +23,7 @@ EXPORTS = [
     "spin_workspace_init", "spin_poll_status", "spin_profile_enable", "spin_profile_read", "spin_pack_kv_pages", "spin_build_summaries",
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
     "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv", "spin_reclaim_tail", "spin_alloc_leaves", "spin_free_leaves",
-    "spin_set_partition_tables", "spin_probe_stream_read", "spin_offload_pages",
+    "spin_set_partition_tables", "spin_probe_stream_read", "spin_offload_pages", "spin_score_select_topk",
 ]
 
 
@@ -72,6 +72,7 @@ def load_library() -> C.CDLL:
     lib.spin_build_summaries.argtypes = [vp, i32, vp, i64, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.spin_score_partitions.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.spin_score_select_topk.argtypes = [vp, i32] + [vp] * 10
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_probe_stream_read.argtypes = [vp, vp, C.c_size_t, vp, vp]
@@ -254,6 +255,13 @@ class Spin:
             self.h, batch, _ptr(scores, torch.float32, "scores"), _ptr(part_offsets, torch.int32, "part_offsets"),
             _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(sel, torch.int32, "sel"),
             _ptr(nsel, torch.int32, "nsel"), _ptr(ws), _stream()), "spin_select_topk")
+
+    def score_select_topk(self, batch, q, summaries, chan_idx, part_offsets, seq_lens, scores, sel, nsel, ws):
+        self._check(self.lib.spin_score_select_topk(
+            self.h, batch, _ptr(q, torch.bfloat16, "q"), _ptr(summaries), _ptr(chan_idx, torch.int32, "chan_idx"),
+            _ptr(part_offsets, torch.int32, "part_offsets"), _ptr(seq_lens, torch.int32, "seq_lens"),
+            _ptr(scores, torch.float32, "scores"), _ptr(sel, torch.int32, "sel"), _ptr(nsel, torch.int32, "nsel"),
+            _ptr(ws), _stream()), "spin_score_select_topk")
 
     def resolve_slots(self, batch, step, sel, nsel, seq_lens, dir_, leaf_pool, slots, page_ids, valid_mask,
                       npages, ws, rev_table=None, slot_base=None, miss_pages=None, miss_slots=None, nmiss=None):

@@ -70,6 +70,16 @@ static inline int spin_launch_status() {
   return hipGetLastError() == hipSuccess ? SPIN_OK : SPIN_ERR_HIP;
 }
 
+// host-side bodies of stages 1 and 2, shared by the stage calls and the combined call.
+// hist != NULL: stage 1 also counts the leading 12 key bits of every candidate's score into the
+// per-row histograms stage 2 of long rows starts from; hist_ready: stage 2 finds them filled.
+int spin_score_impl(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries, const int32_t *chan_idx,
+                    const int32_t *part_offsets, const int32_t *seq_lens, float *scores, void *workspace,
+                    void *stream, int32_t *hist);
+int spin_select_impl(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
+                     const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace, void *stream,
+                     bool hist_ready);
+
 #ifdef __HIPCC__
 // Launch `kernel` on `st`; when timing is enabled the launch carries a start
 // and a stop event that take the kernel's own begin and end timestamps.

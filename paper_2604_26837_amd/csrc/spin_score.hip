@@ -17,6 +17,7 @@
 // exchange for groups of up to four heads (two otherwise).  Summary tiles are
 // stored chunk-major so each load is a contiguous wavefront transaction.
 #include "spin_score_dev.h"
+#include "spin_select_dev.h"   // key order and forced-partition plan of stage 2, for the fused histogram
 
 #define SCORE_WAVES 4
 
@@ -29,11 +30,22 @@ __global__ __launch_bounds__(WAVES * 64) void spin_score_k32_kernel(
                                             scores);
 }
 
+// what stage 2 needs to know to tell candidates from forced partitions
+struct score_hist_args {
+  const int32_t *seq_lens;
+  int32_t *hist;            // [rows][BIG_BINS]
+  int tp, topk, includes_forced, sink_pages, recent_pages, sel_stride;
+};
+
 // SKETCH: one 16x16x16 instruction per tile of 16 tokens (512 bytes).
+// HIST: the workgroup also counts the leading 12 key bits of its candidates' scores (LDS, then one
+// global add per bin it touched), which is the first launch of stage 2 for long rows.
+template <bool HIST>
 __global__ __launch_bounds__(SCORE_WAVES * 64) void spin_score_sketch_kernel(
     const uint16_t *__restrict__ q, const uint2 *__restrict__ summ, const int32_t *__restrict__ chan,
     const int32_t *__restrict__ part_offsets, int Hq, int Hkv, int G, int tiles_per_wg, int wgs_per_row,
-    float *__restrict__ scores) {
+    float *__restrict__ scores, score_hist_args ha) {
+  __shared__ int s_h[HIST ? BIG_BINS : 1];
   const int row = blockIdx.x / wgs_per_row, chunk = blockIdx.x - row * wgs_per_row;
   const int b = row / Hkv, h = row - b * Hkv;
   const int PP = part_offsets[b + 1] - part_offsets[b];
@@ -54,6 +66,14 @@ __global__ __launch_bounds__(SCORE_WAVES * 64) void spin_score_sketch_kernel(
 #pragma unroll
   for (int u = 0; u < U; ++u) a[u] = (t0 + u < t_end) ? tiles[(size_t)(t0 + u) * 64 + lane] : make_uint2(0, 0);
 
+  int cand_lo = 0, cand_hi = 0;           // candidates of stage 2: partitions [cand_lo, cand_hi)
+  if (HIST) {
+    const sel_plan pl = select_plan(ha.seq_lens[b], PP, ha.tp, ha.topk, ha.includes_forced, ha.sink_pages,
+                                    ha.recent_pages, ha.sel_stride);
+    if (pl.kprime > 0) { cand_lo = pl.nf_lo; cand_hi = pl.first_hi; }
+    for (int i = threadIdx.x; i < BIG_BINS; i += SCORE_WAVES * 64) s_h[i] = 0;
+    __syncthreads();
+  }
   // A operand: row n = head, k = sketched channels 4c..4c+3
   spin_s16x4 qf;
   {
@@ -76,16 +96,27 @@ __global__ __launch_bounds__(SCORE_WAVES * 64) void spin_score_sketch_kernel(
       spin_f32x4 s = {0.f, 0.f, 0.f, 0.f};
       s = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(qf, __builtin_bit_cast(spin_s16x4, a[u]), s, 0, 0, 0);
       const float m = spin_head_max(s, c, G);   // lane (n, c): heads 4c+i of token n
-      if (c == 0) scores[base + (size_t)(t0 + u) * 16 + n] = m;
+      if (c == 0) {
+        const int p = (t0 + u) * 16 + n;
+        scores[base + p] = m;
+        if (HIST && p >= cand_lo && p < cand_hi) atomicAdd(&s_h[score_key(m) >> 20], 1);
+      }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) a[u] = nx[u];
   }
+  if (HIST) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < BIG_BINS; i += SCORE_WAVES * 64) {
+      const int cnt = s_h[i];
+      if (cnt) atomicAdd(&ha.hist[(size_t)row * BIG_BINS + i], cnt);
+    }
+  }
 }
 
-extern "C" int spin_score_partitions(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries,
-                                     const int32_t *chan_idx, const int32_t *part_offsets,
-                                     const int32_t *seq_lens, float *scores, void *workspace, void *stream) {
+int spin_score_impl(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries, const int32_t *chan_idx,
+                    const int32_t *part_offsets, const int32_t *seq_lens, float *scores, void *workspace,
+                    void *stream, int32_t *hist) {
   if (!ctx || batch < 0 || batch > ctx->cfg.max_batch) return SPIN_ERR_INVALID;
   if (batch == 0) return SPIN_OK;
   if (!q || !summaries || !part_offsets || !seq_lens || !scores) return SPIN_ERR_INVALID;
@@ -120,11 +151,22 @@ extern "C" int spin_score_partitions(spin_ctx *ctx, int32_t batch, const void *q
 #undef SPIN_SCORE_ARGS
   } else {
     if (!chan_idx) return SPIN_ERR_INVALID;
-    const int tiles_per_wg = 128, max_tiles = max_pp / 16;
+    const int tiles_per_wg = c.score_tiles_per_wg ? c.score_tiles_per_wg : 128, max_tiles = max_pp / 16;
     const int wgs = (max_tiles + tiles_per_wg - 1) / tiles_per_wg;
-    spin_launch(ctx, SPIN_K_SCORE, spin_score_sketch_kernel, dim3((unsigned)rows * wgs), dim3(SCORE_WAVES * 64), 0, st,
-                       (const uint16_t *)q, (const uint2 *)summaries, chan_idx, part_offsets, c.num_q_heads,
-                       c.num_kv_heads, ctx->group, tiles_per_wg, wgs, scores);
+    const score_hist_args ha = {seq_lens, hist, c.partition_tokens, c.topk, c.topk_includes_forced, c.sink_pages,
+                                c.recent_pages, ctx->sel_stride};
+#define SPIN_SKETCH_ARGS                                                                                         \
+  dim3((unsigned)rows * wgs), dim3(SCORE_WAVES * 64), 0, st, (const uint16_t *)q, (const uint2 *)summaries, chan_idx, \
+      part_offsets, c.num_q_heads, c.num_kv_heads, ctx->group, tiles_per_wg, wgs, scores, ha
+    if (hist) spin_launch(ctx, SPIN_K_SCORE, spin_score_sketch_kernel<true>, SPIN_SKETCH_ARGS);
+    else spin_launch(ctx, SPIN_K_SCORE, spin_score_sketch_kernel<false>, SPIN_SKETCH_ARGS);
+#undef SPIN_SKETCH_ARGS
   }
   return spin_launch_status();
+}
+
+extern "C" int spin_score_partitions(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries,
+                                     const int32_t *chan_idx, const int32_t *part_offsets,
+                                     const int32_t *seq_lens, float *scores, void *workspace, void *stream) {
+  return spin_score_impl(ctx, batch, q, summaries, chan_idx, part_offsets, seq_lens, scores, workspace, stream, nullptr);
 }

@@ -164,39 +164,9 @@ __global__ __launch_bounds__(BLOCK) void spin_select_reg_kernel(
 // over both emits the indices ascending, taking the lowest-index ties first.
 // A row whose bin D does not fit the list (heavy ties) falls back, inside the
 // same launch, to the multi-pass algorithms above; the results are the same.
-#define BIG_BINS 4096
 #define BIG_CHUNK 8192
 #define BIG_BLOCK 1024
 #define BIG_CAP 3072
-
-struct sel_plan {
-  int P, nf_lo, first_hi, kprime, take;
-};
-
-// forced prefix / suffix and k' of a row of uniform partitions (same rules as select_reg_row)
-__device__ inline sel_plan select_plan(int N, int PP, int tp, int topk, int includes_forced, int sink_pages,
-                                       int recent_pages, int sel_stride) {
-  sel_plan pl;
-  int P = N > 0 ? (N + tp - 1) / tp : 0;
-  if (P > PP) P = PP;
-  const int pages = (N + 15) >> 4;
-  int sink_end = min(sink_pages, pages);
-  int recent_begin = max(pages - recent_pages, 0);
-  if (sink_end >= recent_begin) { sink_end = pages; recent_begin = pages; }
-  int nf_lo = (N <= sink_end * 16) ? P : min((sink_end * 16) / tp, P);
-  int first_hi = min((recent_begin * 16 + tp - 1) / tp, P);
-  if (first_hi <= nf_lo) { nf_lo = P; first_hi = P; }
-  const int nforced = nf_lo + (P - first_hi);
-  int kprime = includes_forced ? max(topk - nforced, 0) : topk;
-  kprime = min(kprime, P - nforced);
-  int take = nforced + kprime;
-  if (take > sel_stride) {
-    kprime = max(sel_stride - nforced, 0);
-    take = min(nforced + kprime, sel_stride);
-  }
-  pl.P = P; pl.nf_lo = nf_lo; pl.first_hi = first_hi; pl.kprime = kprime; pl.take = take;
-  return pl;
-}
 
 __global__ __launch_bounds__(256) void spin_select_hist_kernel(
     const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
@@ -469,9 +439,9 @@ __global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
   if (tid == 0) nsel[row] = pl.take;
 }
 
-extern "C" int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
-                                const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace,
-                                void *stream) {
+int spin_select_impl(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
+                     const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace, void *stream,
+                     bool hist_ready) {
   if (!ctx || batch < 0 || batch > ctx->cfg.max_batch) return SPIN_ERR_INVALID;
   if (batch == 0) return SPIN_OK;
   if (!scores || !part_offsets || !seq_lens || !sel || !nsel) return SPIN_ERR_INVALID;
@@ -492,10 +462,11 @@ extern "C" int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *score
     int32_t *hist = (int32_t *)((char *)workspace + ctx->ws_hist_off);
     const int words_max = ((ctx->max_parts + 63) / 64) * 2;
     const size_t lds = (size_t)words_max * 8 + (size_t)BIG_CAP * 8;
-    spin_launch(ctx, SPIN_K_SELECT_HIST, spin_select_hist_kernel,
-                dim3((unsigned)((ctx->max_parts + BIG_CHUNK - 1) / BIG_CHUNK), (unsigned)rows), dim3(256), 0,
-                (hipStream_t)stream, scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk,
-                c.topk_includes_forced, c.sink_pages, c.recent_pages, ctx->sel_stride, hist);
+    if (!hist_ready)   // stage 1 may have counted the bins already while it produced the scores
+      spin_launch(ctx, SPIN_K_SELECT_HIST, spin_select_hist_kernel,
+                  dim3((unsigned)((ctx->max_parts + BIG_CHUNK - 1) / BIG_CHUNK), (unsigned)rows), dim3(256), 0,
+                  (hipStream_t)stream, scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk,
+                  c.topk_includes_forced, c.sink_pages, c.recent_pages, ctx->sel_stride, hist);
     spin_launch(ctx, SPIN_K_SELECT, spin_select_big_kernel, dim3((unsigned)rows), dim3(BIG_BLOCK), lds, (hipStream_t)stream,
                 scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk, c.topk_includes_forced,
                 c.sink_pages, c.recent_pages, ctx->sel_stride, sel, nsel, hist, words_max);
@@ -508,4 +479,28 @@ extern "C" int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *score
     spin_launch(ctx, SPIN_K_SELECT, spin_select_kernel, dim3((unsigned)rows), dim3(SEL_BLOCK), SPIN_SELECT_ARGS);
 #undef SPIN_SELECT_ARGS
   return spin_launch_status();
+}
+
+extern "C" int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
+                                const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace,
+                                void *stream) {
+  return spin_select_impl(ctx, batch, scores, part_offsets, seq_lens, sel, nsel, workspace, stream, false);
+}
+
+// Stages 1 and 2 in one call.  Where stage 2 takes two launches and stage 1 can count the leading
+// key bits of its scores as it produces them, the histogram launch is saved; otherwise the two
+// stages are simply issued one after the other.  Same results as the two calls, bit for bit.
+extern "C" int spin_score_select_topk(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries,
+                                      const int32_t *chan_idx, const int32_t *part_offsets,
+                                      const int32_t *seq_lens, float *scores, int32_t *sel, int32_t *nsel,
+                                      void *workspace, void *stream) {
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch) return SPIN_ERR_INVALID;
+  if (batch == 0) return SPIN_OK;
+  if (!sel || !nsel) return SPIN_ERR_INVALID;
+  const bool fuse = ctx->ws_hist_off && workspace && ctx->cfg.score_kind == SPIN_SCORE_SKETCH;
+  int32_t *hist = fuse ? (int32_t *)((char *)workspace + ctx->ws_hist_off) : nullptr;
+  const int st = spin_score_impl(ctx, batch, q, summaries, chan_idx, part_offsets, seq_lens, scores, workspace, stream,
+                                 hist);
+  if (st != SPIN_OK) return st;
+  return spin_select_impl(ctx, batch, scores, part_offsets, seq_lens, sel, nsel, workspace, stream, fuse);
 }

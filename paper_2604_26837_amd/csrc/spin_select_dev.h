@@ -10,6 +10,38 @@ __device__ inline uint32_t score_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// bins of the chip-wide histogram of the leading 12 key bits (stage 2 of long rows)
+#define BIG_BINS 4096
+
+struct sel_plan {
+  int P, nf_lo, first_hi, kprime, take;
+};
+
+// forced prefix / suffix and k' of a row of uniform partitions (same rules as select_reg_row)
+__device__ inline sel_plan select_plan(int N, int PP, int tp, int topk, int includes_forced, int sink_pages,
+                                       int recent_pages, int sel_stride) {
+  sel_plan pl;
+  int P = N > 0 ? (N + tp - 1) / tp : 0;
+  if (P > PP) P = PP;
+  const int pages = (N + 15) >> 4;
+  int sink_end = min(sink_pages, pages);
+  int recent_begin = max(pages - recent_pages, 0);
+  if (sink_end >= recent_begin) { sink_end = pages; recent_begin = pages; }
+  int nf_lo = (N <= sink_end * 16) ? P : min((sink_end * 16) / tp, P);
+  int first_hi = min((recent_begin * 16 + tp - 1) / tp, P);
+  if (first_hi <= nf_lo) { nf_lo = P; first_hi = P; }
+  const int nforced = nf_lo + (P - first_hi);
+  int kprime = includes_forced ? max(topk - nforced, 0) : topk;
+  kprime = min(kprime, P - nforced);
+  int take = nforced + kprime;
+  if (take > sel_stride) {
+    kprime = max(sel_stride - nforced, 0);
+    take = min(nforced + kprime, sel_stride);
+  }
+  pl.P = P; pl.nf_lo = nf_lo; pl.first_hi = first_hi; pl.kprime = kprime; pl.take = take;
+  return pl;
+}
+
 // Register-resident variant for rows of at most BLOCK * KPT partitions: every
 // thread keeps KPT consecutive keys in registers, so scores are read once; each
 // digit has its own LDS histogram, every wavefront does the 256-bin suffix scan

@@ -98,6 +98,17 @@ class LayerState:
         sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
                          self.ws)
 
+    def step12(self, q: torch.Tensor, summaries: Optional[torch.Tensor] = None):
+        """The step with stages 1 and 2 in one call (same results as :meth:`step`)."""
+        sp, w = self.spin, self.w
+        summ = self.summaries if summaries is None else summaries
+        sp.score_select_topk(w.batch, q, summ, self.chan, self.part_offsets, self.seq_lens, self.scores, self.sel,
+                             self.nsel, self.ws)
+        sp.resolve_slots(w.batch, 0, self.sel, self.nsel, self.seq_lens, self.dir, self.leaf_pool, self.slots,
+                         self.page_ids, self.valid_mask, self.npages, self.ws)
+        sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
+                         self.ws)
+
     def step3(self, q: torch.Tensor, summaries: Optional[torch.Tensor] = None):
         """The same step in three launches: stages 2 and 3 share one."""
         sp, w = self.spin, self.w

@@ -1,0 +1,80 @@
+"""Stages 1 and 2 in one call must give exactly what the two stage calls give:
+same score bits, same selection.  Long token rows take the path where stage 1
+counts the leading key bits for stage 2 (the histogram in the workspace must be
+left cleared, so the calls are repeated and interleaved); every other shape
+simply runs the two stages."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import select as oselect
+from paper_2604_26837_amd import runner, synth, tables
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _workloads():
+    c0 = synth.config0()
+    tok = dict(num_q_heads=8, num_kv_heads=2, partition_tokens=1, score_kind=synth.SCORE_SKETCH)
+    return {
+        # two-launch selection: histogram taken by stage 1
+        "long_token_rows": c0.with_(seq_lens=(20000, 17001, 65536), topk=300, sink_pages=1, recent_pages=2,
+                                    name="ss_long", **tok),
+        "long_rows_no_forced": c0.with_(seq_lens=(40000, 16400), topk=1024, sink_pages=0, recent_pages=0,
+                                        name="ss_long_nf", **tok),
+        # one short request in a context sized for long rows; k' = 0 for the request that is all forced
+        "long_context_short_rows": c0.with_(seq_lens=(100, 32, 17000), topk=40, sink_pages=1, recent_pages=1,
+                                            name="ss_mixed", **tok),
+        # shapes where the combined call is the two launches
+        "short_token_rows": c0.with_(seq_lens=(5000, 900), topk=64, sink_pages=1, recent_pages=1, name="ss_short", **tok),
+        "pages_minmax": c0.with_(seq_lens=(4096, 1000, 2049), num_q_heads=8, num_kv_heads=2, topk=24, sink_pages=2,
+                                 recent_pages=3, name="ss_pages"),
+    }
+
+
+@pytest.mark.parametrize("name", list(_workloads()))
+def test_combined_call_equals_the_two_stage_calls(name):
+    w = _workloads()[name]
+    data = synth.generate(w)
+    natural = torch.from_numpy(data.pool_bits.view(np.int16).copy()).to(DEV).view(torch.bfloat16)
+    layer = runner.LayerState.from_natural_pool(w, data.slot_of, natural)
+    if w.score_kind == synth.SCORE_SKETCH:
+        layer.set_channels(synth.sketch_channels(data))
+    layer.build_summaries()
+    sp = layer.spin
+    qs = [torch.from_numpy(synth.make_queries(w, 300 + i).view(np.int16)).to(DEV).view(torch.bfloat16) for i in range(3)]
+    scores2, sel2, nsel2 = torch.zeros_like(layer.scores), torch.zeros_like(layer.sel), torch.zeros_like(layer.nsel)
+    for rep in range(5):
+        q = qs[rep % 3]
+        # the two stage calls
+        sp.score_partitions(w.batch, q, layer.summaries, layer.chan, layer.part_offsets, layer.seq_lens, layer.scores,
+                            layer.ws)
+        sp.select_topk(w.batch, layer.scores, layer.part_offsets, layer.seq_lens, layer.sel, layer.nsel, layer.ws)
+        # the combined call, into its own buffers pre-filled with junk
+        scores2.fill_(-7.0)
+        sel2.fill_(-5)
+        nsel2.fill_(-5)
+        sp.score_select_topk(w.batch, q, layer.summaries, layer.chan, layer.part_offsets, layer.seq_lens, scores2,
+                             sel2, nsel2, layer.ws)
+        torch.cuda.synchronize()
+        assert layer.status() == 0
+        assert torch.equal(nsel2, layer.nsel), f"rep {rep}"
+        assert torch.equal(sel2, layer.sel), f"rep {rep}"
+        s1, s2 = layer.scores.cpu().numpy().view(np.uint32), scores2.cpu().numpy().view(np.uint32)
+        for b in range(w.batch):
+            for h in range(w.num_kv_heads):
+                base = tables.row_base(layer.part_offsets_np, b, h, w.num_kv_heads)
+                P = w.partitions(b)
+                assert np.array_equal(s1[base:base + P], s2[base:base + P]), (rep, b, h)
+    # and against the oracle's selection on the GPU's score bits
+    sc = scores2.cpu().numpy()
+    sel, nsel = sel2.cpu().numpy(), nsel2.cpu().numpy()
+    for b in range(w.batch):
+        for h in range(w.num_kv_heads):
+            r = b * w.num_kv_heads + h
+            base = tables.row_base(layer.part_offsets_np, b, h, w.num_kv_heads)
+            want = oselect.select_topk(sc[base:base + w.partitions(b)].astype(np.float64), w.seq_lens[b], 16,
+                                       w.partition_tokens, w.topk, w.topk_includes_forced, w.sink_pages,
+                                       w.recent_pages)
+            assert sel[r, :nsel[r]].tolist() == list(want), (b, h)
