@@ -14,6 +14,7 @@
  *   spin_gather_misses, spin_copy_misses_host                  Retrieve steps 3-4 (Sections 5.2, 5.5)
  *   spin_offload_pages                                         Offload's copy, slot -> host page (Table 1)
  *   spin_select_resolve                                        stages 2+3 in one launch, same results
+ *   spin_score_select_topk                                     stages 1+2 in one call, same results
  *   spin_set_partition_tables                                  variable-length partitions (Section 5.2)
  *   spin_alloc_leaves, spin_free_leaves, spin_reclaim_tail     on-demand metadata, budget resizing (5.3, 5.4)
  *
