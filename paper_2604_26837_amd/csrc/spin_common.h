@@ -115,6 +115,11 @@ __device__ inline uint4 spin_nt_load(const uint4 *p) {
   return __builtin_bit_cast(uint4, __builtin_nontemporal_load((const spin_u32x4 *)p));
 }
 
+typedef __attribute__((ext_vector_type(2))) unsigned int spin_u32x2;
+__device__ inline uint2 spin_nt_load2(const uint2 *p) {
+  return __builtin_bit_cast(uint2, __builtin_nontemporal_load((const spin_u32x2 *)p));
+}
+
 // fp32 -> bf16 bits, round to nearest even
 __device__ inline uint16_t spin_f32_to_bf16(float f) {
   uint32_t u = __float_as_uint(f);
