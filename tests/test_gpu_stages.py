@@ -50,6 +50,16 @@ def _workloads():
                               recent_pages=4, block_mean_std=0.5, name="g8_blocks"),
         "g16_tokens": c0.with_(seq_lens=(2500,), num_q_heads=32, num_kv_heads=2, partition_tokens=1,
                                score_kind=synth.SCORE_SKETCH, topk=150, planted_frac=0.01, name="g16_tokens"),
+        # token partitions: the four-tile sketch kernel with fewer than four heads and a ragged tile tail,
+        # the one-tile kernel for groups of five and eight heads
+        "g1_tokens": c0.with_(seq_lens=(2500 + 16 * 5, 33), num_q_heads=2, num_kv_heads=2, partition_tokens=1,
+                              score_kind=synth.SCORE_SKETCH, topk=90, name="g1_tokens"),
+        "g3_tokens": c0.with_(seq_lens=(16 * 4 * 9 + 16 * 3 - 5,), num_q_heads=6, num_kv_heads=2, partition_tokens=1,
+                              score_kind=synth.SCORE_SKETCH, topk=60, sink_pages=1, recent_pages=1, name="g3_tokens"),
+        "g5_tokens": c0.with_(seq_lens=(1999,), num_q_heads=10, num_kv_heads=2, partition_tokens=1,
+                              score_kind=synth.SCORE_SKETCH, topk=70, name="g5_tokens"),
+        "g8_tokens": c0.with_(seq_lens=(1200, 640), num_q_heads=16, num_kv_heads=2, partition_tokens=1,
+                              score_kind=synth.SCORE_SKETCH, topk=70, sink_pages=1, name="g8_tokens"),
         "g12_pages": c0.with_(seq_lens=(1500,), num_q_heads=24, num_kv_heads=2, topk=20, sink_pages=1,
                               recent_pages=2, name="g12_pages"),
     }
