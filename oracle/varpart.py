@@ -60,6 +60,21 @@ def minmax_summaries(K_pages: np.ndarray, first_page, tokens, page_tokens: int):
     return mins, maxs
 
 
+def centroids(K_pages: np.ndarray, first_page, tokens, page_tokens: int):
+    """One representative key per partition: the mean key of its tokens (a
+    cluster's centroid, a block's landmark; Section 4.1, Index), rounded to bf16
+    for storage.  Returns the stored values as float64 ``[P][1][D]``, the shape
+    the representative-key score takes."""
+    from . import bf16
+    P, D = len(first_page), K_pages.shape[1]
+    out = np.empty((P, 1, D))
+    for p in range(P):
+        t0 = first_page[p] * page_tokens
+        blk = K_pages[t0: t0 + tokens[p]]
+        out[p, 0] = bf16.decode(bf16.encode_rne(blk.sum(axis=0) / float(tokens[p])))
+    return out
+
+
 def forced_pages(first_page, tokens, page_tokens, sink_pages, recent_pages) -> List[int]:
     pages = row_pages(first_page, tokens, page_tokens)
     s = set(range(0, min(sink_pages, pages)))

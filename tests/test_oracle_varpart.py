@@ -26,6 +26,8 @@ def test_uniform_layout_reproduces_fixed_size_oracle(seq_len, tp, sinks, recents
     a = varpart.minmax_summaries(K, first, toks, 16)
     b = index.minmax_summaries(K, seq_len, tp)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    # one mean key per partition: the fixed-size representatives with a single sub-range
+    assert np.array_equal(varpart.centroids(K, first, toks, 16), index.block_representatives(K, seq_len, tp, 1))
 
 
 def test_hand_worked_ragged_layout():
@@ -52,3 +54,27 @@ def test_hand_worked_ragged_layout():
     mins, maxs = varpart.minmax_summaries(K, first, toks, 16)
     assert mins[2].tolist() == [96.0, -105.0] and maxs[2].tolist() == [104.0, -97.0]
     assert maxs[3][0] == (64 + 39) * 2 and mins[4][0] == 112 * 2
+
+
+def test_centroids_by_hand():
+    """The centroid is the arithmetic mean of the partition's own tokens (not of its pages'
+    padding), stored with one bf16 rounding."""
+    toks = [20, 16, 5, 40, 33]
+    first = [0, 2, 3, 4, 7]
+    K = np.arange(160 * 2, dtype=np.float64).reshape(160, 2) * np.array([1.0, -1.0])
+    c = varpart.centroids(K, first, toks, 16)
+    assert c.shape == (5, 1, 2)
+    # partition 0: tokens 0..19, channel 0 holds 0, 2, .., 38 -> mean 19; channel 1 holds -1, -3, .., -39 -> -20
+    assert c[0, 0].tolist() == [19.0, -20.0]
+    # partition 2: 5 tokens from page 3 (token 48): 96..104 step 2 -> 100; -97..-105 -> -101
+    assert c[2, 0].tolist() == [100.0, -101.0]
+    # partition 4: 33 tokens from token 112: mean of 224..288 step 2 = 256; bf16 keeps it
+    assert c[4, 0, 0] == 256.0
+    # constant keys: the centroid is that key, whatever the partition sizes
+    Kc = np.tile(np.array([[0.5, -3.0, 7.0]]), (160, 1))
+    assert np.array_equal(varpart.centroids(Kc, first, toks, 16), np.tile(Kc[0], (5, 1, 1)))
+    # one rounding to bf16 (8 significant bits): mean 1 + 2^-9 of two tokens rounds to 1
+    Kr = np.zeros((160, 1))
+    Kr[32] = 1.0
+    Kr[33] = 1.0 + 2.0 ** -8
+    assert varpart.centroids(Kr, [0, 2], [32, 2], 16)[1, 0, 0] == 1.0
