@@ -103,7 +103,7 @@ typedef struct spin_config {
   int32_t partition_tokens;     /* divides 16, or a multiple of 16 */
   int32_t score_kind;           /* spin_score_kind */
   int32_t sketch_channels;      /* 16 (SKETCH) */
-  int32_t reps_per_partition;   /* 4  (REPMAX) */
+  int32_t reps_per_partition;   /* REPMAX: 1 (one mean key per partition: a landmark or centroid), 2 or 4 */
   int32_t topk;                 /* partitions per row (tokens when partition_tokens == 1) */
   int32_t topk_includes_forced; /* 1: forced partitions count against topk; 0: they come on top */
   int32_t sink_pages;           /* first pages of a context, always attended */
@@ -179,7 +179,9 @@ int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_
  * cfg.partition_tokens tokens: cfg.partition_tokens is then the LARGEST partition
  * (it sizes the strides) and seq_lens is not consulted by stages 2 and 3.  Sink and
  * recent pages are the first / last pages of the row's page list.  Supported for
- * MINMAX scores, in all-resident and in budget mode, rows of at most 65536 partitions.  Passing
+ * MINMAX scores and for REPMAX with one representative (the mean key of the partition's
+ * tokens: a cluster's centroid), in all-resident and in budget mode, rows of at most
+ * 65536 partitions.  Passing
  * NULL for the three tables returns to uniform partitions.  The pointers are kept,
  * not copied: the tables must outlive the calls that use them. */
 int spin_set_partition_tables(spin_ctx *ctx, const int32_t *part_offsets, const int32_t *part_count,

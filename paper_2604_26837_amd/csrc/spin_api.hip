@@ -44,8 +44,10 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   switch (c->score_kind) {
     case SPIN_SCORE_MINMAX: x->kd = 256; x->rows_per_part = 1; break;
     case SPIN_SCORE_REPMAX:
-      if (c->reps_per_partition != 4 || tp % 4 != 0) { delete x; return SPIN_ERR_UNSUPPORTED; }
-      x->kd = 128; x->rows_per_part = 4; break;
+      // 1 = one mean key per partition (a landmark / centroid), 2 or 4 = means of equal sub-ranges
+      if ((c->reps_per_partition != 1 && c->reps_per_partition != 2 && c->reps_per_partition != 4) ||
+          tp % c->reps_per_partition != 0) { delete x; return SPIN_ERR_UNSUPPORTED; }
+      x->kd = 128; x->rows_per_part = c->reps_per_partition; break;
     case SPIN_SCORE_SKETCH:
       if (c->sketch_channels != 16) { delete x; return SPIN_ERR_UNSUPPORTED; }
       x->kd = 16; x->rows_per_part = 1; break;
@@ -193,7 +195,10 @@ extern "C" int spin_set_partition_tables(spin_ctx *ctx, const int32_t *part_offs
   }
   if (!part_offsets || !part_count || !part_first_page || !part_tokens) return SPIN_ERR_INVALID;
   const spin_config &c = ctx->cfg;
-  if (c.partition_tokens < 16 || c.score_kind != SPIN_SCORE_MINMAX) return SPIN_ERR_UNSUPPORTED;
+  // summaries that exist for partitions of any length: min / max keys, or one mean key (centroid)
+  const bool kind_ok = c.score_kind == SPIN_SCORE_MINMAX ||
+                       (c.score_kind == SPIN_SCORE_REPMAX && c.reps_per_partition == 1);
+  if (c.partition_tokens < 16 || !kind_ok) return SPIN_ERR_UNSUPPORTED;
   ctx->var = spin_var{part_offsets, part_count, part_first_page, part_tokens};
   return SPIN_OK;
 }

@@ -230,14 +230,16 @@ __global__ __launch_bounds__(256) void spin_index_repmean_pages_kernel(
     const uint4 *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
     const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int reps, int dir_stride, int leaf_entries,
-    int max_tiles, uint16_t *__restrict__ summ, int32_t *status) {
+    int max_tiles, uint16_t *__restrict__ summ, int32_t *status, spin_var var) {
   __shared__ uint4 s_tile[4][SPIN_KTILE_U4];
   const int row = blockIdx.x / max_tiles, tile = blockIdx.x - row * max_tiles;
   const int b = row / Hkv, h = row - b * Hkv;
   const int PP = part_offsets[b + 1] - part_offsets[b];
   if (tile * 16 >= PP * reps) return;
   const int N = seq_lens[b];
-  const int P = (N + tp - 1) / tp;
+  // variable-length partitions (one representative each: the mean key of the partition's own tokens)
+  int P = var.count ? var.count[row] : (N + tp - 1) / tp;
+  P = P < 0 ? 0 : (P > PP ? PP : P);
   const size_t base = ((size_t)Hkv * part_offsets[b] + (size_t)h * PP) * reps;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ch = lane >> 2, tq = lane & 3;      // after regrouping: chunk of 8 channels, tokens 4tq..4tq+3
@@ -252,6 +254,10 @@ __global__ __launch_bounds__(256) void spin_index_repmean_pages_kernel(
       // an empty sub-range repeats representative 0 of the partition
       int t0 = p * tp + rep * sub, t1 = min(t0 + sub, N);
       if (t1 <= t0) { t0 = p * tp; t1 = min(t0 + sub, N); }
+      if (var.count) {                           // reps == 1: base indexes the tables as it does the rows
+        t0 = var.first_page[base + p] * 16;
+        t1 = t0 + var.tokens[base + p];
+      }
       double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
       for (int pg = t0 >> 4; pg <= (t1 - 1) >> 4; ++pg) {
         const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
@@ -344,7 +350,11 @@ extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv
   if (!kv_pool || !dir || !leaf_pool || !part_offsets || !seq_lens || !summaries) return SPIN_ERR_INVALID;
   if (!workspace) return SPIN_ERR_WORKSPACE;
   const spin_config &c = ctx->cfg;
-  if (ctx->var.count && !(c.score_kind == SPIN_SCORE_MINMAX && c.partition_tokens >= 16)) return SPIN_ERR_UNSUPPORTED;
+  // variable-length partitions: min/max keys, or one mean key (centroid) per partition
+  if (ctx->var.count && !(c.partition_tokens >= 16 &&
+                          (c.score_kind == SPIN_SCORE_MINMAX ||
+                           (c.score_kind == SPIN_SCORE_REPMAX && c.reps_per_partition == 1))))
+    return SPIN_ERR_UNSUPPORTED;
   const int rows = batch * c.num_kv_heads;
   const int max_pp = ((ctx->max_parts + 15) / 16) * 16;
   hipStream_t st = (hipStream_t)stream;
@@ -363,11 +373,11 @@ extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv
                        (uint16_t *)summaries, status, ctx->k_token_major);
   } else if (c.score_kind == SPIN_SCORE_REPMAX) {
     const int max_tiles = max_pp * c.reps_per_partition / 16;
-    if ((c.partition_tokens / c.reps_per_partition) % 16 == 0)
+    if ((c.partition_tokens / c.reps_per_partition) % 16 == 0 || ctx->var.count)
       spin_launch(ctx, SPIN_K_INDEX, spin_index_repmean_pages_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
                   (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
                   c.num_kv_heads, c.partition_tokens, c.reps_per_partition, ctx->dir_stride, c.leaf_entries,
-                  max_tiles, (uint16_t *)summaries, status);
+                  max_tiles, (uint16_t *)summaries, status, ctx->var);
     else
       spin_launch(ctx, SPIN_K_INDEX, spin_index_repmean_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
                   (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,

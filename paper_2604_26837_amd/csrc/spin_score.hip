@@ -246,14 +246,15 @@ int spin_score_impl(spin_ctx *ctx, int32_t batch, const void *q, const void *sum
       spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_kernel<8, true, 4>, dim3((unsigned)rows * wgs), dim3(256),
                   SPIN_SCORE_ARGS(1));
   } else if (c.score_kind == SPIN_SCORE_REPMAX) {
-    const int tiles_per_wg = c.score_tiles_per_wg ? c.score_tiles_per_wg : 2 * W, max_tiles = max_pp * 4 / 16;
+    const int R = c.reps_per_partition;
+    const int tiles_per_wg = c.score_tiles_per_wg ? c.score_tiles_per_wg : 2 * W, max_tiles = max_pp * R / 16;
     const int wgs = (max_tiles + tiles_per_wg - 1) / tiles_per_wg;
     if (W == 8)
       spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_kernel<4, false, 8>, dim3((unsigned)rows * wgs), dim3(512),
-                  SPIN_SCORE_ARGS(4));
+                  SPIN_SCORE_ARGS(R));
     else
       spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_kernel<4, false, 4>, dim3((unsigned)rows * wgs), dim3(256),
-                  SPIN_SCORE_ARGS(4));
+                  SPIN_SCORE_ARGS(R));
 #undef SPIN_SCORE_ARGS
   } else {
     if (!chan_idx) return SPIN_ERR_INVALID;

@@ -40,7 +40,7 @@ __device__ inline float spin_head_max(const spin_f32x4 &s, int c, int G) {
 
 template <int NJ, bool MINMAX>
 __device__ inline void consume_tile(const score_tile<NJ> &r, const spin_bf16x8 (&qf)[NJ], int n, int c, int G,
-                                    float *__restrict__ scores, size_t base, int t) {
+                                    int rpp, float *__restrict__ scores, size_t base, int t) {
   // the queries are the A operand, the summary rows the B operand: lane (n, c) ends up with
   // S[head 4c+i][summary row n], so the maximum over the group's heads stays inside the lane
   // (plus two exchanges between the lane quarters when the group has more than 4 heads)
@@ -54,11 +54,12 @@ __device__ inline void consume_tile(const score_tile<NJ> &r, const spin_bf16x8 (
       scores[base + (size_t)t * 16 + n] = m;
     }
   } else {
-    // rows 4p..4p+3 are the four representatives of partition 4t + p: lanes n = 4p .. 4p+3
-    m = fmaxf(m, spin_dpp<SPIN_DPP_XOR1>(m));
-    m = fmaxf(m, spin_dpp<SPIN_DPP_XOR2>(m));
-    if (c == 0 && (n & 3) == 0) {
-      scores[base + (size_t)t * 4 + (n >> 2)] = m;
+    // rows rpp*p .. rpp*p + rpp-1 (rpp = 1, 2 or 4) are the representatives of partition (16/rpp) t + p:
+    // neighbouring lanes n
+    if (rpp >= 2) m = fmaxf(m, spin_dpp<SPIN_DPP_XOR1>(m));
+    if (rpp == 4) m = fmaxf(m, spin_dpp<SPIN_DPP_XOR2>(m));
+    if (c == 0 && (n & (rpp - 1)) == 0) {
+      scores[base + (size_t)t * (16 / rpp) + n / rpp] = m;
     }
   }
 }
@@ -104,9 +105,9 @@ __device__ inline void score_row_tiles(
   for (; t < t_end; t += 2 * WAVES) {
     const int t1 = t + WAVES, t2 = t + 2 * WAVES;
     if (t1 < t_end) load_tile<NJ>(rb, tiles + (size_t)t1 * (NJ * 64), lane);
-    consume_tile<NJ, MINMAX>(ra, qf, n, c, G, scores, base, t);
+    consume_tile<NJ, MINMAX>(ra, qf, n, c, G, rows_per_part, scores, base, t);
     if (t2 < t_end) load_tile<NJ>(ra, tiles + (size_t)t2 * (NJ * 64), lane);
-    if (t1 < t_end) consume_tile<NJ, MINMAX>(rb, qf, n, c, G, scores, base, t1);
+    if (t1 < t_end) consume_tile<NJ, MINMAX>(rb, qf, n, c, G, rows_per_part, scores, base, t1);
   }
 }
 

@@ -109,6 +109,10 @@ int main() {
     c.max_context = 131072; good.push_back(c); c.max_context = 262144; good.push_back(c); }
   { spin_config c = base_config(); c.partition_tokens = 128; c.score_kind = SPIN_SCORE_REPMAX; c.topk = 32;
     c.topk_includes_forced = 0; c.sink_pages = 4; c.recent_pages = 64; c.max_context = 131072; good.push_back(c); }
+  for (int reps : {1, 2}) { spin_config c = base_config(); c.score_kind = SPIN_SCORE_REPMAX; c.reps_per_partition = reps;
+    c.partition_tokens = 64; good.push_back(c); c.partition_tokens = 16; good.push_back(c); }
+  { spin_config c = base_config(); c.score_kind = SPIN_SCORE_REPMAX; c.reps_per_partition = 1; c.variable_partitions = 1;
+    c.partition_tokens = 128; good.push_back(c); }
   for (int pol : {0, 1}) for (int exact : {0, 1}) {
     spin_config c = base_config(); c.lru_timestamps = 64; c.lru_policy = pol; c.lru_evict_exact = exact;
     c.max_context = 262144; c.max_batch = 32; good.push_back(c);
@@ -148,6 +152,7 @@ int main() {
   { spin_config c = base_config(); c.max_batch = 0; bad.push_back(c); }
   { spin_config c = base_config(); c.max_context = 0; bad.push_back(c); }
   { spin_config c = base_config(); c.score_kind = 7; bad.push_back(c); }
+  { spin_config c = base_config(); c.score_kind = SPIN_SCORE_REPMAX; c.reps_per_partition = 3; bad.push_back(c); }
   { spin_config c = base_config(); c.topk = -1; bad.push_back(c); }
   { spin_config c = base_config(); c.sink_pages = -1; bad.push_back(c); }
   { spin_config c = base_config(); c.decode_waves = 3; bad.push_back(c); }

@@ -28,7 +28,7 @@ def _oracle_rows(w, K, n, chan_h):
     return index.key_sketch(K, n, chan_h)
 
 
-@pytest.mark.parametrize("kind", ["minmax_page", "minmax_block", "repmax", "sketch"])
+@pytest.mark.parametrize("kind", ["minmax_page", "minmax_block", "repmax", "sketch", "mean_page", "two_reps_block"])
 def test_append_tokens(kind):
     c0 = synth.config0().with_(num_q_heads=8, num_kv_heads=2)
     final = (500, 128 * 3 + 37, 70)
@@ -38,6 +38,11 @@ def test_append_tokens(kind):
         "minmax_block": c0.with_(seq_lens=final, partition_tokens=64, topk=3, sink_pages=1, recent_pages=1, name="a2"),
         "repmax": c0.with_(seq_lens=final, partition_tokens=128, score_kind=synth.SCORE_REPMAX, topk=2,
                            topk_includes_forced=False, sink_pages=1, recent_pages=2, block_mean_std=0.5, name="a3"),
+        "mean_page": c0.with_(seq_lens=final, score_kind=synth.SCORE_REPMAX, reps_per_partition=1, topk=8,
+                              sink_pages=1, recent_pages=1, block_mean_std=0.5, name="a5"),
+        "two_reps_block": c0.with_(seq_lens=final, partition_tokens=64, score_kind=synth.SCORE_REPMAX,
+                                   reps_per_partition=2, topk=3, topk_includes_forced=False, sink_pages=1,
+                                   recent_pages=1, block_mean_std=0.5, name="a6"),
         "sketch": c0.with_(seq_lens=final, partition_tokens=1, score_kind=synth.SCORE_SKETCH, topk=40,
                            sink_pages=0, recent_pages=0, name="a4"),
     }[kind]

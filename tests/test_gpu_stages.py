@@ -41,6 +41,18 @@ def _workloads():
         "blocks_small": c0.with_(seq_lens=(70 * 32 + 9, 32 * 16), partition_tokens=32, score_kind=synth.SCORE_REPMAX,
                                  topk=7, topk_includes_forced=False, sink_pages=2, recent_pages=3, block_mean_std=0.5,
                                  name="blocks_small"),
+        # one mean key per partition (a landmark per page, a centroid per block) and two representatives
+        "mean_pages": c0.with_(seq_lens=(3000, 16 * 130 + 5), score_kind=synth.SCORE_REPMAX, reps_per_partition=1,
+                               topk=24, sink_pages=2, recent_pages=3, block_mean_std=0.5, name="mean_pages"),
+        "mean_blocks": c0.with_(seq_lens=(64 * 50 + 17, 640), partition_tokens=64, score_kind=synth.SCORE_REPMAX,
+                                reps_per_partition=1, topk=6, topk_includes_forced=False, sink_pages=1,
+                                recent_pages=5, block_mean_std=0.5, name="mean_blocks"),
+        "two_reps_blocks": c0.with_(seq_lens=(64 * 41 + 33,), partition_tokens=64, score_kind=synth.SCORE_REPMAX,
+                                    reps_per_partition=2, topk=6, topk_includes_forced=False, sink_pages=1,
+                                    recent_pages=2, block_mean_std=0.5, name="two_reps_blocks"),
+        "mean_quarter_pages": c0.with_(seq_lens=(777,), partition_tokens=4, score_kind=synth.SCORE_REPMAX,
+                                       reps_per_partition=1, topk=40, sink_pages=1, recent_pages=1,
+                                       block_mean_std=0.5, name="mean_quarter_pages"),
         # group sizes other than 4: one head, a group that is no power of two, more than one lane quarter
         "g1_pages": c0.with_(seq_lens=(900, 333), num_q_heads=2, num_kv_heads=2, topk=12, sink_pages=1,
                              recent_pages=1, name="g1_pages"),

@@ -20,7 +20,9 @@ def _check(w, layouts, data, layer, three_launch):
     torch.cuda.synchronize()
     assert layer.status() == 0
     raw = layer.summaries.cpu().numpy().view(np.uint16)
-    rows16 = raw.reshape(-1, 32, 16, 8).transpose(0, 2, 1, 3).reshape(-1, 256)
+    centroid = w.score_kind == synth.SCORE_REPMAX          # one mean key per partition instead of min / max
+    kd = 128 if centroid else 256
+    rows16 = raw.reshape(-1, kd // 8, 16, 8).transpose(0, 2, 1, 3).reshape(-1, kd)
     scores = layer.scores.cpu().numpy()
     sel, nsel = layer.sel.cpu().numpy(), layer.nsel.cpu().numpy()
     slots, npages = layer.slots.cpu().numpy(), layer.npages.cpu().numpy()
@@ -36,12 +38,18 @@ def _check(w, layouts, data, layer, three_launch):
             kb, vb = data.logical_kv_bits(b, h)
             K = bf16.decode(kb)
             qh = bf16.decode(data.q_bits[b, h * g:(h + 1) * g])
-            mins, maxs = varpart.minmax_summaries(K, first, toks, 16)
             base = layer.row_base(b, h)
             got = bf16.decode(rows16[base: base + P])
-            assert np.array_equal(got, np.concatenate([maxs, mins], axis=1)), f"summaries row {r}"
-            s64 = score.score_minmax(qh, mins, maxs)
-            eps = 256 * 2.0 ** -24 * np.maximum(np.abs(qh[:, None] * mins[None]), np.abs(qh[:, None] * maxs[None])).sum(-1).max()
+            if centroid:
+                cents = varpart.centroids(K, first, toks, 16)
+                assert np.array_equal(got, cents[:, 0]), f"summaries row {r}"
+                s64 = score.score_repmax(qh, cents)
+                eps = 128 * 2.0 ** -24 * np.abs(qh[:, None] * cents[None, :, 0]).sum(-1).max()
+            else:
+                mins, maxs = varpart.minmax_summaries(K, first, toks, 16)
+                assert np.array_equal(got, np.concatenate([maxs, mins], axis=1)), f"summaries row {r}"
+                s64 = score.score_minmax(qh, mins, maxs)
+                eps = 256 * 2.0 ** -24 * np.maximum(np.abs(qh[:, None] * mins[None]), np.abs(qh[:, None] * maxs[None])).sum(-1).max()
             s32 = scores[base: base + P]
             assert np.all(np.abs(s32.astype(np.float64) - s64) <= eps)
             want = varpart.select_topk(s32, first, toks, 16, w.topk, w.topk_includes_forced, w.sink_pages,
@@ -62,10 +70,15 @@ def _check(w, layouts, data, layer, three_launch):
 
 
 @pytest.mark.parametrize("three_launch", [False, True])
-@pytest.mark.parametrize("case", ["clusters", "mostly_single_pages", "forced_heavy"])
+@pytest.mark.parametrize("case", ["clusters", "mostly_single_pages", "forced_heavy", "cluster_centroids"])
 def test_variable_length_partitions(case, three_launch):
     c0 = synth.config0().with_(num_q_heads=8, num_kv_heads=2)
     w, min_tok = {
+        # clusters scored through their centroid (one mean key per partition)
+        "cluster_centroids": (c0.with_(seq_lens=(16 * 300, 16 * 77, 16 * 1000), partition_tokens=96,
+                                       score_kind=synth.SCORE_REPMAX, reps_per_partition=1, topk=12,
+                                       topk_includes_forced=False, sink_pages=3, recent_pages=5,
+                                       block_mean_std=0.5, name="v4"), 1),
         "clusters": (c0.with_(seq_lens=(16 * 300, 16 * 77, 16 * 1000), partition_tokens=80, topk=12,
                               topk_includes_forced=False, sink_pages=3, recent_pages=5, name="v1"), 1),
         "mostly_single_pages": (c0.with_(seq_lens=(16 * 500, 16 * 40), partition_tokens=32, topk=30,
