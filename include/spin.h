@@ -15,6 +15,7 @@
  *   spin_offload_pages                                         Offload's copy, slot -> host page (Table 1)
  *   spin_select_resolve                                        stages 2+3 in one launch, same results
  *   spin_score_select_topk                                     stages 1+2 in one call, same results
+ *   spin_pin_partitions                                        always-attended outlier partitions (Section 4.2)
  *   spin_set_partition_tables                                  variable-length partitions (Section 5.2)
  *   spin_alloc_leaves, spin_free_leaves, spin_reclaim_tail     on-demand metadata, budget resizing (5.3, 5.4)
  *
@@ -249,6 +250,17 @@ int spin_score_partitions(spin_ctx *ctx, int32_t batch, const void *q, const voi
 int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
                      const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace,
                      void *stream);
+
+/* Pinned partitions (Section 4.2: outliers found by an algorithm's Index, like the
+ * recent window, always participate in attention).  Run between stages 1 and 2:
+ * pinned (DEVICE int32 [rows][pinned_stride]) lists npinned[row] (DEVICE int32
+ * [rows]) partition ids per row, in any order; their scores become +inf, so stage
+ * 2 takes them before every other candidate (they count against k'; ties among
+ * +inf scores go to the lower id) and, under a budget, stage 3b keeps their pages
+ * resident because they are selected in every step.  Ids outside the row are
+ * ignored; forced partitions are unaffected (they are no candidates). */
+int spin_pin_partitions(spin_ctx *ctx, int32_t batch, float *scores, const int32_t *part_offsets,
+                        const int32_t *pinned, const int32_t *npinned, int32_t pinned_stride, void *stream);
 
 /* Stages 1 and 2 in ONE call: arguments and results are exactly those of
  * spin_score_partitions followed by spin_select_topk, bit for bit (the scores

@@ -68,3 +68,17 @@ def select_topk(scores, seq_len: int, page_tokens: int, partition_tokens: int, t
     cands = [p for p in range(P) if p not in fset]
     best = sorted(cands, key=rank_key)[:kprime]
     return sorted(fset | set(best))
+
+
+def pin_scores(scores, seq_len: int, partition_tokens: int, pinned):
+    """Outlier partitions that, like the recent window, always participate in
+    attention (Section 4.2): a pinned partition ranks above every finite score,
+    i.e. as a score of +inf.  Returns a copy of ``scores`` (float64); ids outside
+    the row's partitions are ignored."""
+    import numpy as np
+    P = -(-seq_len // partition_tokens)
+    out = np.array(scores, dtype=np.float64, copy=True)
+    for p in pinned:
+        if 0 <= p < P:
+            out[p] = math.inf
+    return out

@@ -23,7 +23,7 @@ EXPORTS = [
     "spin_workspace_init", "spin_poll_status", "spin_profile_enable", "spin_profile_read", "spin_pack_kv_pages", "spin_build_summaries",
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
     "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv", "spin_reclaim_tail", "spin_alloc_leaves", "spin_free_leaves",
-    "spin_set_partition_tables", "spin_probe_stream_read", "spin_offload_pages", "spin_score_select_topk",
+    "spin_set_partition_tables", "spin_probe_stream_read", "spin_offload_pages", "spin_score_select_topk", "spin_pin_partitions",
 ]
 
 
@@ -73,6 +73,7 @@ def load_library() -> C.CDLL:
     lib.spin_score_partitions.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_score_select_topk.argtypes = [vp, i32] + [vp] * 10
+    lib.spin_pin_partitions.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_probe_stream_read.argtypes = [vp, vp, C.c_size_t, vp, vp]
@@ -255,6 +256,12 @@ class Spin:
             self.h, batch, _ptr(scores, torch.float32, "scores"), _ptr(part_offsets, torch.int32, "part_offsets"),
             _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(sel, torch.int32, "sel"),
             _ptr(nsel, torch.int32, "nsel"), _ptr(ws), _stream()), "spin_select_topk")
+
+    def pin_partitions(self, batch, scores, part_offsets, pinned, npinned):
+        self._check(self.lib.spin_pin_partitions(
+            self.h, batch, _ptr(scores, torch.float32, "scores"), _ptr(part_offsets, torch.int32, "part_offsets"),
+            _ptr(pinned, torch.int32, "pinned"), _ptr(npinned, torch.int32, "npinned"), pinned.shape[1], _stream()),
+            "spin_pin_partitions")
 
     def score_select_topk(self, batch, q, summaries, chan_idx, part_offsets, seq_lens, scores, sel, nsel, ws):
         self._check(self.lib.spin_score_select_topk(

@@ -42,6 +42,8 @@ static void poke(spin_ctx *x, const spin_config &c) {
     EXPECT(want_ok ? st == SPIN_OK : st == SPIN_ERR_INVALID);
     st = spin_score_select_topk(x, batch, n, n, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, ws, n);
     EXPECT(want_ok ? st == SPIN_OK : st == SPIN_ERR_INVALID);
+    st = spin_pin_partitions(x, batch, nullptr, nullptr, nullptr, nullptr, 4, n);
+    EXPECT(want_ok ? st == SPIN_OK : st == SPIN_ERR_INVALID);
     st = spin_resolve_slots(x, batch, 0, nullptr, nullptr, nullptr, nullptr, nullptr, 1, nullptr, nullptr, nullptr,
                             nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, ws, n);
     EXPECT(want_ok ? st == SPIN_OK : st < 0);

@@ -121,3 +121,27 @@ def test_token_partitions_forced_pages_force_their_tokens():
     s[21] = 2.0
     got = select.select_topk(s, seq, 16, 1, 24, True, 1, 1)
     assert got == sorted(f + [20, 40])
+
+
+def test_pinned_partitions_always_participate():
+    """Pinned (outlier) partitions are taken before every other candidate: an
+    independent statement of the rule -- pinned candidates first, ascending id, then
+    the best of the rest -- must agree with selecting on the pinned scores."""
+    rng = np.random.default_rng(11)
+    seq_len, tp, k = 16 * 60, 16, 12
+    for trial in range(20):
+        scores = np.round(rng.standard_normal(60) * 4) / 4
+        pinned = sorted(set(int(x) for x in rng.integers(-3, 66, size=int(rng.integers(0, 9)))))
+        sinks, recents = int(rng.integers(0, 3)), int(rng.integers(0, 4))
+        got = select.select_topk(select.pin_scores(scores, seq_len, tp, pinned), seq_len, 16, tp, k, True, sinks, recents)
+        forced = select.forced_partitions(seq_len, 16, tp, sinks, recents)
+        kprime = max(k - len(forced), 0)
+        pin_c = [p for p in pinned if 0 <= p < 60 and p not in forced][:kprime]
+        rest = [p for p in range(60) if p not in forced and p not in pin_c]
+        rest.sort(key=lambda p: (-scores[p], p))
+        want = sorted(set(forced) | set(pin_c) | set(rest[:kprime - len(pin_c)]))
+        assert got == want, trial
+    # the input is left alone and out-of-row ids are ignored
+    s = np.zeros(4)
+    out = select.pin_scores(s, 64, 16, [1, 9, -1])
+    assert s.tolist() == [0, 0, 0, 0] and out.tolist() == [0.0, math.inf, 0.0, 0.0]
