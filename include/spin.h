@@ -268,7 +268,8 @@ int spin_pin_partitions(spin_ctx *ctx, int32_t batch, float *scores, const int32
  * launches (rows of 16385 to 131072 partitions) stage 1 counts the leading key
  * bits of its scores while it still holds them, so the histogram launch over
  * the score array is saved; every other configuration simply runs the two
- * stages one after the other.  The workspace is needed as for the two calls. */
+ * stages one after the other.  The workspace is needed as for the two calls.
+ * (Pinned partitions go between the two stages: use the separate calls then.) */
 int spin_score_select_topk(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries,
                            const int32_t *chan_idx, const int32_t *part_offsets, const int32_t *seq_lens,
                            float *scores, int32_t *sel, int32_t *nsel, void *workspace, void *stream);
