@@ -451,7 +451,7 @@ int spin_select_impl(spin_ctx *ctx, int32_t batch, const float *scores, const in
   0, (hipStream_t)stream, scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk,         \
       c.topk_includes_forced, c.sink_pages, c.recent_pages, ctx->sel_stride, sel, nsel
   if (ctx->max_parts <= 2048)
-    spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<256, 8>, dim3((unsigned)rows), dim3(256), SPIN_SELECT_ARGS, ctx->var);
+    spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<512, 4>, dim3((unsigned)rows), dim3(512), SPIN_SELECT_ARGS, ctx->var);
   else if (ctx->max_parts <= 4096)
     spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<512, 8>, dim3((unsigned)rows), dim3(512), SPIN_SELECT_ARGS, ctx->var);
   else if (ctx->max_parts <= 16384)

@@ -42,7 +42,7 @@ extern "C" int spin_select_resolve(spin_ctx *ctx, int32_t batch, const float *sc
       leaf_chunks, ctx->page_stride, ctx->dir_stride, c.leaf_entries, slots, page_ids, valid_mask, npages,    \
       (int32_t *)workspace, ctx->var
   if (ctx->max_parts <= 2048)
-    spin_launch(ctx, SPIN_K_SELECT, spin_select_resolve_kernel<256, 8>, dim3((unsigned)rows), dim3(256), SPIN_SR_ARGS);
+    spin_launch(ctx, SPIN_K_SELECT, spin_select_resolve_kernel<512, 4>, dim3((unsigned)rows), dim3(512), SPIN_SR_ARGS);
   else if (ctx->max_parts <= 4096)
     spin_launch(ctx, SPIN_K_SELECT, spin_select_resolve_kernel<512, 8>, dim3((unsigned)rows), dim3(512), SPIN_SR_ARGS);
   else
