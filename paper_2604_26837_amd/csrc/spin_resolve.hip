@@ -34,7 +34,7 @@ __global__ __launch_bounds__(RES_BLOCK) void spin_resolve_kernel(
 // count covers the net demand, and the pages at or below x are evicted,
 // (4) the misses (ascending page id) take the free slots (ascending slot id),
 // found with one prefix sum over the slots.
-#define LRU_BLOCK 256
+#define LRU_BLOCK 512
 #define LRU_WAVES (LRU_BLOCK / 64)
 #define LRU_MAX_TS 256
 
