@@ -17,6 +17,7 @@
  *   spin_score_select_topk                                     stages 1+2 in one call, same results
  *   spin_pin_partitions                                        always-attended outlier partitions (Section 4.2)
  *   spin_set_partition_tables                                  variable-length partitions (Section 5.2)
+ *   spin_set_host_page_table                                   CPU page table (Section 5.2)
  *   spin_alloc_leaves, spin_free_leaves, spin_reclaim_tail     on-demand metadata, budget resizing (5.3, 5.4)
  *
  * Conventions
@@ -348,6 +349,20 @@ int spin_alloc_leaves(spin_ctx *ctx, int32_t batch, const int32_t *sel, const in
                       uint32_t *leaf_bitmap, void *workspace, void *stream);
 int spin_free_leaves(spin_ctx *ctx, int32_t batch, int32_t *dir, int64_t leaf_chunks, uint32_t *leaf_bitmap,
                      void *workspace, void *stream);
+
+/* CPU page table (Section 5.2: the Partition Offset table says where a partition's
+ * page list starts in the CPU page table, a flat array of physical CPU page ids).
+ * Without one, page p of row r lives at page host_row_base[r] + p of the pinned
+ * host pool.  With one registered, that sum is an OFFSET into cpu_pages
+ * (int32 [entries], in pinned host memory so that both the copy kernel and
+ * spin_copy_misses_host read it), and the entry there is the physical host page
+ * (in [0, host_pages)): a request's pages may lie anywhere in the host pool, e.g.
+ * as they were allocated while its context grew.  Applies to
+ * spin_gather_misses, spin_offload_pages and spin_copy_misses_host; an offset or
+ * entry out of range raises SPIN_ERR_SLOT_RANGE (SPIN_ERR_INVALID from the
+ * host-driven copier) and skips the page.  NULL returns to the identity.  The
+ * pointer is kept, not copied. */
+int spin_set_host_page_table(spin_ctx *ctx, const int32_t *cpu_pages, int64_t entries, int64_t host_pages);
 
 /* Retrieve steps 3-4 (Section 5.2), after budget-mode stage 3: copy every missed
  * page into the slot assigned to it.  The full KV lives in pinned host memory as

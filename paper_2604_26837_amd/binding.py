@@ -24,6 +24,7 @@ EXPORTS = [
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
     "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv", "spin_reclaim_tail", "spin_alloc_leaves", "spin_free_leaves",
     "spin_set_partition_tables", "spin_probe_stream_read", "spin_offload_pages", "spin_score_select_topk", "spin_pin_partitions",
+    "spin_set_host_page_table",
 ]
 
 
@@ -74,6 +75,7 @@ def load_library() -> C.CDLL:
     lib.spin_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_score_select_topk.argtypes = [vp, i32] + [vp] * 10
     lib.spin_pin_partitions.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
+    lib.spin_set_host_page_table.argtypes = [vp, vp, i64, i64]
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_probe_stream_read.argtypes = [vp, vp, C.c_size_t, vp, vp]
@@ -225,6 +227,17 @@ class Spin:
             self.h, _ptr(part_offsets, torch.int32, "part_offsets"), _ptr(part_count, torch.int32, "part_count"),
             _ptr(part_first_page, torch.int32, "part_first_page"), _ptr(part_tokens, torch.int32, "part_tokens")),
             "spin_set_partition_tables")
+
+    def set_host_page_table(self, cpu_pages=None, host_pages=0):
+        """cpu_pages: pinned int32 CPU tensor (kept alive here: the library stores its address)."""
+        self._cpu_table = cpu_pages
+        if cpu_pages is None:
+            self._check(self.lib.spin_set_host_page_table(self.h, None, 0, 0), "spin_set_host_page_table")
+            return
+        if not cpu_pages.is_pinned() or cpu_pages.dtype != torch.int32 or not cpu_pages.is_contiguous():
+            raise ValueError("cpu_pages must be a contiguous pinned int32 host tensor")
+        self._check(self.lib.spin_set_host_page_table(self.h, cpu_pages.data_ptr(), cpu_pages.numel(), host_pages),
+                    "spin_set_host_page_table")
 
     def reclaim_tail(self, batch, slot_range, new_count, dir_, leaf_pool, rev_table, ws):
         self._check(self.lib.spin_reclaim_tail(

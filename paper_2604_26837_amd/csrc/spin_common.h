@@ -48,6 +48,10 @@ struct spin_ctx {
   size_t ws_hist_off;     // per-row first-digit histograms of stage 2 for long rows; 0 = not used
   size_t ws_zero_bytes;   // leading part of the workspace that spin_workspace_init clears
   spin_var var;           // registered partition tables (all NULL: uniform partitions)
+  // CPU page table (Section 5.2): entry host_row_base[row] + logical page -> physical page of the pinned
+  // host pool; table == NULL: the identity
+  const int32_t *cpu_table;
+  int64_t cpu_table_entries, cpu_pages;
   int32_t k_token_major;  // layout of a slot's K tile, see spin_k_unit(): 1 for partitions smaller than a page
   // optional per-kernel timing: pairs of HIP events handed to the launches
   int32_t prof_cap;

@@ -27,7 +27,13 @@ extern "C" int spin_copy_misses_host(spin_ctx *ctx, int32_t batch, const void *h
     for (int i = 0; i < n; ++i) {
       const int32_t pg = miss_pages[(size_t)r * stride + i], slot = miss_slots[(size_t)r * stride + i];
       if (pg < 0 || slot < 0 || (int64_t)slot >= pool_slots) return SPIN_ERR_INVALID;
-      const char *src = (const char *)host_kv + (size_t)(host_row_base[r] + pg) * SPIN_SLOT_BYTES;
+      int64_t hp = host_row_base[r] + pg;
+      if (ctx->cpu_table) {                 // pinned host memory: readable from here as well
+        if (hp < 0 || hp >= ctx->cpu_table_entries) return SPIN_ERR_INVALID;
+        hp = ctx->cpu_table[hp];
+        if (hp < 0 || hp >= ctx->cpu_pages) return SPIN_ERR_INVALID;
+      }
+      const char *src = (const char *)host_kv + (size_t)hp * SPIN_SLOT_BYTES;
       char *dst = (char *)kv_pool + (size_t)slot * SPIN_SLOT_BYTES;
       SPIN_HIP_CHECK(hipMemcpyAsync(dst, src, SPIN_SLOT_BYTES, hipMemcpyHostToDevice, (hipStream_t)copy_stream));
       ++total;
@@ -40,13 +46,18 @@ extern "C" int spin_copy_misses_host(spin_ctx *ctx, int32_t batch, const void *h
 #define GATHER_WAVES 4
 #define GATHER_PAGES_PER_WG 16
 
+struct host_map {
+  const int32_t *table;     // NULL: identity
+  int64_t entries, pages;
+};
+
 // TO_HOST = false: host page -> slot (Retrieve).  TO_HOST = true: slot -> host page (Offload's copy,
 // Table 1: copy(gpu_kv, cpu_kv, map)); the lists have the same shape in both directions.
 template <bool TO_HOST>
 __global__ __launch_bounds__(GATHER_WAVES * 64) void spin_gather_kernel(
     uint4 *__restrict__ host_kv, const int64_t *__restrict__ row_base, const int32_t *__restrict__ nmiss,
     const int32_t *__restrict__ miss_pages, const int32_t *__restrict__ miss_slots, uint4 *__restrict__ pool,
-    int64_t pool_slots, int page_stride, int chunks_per_row, int32_t *status) {
+    int64_t pool_slots, int page_stride, int chunks_per_row, int32_t *status, host_map hm) {
   const int row = blockIdx.x / chunks_per_row, chunk = blockIdx.x - row * chunks_per_row;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int n = nmiss[row];
@@ -61,7 +72,16 @@ __global__ __launch_bounds__(GATHER_WAVES * 64) void spin_gather_kernel(
       if (lane == 0) spin_raise(status, SPIN_ERR_SLOT_RANGE);
       continue;
     }
-    uint4 *hp = host_kv + (size_t)(rb + pg) * SPIN_SLOT_U4 + lane;
+    int64_t hpage = rb + pg;
+    if (hm.table) {                         // CPU page table: offset of the page in the row's list -> physical host page
+      const bool in_table = hpage >= 0 && hpage < hm.entries;
+      hpage = in_table ? hm.table[hpage] : -1;
+      if (hpage < 0 || hpage >= hm.pages) {
+        if (lane == 0) spin_raise(status, SPIN_ERR_SLOT_RANGE);
+        continue;
+      }
+    }
+    uint4 *hp = host_kv + (size_t)hpage * SPIN_SLOT_U4 + lane;
     uint4 *dp = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
     const uint4 *src = TO_HOST ? dp : hp;
     uint4 *dst = TO_HOST ? hp : dp;
@@ -84,7 +104,8 @@ extern "C" int spin_gather_misses(spin_ctx *ctx, int32_t batch, const void *host
   const int chunks = (ctx->page_stride + GATHER_PAGES_PER_WG - 1) / GATHER_PAGES_PER_WG;
   spin_launch(ctx, SPIN_K_GATHER, spin_gather_kernel<false>, dim3((unsigned)(rows * chunks)), dim3(GATHER_WAVES * 64), 0,
               (hipStream_t)stream, (uint4 *)const_cast<void *>(host_kv), row_base, nmiss, miss_pages, miss_slots,
-              (uint4 *)kv_pool, pool_slots, ctx->page_stride, chunks, (int32_t *)workspace);
+              (uint4 *)kv_pool, pool_slots, ctx->page_stride, chunks, (int32_t *)workspace,
+              host_map{ctx->cpu_table, ctx->cpu_table_entries, ctx->cpu_pages});
   return spin_launch_status();
 }
 
@@ -99,6 +120,18 @@ extern "C" int spin_offload_pages(spin_ctx *ctx, int32_t batch, const void *kv_p
   const int chunks = (ctx->page_stride + GATHER_PAGES_PER_WG - 1) / GATHER_PAGES_PER_WG;
   spin_launch(ctx, SPIN_K_OFFLOAD, spin_gather_kernel<true>, dim3((unsigned)(rows * chunks)), dim3(GATHER_WAVES * 64), 0,
               (hipStream_t)stream, (uint4 *)host_kv, row_base, count, pages, slots,
-              (uint4 *)const_cast<void *>(kv_pool), pool_slots, ctx->page_stride, chunks, (int32_t *)workspace);
+              (uint4 *)const_cast<void *>(kv_pool), pool_slots, ctx->page_stride, chunks, (int32_t *)workspace,
+              host_map{ctx->cpu_table, ctx->cpu_table_entries, ctx->cpu_pages});
   return spin_launch_status();
+}
+
+extern "C" int spin_set_host_page_table(spin_ctx *ctx, const int32_t *cpu_pages, int64_t entries, int64_t host_pages) {
+  if (!ctx) return SPIN_ERR_INVALID;
+  if (!cpu_pages) {
+    ctx->cpu_table = nullptr; ctx->cpu_table_entries = 0; ctx->cpu_pages = 0;
+    return SPIN_OK;
+  }
+  if (entries <= 0 || host_pages <= 0) return SPIN_ERR_INVALID;
+  ctx->cpu_table = cpu_pages; ctx->cpu_table_entries = entries; ctx->cpu_pages = host_pages;
+  return SPIN_OK;
 }

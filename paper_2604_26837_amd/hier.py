@@ -21,7 +21,8 @@ def request_workload(w: synth.Workload, b: int) -> synth.Workload:
 
 class HierLayer:
     def __init__(self, w: synth.Workload, budget_frac: float = 0.25, n_ts: int = 64, evict_exact: bool = False,
-                 device: str = "cuda:0", copy_mode: str = "memcpy", keep_natural: bool = False, **cfg_over):
+                 device: str = "cuda:0", copy_mode: str = "memcpy", keep_natural: bool = False,
+                 scatter_host_pages: bool = False, **cfg_over):
         # any uniform partition size; scores that need no per-head channel table
         assert w.score_kind in (synth.SCORE_MINMAX, synth.SCORE_REPMAX)
         assert copy_mode in ("memcpy", "gather")
@@ -47,7 +48,17 @@ class HierLayer:
         self.host_row_base_np = hrb
         self.host_row_base = torch.from_numpy(hrb[:-1].copy())                  # host int64 [rows]
         self.host_row_base_dev = self.host_row_base.to(device)
-        self.host_kv = torch.empty((int(hrb[-1]), 4096), dtype=torch.bfloat16, pin_memory=True)
+        # the host pool; with scatter_host_pages a request's pages lie anywhere in a somewhat larger pool and a
+        # CPU page table (offset in the row's page list -> physical host page) says where
+        n_host = int(hrb[-1])
+        self.cpu_table = None
+        if scatter_host_pages:
+            pool_pages = n_host + max(n_host // 16, 3)
+            perm = np.random.Generator(np.random.PCG64(w.seed + 4242)).permutation(pool_pages)[:n_host]
+            self.cpu_table = torch.from_numpy(perm.astype(np.int32)).pin_memory()
+            self.spin.set_host_page_table(self.cpu_table, pool_pages)
+            n_host = pool_pages
+        self.host_kv = torch.empty((n_host, 4096), dtype=torch.bfloat16, pin_memory=True)
         # metadata: leaves for every page range inside a row's context, nothing resident yet
         empty = [np.full((hkv, w.pages(b)), -1, dtype=np.int32) for b in range(w.batch)]
         d, l = tables.build_two_level(empty, sp.dir_stride, w.leaf_entries, allocate_all=True)
@@ -97,7 +108,10 @@ class HierLayer:
                 r = b * hkv + h
                 slots = torch.from_numpy(tmp.slot_of[0][h].astype(np.int64)).to(self.device)
                 lo, hi = int(self.host_row_base_np[r]), int(self.host_row_base_np[r + 1])
-                self.host_kv[lo:hi].copy_(tmp.kv_pool[slots])
+                if self.cpu_table is None:
+                    self.host_kv[lo:hi].copy_(tmp.kv_pool[slots])
+                else:
+                    self.host_kv[self.cpu_table[lo:hi].long()] = tmp.kv_pool[slots].cpu()
             if keep_natural:
                 self.natural.append(natural.cpu())
                 self.natural_slot_of.append(tmp.slot_of[0])
@@ -160,7 +174,9 @@ class HierLayer:
             for h in range(hkv):
                 r = b * hkv + h
                 lo = int(self.host_row_base_np[r])
-                tmp[h * pages_b:(h + 1) * pages_b].copy_(self.host_kv[lo:lo + pages_b])
+                src = (self.host_kv[lo:lo + pages_b] if self.cpu_table is None
+                       else self.host_kv[self.cpu_table[lo:lo + pages_b].long()])
+                tmp[h * pages_b:(h + 1) * pages_b].copy_(src)
                 slot_of[h] = np.arange(h * pages_b, (h + 1) * pages_b, dtype=np.int32)
             d, l = tables.build_two_level([slot_of], sp.dir_stride, w.leaf_entries)
             pp = int(self.part_offsets_np[b + 1] - self.part_offsets_np[b])

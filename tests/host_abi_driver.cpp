@@ -80,6 +80,12 @@ static void poke(spin_ctx *x, const spin_config &c) {
   EXPECT(spin_profile_read(x, 1000, &cnt, &mean, &mn) == SPIN_ERR_INVALID);
   EXPECT(spin_profile_read(x, SPIN_K_DECODE, nullptr, &mean, &mn) == SPIN_ERR_INVALID);
   EXPECT(spin_profile_read(x, SPIN_K_META, &cnt, &mean, &mn) == SPIN_OK && cnt == 0);   // nothing timed
+  // CPU page table: a table needs positive sizes; NULL returns to the identity
+  int32_t cpu_table[4] = {3, 2, 1, 0};
+  EXPECT(spin_set_host_page_table(x, cpu_table, 4, 4) == SPIN_OK);
+  EXPECT(spin_set_host_page_table(x, cpu_table, 0, 4) == SPIN_ERR_INVALID);
+  EXPECT(spin_set_host_page_table(x, cpu_table, 4, 0) == SPIN_ERR_INVALID);
+  EXPECT(spin_set_host_page_table(x, nullptr, 0, 0) == SPIN_OK);
   // partition tables: all four or none
   int32_t t[4] = {0, 0, 0, 0};
   EXPECT(spin_set_partition_tables(x, nullptr, nullptr, nullptr, nullptr) == SPIN_OK);

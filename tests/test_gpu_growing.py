@@ -19,14 +19,18 @@ ATOL, RTOL = 2e-2, 1e-2
 DEV = "cuda:0"
 
 
-def test_append_offload_retrieve_over_many_steps():
+@pytest.mark.parametrize("scatter", [False, True])
+def test_append_offload_retrieve_over_many_steps(scatter):
     final = (1200, 2100)
     start = (1100, 2043)
     steps = 57                                     # crosses several page boundaries in both requests
     w = synth.config4().with_(seq_lens=final, num_q_heads=8, num_kv_heads=2, topk=16, sink_pages=1,
                               recent_pages=2, name="growing")
     n_ts = 5
-    layer = hier.HierLayer(w, budget_frac=0.02, n_ts=n_ts, copy_mode="gather", keep_natural=True)
+    # scatter: the requests' pages lie anywhere in the host pool, found through the CPU page table
+    layer = hier.HierLayer(w, budget_frac=0.02, n_ts=n_ts, copy_mode="gather", keep_natural=True,
+                           scatter_host_pages=scatter)
+    hpage = (lambda i: i) if layer.cpu_table is None else (lambda i: int(layer.cpu_table[i]))
     sp, hkv, g, rows = layer.spin, w.num_kv_heads, w.group, w.rows
     # logical K/V per row in token order (bf16 bits), the truth the appended tokens are taken from
     nat = [n.view(torch.int16).numpy().view(np.uint16) for n in layer.natural]
@@ -41,7 +45,8 @@ def test_append_offload_retrieve_over_many_steps():
         b = r // hkv
         lo = int(layer.host_row_base_np[r])
         first_partial = cur[b] // 16
-        layer.host_kv[lo + first_partial: lo + w.pages(b)].zero_()
+        for i in range(lo + first_partial, lo + w.pages(b)):
+            layer.host_kv[hpage(i)].zero_()
         # tokens of the partial tail page that already exist stay; the rest of that page is zero
         if cur[b] % 16:
             k, v = logical[r]
@@ -53,7 +58,7 @@ def test_append_offload_retrieve_over_many_steps():
             pk = bits_to_bf16(page)
             sp.pack_kv_pages(pk[0:1].contiguous(), pk[1:2].contiguous(), ids, tmp)
             torch.cuda.synchronize()
-            layer.host_kv[lo + first_partial].copy_(tmp[0].cpu())
+            layer.host_kv[hpage(lo + first_partial)].copy_(tmp[0].cpu())
     # summaries of the shorter contexts, built from a temporary all-resident copy of the host pages
     layer.seq_lens.copy_(torch.tensor(cur, dtype=torch.int32))
     layer.rebuild_summaries_from_host()
@@ -117,7 +122,7 @@ def test_append_offload_retrieve_over_many_steps():
             tmp = torch.zeros((1, 4096), dtype=torch.bfloat16, device=DEV)
             sp.pack_kv_pages(pk[0:1].contiguous(), pk[1:2].contiguous(), torch.zeros(1, dtype=torch.int32, device=DEV), tmp)
             torch.cuda.synchronize()
-            assert torch.equal(tmp[0].cpu().view(torch.int16), layer.host_kv[lo + pg].view(torch.int16)), (r, pg)
+            assert torch.equal(tmp[0].cpu().view(torch.int16), layer.host_kv[hpage(lo + pg)].view(torch.int16)), (r, pg)
             checked += 1
     assert checked >= 3 * rows
     overall, warm = layer.hit_rates()

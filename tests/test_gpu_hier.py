@@ -20,13 +20,15 @@ def _small():
                                  sink_pages=2, recent_pages=3, name="hier_small")
 
 
-@pytest.mark.parametrize("copy_mode,exact,policy", [("memcpy", False, 0), ("gather", False, 0), ("gather", True, 0),
-                                                    ("gather", False, 1)])
-def test_steps_match_oracle(copy_mode, exact, policy):
+# the last two cases: the request's pages scattered over the host pool behind a CPU page table
+@pytest.mark.parametrize("copy_mode,exact,policy,scatter", [("memcpy", False, 0, False), ("gather", False, 0, False),
+                                                            ("gather", True, 0, False), ("gather", False, 1, False),
+                                                            ("gather", False, 0, True), ("memcpy", False, 0, True)])
+def test_steps_match_oracle(copy_mode, exact, policy, scatter):
     w = _small()
     n_ts = 6                      # small range: demotion kicks in within the trace
     layer = hier.HierLayer(w, budget_frac=0.06, n_ts=n_ts, evict_exact=exact, copy_mode=copy_mode, keep_natural=True,
-                           lru_policy=policy)
+                           lru_policy=policy, scatter_host_pages=scatter)
     rows, g = w.rows, w.group
     caches = [lru.RowCache(layer.budgets[r]) for r in range(rows)]
     nat = [n.view(torch.int16).numpy().view(np.uint16) for n in layer.natural]      # per request [slots][2][16][D]
@@ -142,3 +144,25 @@ def test_other_granularities_under_a_budget(name, policy):
         q = torch.from_numpy(synth.next_query_ar1(q_bits, 0.9, w.seed + 6000 + step).view(np.int16)).to(q.device).view(torch.bfloat16)
     overall, warm = layer.hit_rates()
     assert 0.0 < warm < 1.0
+
+
+def test_cpu_page_table_entries_out_of_range_are_reported_not_followed():
+    """A CPU page table entry outside the host pool must raise the status word and skip
+    the page (nothing is read out of bounds), in the copy kernel and in the host-driven copier."""
+    w = _small()
+    layer = hier.HierLayer(w, budget_frac=0.06, n_ts=6, copy_mode="gather", scatter_host_pages=True)
+    pool_pages = layer.host_kv.shape[0]
+    layer.cpu_table[:] = pool_pages + 5                       # every entry points past the pool
+    layer.step(layer.q0, 0)
+    torch.cuda.synchronize()
+    assert layer.status() == -7                               # SPIN_ERR_SLOT_RANGE
+    layer.spin.workspace_init(layer.ws)
+    layer.cpu_table[:] = -1
+    h = torch.zeros_like(layer.nmiss).cpu()
+    h_pages, h_slots = layer.miss_pages.cpu(), layer.miss_slots.cpu()
+    h.copy_(layer.nmiss)
+    from paper_2604_26837_amd.binding import SpinError
+    assert int(h.sum()) > 0                                   # step 0 is all misses
+    with pytest.raises(SpinError):
+        layer.spin.copy_misses_host(w.batch, layer.host_kv, layer.host_row_base, h, h_pages, h_slots, layer.kv_pool,
+                                    layer.copy_stream)
