@@ -305,13 +305,22 @@ int spin_score_select_topk(spin_ctx *ctx, int32_t batch, const void *q, const vo
  * are skipped circularly; in the set reached the lowest empty way is taken,
  * else the way not selected in this step with the smallest timestamp (lowest
  * way on ties) is evicted.  Timestamps and every output are as above; at most
- * 32768 slots per row. */
+ * 32768 slots per row.
+ * `step` is the decode step (>= 0) the timestamps are taken from.  A launch that is
+ * recorded once and replayed (a HIP graph) would freeze that value: pass
+ * SPIN_STEP_FROM_WORKSPACE instead and the kernel reads the workspace's own step
+ * counter, which spin_workspace_init zeroes, spin_set_step sets and
+ * spin_advance_step increments (small kernels on `stream`, recordable too). */
+#define SPIN_STEP_FROM_WORKSPACE (-1)
 int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, const int32_t *sel,
                        const int32_t *nsel, const int32_t *seq_lens, const int32_t *dir,
                        int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev_table,
                        const int32_t *slot_range, int32_t *slots, int32_t *page_ids,
                        uint16_t *valid_mask, int32_t *npages, int32_t *miss_pages,
                        int32_t *miss_slots, int32_t *nmiss, void *workspace, void *stream);
+
+int spin_set_step(spin_ctx *ctx, void *workspace, int32_t step, void *stream);
+int spin_advance_step(spin_ctx *ctx, void *workspace, void *stream);
 
 /* Stages 2 and 3 in ONE launch (all-resident mode, rows of at most 16384
  * partitions; otherwise SPIN_ERR_UNSUPPORTED and the two calls above apply).

@@ -24,7 +24,7 @@ EXPORTS = [
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
     "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv", "spin_reclaim_tail", "spin_alloc_leaves", "spin_free_leaves",
     "spin_set_partition_tables", "spin_probe_stream_read", "spin_offload_pages", "spin_score_select_topk", "spin_pin_partitions",
-    "spin_set_host_page_table",
+    "spin_set_host_page_table", "spin_set_step", "spin_advance_step",
 ]
 
 
@@ -76,6 +76,8 @@ def load_library() -> C.CDLL:
     lib.spin_score_select_topk.argtypes = [vp, i32] + [vp] * 10
     lib.spin_pin_partitions.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
     lib.spin_set_host_page_table.argtypes = [vp, vp, i64, i64]
+    lib.spin_set_step.argtypes = [vp, vp, i32, vp]
+    lib.spin_advance_step.argtypes = [vp, vp, vp]
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_probe_stream_read.argtypes = [vp, vp, C.c_size_t, vp, vp]
@@ -238,6 +240,14 @@ class Spin:
             raise ValueError("cpu_pages must be a contiguous pinned int32 host tensor")
         self._check(self.lib.spin_set_host_page_table(self.h, cpu_pages.data_ptr(), cpu_pages.numel(), host_pages),
                     "spin_set_host_page_table")
+
+    STEP_FROM_WORKSPACE = -1
+
+    def set_step(self, ws, step: int):
+        self._check(self.lib.spin_set_step(self.h, _ptr(ws), step, _stream()), "spin_set_step")
+
+    def advance_step(self, ws):
+        self._check(self.lib.spin_advance_step(self.h, _ptr(ws), _stream()), "spin_advance_step")
 
     def reclaim_tail(self, batch, slot_range, new_count, dir_, leaf_pool, rev_table, ws):
         self._check(self.lib.spin_reclaim_tail(

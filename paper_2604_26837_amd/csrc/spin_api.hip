@@ -254,6 +254,25 @@ extern "C" int spin_workspace_init(spin_ctx *ctx, void *workspace, void *stream)
   return spin_launch_status();
 }
 
+// step counter of a workspace (word 1 of its header), for launches recorded once and replayed
+__global__ void spin_step_kernel(int32_t *ws, int32_t set_to) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) ws[1] = set_to >= 0 ? set_to : ws[1] + 1;
+}
+
+extern "C" int spin_set_step(spin_ctx *ctx, void *workspace, int32_t step, void *stream) {
+  if (!ctx || step < 0) return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  hipLaunchKernelGGL(spin_step_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (int32_t *)workspace, step);
+  return spin_launch_status();
+}
+
+extern "C" int spin_advance_step(spin_ctx *ctx, void *workspace, void *stream) {
+  if (!ctx) return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  hipLaunchKernelGGL(spin_step_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, (int32_t *)workspace, -1);
+  return spin_launch_status();
+}
+
 extern "C" int spin_poll_status(spin_ctx *ctx, const void *workspace, void *stream) {
   if (!ctx) return SPIN_ERR_INVALID;
   if (!workspace) return SPIN_ERR_WORKSPACE;

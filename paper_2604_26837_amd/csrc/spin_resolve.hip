@@ -99,11 +99,14 @@ __global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_lru_kernel(
     const int32_t *__restrict__ sel, const int32_t *__restrict__ nsel, const int32_t *__restrict__ seq_lens,
     const int32_t *__restrict__ dir, int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev,
     const int32_t *__restrict__ slot_base, int Hkv, int sel_stride, int page_stride, int dir_stride,
-    int leaf_entries, int step, int n_ts, int evict_exact, int max_slots_lds, int32_t *slots,
+    int leaf_entries, int step_arg, int n_ts, int evict_exact, int max_slots_lds, int32_t *slots,
     int32_t *page_ids, uint16_t *valid_mask, int32_t *npages,
     int32_t *__restrict__ miss_pages, int32_t *__restrict__ miss_slots, int32_t *__restrict__ nmiss,
     int32_t *status, lru_expand ex) {
   extern __shared__ int32_t lds[];
+  // a negative step asks for the workspace's own step counter (word 1 of its header): a captured
+  // launch then follows the counter from replay to replay
+  const int step = step_arg >= 0 ? step_arg : max(status[1], 0);
   int32_t *s_loc = lds;                                  // [page_stride]  leaf entry address (as chunk*LE+idx) per selected page
   int32_t *s_free = lds + page_stride;                   // [page_stride]  free slot (local) by rank
   uint8_t *s_flag = (uint8_t *)(lds + 2 * page_stride);  // [S] 1 = holds a selected page
@@ -318,11 +321,14 @@ __global__ __launch_bounds__(LRU_BLOCK) void spin_resolve_sa_kernel(
     const int32_t *__restrict__ sel, const int32_t *__restrict__ nsel, const int32_t *__restrict__ seq_lens,
     const int32_t *__restrict__ dir, int32_t *leaf_pool, int64_t leaf_chunks, int32_t *rev,
     const int32_t *__restrict__ slot_base, int Hkv, int sel_stride, int page_stride, int dir_stride,
-    int leaf_entries, int step, int n_ts, int max_slots_lds, int32_t *slots,
+    int leaf_entries, int step_arg, int n_ts, int max_slots_lds, int32_t *slots,
     int32_t *page_ids, uint16_t *valid_mask, int32_t *npages,
     int32_t *__restrict__ miss_pages, int32_t *__restrict__ miss_slots, int32_t *__restrict__ nmiss,
     int32_t *status, lru_expand ex) {
   extern __shared__ int32_t lds[];
+  // a negative step asks for the workspace's own step counter (word 1 of its header): a captured
+  // launch then follows the counter from replay to replay
+  const int step = step_arg >= 0 ? step_arg : max(status[1], 0);
   int32_t *s_loc = lds;                                   // [page_stride] leaf entry address per selected page
   int32_t *s_mi = lds + page_stride;                      // [page_stride] selection index of the m-th miss
   int32_t *s_set = lds + 2 * page_stride;                 // [page_stride] home set, then set reached, then victim slot
@@ -523,7 +529,8 @@ extern "C" int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, co
                                   const int32_t *slot_base, int32_t *slots, int32_t *page_ids,
                                   uint16_t *valid_mask, int32_t *npages, int32_t *miss_pages,
                                   int32_t *miss_slots, int32_t *nmiss, void *workspace, void *stream) {
-  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || step < 0 || leaf_chunks <= 0) return SPIN_ERR_INVALID;
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || step < SPIN_STEP_FROM_WORKSPACE || leaf_chunks <= 0)
+    return SPIN_ERR_INVALID;
   if (batch == 0) return SPIN_OK;
   if (!sel || !nsel || !seq_lens || !dir || !leaf_pool || !slots || !page_ids || !valid_mask || !npages)
     return SPIN_ERR_INVALID;

@@ -120,12 +120,15 @@ class HierLayer:
         torch.cuda.synchronize()
 
     # ------------------------------------------------------------------
-    def step(self, q: torch.Tensor, step: int, summaries: Optional[torch.Tensor] = None, count: bool = True):
+    def step(self, q: torch.Tensor, step: int, summaries: Optional[torch.Tensor] = None, count: bool = True,
+             device_step: bool = False):
+        """``device_step``: the replacement policy reads the step from the workspace's own counter and the
+        counter is advanced after the step (what a step recorded in a HIP graph needs; ``step`` is ignored)."""
         sp, w = self.spin, self.w
         summ = self.summaries if summaries is None else summaries
         sp.score_partitions(w.batch, q, summ, None, self.part_offsets, self.seq_lens, self.scores, self.ws)
         sp.select_topk(w.batch, self.scores, self.part_offsets, self.seq_lens, self.sel, self.nsel, self.ws)
-        sp.resolve_slots(w.batch, step, self.sel, self.nsel, self.seq_lens, self.dir, self.leaf_pool, self.slots,
+        sp.resolve_slots(w.batch, sp.STEP_FROM_WORKSPACE if device_step else step, self.sel, self.nsel, self.seq_lens, self.dir, self.leaf_pool, self.slots,
                          self.page_ids, self.valid_mask, self.npages, self.ws, rev_table=self.rev,
                          slot_base=self.slot_base, miss_pages=self.miss_pages, miss_slots=self.miss_slots,
                          nmiss=self.nmiss)
@@ -146,6 +149,8 @@ class HierLayer:
             copied = None
         sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
                          self.ws)
+        if device_step:
+            sp.advance_step(self.ws)
         if count:
             if copied is None:
                 copied = int(self.nmiss.sum().item())

@@ -73,6 +73,10 @@ static void poke(spin_ctx *x, const spin_config &c) {
   EXPECT(spin_pack_kv_pages(x, 4, n, n, nullptr, n, 1, n) == SPIN_ERR_INVALID);
   EXPECT(spin_pack_kv_pages(x, -1, n, n, nullptr, n, 1, n) == SPIN_ERR_INVALID);
   EXPECT(spin_workspace_init(x, nullptr, n) == SPIN_ERR_WORKSPACE);
+  EXPECT(spin_set_step(x, nullptr, 0, n) == SPIN_ERR_WORKSPACE && spin_set_step(x, ws, -1, n) == SPIN_ERR_INVALID);
+  EXPECT(spin_advance_step(x, nullptr, n) == SPIN_ERR_WORKSPACE);
+  EXPECT(spin_resolve_slots(x, 1, -2, nullptr, nullptr, nullptr, nullptr, nullptr, 1, nullptr, nullptr, nullptr, nullptr,
+                            nullptr, nullptr, nullptr, nullptr, nullptr, ws, n) == SPIN_ERR_INVALID);
   EXPECT(spin_probe_stream_read(x, nullptr, 16, ws, n) < 0);
   EXPECT(spin_profile_enable(x, -1) == SPIN_ERR_INVALID);
   int32_t cnt = 0; float mean = 0, mn = 0;

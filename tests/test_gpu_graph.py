@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2604_26837_amd import runner, synth
+from paper_2604_26837_amd import hier, runner, synth
 
 pytestmark = pytest.mark.gpu
 
@@ -66,3 +66,44 @@ def test_step_replays_from_a_graph(name):
         assert layer.status() == 0
         assert torch.equal(layer.out.view(torch.int16), eager[i][0].view(torch.int16)), f"replay {rep}"
         assert torch.equal(layer.sel, eager[i][1]) and torch.equal(layer.slots, eager[i][2])
+
+
+def test_budget_step_replays_with_the_workspace_step_counter():
+    """A budget-mode step recorded once: the replacement policy must see step 0, 1, 2, ... on the
+    replays (the workspace's counter), not the value present at capture.  A twin layer run eagerly
+    with explicit steps gives the expected slots, misses and outputs, bit for bit; the timestamp
+    range is short so that demotion (which depends on the step) happens within the trace."""
+    w = synth.config4().with_(seq_lens=(16 * 700, 16 * 420), num_q_heads=8, num_kv_heads=2, topk=24, sink_pages=2,
+                              recent_pages=3, name="graph_budget")
+    mk = lambda: hier.HierLayer(w, budget_frac=0.06, n_ts=4, copy_mode="gather")
+    ref, cap = mk(), mk()
+    qs = [ref.q0]
+    for s in range(9):
+        bits = qs[-1].view(torch.int16).cpu().numpy().view(np.uint16)
+        qs.append(torch.from_numpy(synth.next_query_ar1(bits, 0.7, w.seed + 50 + s).view(np.int16)).to("cuda:0")
+                  .view(torch.bfloat16))
+    eager = []
+    for s, q in enumerate(qs):
+        ref.step(q, s, count=False)
+        torch.cuda.synchronize()
+        assert ref.status() == 0
+        eager.append(tuple(t.clone() for t in (ref.slots, ref.npages, ref.nmiss, ref.miss_pages, ref.miss_slots, ref.out)))
+    q_static = qs[0].clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        cap.step(q_static, 12345, count=False, device_step=True)      # the step argument is not used
+    for s, q in enumerate(qs):
+        q_static.copy_(q)
+        cap.out.fill_(3.0)                                             # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert cap.status() == 0
+        got = (cap.slots, cap.npages, cap.nmiss, cap.miss_pages, cap.miss_slots)
+        for a, b in zip(got, eager[s][:5]):
+            assert torch.equal(a, b), f"replay {s}"
+        assert torch.equal(cap.out.view(torch.int16), eager[s][5].view(torch.int16)), f"replay {s}"
+    # the counter can be set: going back to step 0 semantics is not needed here, only that it reads back
+    cap.spin.set_step(cap.ws, 7)
+    torch.cuda.synchronize()
+    assert int(cap.ws.view(torch.int32)[1].item()) == 7
