@@ -79,6 +79,7 @@ __global__ __launch_bounds__(256) void spin_index_minmax_pages_kernel(
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int dir_stride, int leaf_entries, int max_tiles,
     uint16_t *__restrict__ summ, int32_t *status, spin_var var) {
   __shared__ uint4 s_tile[4][SPIN_KTILE_U4];
+  __shared__ uint4 s_out[512];
   const int row = blockIdx.x / max_tiles, tile = blockIdx.x - row * max_tiles;
   const int b = row / Hkv, h = row - b * Hkv;
   const int PP = part_offsets[b + 1] - part_offsets[b];
@@ -152,12 +153,15 @@ __global__ __launch_bounds__(256) void spin_index_minmax_pages_kernel(
         omx[i] = any ? ((__float_as_uint(mx[2 * i]) >> 16) | (__float_as_uint(mx[2 * i + 1]) & 0xffff0000u)) : 0u;
         omn[i] = any ? ((__float_as_uint(mn[2 * i]) >> 16) | (__float_as_uint(mn[2 * i + 1]) & 0xffff0000u)) : 0u;
       }
-      const size_t R = base + p;
-      const size_t tbase = (R >> 4) * (size_t)(16 * 256 / 8);
-      o[tbase + (size_t)ch * 16 + (R & 15)] = make_uint4(omx[0], omx[1], omx[2], omx[3]);
-      o[tbase + (size_t)(16 + ch) * 16 + (R & 15)] = make_uint4(omn[0], omn[1], omn[2], omn[3]);
+      // the workgroup's 16 partitions are one 8 KiB summary tile: collected in LDS, written out whole
+      s_out[ch * 16 + r] = make_uint4(omx[0], omx[1], omx[2], omx[3]);
+      s_out[(16 + ch) * 16 + r] = make_uint4(omn[0], omn[1], omn[2], omn[3]);
     }
   }
+  __syncthreads();
+  const size_t tbase = ((base + (size_t)tile * 16) >> 4) * (size_t)(16 * 256 / 8);   // base is a multiple of 16
+  o[tbase + threadIdx.x] = s_out[threadIdx.x];
+  o[tbase + 256 + threadIdx.x] = s_out[256 + threadIdx.x];
 }
 
 // fp64 -> bf16 with a single rounding: truncate to fp32 with a sticky low bit
