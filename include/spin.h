@@ -120,7 +120,7 @@ typedef struct spin_config {
   int32_t decode_waves;         /* wavefronts per decode workgroup: 2, 4 or 8; 0 = 8 */
   int32_t decode_depth;         /* page buffers per decode wavefront (pages in flight + 1): 2, 3 or 4; 0 = choose */
   int32_t score_tiles_per_wg;   /* 16-row summary tiles per stage-1 workgroup; 0 = choose */
-  int32_t score_waves;          /* wavefronts per stage-1 workgroup: 4 or 8; 0 = 4 */
+  int32_t score_waves;          /* wavefronts per stage-1 workgroup: 1, 2, 4 or 8; 0 = 4 */
   int32_t variable_partitions;  /* 1: strides are sized for spin_set_partition_tables (partitions of 1 page up to
                                    partition_tokens tokens) */
   float softmax_scale;          /* 0 = 1/sqrt(head_dim) */

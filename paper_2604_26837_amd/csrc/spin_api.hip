@@ -24,7 +24,7 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   if (c->lru_policy != 0 && c->lru_policy != 1) return SPIN_ERR_INVALID;
   if (c->decode_depth != 0 && (c->decode_depth < 2 || c->decode_depth > 4)) return SPIN_ERR_INVALID;
   if (c->variable_partitions && tp < 16) return SPIN_ERR_UNSUPPORTED;
-  if (c->score_tiles_per_wg < 0 || (c->score_waves != 0 && c->score_waves != 4 && c->score_waves != 8))
+  if (c->score_tiles_per_wg < 0 || (c->score_waves != 0 && c->score_waves != 1 && c->score_waves != 2 && c->score_waves != 4 && c->score_waves != 8))
     return SPIN_ERR_INVALID;
 
   spin_ctx *x = new (std::nothrow) spin_ctx;

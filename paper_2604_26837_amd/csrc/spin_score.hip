@@ -30,6 +30,15 @@ __global__ __launch_bounds__(WAVES * 64) void spin_score_k32_kernel(
                                             scores);
 }
 
+template <int NJ, bool MINMAX, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void spin_score_k32_single_kernel(
+    const uint16_t *__restrict__ q, const uint4 *__restrict__ summ, const int32_t *__restrict__ part_offsets,
+    int Hq, int Hkv, int G, int rows_per_part, int tiles_per_wg, int wgs_per_row, float *__restrict__ scores) {
+  (void)tiles_per_wg;   // == WAVES
+  const int row = blockIdx.x / wgs_per_row, chunk = blockIdx.x - row * wgs_per_row;
+  score_row_single_tile<NJ, MINMAX, WAVES>(q, summ, part_offsets, Hq, Hkv, G, rows_per_part, row, chunk, scores);
+}
+
 // what stage 2 needs to know to tell candidates from forced partitions
 struct score_hist_args {
   const int32_t *seq_lens;
@@ -239,8 +248,20 @@ int spin_score_impl(spin_ctx *ctx, int32_t batch, const void *q, const void *sum
 #define SPIN_SCORE_ARGS(RPP)                                                                                  \
   0, st, (const uint16_t *)q, (const uint4 *)summaries, part_offsets, c.num_q_heads, c.num_kv_heads, ctx->group, \
       RPP, tiles_per_wg, wgs, scores
-    if (W == 8)
+    if (W == 2 && tiles_per_wg == 2)
+      spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_single_kernel<8, true, 2>, dim3((unsigned)rows * wgs), dim3(128),
+                  SPIN_SCORE_ARGS(1));
+    else if (W == 1 && tiles_per_wg == 1)
+      spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_single_kernel<8, true, 1>, dim3((unsigned)rows * wgs), dim3(64),
+                  SPIN_SCORE_ARGS(1));
+    else if (W == 8 && tiles_per_wg == 8)
+      spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_single_kernel<8, true, 8>, dim3((unsigned)rows * wgs), dim3(512),
+                  SPIN_SCORE_ARGS(1));
+    else if (W == 8)
       spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_kernel<8, true, 8>, dim3((unsigned)rows * wgs), dim3(512),
+                  SPIN_SCORE_ARGS(1));
+    else if (tiles_per_wg == 4)
+      spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_single_kernel<8, true, 4>, dim3((unsigned)rows * wgs), dim3(256),
                   SPIN_SCORE_ARGS(1));
     else
       spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_kernel<8, true, 4>, dim3((unsigned)rows * wgs), dim3(256),

@@ -111,3 +111,39 @@ __device__ inline void score_row_tiles(
   }
 }
 
+// One tile per wavefront (tiles_per_wg == WAVES, the default launch): no loop and no second
+// tile buffer, which keeps the kernel at fewer registers and more wavefronts in flight per
+// compute unit; the tile is requested before the query vectors are gathered.
+template <int NJ, bool MINMAX, int WAVES>
+__device__ inline void score_row_single_tile(
+    const uint16_t *__restrict__ q, const uint4 *__restrict__ summ, const int32_t *__restrict__ part_offsets,
+    int Hq, int Hkv, int G, int rows_per_part, int row, int chunk, float *__restrict__ scores) {
+  const int b = row / Hkv, h = row - b * Hkv;
+  const int off_b = part_offsets[b];
+  const int PP = part_offsets[b + 1] - off_b;
+  const int ntiles = PP * rows_per_part / 16;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t = chunk * WAVES + wave;
+  if (t >= ntiles) return;
+  const int n = lane & 15, c = lane >> 4;
+  const size_t base = (size_t)Hkv * off_b + (size_t)h * PP;   // in partitions
+  const uint4 *tiles = summ + base * rows_per_part * (NJ * 4);
+  score_tile<NJ> r;
+  load_tile<NJ>(r, tiles + (size_t)t * (NJ * 64), lane);
+  spin_bf16x8 qf[NJ];
+  {
+    const uint4 *qrow = (const uint4 *)(q + ((size_t)(b * Hq + h * G + (n < G ? n : 0))) * SPIN_HEAD_DIM);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      uint4 v = qrow[(j & 3) * 4 + c];
+      if (MINMAX) {
+        const bool pos = j < 4;   // first 128 elements pair with max, the rest with min
+        v = make_uint4(relu_pack(v.x, pos), relu_pack(v.y, pos), relu_pack(v.z, pos), relu_pack(v.w, pos));
+      }
+      if (n >= G) v = make_uint4(0, 0, 0, 0);
+      qf[j] = __builtin_bit_cast(spin_bf16x8, v);
+    }
+  }
+  consume_tile<NJ, MINMAX>(r, qf, n, c, G, rows_per_part, scores, base, t);
+}
+
