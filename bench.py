@@ -34,10 +34,10 @@ def parse_args():
     ap.add_argument("--cpu-rows", type=int, default=32, help="rows of the workload timed on the CPU oracle")
     ap.add_argument("--cpu-reps", type=int, default=8)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "cfg3", "cfg4", "setup"],
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "cfg3", "cfg4", "setup", "cfg1_mean"],
                     help="cfg1: the headline all-resident layer (the metric's workload); cfg2: token partitions scored "
                          "on a key sketch; cfg3: 128-token blocks with representative keys; cfg4: hierarchical HBM "
-                         "budget, 64 decode steps; setup: the layout, Index, append, copy and metadata kernels at "
+                         "budget, 64 decode steps; cfg1_mean: cfg1's shape with one mean key per page as the summary; setup: the layout, Index, append, copy and metadata kernels at "
                          "cfg1's shape")
     ap.add_argument("--copy-mode", default="both", choices=["memcpy", "gather", "both"])
     ap.add_argument("--budget-frac", type=float, default=0.25)
@@ -372,7 +372,12 @@ def main():
     if args.workload == "setup":
         run_setup(args)
         return
-    w = {"cfg1": synth.config1, "cfg2": synth.config2, "cfg3": synth.config3}[args.workload]()
+    if args.workload == "cfg1_mean":
+        # the headline shape scored the way the paper's page-partition algorithm does: one mean key
+        # (landmark) per page instead of its min / max keys
+        w = synth.config1().with_(score_kind=synth.SCORE_REPMAX, reps_per_partition=1, name="cfg1_mean_landmarks")
+    else:
+        w = {"cfg1": synth.config1, "cfg2": synth.config2, "cfg3": synth.config3}[args.workload]()
     layer, natural = runner.build_device_layer(w, device=dev, keep_natural=not args.no_cpu,
                                                decode_splits=args.decode_splits, decode_waves=args.decode_waves,
                                                decode_depth=args.decode_depth, score_waves=args.score_waves,
