@@ -27,6 +27,7 @@ extern "C" int spin_pin_partitions(spin_ctx *ctx, int32_t batch, float *scores, 
   if (batch == 0 || pinned_stride == 0) return SPIN_OK;
   if (!scores || !part_offsets || !pinned || !npinned) return SPIN_ERR_INVALID;
   const int rows = batch * ctx->cfg.num_kv_heads;
+  if (rows > 65535) return SPIN_ERR_UNSUPPORTED;   // rows are the grid's second dimension
   spin_launch(ctx, SPIN_K_SELECT_HIST, spin_pin_kernel, dim3((unsigned)((pinned_stride + 255) / 256), (unsigned)rows),
               dim3(256), 0, (hipStream_t)stream, scores, part_offsets, pinned, npinned, pinned_stride,
               ctx->cfg.num_kv_heads);

@@ -468,7 +468,7 @@ int spin_select_impl(spin_ctx *ctx, int32_t batch, const float *scores, const in
   else if (ctx->max_parts <= 16384)
     spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<1024, 16>, dim3((unsigned)rows), dim3(1024),
                 SPIN_SELECT_ARGS, ctx->var);
-  else if (ctx->ws_hist_off && workspace) {
+  else if (ctx->ws_hist_off && workspace && rows <= 65535) {   // rows are the histogram grid's second dimension
     // two launches: histogram of the first 12 key bits by many workgroups per row, then one workgroup per row
     int32_t *hist = (int32_t *)((char *)workspace + ctx->ws_hist_off);
     const int words_max = ((ctx->max_parts + 63) / 64) * 2;
@@ -508,7 +508,9 @@ extern "C" int spin_score_select_topk(spin_ctx *ctx, int32_t batch, const void *
   if (!ctx || batch < 0 || batch > ctx->cfg.max_batch) return SPIN_ERR_INVALID;
   if (batch == 0) return SPIN_OK;
   if (!sel || !nsel) return SPIN_ERR_INVALID;
-  const bool fuse = ctx->ws_hist_off && workspace && ctx->cfg.score_kind == SPIN_SCORE_SKETCH;
+  // (same condition as the two-launch path of stage 2: the histogram must be consumed by the launch that follows)
+  const bool fuse = ctx->ws_hist_off && workspace && ctx->cfg.score_kind == SPIN_SCORE_SKETCH &&
+                    batch * ctx->cfg.num_kv_heads <= 65535;
   int32_t *hist = fuse ? (int32_t *)((char *)workspace + ctx->ws_hist_off) : nullptr;
   const int st = spin_score_impl(ctx, batch, q, summaries, chan_idx, part_offsets, seq_lens, scores, workspace, stream,
                                  hist);
