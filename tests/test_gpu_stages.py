@@ -114,8 +114,51 @@ def _kd_kc(w):
 
 @pytest.mark.parametrize("name", list(_workloads()))
 def test_stage_by_stage(name):
+    _check_workload(_workloads()[name], name)
+
+
+def _random_workload(seed):
+    """A valid workload drawn at random: score kind, partition size, group size, heads, ragged
+    contexts (down to a single token), top-k (down to 0, up to beyond the row) and forced windows."""
+    rng = np.random.default_rng(1000 + seed)
+    kind = int(rng.choice([synth.SCORE_MINMAX, synth.SCORE_SKETCH, synth.SCORE_REPMAX]))
+    reps = 4
+    if kind == synth.SCORE_SKETCH:
+        tp = 1
+    elif kind == synth.SCORE_MINMAX:
+        tp = int(rng.choice([1, 2, 4, 8, 16, 16, 32, 64, 128]))
+    else:
+        reps = int(rng.choice([1, 2, 4]))
+        tp = int(rng.choice([t for t in (4, 8, 16, 16, 32, 64, 128) if t % reps == 0]))
+    g = int(rng.choice([1, 2, 3, 4, 4, 5, 8, 16]))
+    hkv = int(rng.choice([1, 2, 3]))
+    batch = int(rng.integers(1, 4))
+    lens = []
+    for _ in range(batch):
+        style = rng.integers(0, 4)
+        lens.append(int({0: rng.integers(1, 40), 1: rng.integers(40, 700), 2: rng.integers(700, 3000),
+                         3: 16 * rng.integers(1, 120)}[int(style)]))
+    max_parts = max(-(-n // tp) for n in lens)
+    topk = int(rng.choice([0, 1, 2, rng.integers(3, 40), rng.integers(3, max(max_parts, 4) + 20)]))
+    c0 = synth.config0()
+    return c0.with_(seq_lens=tuple(lens), num_q_heads=g * hkv, num_kv_heads=hkv, partition_tokens=tp, score_kind=kind,
+                    reps_per_partition=reps, topk=topk, topk_includes_forced=bool(rng.integers(0, 2)),
+                    sink_pages=int(rng.integers(0, 4)), recent_pages=int(rng.integers(0, 5)),
+                    block_mean_std=0.5 if kind == synth.SCORE_REPMAX else 0.0, seed=c0.seed + 17 * seed,
+                    name=f"random{seed}")
+
+
+@pytest.mark.parametrize("seed", range(64))
+def test_random_workloads_stage_by_stage(seed):
+    w = _random_workload(seed)
+    print(f"seed {seed}: kind {w.score_kind} tp {w.partition_tokens} reps {w.reps_per_partition} group {w.group} "
+          f"kv {w.num_kv_heads} lens {w.seq_lens} topk {w.topk} incl {w.topk_includes_forced} "
+          f"sink {w.sink_pages} recent {w.recent_pages}", flush=True)
+    _check_workload(w, w.name)
+
+
+def _check_workload(w, name):
     from gpu_harness import DeviceWorkload, bf16_to_bits, build_summaries, run_step, unpack_summary_rows
-    w = _workloads()[name]
     data = synth.generate(w, spare_slots=3)
     dw = DeviceWorkload(data)
     sp = dw.spin
