@@ -249,17 +249,40 @@ def _granularity_workloads():
 @pytest.mark.parametrize("policy", [0, 1])
 @pytest.mark.parametrize("name", list(_granularity_workloads()))
 def test_budget_mode_any_uniform_granularity(name, policy):
+    _check_budget_steps(_granularity_workloads()[name], policy, n_ts=5, exact=False, seed=31 + policy, steps=16)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_budget_mode_random_workloads(seed):
+    """Randomly drawn partition size, heads, ragged contexts, top-k, forced windows, timestamp range,
+    policy and eviction mode: selection -> page list -> replacement against the oracle, step by step."""
+    rng = np.random.default_rng(500 + seed)
+    tp = int(rng.choice([1, 2, 4, 8, 16, 16, 16, 32, 64, 128]))
+    hkv = int(rng.choice([1, 2, 3]))
+    lens = tuple(int(x) for x in rng.integers(40, 4000, size=int(rng.integers(1, 4))))
+    max_parts = max(-(-n // tp) for n in lens)
+    topk = int(rng.integers(1, min(max(max_parts, 2), 48) + 1))
+    policy = int(rng.integers(0, 2))
+    w = synth.config0().with_(seq_lens=lens, num_q_heads=hkv, num_kv_heads=hkv, partition_tokens=tp, topk=topk,
+                              topk_includes_forced=bool(rng.integers(0, 2)), sink_pages=int(rng.integers(0, 4)),
+                              recent_pages=int(rng.integers(0, 5)), name=f"lru_random{seed}")
+    n_ts = int(rng.integers(2, 9))
+    exact = bool(rng.integers(0, 2)) and policy == 0
+    print(f"seed {seed}: tp {tp} kv {hkv} lens {lens} topk {topk} policy {policy} n_ts {n_ts} exact {exact}", flush=True)
+    _check_budget_steps(w, policy, n_ts, exact, seed=900 + seed, steps=int(rng.integers(8, 20)))
+
+
+def _check_budget_steps(w, policy, n_ts, exact, seed, steps):
     from oracle import resolve as oresolve, select as oselect
-    w = _granularity_workloads()[name]
-    rows, n_ts = w.rows, 5
+    rows = w.rows
     probe = binding.Spin.for_workload(w, lru_timestamps=n_ts, lru_policy=policy)
     budgets = [probe.page_stride + 8 * (r % 3) + (0 if policy else r) for r in range(rows)]
     if policy:
         budgets = [8 * -(-b // 8) for b in budgets]
-    bd = Budget(w, budgets, n_ts, policy=policy)
+    bd = Budget(w, budgets, n_ts, evict_exact=exact, policy=policy)
     caches = [lru.RowCache(budgets[r]) for r in range(rows)]
-    rng = np.random.default_rng(31 + policy)
-    for step in range(16):
+    rng = np.random.default_rng(seed)
+    for step in range(steps):
         selections, want_pages = [], []
         for r in range(rows):
             b = r // w.num_kv_heads
@@ -280,7 +303,7 @@ def test_budget_mode_any_uniform_granularity(name, policy):
             if policy:
                 want_slots, want_miss, _ = lru.setassoc_step(caches[r], pages, step, n_ts, row=r)
             else:
-                want_slots, want_miss, _ = lru.lru_step(caches[r], pages, step, n_ts)
+                want_slots, want_miss, _ = lru.lru_step(caches[r], pages, step, n_ts, evict_exact=exact)
             base = int(bd.slot_base_np[r])
             assert npg[r] == len(pages), f"step {step} row {r}"
             assert page_ids[r, :npg[r]].tolist() == pages
