@@ -93,6 +93,31 @@ def test_variable_length_partitions(case, three_launch):
     _check(w, layouts, data, layer, three_launch)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_variable_length_partitions_random(seed):
+    """Randomly drawn cluster layouts, largest cluster size, summary kind (min / max keys or the
+    centroid), heads, top-k and forced windows, through both launch shapes."""
+    rng = np.random.default_rng(700 + seed)
+    hkv = int(rng.choice([1, 2, 3]))
+    g = int(rng.choice([1, 2, 4, 5, 8]))
+    lens = tuple(16 * int(x) for x in rng.integers(2, 400, size=int(rng.integers(1, 4))))
+    centroid = bool(rng.integers(0, 2))
+    w = synth.config0().with_(seq_lens=lens, num_q_heads=g * hkv, num_kv_heads=hkv,
+                              partition_tokens=16 * int(rng.integers(1, 10)),
+                              score_kind=synth.SCORE_REPMAX if centroid else synth.SCORE_MINMAX,
+                              reps_per_partition=1 if centroid else 4, topk=int(rng.integers(0, 30)),
+                              topk_includes_forced=bool(rng.integers(0, 2)), sink_pages=int(rng.integers(0, 5)),
+                              recent_pages=int(rng.integers(0, 7)), block_mean_std=0.5 if centroid else 0.0,
+                              name=f"var_random{seed}")
+    print(f"seed {seed}: lens {lens} largest {w.partition_tokens} centroid {centroid} group {g} kv {hkv} "
+          f"topk {w.topk} incl {w.topk_includes_forced} sink {w.sink_pages} recent {w.recent_pages}", flush=True)
+    data = synth.generate(w, spare_slots=3)
+    layouts = synth.variable_layouts(w, seed=w.seed + seed, min_tokens=int(rng.integers(1, 17)))
+    natural = torch.from_numpy(data.pool_bits.view(np.int16).copy()).to(DEV).view(torch.bfloat16)
+    layer = runner.LayerState.from_natural_pool(w, data.slot_of, natural, layouts=layouts)
+    _check(w, layouts, data, layer, three_launch=bool(seed % 2))
+
+
 def test_uniform_tables_give_the_uniform_results():
     """Registering the tables of a uniform layout must not change any output bit."""
     w = synth.config0().with_(seq_lens=(2000, 4096), num_q_heads=8, num_kv_heads=2, partition_tokens=64, topk=9,
