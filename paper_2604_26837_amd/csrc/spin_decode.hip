@@ -482,8 +482,9 @@ extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, c
   const int W = ctx->waves;
   const size_t lds = (size_t)W * G * (SPIN_HEAD_DIM + 2) * sizeof(float);
   if (ctx->k_token_major) {
-    // token-major slots: tiles of gathered tokens (8 wavefronts; the depth knob does not apply)
-    const size_t lds_tok = lds + (size_t)8 * TOK_LIST * sizeof(uint32_t);
+    // token-major slots: tiles of gathered tokens (always 8 wavefronts: the waves and depth knobs do not
+    // apply, and the merge buffers are sized for 8 whatever the waves knob says)
+    const size_t lds_tok = (size_t)8 * G * (SPIN_HEAD_DIM + 2) * sizeof(float) + (size_t)8 * TOK_LIST * sizeof(uint32_t);
     spin_launch(ctx, SPIN_K_DECODE, spin_decode_tokens_kernel<8>, dim3((unsigned)(rows * nsplit)), dim3(512), lds_tok,
                 (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, slots, valid_mask, npages,
                 ctx->page_stride, G, ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, scale_log2e, part_ml,

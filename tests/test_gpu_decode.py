@@ -204,3 +204,40 @@ def test_token_partitions_gathered_tiles(splits, npages, sparse):
     ml0 = [[0] * len(m) for m in ml]
     got0, lgot0 = _run_decode(dw, pl, ml0)
     assert (got0 == 0).all() and np.isneginf(lgot0).all()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_launch_shapes_and_page_lists(seed):
+    """Randomly drawn group size, heads, contexts, page-list lengths (some rows empty), token masks,
+    split-K factor, wavefronts per workgroup and page buffers, for whole-page and token-major slots."""
+    from gpu_harness import DeviceWorkload
+    rng = np.random.default_rng(300 + seed)
+    g = int(rng.choice([1, 2, 3, 4, 4, 5, 8, 12, 16]))
+    hkv = int(rng.choice([1, 2, 3]))
+    lens = tuple(int(x) for x in rng.integers(1, 5000, size=int(rng.integers(1, 4))))
+    token_major = bool(rng.integers(0, 3) == 0)               # partitions smaller than a page: gathered tiles
+    w = synth.config0().with_(seq_lens=lens, num_q_heads=g * hkv, num_kv_heads=hkv, topk=int(rng.integers(8, 200)),
+                              partition_tokens=4 if token_major else 16, name=f"decode_random{seed}")
+    over = dict(decode_splits=int(rng.choice([0, 1, 2, 3, 5, 8])), decode_waves=int(rng.choice([0, 2, 4, 8])),
+                decode_depth=int(rng.choice([0, 2, 3, 4])))
+    print(f"seed {seed}: group {g} kv {hkv} lens {lens} token-major {token_major} {over}", flush=True)
+    dw = DeviceWorkload(synth.generate(w), **over)
+    stride = dw.spin.page_stride
+    page_lists, mask_lists = [], []
+    for b in range(w.batch):
+        pages = w.pages(b)
+        for h in range(hkv):
+            n = int(rng.choice([0, 1, min(pages, stride), rng.integers(0, min(pages, stride) + 1)]))
+            pl = sorted(int(x) for x in rng.choice(pages, size=n, replace=False))
+            ml = []
+            for p in pl:
+                full = (1 << min(16, w.seq_lens[b] - 16 * p)) - 1
+                style = rng.integers(0, 3)
+                ml.append(full if style == 0 else int(full & int(rng.integers(0, 1 << 16))) if style == 1
+                          else int(full & (1 << int(rng.integers(0, 16)))))
+            page_lists.append(pl)
+            mask_lists.append(ml)
+    ref, lref = _oracle_rows(dw, page_lists, mask_lists)
+    got, lgot = _run_decode(dw, page_lists, mask_lists)
+    # rows that attend to no token at all: zeros, lse = -inf
+    _compare(got, np.nan_to_num(ref), lgot, lref)
