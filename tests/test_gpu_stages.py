@@ -374,6 +374,45 @@ def test_select_rows_beyond_the_register_variants():
     _check_select(w3, [rng.standard_normal(140000).astype(np.float32)])
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_select_random_rows(seed):
+    """Row length drawn log-uniformly from 1 to 150000 partitions (every kernel variant and the
+    two-launch path), random k, windows and score distributions with ties and special values."""
+    rng = np.random.default_rng(4000 + seed)
+    tp = int(rng.choice([1, 16]))
+    P0 = int(np.exp(rng.uniform(0, np.log(150000))))
+    lens = tuple(max(1, int(P0 * f)) * tp - int(rng.integers(0, tp)) for f in (1.0, rng.uniform(0.01, 1.0), 0.5))
+    lens = tuple(max(n, 1) for n in lens)
+    topk = int(rng.choice([0, 1, rng.integers(1, 64), rng.integers(1, 2000)]))
+    w = synth.config0().with_(num_q_heads=4, num_kv_heads=1, seq_lens=lens, partition_tokens=tp, topk=topk,
+                              topk_includes_forced=bool(rng.integers(0, 2)), sink_pages=int(rng.integers(0, 5)),
+                              recent_pages=int(rng.integers(0, 9)),
+                              score_kind=synth.SCORE_SKETCH if tp == 1 else synth.SCORE_MINMAX, name=f"selrand{seed}")
+    print(f"seed {seed}: tp {tp} lens {lens} topk {topk} incl {w.topk_includes_forced} sink {w.sink_pages} "
+          f"recent {w.recent_pages}", flush=True)
+
+    def scores(P):
+        kind = int(rng.integers(0, 6))
+        x = rng.standard_normal(P)
+        if kind == 0:
+            out = x * 3
+        elif kind == 1:
+            out = np.round(x * 8) / 8                                          # heavy ties
+        elif kind == 2:
+            out = rng.choice([-1.0, 1.0], size=P) * np.exp2(rng.uniform(-60, 60, size=P))
+        elif kind == 3:
+            out = x.copy()
+            idx = rng.choice(P, size=max(P // 6, 1), replace=False)
+            out[idx] = rng.choice(np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-40]), size=idx.size)
+        elif kind == 4:
+            out = np.full(P, float(rng.integers(-3, 4)))                        # all equal
+        else:
+            out = 100.0 + x * 1e-3                                             # equal leading bits
+        return out.astype(np.float32)
+
+    _check_select(w, [scores(w.partitions(b)) for b in range(w.batch)])
+
+
 def test_resolve_reports_missing_leaf_and_missing_slot():
     from gpu_harness import DEV, DeviceWorkload, build_summaries, run_step
     w = synth.config0().with_(seq_lens=(4096,), name="holes")
