@@ -157,10 +157,24 @@ def test_random_workloads_stage_by_stage(seed):
     _check_workload(w, w.name)
 
 
-def _check_workload(w, name):
+@pytest.mark.parametrize("seed", range(32))
+def test_random_workloads_with_random_launch_knobs(seed):
+    """The same draw with the launch-shape knobs of stages 1 and 4 drawn as well: results may not
+    depend on them beyond the tolerances."""
+    w = _random_workload(100 + seed)
+    rng = np.random.default_rng(77 + seed)
+    over = dict(score_waves=int(rng.choice([0, 1, 2, 4, 8])), score_tiles_per_wg=int(rng.choice([0, 1, 2, 3, 4, 8, 16, 64])),
+                decode_splits=int(rng.choice([0, 1, 2, 3, 7])), decode_waves=int(rng.choice([0, 2, 4, 8])),
+                decode_depth=int(rng.choice([0, 2, 3, 4])))
+    print(f"seed {seed}: kind {w.score_kind} tp {w.partition_tokens} reps {w.reps_per_partition} group {w.group} "
+          f"kv {w.num_kv_heads} lens {w.seq_lens} topk {w.topk} {over}", flush=True)
+    _check_workload(w, w.name, **over)
+
+
+def _check_workload(w, name, **cfg_over):
     from gpu_harness import DeviceWorkload, bf16_to_bits, build_summaries, run_step, unpack_summary_rows
     data = synth.generate(w, spare_slots=3)
-    dw = DeviceWorkload(data)
+    dw = DeviceWorkload(data, **cfg_over)
     sp = dw.spin
     chan = synth.sketch_channels(data) if w.score_kind == synth.SCORE_SKETCH else None
     build_summaries(dw, chan)
