@@ -46,6 +46,36 @@ def test_append_tokens(kind):
         "sketch": c0.with_(seq_lens=final, partition_tokens=1, score_kind=synth.SCORE_SKETCH, topk=40,
                            sink_pages=0, recent_pages=0, name="a4"),
     }[kind]
+    _check_append(w, start)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_append_random_workloads(seed):
+    """Summary kind, partition size (down to single tokens: token-major slots), representative count,
+    heads and the appended stretch drawn at random."""
+    rng = np.random.default_rng(600 + seed)
+    kind = int(rng.choice([synth.SCORE_MINMAX, synth.SCORE_REPMAX, synth.SCORE_SKETCH]))
+    reps = int(rng.choice([1, 2, 4])) if kind == synth.SCORE_REPMAX else 4
+    if kind == synth.SCORE_SKETCH:
+        tp = 1
+    elif kind == synth.SCORE_MINMAX:
+        tp = int(rng.choice([1, 2, 4, 8, 16, 32, 64, 128]))
+    else:
+        tp = int(rng.choice([t for t in (4, 8, 16, 32, 64, 128) if t % reps == 0]))
+    hkv, g = int(rng.choice([1, 2, 3])), int(rng.choice([1, 2, 4, 5]))
+    final = tuple(int(x) for x in rng.integers(20, 700, size=int(rng.integers(1, 4))))
+    start = tuple(max(1, f - int(rng.integers(1, 90))) for f in final)
+    w = synth.config0().with_(seq_lens=final, num_q_heads=g * hkv, num_kv_heads=hkv, partition_tokens=tp,
+                              score_kind=kind, reps_per_partition=reps, topk=int(rng.integers(1, 30)),
+                              topk_includes_forced=bool(rng.integers(0, 2)), sink_pages=int(rng.integers(0, 3)),
+                              recent_pages=int(rng.integers(0, 3)),
+                              block_mean_std=0.5 if kind == synth.SCORE_REPMAX else 0.0, name=f"append_random{seed}")
+    print(f"seed {seed}: kind {kind} reps {reps} tp {tp} group {g} kv {hkv} final {final} start {start}", flush=True)
+    _check_append(w, start)
+
+
+def _check_append(w, start):
+    final = w.seq_lens
     data = synth.generate(w)
     truth = torch.from_numpy(data.pool_bits.view(np.int16).copy()).to(DEV).view(torch.bfloat16)
     # the layer starts from a pool whose tokens in [start, final) hold junk
