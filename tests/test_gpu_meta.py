@@ -46,6 +46,51 @@ def test_reclaim_tail_matches_oracle_over_a_trace():
             assert (rev[base + S: base + cap[r], 0] == -1).all()          # reclaimed slots are empty
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_reclaim_tail_random_plans(seed):
+    """Random slot counts, selections, policies and shrink / grow plans: after every change the
+    replacement state and every later step must equal the oracle's."""
+    rng = np.random.default_rng(1200 + seed)
+    policy = int(rng.integers(0, 2))
+    k = int(rng.integers(4, 14))
+    hkv = int(rng.choice([1, 2]))
+    lens = tuple(int(x) for x in rng.integers(400, 2500, size=int(rng.integers(1, 3))))
+    w = synth.config0().with_(seq_lens=lens, num_q_heads=hkv, num_kv_heads=hkv, topk=k, sink_pages=0, recent_pages=0,
+                              name=f"reclaim_random{seed}")
+    rows = w.rows
+    unit = 8 if policy else 1
+    cap = [unit * int(rng.integers(-(-2 * k // unit), -(-6 * k // unit) + 1)) for _ in range(rows)]
+    n_ts = int(rng.integers(3, 9))
+    bd = Budget(w, cap, n_ts, policy=policy)
+    caches = [lru.RowCache(c) for c in cap]
+    steps = 20
+    trace = _trace(rng, rows, [w.pages(r // hkv) for r in range(rows)], k, steps, hot_frac=0.6)
+    print(f"seed {seed}: policy {policy} k {k} kv {hkv} lens {lens} caps {cap} n_ts {n_ts}", flush=True)
+    for step, selections in enumerate(trace):
+        if step and rng.random() < 0.35:
+            # a new count per row between "just enough for one step" and the full capacity
+            new = [unit * int(rng.integers(-(-k // unit), cap[r] // unit + 1)) for r in range(rows)]
+            bd.sp.reclaim_tail(w.batch, bd.slot_base, torch.tensor(new, dtype=torch.int32, device=DEV), bd.dir,
+                               bd.leaf, bd.rev, bd.ws)
+            for r in range(rows):
+                lru.reclaim_tail(caches[r], new[r])
+            assert bd.slot_base.cpu().numpy()[:, 1].tolist() == new
+        slots, npg, mpages, mslots, nmiss = bd.step(step, selections)
+        assert bd.sp.poll_status(bd.ws) == 0, f"step {step}"
+        rev = bd.rev.cpu().numpy()
+        for r in range(rows):
+            if policy:
+                want_slots, want_miss, _ = lru.setassoc_step(caches[r], selections[r], step, n_ts, row=r)
+            else:
+                want_slots, want_miss, _ = lru.lru_step(caches[r], selections[r], step, n_ts)
+            base = int(bd.slot_base_np[r])
+            assert slots[r, :npg[r]].tolist() == [base + s for s in want_slots], f"step {step} row {r}"
+            assert mslots[r, :nmiss[r]].tolist() == [base + s for _, s in want_miss]
+            S = len(caches[r].page)
+            assert rev[base:base + S, 0].tolist() == caches[r].page
+            assert (rev[base + S: base + cap[r], 0] == -1).all()
+
+
 def test_leaves_allocated_on_demand_equal_preallocated_run():
     k = 16
     w = synth.config0().with_(seq_lens=(16 * 5000, 16 * 700, 16 * 2100), num_q_heads=4, num_kv_heads=2, topk=k,
