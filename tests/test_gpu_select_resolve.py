@@ -66,3 +66,30 @@ def test_headline_size_and_unsupported_shape():
                                sink_pages=0, recent_pages=0, name="sk")
     sp = binding.Spin.for_workload(w2)
     assert sp.lib.spin_select_resolve(sp.h, 1, *([8] * 7), 1, *([8] * 6), 8, None) == -2
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_workloads_both_combined_calls(seed):
+    """Random workloads (the draw of the stage tests): the stages 2+3 launch and the stages 1+2 call
+    must each reproduce the separate stage calls bit for bit."""
+    from test_gpu_stages import _random_workload
+    w = _random_workload(200 + seed)
+    print(f"seed {seed}: kind {w.score_kind} tp {w.partition_tokens} reps {w.reps_per_partition} group {w.group} "
+          f"kv {w.num_kv_heads} lens {w.seq_lens} topk {w.topk}", flush=True)
+    data = synth.generate(w, spare_slots=2)
+    natural = torch.from_numpy(data.pool_bits.view(np.int16).copy()).to("cuda:0").view(torch.bfloat16)
+    layer = runner.LayerState.from_natural_pool(w, data.slot_of, natural)
+    if w.score_kind == synth.SCORE_SKETCH:
+        layer.set_channels(synth.sketch_channels(data))
+    layer.build_summaries()
+    q = torch.from_numpy(data.q_bits.view(np.int16).copy()).to("cuda:0").view(torch.bfloat16)
+    _compare(layer, q)                       # stages 2+3 in one launch (rows of at most 16384 partitions here)
+    ref = _snapshot(layer)
+    for t in (layer.sel, layer.nsel, layer.slots, layer.page_ids, layer.valid_mask, layer.npages):
+        t.fill_(-7)
+    layer.out.fill_(3.0)
+    layer.step12(q)                          # stages 1+2 in one call
+    torch.cuda.synchronize()
+    assert layer.status() == 0
+    for a, b in zip(ref, _snapshot(layer)):
+        assert np.array_equal(a, b)
