@@ -193,21 +193,27 @@ __device__ __forceinline__ void decode_finish(softmax_state &st, int row, int sp
   // barrier, so the merge costs about one memory round trip.
   const size_t pbase = (size_t)row * nsplit * G;
   float *t_m = s_acc, *t_l = s_acc + nsplit * G;   // s_acc is free: the wave partials were consumed above
-  constexpr int CH = 8;
-  float a0[CH];
-  {
-    const int g = threadIdx.x >> 7, d = threadIdx.x & 127;
+  constexpr int CH = 8;        // splits whose accumulators a thread requests at a time
+  constexpr int KPRE = 4;      // output elements per thread requested before the barrier (groups of up to
+                               // 16 heads with 8 wavefronts; further ones are requested in the loop)
+  constexpr int NT = WAVES * 64;
+  const int GD = G * SPIN_HEAD_DIM;
+  float a0[KPRE][CH];
+#pragma unroll
+  for (int k = 0; k < KPRE; ++k) {
+    const int idx = threadIdx.x + k * NT;
+    const int g = idx >> 7, d = idx & 127;
 #pragma unroll
     for (int s = 0; s < CH; ++s)
-      a0[s] = (threadIdx.x < G * SPIN_HEAD_DIM && s < nsplit)
-                  ? spin_dev_load(&part_acc[(pbase + (size_t)s * G + g) * SPIN_HEAD_DIM + d]) : 0.f;
+      a0[k][s] = (idx < GD && s < nsplit) ? spin_dev_load(&part_acc[(pbase + (size_t)s * G + g) * SPIN_HEAD_DIM + d]) : 0.f;
   }
-  for (int i = threadIdx.x; i < nsplit * G; i += WAVES * 64) {
+  for (int i = threadIdx.x; i < nsplit * G; i += NT) {
     t_m[i] = spin_dev_load(&part_ml[(pbase + i) * 2]);
     t_l[i] = spin_dev_load(&part_ml[(pbase + i) * 2 + 1]);
   }
   __syncthreads();
-  for (int idx = threadIdx.x; idx < G * SPIN_HEAD_DIM; idx += WAVES * 64) {
+  // output element idx = (head g, channel d): the splits merged in split order
+  auto merge_one = [&](int idx, const float (&first)[CH], bool have_first) {
     const int g = idx >> 7, d = idx & 127;
     float M = NEG_INF;
     for (int s = 0; s < nsplit; ++s) M = fmaxf(M, t_m[s * G + g]);
@@ -217,7 +223,7 @@ __device__ __forceinline__ void decode_finish(softmax_state &st, int row, int sp
       float a[CH];
 #pragma unroll
       for (int s = 0; s < CH; ++s) {
-        if (idx == (int)threadIdx.x && s0 == 0) a[s] = a0[s];
+        if (have_first && s0 == 0) a[s] = first[s];
         else a[s] = (s0 + s < nsplit) ? spin_dev_load(&part_acc[(pbase + (size_t)(s0 + s) * G + g) * SPIN_HEAD_DIM + d]) : 0.f;
       }
 #pragma unroll
@@ -230,7 +236,13 @@ __device__ __forceinline__ void decode_finish(softmax_state &st, int row, int sp
       }
     }
     write_out(out, lse, b * Hq + h * G + g, d, M, L, O);
+  };
+#pragma unroll
+  for (int k = 0; k < KPRE; ++k) {
+    const int idx = threadIdx.x + k * NT;
+    if (idx < GD) merge_one(idx, a0[k], true);
   }
+  for (int idx = threadIdx.x + KPRE * NT; idx < GD; idx += NT) merge_one(idx, a0[0], false);
   if (threadIdx.x == 0)   // ready for the next launch
     __hip_atomic_store(&tickets[row], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
