@@ -70,3 +70,18 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(build, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         binding.load_library()
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/spin.h must compile as C99 with no extensions: the boundary is a C ABI."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_spin.c"
+    src.write_text('#include "spin.h"\nint main(void) { spin_config c; (void)c; return spin_status_string(0) == 0; }\n')
+    res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                          "-c", str(src), "-o", str(tmp_path / "use_spin.o")], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+
