@@ -170,6 +170,13 @@ def run_cfg4(args):
                                 first_step_us=round(lat[0], 1), topk_persistence=round(float(np.mean(persist)), 4),
                                 kernel_us=kern, pool_gib=round(layer.pool_slots * 8192 / 2**30, 2),
                                 host_kv_gib=round(layer.host_kv.numel() * 2 / 2**30, 2))
+            # the paper's envelope for this step (Eq. 3 with T_MLP = 0): summary and attended bytes over the
+            # HBM peak plus the missed pages over the host link's raw rate (PCIe Gen5 x16, 64 GB/s)
+            summary_bytes = int(layer.summaries.numel())
+            attended_bytes = layer.stats["selected"] / steps * 8192
+            miss_bytes = results[key]["misses_per_step"] * 8192
+            results[key]["eq3_ideal_us"] = round((summary_bytes + attended_bytes) / PEAK_HBM_GBPS / 1e3
+                                                 + miss_bytes / 64.0 / 1e3, 1)
             if trace is not None:
                 from oracle import lru as olru
                 rows_b = list(range(0, w.rows, 8))          # one KV head per request: 32 rows
