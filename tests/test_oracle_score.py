@@ -126,16 +126,19 @@ def test_repmax_constant_blocks_reduce_to_dot():
     assert np.allclose(s, (q @ centers.T).max(axis=0), rtol=1e-14, atol=1e-14)
 
 
-def test_repmax_brute_force_and_ragged_tail():
+@pytest.mark.parametrize("R", [1, 2, 4])
+def test_repmax_brute_force_and_ragged_tail(R):
+    """R = 4: quarter means; R = 2: half means; R = 1: the mean key of the whole partition (a landmark)."""
     q, K = _row(7, 64, D=8, G=2)
-    seq_len, T, R = 37, 16, 4          # last block has 5 tokens: quarters 2,3 empty
+    seq_len, T = 37, 16                # last block has 5 tokens: with R = 4 its quarters 2, 3 are empty
     K[seq_len:] = 1e6
     reps = index.block_representatives(K, seq_len, T, R)
-    assert reps.shape == (3, 4, 8)
-    # quarter means rounded to bf16, written out by hand
+    assert reps.shape == (3, R, 8)
+    sub = T // R
+    # sub-range means rounded to bf16, written out by hand
     for p in range(3):
         for r in range(R):
-            t0, t1 = p * T + r * 4, min(p * T + r * 4 + 4, seq_len)
+            t0, t1 = p * T + r * sub, min(p * T + r * sub + sub, seq_len)
             if t1 > t0:
                 mean = sum(K[t] for t in range(t0, t1)) / (t1 - t0)
                 assert np.array_equal(reps[p, r], bf16.decode(bf16.encode_rne(mean)))
