@@ -235,7 +235,10 @@ int spin_append_kv(spin_ctx *ctx, int32_t batch, const void *k_new, const void *
  *   REPMAX  max_g max_r q[g] . rep[p][r]
  * over the G query heads of the row's group; bf16 inputs, exact products, fp32
  * accumulation on the matrix cores.  Entries beyond a row's partition count are
- * unspecified. */
+ * unspecified.  Summaries must be finite: the kernels pair some summary values
+ * with exact zeros of the query-side operand, and 0 x inf would turn the scores
+ * of the partition (SKETCH with groups of up to four heads: of the up to 64
+ * tokens scored together) into NaN, which stage 2 ranks lowest. */
 int spin_score_partitions(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries,
                           const int32_t *chan_idx, const int32_t *part_offsets,
                           const int32_t *seq_lens, float *scores, void *workspace, void *stream);
