@@ -117,6 +117,14 @@ def test_stage_by_stage(name):
     _check_workload(_workloads()[name], name)
 
 
+def test_million_token_context():
+    """One request of a million tokens (62 500 pages: 123 leaf chunks per row, the two-launch stage 2)
+    through every stage against the oracle."""
+    w = synth.config0().with_(seq_lens=(1_000_000 - 7,), num_q_heads=4, num_kv_heads=1, topk=256, sink_pages=4,
+                              recent_pages=8, name="million")
+    _check_workload(w, w.name)
+
+
 def _random_workload(seed):
     """A valid workload drawn at random: score kind, partition size, group size, heads, ragged
     contexts (down to a single token), top-k (down to 0, up to beyond the row) and forced windows."""
