@@ -125,6 +125,15 @@ def test_million_token_context():
     _check_workload(w, w.name)
 
 
+def test_many_short_requests():
+    """A large batch of short ragged requests: 1200 rows, most of them smaller than one summary tile."""
+    rng = np.random.default_rng(3)
+    lens = tuple(int(x) for x in rng.integers(1, 400, size=300))
+    w = synth.config0().with_(seq_lens=lens, num_q_heads=8, num_kv_heads=4, topk=6, sink_pages=1, recent_pages=1,
+                              name="many_rows")
+    _check_workload(w, w.name)
+
+
 def _random_workload(seed):
     """A valid workload drawn at random: score kind, partition size, group size, heads, ragged
     contexts (down to a single token), top-k (down to 0, up to beyond the row) and forced windows."""
