@@ -252,6 +252,15 @@ def test_budget_mode_any_uniform_granularity(name, policy):
     _check_budget_steps(_granularity_workloads()[name], policy, n_ts=5, exact=False, seed=31 + policy, steps=16)
 
 
+@pytest.mark.parametrize("policy,exact", [(0, False), (0, True), (1, False)])
+def test_single_timestamp_value(policy, exact):
+    """n = 1: every resident page carries timestamp 0, so the threshold bucket is always the only one
+    (whole-bucket eviction empties everything not selected; the exact mode evicts by slot order)."""
+    w = synth.config0().with_(seq_lens=(1500, 700), num_q_heads=2, num_kv_heads=2, topk=12, sink_pages=1,
+                              recent_pages=2, name="lru_n1")
+    _check_budget_steps(w, policy, n_ts=1, exact=exact, seed=5, steps=12)
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_budget_mode_random_workloads(seed):
     """Randomly drawn partition size, heads, ragged contexts, top-k, forced windows, timestamp range,
