@@ -261,6 +261,14 @@ def test_single_timestamp_value(policy, exact):
     _check_budget_steps(w, policy, n_ts=1, exact=exact, seed=5, steps=12)
 
 
+def test_largest_timestamp_range_and_beyond():
+    """n = 256 is the largest range the kernels take (the timestamp histogram lives in LDS); more is refused."""
+    w = synth.config0().with_(seq_lens=(900,), num_q_heads=2, num_kv_heads=2, topk=10, name="lru_n256")
+    _check_budget_steps(w, 0, n_ts=256, exact=False, seed=6, steps=10)
+    with pytest.raises(binding.SpinError, match="UNSUPPORTED"):
+        binding.Spin.for_workload(w, lru_timestamps=257)
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_budget_mode_random_workloads(seed):
     """Randomly drawn partition size, heads, ragged contexts, top-k, forced windows, timestamp range,
