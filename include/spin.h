@@ -112,7 +112,7 @@ typedef struct spin_config {
   int32_t recent_pages;         /* last pages of a context, always attended */
   int32_t max_context;          /* tokens; sizes strides and the workspace */
   int32_t leaf_entries;         /* entries per second-level table chunk (512) */
-  int32_t lru_timestamps;       /* 0 = all-resident mode; n > 0 = bucketed LRU with n timestamp values */
+  int32_t lru_timestamps;       /* 0 = all-resident mode; n > 0 = bucketed LRU with n timestamp values (n <= 256) */
   int32_t lru_evict_exact;      /* 0 = evict whole buckets <= x; 1 = only as many pages of bucket x as needed */
   int32_t lru_policy;           /* budget mode: 0 = bucketed LRU (Section 5.3); 1 = 8-way set-associative placement:
                                    home set = mix32(row, page) mod (slots / 8), see spin_resolve_slots */
