@@ -8,6 +8,11 @@
 //   SKETCH  row = token,            KD = 16,  KC = 4
 #include "spin_common.h"
 
+// Index of a 16-byte unit in a wavefront's regrouping buffer: one unit of padding after every 16, so
+// that the regrouped reads (lane l reads unit 4 l + i, a 64-byte stride) spread over all LDS banks
+// instead of hitting every fourth one.
+__device__ inline int spin_lds_pad(int unit) { return unit + (unit >> 4); }
+
 // element offset of (summary row R, element e)
 __device__ inline size_t summ_off(size_t R, int e, int kd, int kc) {
   return (R >> 4) * (size_t)(16 * kd) + ((size_t)(e / kc) * 16 + (R & 15)) * kc + (e % kc);
@@ -78,7 +83,7 @@ __global__ __launch_bounds__(256) void spin_index_minmax_pages_kernel(
     const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int dir_stride, int leaf_entries, int max_tiles,
     uint16_t *__restrict__ summ, int32_t *status, spin_var var) {
-  __shared__ uint4 s_tile[4][SPIN_KTILE_U4];
+  __shared__ uint4 s_tile[4][SPIN_KTILE_U4 + SPIN_KTILE_U4 / 16];   // padded: see spin_lds_pad()
   __shared__ uint4 s_out[512];
   const int row = blockIdx.x / max_tiles, tile = blockIdx.x - row * max_tiles;
   const int b = row / Hkv, h = row - b * Hkv;
@@ -120,12 +125,12 @@ __global__ __launch_bounds__(256) void spin_index_minmax_pages_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] = spin_nt_load(kt + j * 64);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) lds[j * 64 + lane] = v[j];
+        for (int j = 0; j < 4; ++j) lds[spin_lds_pad(j * 64 + lane)] = v[j];
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // same wavefront writes and reads: program order
         const int nvalid = min(t1 - pg * 16, 16);                // tokens of this page inside the partition
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const uint4 u = lds[ch * 16 + 4 * tq + i];
+          const uint4 u = lds[spin_lds_pad(ch * 16 + 4 * tq + i)];
           if (4 * tq + i < nvalid) {
             const uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
@@ -235,7 +240,7 @@ __global__ __launch_bounds__(256) void spin_index_repmean_pages_kernel(
     const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int reps, int dir_stride, int leaf_entries,
     int max_tiles, uint16_t *__restrict__ summ, int32_t *status, spin_var var) {
-  __shared__ uint4 s_tile[4][SPIN_KTILE_U4];
+  __shared__ uint4 s_tile[4][SPIN_KTILE_U4 + SPIN_KTILE_U4 / 16];   // padded: see spin_lds_pad()
   const int row = blockIdx.x / max_tiles, tile = blockIdx.x - row * max_tiles;
   const int b = row / Hkv, h = row - b * Hkv;
   const int PP = part_offsets[b + 1] - part_offsets[b];
@@ -274,12 +279,12 @@ __global__ __launch_bounds__(256) void spin_index_repmean_pages_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] = spin_nt_load(kt + j * 64);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) lds[j * 64 + lane] = v[j];
+        for (int j = 0; j < 4; ++j) lds[spin_lds_pad(j * 64 + lane)] = v[j];
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // same wavefront writes and reads: program order
         const int nvalid = min(t1 - pg * 16, 16);                // the sub-range starts on a page boundary
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const uint4 u = lds[ch * 16 + 4 * tq + i];
+          const uint4 u = lds[spin_lds_pad(ch * 16 + 4 * tq + i)];
           if (4 * tq + i < nvalid) {
             const uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
