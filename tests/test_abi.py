@@ -85,3 +85,13 @@ def test_header_is_plain_c(tmp_path):
                           "-c", str(src), "-o", str(tmp_path / "use_spin.o")], capture_output=True, text=True)
     assert res.returncode == 0, res.stderr
 
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only and says so (no collective is involved in this path)."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
+
