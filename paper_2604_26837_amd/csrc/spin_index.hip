@@ -114,6 +114,14 @@ __global__ __launch_bounds__(256) void spin_index_minmax_pages_kernel(
   const int ch = lane >> 2, tq = lane & 3;      // after regrouping: chunk of 8 channels, tokens 4tq..4tq+3
   uint4 *lds = s_tile[wave];
   uint4 *o = (uint4 *)summ;
+  // uniform partitions: the wavefront's four partitions cover consecutive pages, whose slots are looked
+  // up once, one page per lane (two dependent loads for the whole wavefront instead of per page)
+  const int ppp = tp >> 4;
+  const int pgA = (tile * 16 + wave * 4) * ppp;
+  const bool pre = !var.count && 4 * ppp <= 64;
+  int32_t myslot = -1;
+  if (pre && lane < 4 * ppp && pgA + lane < ((N + 15) >> 4))
+    myslot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pgA + lane);
   for (int k = 0; k < 4; ++k) {
     const int r = wave * 4 + k;                  // partition inside the tile
     const int p = tile * 16 + r;
@@ -135,7 +143,8 @@ __global__ __launch_bounds__(256) void spin_index_minmax_pages_kernel(
         t1 = min(p * tp + tp, N);
       }
       for (int pg = pg0; pg <= (t1 - 1) >> 4; ++pg) {
-        const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
+        const int32_t slot = pre ? __builtin_amdgcn_readlane(myslot, pg - pgA)
+                                 : spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
         if (slot < 0 || (int64_t)slot >= pool_slots) {
           if (lane == 0) spin_raise(status, SPIN_ERR_NOT_RESIDENT);
           continue;
