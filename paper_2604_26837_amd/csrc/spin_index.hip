@@ -122,6 +122,20 @@ __global__ __launch_bounds__(256) void spin_index_minmax_pages_kernel(
   int32_t myslot = -1;
   if (pre && lane < 4 * ppp && pgA + lane < ((N + 15) >> 4))
     myslot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pgA + lane);
+  // ... and the page after the one being folded is already on its way (the wavefront's pages are consecutive)
+  const int pgEnd = pre ? min(pgA + 4 * ppp, (N + 15) >> 4) : 0;
+  uint4 nv[4];
+  bool nok = false;
+  auto fetch = [&](int pg) {
+    const int32_t slot = __builtin_amdgcn_readlane(myslot, pg - pgA);
+    nok = slot >= 0 && (int64_t)slot < pool_slots;
+    if (nok) {
+      const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) nv[j] = spin_nt_load(kt + j * 64);
+    }
+  };
+  if (pgA < pgEnd) fetch(pgA);
   for (int k = 0; k < 4; ++k) {
     const int r = wave * 4 + k;                  // partition inside the tile
     const int p = tile * 16 + r;
@@ -143,18 +157,31 @@ __global__ __launch_bounds__(256) void spin_index_minmax_pages_kernel(
         t1 = min(p * tp + tp, N);
       }
       for (int pg = pg0; pg <= (t1 - 1) >> 4; ++pg) {
-        const int32_t slot = pre ? __builtin_amdgcn_readlane(myslot, pg - pgA)
-                                 : spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
-        if (slot < 0 || (int64_t)slot >= pool_slots) {
-          if (lane == 0) spin_raise(status, SPIN_ERR_NOT_RESIDENT);
-          continue;
+        if (pre) {
+          const bool ok = nok;
+          if (ok) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) lds[spin_lds_pad(j * 64 + lane)] = nv[j];
+          }
+          nok = false;
+          if (pg + 1 < pgEnd) fetch(pg + 1);
+          if (!ok) {
+            if (lane == 0) spin_raise(status, SPIN_ERR_NOT_RESIDENT);
+            continue;
+          }
+        } else {
+          const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
+          if (slot < 0 || (int64_t)slot >= pool_slots) {
+            if (lane == 0) spin_raise(status, SPIN_ERR_NOT_RESIDENT);
+            continue;
+          }
+          const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
+          uint4 v[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = spin_nt_load(kt + j * 64);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) lds[spin_lds_pad(j * 64 + lane)] = v[j];
         }
-        const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
-        uint4 v[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = spin_nt_load(kt + j * 64);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) lds[spin_lds_pad(j * 64 + lane)] = v[j];
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // same wavefront writes and reads: program order
         const int nvalid = min(t1 - pg * 16, 16);                // tokens of this page inside the partition
         if (nvalid == 16) {                                      // a full page (wave-uniform): no per-token test
