@@ -203,7 +203,8 @@ int spin_pack_kv_pages(spin_ctx *ctx, int64_t n_pages, const void *src_k, const 
 
 /* Index: build the summaries of every partition of every row from the keys in
  * the pool, reached through the two-level table (every page must be resident).
- * MINMAX: elementwise min and max key over the partition's valid tokens.
+ * MINMAX: elementwise min and max key over the partition's valid tokens (keys must be finite; where a
+ *         channel holds both -0 and +0 inside one partition, which zero is stored is unspecified).
  * REPMAX: mean key of each of the R equal sub-ranges, rounded to bf16 (an empty
  *         sub-range of a ragged last partition repeats representative 0).
  * SKETCH: the key restricted to chan_idx[h][0..C) (DEVICE int32 [num_kv_heads][C]).
