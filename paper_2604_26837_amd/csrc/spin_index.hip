@@ -30,6 +30,16 @@ __device__ inline spin_i16x2 spin_dpp_i16x2(spin_i16x2 v) {
   return __builtin_bit_cast(spin_i16x2, __builtin_amdgcn_update_dpp(x, x, CTRL, 0xf, 0xf, false));
 }
 
+// a double from the lane CTRL names, as two 32-bit exchanges
+template <int CTRL>
+__device__ inline double spin_dpp_f64(double v) {
+  const unsigned long long u = (unsigned long long)__double_as_longlong(v);
+  const int lo = (int)(uint32_t)u, hi = (int)(uint32_t)(u >> 32);
+  const uint32_t rlo = (uint32_t)__builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, false);
+  const uint32_t rhi = (uint32_t)__builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, false);
+  return __longlong_as_double((long long)(((unsigned long long)rhi << 32) | rlo));
+}
+
 // element offset of (summary row R, element e)
 __device__ inline size_t summ_off(size_t R, int e, int kd, int kc) {
   return (R >> 4) * (size_t)(16 * kd) + ((size_t)(e / kc) * 16 + (R & 15)) * kc + (e % kc);
@@ -327,8 +337,31 @@ __global__ __launch_bounds__(256) void spin_index_repmean_pages_kernel(
   const int sub = tp / reps;
   uint4 *lds = s_tile[wave];
   uint4 *o = (uint4 *)summ;
+  // uniform partitions with no empty sub-range among the wavefront's four summary rows: their pages are
+  // consecutive, so the slots are looked up once (one page per lane) and the next page is requested
+  // while the current one is added up
+  const int ppr = sub >> 4;
+  const int sr0 = tile * 16 + wave * 4;
+  const int pgA = sr0 * ppr;
+  const bool pre = !var.count && 4 * ppr <= 64 && (int64_t)(sr0 + 3) * sub < N;
+  const int pgEnd = pre ? min(pgA + 4 * ppr, (N + 15) >> 4) : 0;
+  int32_t myslot = -1;
+  if (lane < 4 * ppr && pgA + lane < pgEnd)
+    myslot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pgA + lane);
+  uint4 nv[4];
+  bool nok = false;
+  auto fetch = [&](int pg) {
+    const int32_t slot = __builtin_amdgcn_readlane(myslot, pg - pgA);
+    nok = slot >= 0 && (int64_t)slot < pool_slots;
+    if (nok) {
+      const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) nv[j] = spin_nt_load(kt + j * 64);
+    }
+  };
+  if (pgA < pgEnd) fetch(pgA);
   for (int k = 0; k < 4; ++k) {
-    const int sr = tile * 16 + wave * 4 + k;     // summary row inside this KV row
+    const int sr = sr0 + k;                      // summary row inside this KV row
     const int p = sr / reps, rep = sr - p * reps;
     uint32_t outw[4] = {0, 0, 0, 0};
     if (p < P) {
@@ -341,17 +374,31 @@ __global__ __launch_bounds__(256) void spin_index_repmean_pages_kernel(
       }
       double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
       for (int pg = t0 >> 4; pg <= (t1 - 1) >> 4; ++pg) {
-        const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
-        if (slot < 0 || (int64_t)slot >= pool_slots) {
-          if (lane == 0) spin_raise(status, SPIN_ERR_NOT_RESIDENT);
-          continue;
+        if (pre) {
+          const bool ok = nok;
+          if (ok) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) lds[spin_lds_pad(j * 64 + lane)] = nv[j];
+          }
+          nok = false;
+          if (pg + 1 < pgEnd) fetch(pg + 1);
+          if (!ok) {
+            if (lane == 0) spin_raise(status, SPIN_ERR_NOT_RESIDENT);
+            continue;
+          }
+        } else {
+          const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pg);
+          if (slot < 0 || (int64_t)slot >= pool_slots) {
+            if (lane == 0) spin_raise(status, SPIN_ERR_NOT_RESIDENT);
+            continue;
+          }
+          const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
+          uint4 v[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = spin_nt_load(kt + j * 64);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) lds[spin_lds_pad(j * 64 + lane)] = v[j];
         }
-        const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
-        uint4 v[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = spin_nt_load(kt + j * 64);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) lds[spin_lds_pad(j * 64 + lane)] = v[j];
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // same wavefront writes and reads: program order
         const int nvalid = min(t1 - pg * 16, 16);                // the sub-range starts on a page boundary
 #pragma unroll
@@ -371,13 +418,22 @@ __global__ __launch_bounds__(256) void spin_index_repmean_pages_kernel(
       // add the four token quads (lanes 4ch .. 4ch+3); exact sums, so the order does not matter
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        acc[i] += __shfl_xor(acc[i], 1);
-        acc[i] += __shfl_xor(acc[i], 2);
+        acc[i] += spin_dpp_f64<SPIN_DPP_XOR1>(acc[i]);
+        acc[i] += spin_dpp_f64<SPIN_DPP_XOR2>(acc[i]);
       }
-      const double cnt = (double)(t1 - t0);
+      // the mean: a token count that is a power of two (the usual case) divides exactly through its reciprocal
+      const int n = t1 - t0;
+      const double cnt = (double)n, inv = 1.0 / cnt;
+      if ((n & (n - 1)) == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] *= inv;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] /= cnt;
+      }
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        outw[i] = (uint32_t)spin_f64_to_bf16(acc[2 * i] / cnt) | ((uint32_t)spin_f64_to_bf16(acc[2 * i + 1] / cnt) << 16);
+        outw[i] = (uint32_t)spin_f64_to_bf16(acc[2 * i]) | ((uint32_t)spin_f64_to_bf16(acc[2 * i + 1]) << 16);
     }
     if (tq == 0) {
       const size_t R = base + sr;
