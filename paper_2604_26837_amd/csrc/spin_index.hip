@@ -443,39 +443,75 @@ __global__ __launch_bounds__(256) void spin_index_repmean_pages_kernel(
   }
 }
 
-// One thread per (token, channel quad): gathers the sketched channels of a key.
+// SKETCH (token partitions): the 16 sketched channels of every key.  One workgroup per 16 pages, four
+// per wavefront: a page's K tile is fetched whole with four contiguous 1 KiB loads (picking 2-byte
+// elements straight from HBM moved the same cache lines at 4 TB/s), the next page being requested
+// while the current one is used; lane (channel quad, token) then picks its four elements from the
+// wavefront's LDS copy, and the page's 512-byte summary tile leaves as one contiguous store.
 __global__ __launch_bounds__(256) void spin_index_sketch_kernel(
-    const uint16_t *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
+    const uint4 *__restrict__ pool, int64_t pool_slots, const int32_t *__restrict__ dir,
     const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ chan, int Hkv, int dir_stride,
-    int leaf_entries, int max_blocks, uint16_t *__restrict__ summ, int32_t *status, int k_token_major) {
-  const int row = blockIdx.x / max_blocks, blk = blockIdx.x - row * max_blocks;
+    int leaf_entries, int max_tiles, uint16_t *__restrict__ summ, int32_t *status, int k_token_major) {
+  __shared__ uint4 s_tile[4][SPIN_KTILE_U4 + SPIN_KTILE_U4 / 16];   // padded: see spin_lds_pad()
+  const int row = blockIdx.x / max_tiles, tile = blockIdx.x - row * max_tiles;
   const int b = row / Hkv, h = row - b * Hkv;
-  const int PP = part_offsets[b + 1] - part_offsets[b];
-  const int t = blk * 64 + (threadIdx.x & 63);   // token; 64 tokens x 4 channel quads per workgroup
-  const int cq = threadIdx.x >> 6;
-  if (t >= PP) return;
+  const int PP = part_offsets[b + 1] - part_offsets[b];   // tokens of the padded row, a multiple of 16
+  const int pages_pad = PP >> 4;
+  if (tile * 16 >= pages_pad) return;
   const int N = seq_lens[b];
+  const int pages = min((N + 15) >> 4, pages_pad);
   const size_t base = (size_t)Hkv * part_offsets[b] + (size_t)h * PP;
-  uint16_t e[4] = {0, 0, 0, 0};
-  if (t < N) {
-    const int32_t slot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, t >> 4);
-    if (slot < 0 || (int64_t)slot >= pool_slots) {
-      spin_raise(status, SPIN_ERR_NOT_RESIDENT);
-    } else {
-      const uint16_t *kt = pool + (size_t)slot * (SPIN_SLOT_U4 * 8);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int cq = lane >> 4, r = lane & 15;       // channel quad, token of the page
+  const uint16_t *lds = (const uint16_t *)s_tile[wave];
+  uint4 *ldsw = s_tile[wave];
+  int at[4];                                     // where the lane's four elements sit in the LDS copy
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int d = chan[h * 16 + cq * 4 + i];
-        e[i] = kt[(spin_k_unit(k_token_major, t & 15, d >> 3) << 3) + (d & 7)];
+  for (int i = 0; i < 4; ++i) {
+    const int d = chan[h * 16 + cq * 4 + i] & (SPIN_HEAD_DIM - 1);   // a channel outside the head reads inside it
+    at[i] = spin_lds_pad(spin_k_unit(k_token_major, r, d >> 3)) * 8 + (d & 7);
+  }
+  const int pgA = tile * 16 + wave * 4;
+  const int pgEnd = min(pgA + 4, pages);
+  int32_t myslot = -1;
+  if (lane < 4 && pgA + lane < pgEnd)
+    myslot = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, pgA + lane);
+  uint4 nv[4];
+  bool nok = false;
+  auto fetch = [&](int pg) {
+    const int32_t slot = __builtin_amdgcn_readlane(myslot, pg - pgA);
+    nok = slot >= 0 && (int64_t)slot < pool_slots;
+    if (nok) {
+      const uint4 *kt = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) nv[j] = spin_nt_load(kt + j * 64);
+    }
+  };
+  if (pgA < pgEnd) fetch(pgA);
+  uint2 *o = (uint2 *)summ;
+  for (int pg = pgA; pg < min(pgA + 4, pages_pad); ++pg) {
+    uint2 out = make_uint2(0u, 0u);              // tokens past the context and pages that are not resident: zeros
+    if (pg < pgEnd) {
+      const bool ok = nok;
+      if (ok) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ldsw[spin_lds_pad(j * 64 + lane)] = nv[j];
+      }
+      nok = false;
+      if (pg + 1 < pgEnd) fetch(pg + 1);
+      if (!ok) {
+        if (lane == 0) spin_raise(status, SPIN_ERR_NOT_RESIDENT);
+      } else {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // same wavefront writes and reads: program order
+        if (pg * 16 + r < N)
+          out = make_uint2(lds[at[0]] | ((uint32_t)lds[at[1]] << 16), lds[at[2]] | ((uint32_t)lds[at[3]] << 16));
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       }
     }
+    // the page's summary tile [4 channel quads][16 tokens][4 elements]: 64 x 8 bytes, lane by lane
+    o[((base >> 4) + (size_t)pg) * 64 + lane] = out;
   }
-  const size_t R = base + t;
-  // tile [4 chunks][16 rows][4 elements]
-  uint2 *o = (uint2 *)summ;
-  o[(R >> 4) * 64 + (size_t)cq * 16 + (R & 15)] =
-      make_uint2(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16));
 }
 
 extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv_pool, int64_t pool_slots,
@@ -523,10 +559,10 @@ extern "C" int spin_build_summaries(spin_ctx *ctx, int32_t batch, const void *kv
   } else {
     if (!chan_idx) return SPIN_ERR_INVALID;
     if (c.partition_tokens != 1) return SPIN_ERR_UNSUPPORTED;
-    const int max_blocks = (max_pp + 63) / 64;
-    spin_launch(ctx, SPIN_K_INDEX, spin_index_sketch_kernel, dim3((unsigned)rows * max_blocks), dim3(256), 0, st,
-                       (const uint16_t *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
-                       chan_idx, c.num_kv_heads, ctx->dir_stride, c.leaf_entries, max_blocks,
+    const int max_tiles = (max_pp / 16 + 15) / 16;   // 16 pages per workgroup
+    spin_launch(ctx, SPIN_K_INDEX, spin_index_sketch_kernel, dim3((unsigned)rows * max_tiles), dim3(256), 0, st,
+                       (const uint4 *)kv_pool, pool_slots, dir, leaf_pool, leaf_chunks, part_offsets, seq_lens,
+                       chan_idx, c.num_kv_heads, ctx->dir_stride, c.leaf_entries, max_tiles,
                        (uint16_t *)summaries, status, ctx->k_token_major);
   }
   return spin_launch_status();
