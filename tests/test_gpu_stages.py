@@ -444,6 +444,54 @@ def test_select_random_rows(seed):
     _check_select(w, [scores(w.partitions(b)) for b in range(w.batch)])
 
 
+@pytest.mark.parametrize("name", ["ragged_pages", "minmax_blocks", "mean_pages", "mean_blocks", "two_reps_blocks",
+                                  "mean_quarter_pages", "tokens", "g8_blocks"])
+def test_index_with_pages_that_are_not_resident(name):
+    """Index over a row with holes (no slot, a slot number outside the pool): the fault is reported and every
+    summary row that does not touch a missing page is still exactly the oracle's (the kernels look the
+    slots of several pages up at once and keep the next page in flight: a hole must not shift that)."""
+    from gpu_harness import DeviceWorkload, build_summaries, unpack_summary_rows
+    w = _workloads()[name]
+    data = synth.generate(w, spare_slots=3)
+    dw = DeviceWorkload(data)
+    chan = synth.sketch_channels(data) if w.score_kind == synth.SCORE_SKETCH else None
+    rng = np.random.default_rng(5)
+    dirs = dw.dir.cpu().numpy()
+    holes = {}
+    r = 0
+    for b in range(w.batch):
+        pages = (w.seq_lens[b] + 15) // 16
+        for h in range(w.num_kv_heads):
+            pick = sorted(set([0, pages - 1, pages // 2] + rng.integers(0, pages, size=3).tolist()))
+            if (b + h) % 2:
+                pick = pick[1:-1]                                     # rows whose first and last page stay
+            holes[(b, h)] = pick
+            for i, pg in enumerate(pick):
+                chunk = int(dirs[r, pg // w.leaf_entries])
+                dw.leaf_pool[chunk, pg % w.leaf_entries] = -1 if i % 2 == 0 else dw.pool_slots + 7 * i
+            r += 1
+    build_summaries(dw, chan)
+    torch.cuda.synchronize()
+    assert dw.spin.poll_status(dw.ws) == -6
+    kd, kc = _kd_kc(w)
+    summ_rows = unpack_summary_rows(dw.summaries, kd, kc)
+    rpp = w.reps_per_partition if w.score_kind == synth.SCORE_REPMAX else 1
+    tp = w.partition_tokens
+    compared = 0
+    for b in range(w.batch):
+        for h in range(w.num_kv_heads):
+            _, _, _, _, ref_rows, _, _ = _oracle_row_inputs(dw, b, h, chan)
+            base = dw.row_base(b, h)
+            got_rows = bf16.decode(summ_rows[base * rpp: base * rpp + ref_rows.shape[0]])
+            touched = np.zeros(ref_rows.shape[0], dtype=bool)
+            for pg in holes[(b, h)]:
+                for p in range(16 * pg // tp, min((16 * pg + 15) // tp + 1, ref_rows.shape[0] // rpp)):
+                    touched[p * rpp:(p + 1) * rpp] = True
+            compared += int((~touched).sum())
+            assert np.array_equal(got_rows[~touched], ref_rows[~touched]), f"{name}: rows away from the holes differ ({b}, {h})"
+    assert compared > 0
+
+
 def test_resolve_reports_missing_leaf_and_missing_slot():
     from gpu_harness import DEV, DeviceWorkload, build_summaries, run_step
     w = synth.config0().with_(seq_lens=(4096,), name="holes")
