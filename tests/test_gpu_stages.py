@@ -53,6 +53,17 @@ def _workloads():
         "mean_quarter_pages": c0.with_(seq_lens=(777,), partition_tokens=4, score_kind=synth.SCORE_REPMAX,
                                        reps_per_partition=1, topk=40, sink_pages=1, recent_pages=1,
                                        block_mean_std=0.5, name="mean_quarter_pages"),
+        # partitions of 32 pages: more pages per wavefront than the Index kernels look up at once
+        "minmax_big_blocks": c0.with_(seq_lens=(512 * 9 + 300, 512 * 2 + 5), partition_tokens=512, topk=3,
+                                      topk_includes_forced=False, sink_pages=1, recent_pages=2, name="mm_big_blocks"),
+        "mean_big_blocks": c0.with_(seq_lens=(512 * 7 + 130,), partition_tokens=512, score_kind=synth.SCORE_REPMAX,
+                                    reps_per_partition=1, topk=2, topk_includes_forced=False, sink_pages=1,
+                                    recent_pages=2, block_mean_std=0.5, name="mean_big_blocks"),
+        # a ragged last partition whose trailing representatives are empty (they repeat representative 0)
+        "four_reps_ragged": c0.with_(seq_lens=(128 * 6 + 20, 128 * 3 + 70), partition_tokens=128,
+                                     score_kind=synth.SCORE_REPMAX, reps_per_partition=4, topk=3,
+                                     topk_includes_forced=False, sink_pages=1, recent_pages=2, block_mean_std=0.5,
+                                     name="four_reps_ragged"),
         # group sizes other than 4: one head, a group that is no power of two, more than one lane quarter
         "g1_pages": c0.with_(seq_lens=(900, 333), num_q_heads=2, num_kv_heads=2, topk=12, sink_pages=1,
                              recent_pages=1, name="g1_pages"),
