@@ -389,9 +389,9 @@ def main():
                                                decode_splits=args.decode_splits, decode_waves=args.decode_waves,
                                                decode_depth=args.decode_depth, score_waves=args.score_waves,
                                                score_tiles_per_wg=args.score_tiles)
-    # stages 2+3 share a launch only for rows the one-launch kernel takes (at most 16384 partitions)
+    # rows of at most 16384 partitions: stage 2 is one launch, which also resolves
     one_launch_23 = max(w.partitions(b) for b in range(w.batch)) <= 16384
-    # longer rows: stages 1+2 share a call instead (stage 1 takes stage 2's histogram along)
+    # longer rows: stages 1-3 in one call (stage 1 takes stage 2's histogram along, stage 2's last launch resolves)
     fused_12 = not one_launch_23 and not args.four_calls
     sp = layer.spin
 
@@ -409,7 +409,7 @@ def main():
     # the step as timed: score, select+resolve in one launch, attention (three
     # launches, same results bit for bit); the four separate calls are timed beside it
     def run_12(i):
-        layer.step12(qsets[i % len(qsets)], summ_copies[i % len(summ_copies)])
+        layer.step123(qsets[i % len(qsets)], summ_copies[i % len(summ_copies)])
 
     run = run_four if args.four_calls else (run_12 if fused_12 else run_three)
 
@@ -470,7 +470,7 @@ def main():
         for name in ("score", "select_hist", "select", "resolve", "decode"):
             n, mean, mn = sp.profile_read(name)
             if n:
-                label = "select+resolve" if (name == "select" and not args.four_calls and one_launch_23) else name
+                label = "select+resolve" if (name == "select" and not args.four_calls) else name
                 kernels[label] = dict(launches=n, mean_us=round(mean, 3), min_us=round(mn, 3))
         sp.profile_enable(0)
         assert layer.status() == 0, "device fault during the event-bracketed pass"
@@ -553,7 +553,7 @@ def main():
         "attended_kv_gbps": roofline["achieved"] if roofline else None,
         "attended_kv_pct_peak": round(100 * roofline["frac"], 2) if roofline else None,
         "step_launches": "four stage calls" if args.four_calls else (
-            "score+select in one call (stage 1 counts stage 2's histogram), resolve, attention (4 launches)" if fused_12
+            "stages 1-3 in one call (stage 1 counts stage 2's histogram, stage 2's launch resolves), attention (3 launches)" if fused_12
             else "score, select+resolve, attention (3 launches)"),
         ("us_per_layer_fused_calls" if args.four_calls else "us_per_layer_four_calls"): round(us_per_step_other, 2) if us_per_step_other else None,
         "us_per_layer_with_kernel_events": round(us_per_step_events, 2) if us_per_step_events else None,

@@ -15,6 +15,7 @@
  *   spin_offload_pages                                         Offload's copy, slot -> host page (Table 1)
  *   spin_select_resolve                                        stages 2+3 in one launch, same results
  *   spin_score_select_topk                                     stages 1+2 in one call, same results
+ *   spin_score_select_resolve                                  stages 1-3 in one call, same results
  *   spin_pin_partitions                                        always-attended outlier partitions (Section 4.2)
  *   spin_set_partition_tables                                  variable-length partitions (Section 5.2)
  *   spin_set_host_page_table                                   CPU page table (Section 5.2)
@@ -326,14 +327,25 @@ int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, const int32_t
 int spin_set_step(spin_ctx *ctx, void *workspace, int32_t step, void *stream);
 int spin_advance_step(spin_ctx *ctx, void *workspace, void *stream);
 
-/* Stages 2 and 3 in ONE launch (all-resident mode, rows of at most 16384
- * partitions; otherwise SPIN_ERR_UNSUPPORTED and the two calls above apply).
+/* Stages 2 and 3 together (all-resident mode): ONE launch for rows of at most 16384
+ * partitions; for uniform partitions, rows of up to 131072 partitions take stage 2's
+ * histogram launch first and the launch that finishes stage 2 resolves.  Anything
+ * else is SPIN_ERR_UNSUPPORTED before a kernel is issued, and the two calls above apply.
  * Arguments and results are exactly those of spin_select_topk followed by
  * spin_resolve_slots, bit for bit: the workgroup that selected a row resolves it. */
 int spin_select_resolve(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
                         const int32_t *seq_lens, int32_t *sel, int32_t *nsel, const int32_t *dir,
                         const int32_t *leaf_pool, int64_t leaf_chunks, int32_t *slots, int32_t *page_ids,
                         uint16_t *valid_mask, int32_t *npages, void *workspace, void *stream);
+
+/* Stages 1, 2 and 3 in two launches: spin_score_partitions (taking stage 2's first
+ * histogram along where spin_score_select_topk would) followed by spin_select_resolve.
+ * Arguments, results and refusals are those of the stage calls, bit for bit. */
+int spin_score_select_resolve(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries,
+                              const int32_t *chan_idx, const int32_t *part_offsets, const int32_t *seq_lens,
+                              float *scores, int32_t *sel, int32_t *nsel, const int32_t *dir,
+                              const int32_t *leaf_pool, int64_t leaf_chunks, int32_t *slots, int32_t *page_ids,
+                              uint16_t *valid_mask, int32_t *npages, void *workspace, void *stream);
 
 /* Buffer elasticity, mechanism only (Section 5.3: buffer pages are reclaimed from
  * the tail of a request's GPU page table).  Sets the slot count of every row to

@@ -23,7 +23,7 @@ EXPORTS = [
     "spin_workspace_init", "spin_poll_status", "spin_profile_enable", "spin_profile_read", "spin_pack_kv_pages", "spin_build_summaries",
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
     "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv", "spin_reclaim_tail", "spin_alloc_leaves", "spin_free_leaves",
-    "spin_set_partition_tables", "spin_probe_stream_read", "spin_offload_pages", "spin_score_select_topk", "spin_pin_partitions",
+    "spin_set_partition_tables", "spin_probe_stream_read", "spin_offload_pages", "spin_score_select_topk", "spin_score_select_resolve", "spin_pin_partitions",
     "spin_set_host_page_table", "spin_set_step", "spin_advance_step",
 ]
 
@@ -74,6 +74,7 @@ def load_library() -> C.CDLL:
     lib.spin_score_partitions.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_select_topk.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_score_select_topk.argtypes = [vp, i32] + [vp] * 10
+    lib.spin_score_select_resolve.argtypes = [vp, i32] + [vp] * 10 + [i64] + [vp] * 6
     lib.spin_pin_partitions.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp]
     lib.spin_set_host_page_table.argtypes = [vp, vp, i64, i64]
     lib.spin_set_step.argtypes = [vp, vp, i32, vp]
@@ -314,6 +315,17 @@ class Spin:
             _ptr(slots, torch.int32, "slots"), _ptr(page_ids, torch.int32, "page_ids"),
             _ptr(valid_mask, torch.int16, "valid_mask"), _ptr(npages, torch.int32, "npages"), _ptr(ws), _stream()),
             "spin_select_resolve")
+
+    def score_select_resolve(self, batch, q, summaries, chan_idx, part_offsets, seq_lens, scores, sel, nsel, dir_,
+                             leaf_pool, slots, page_ids, valid_mask, npages, ws):
+        self._check(self.lib.spin_score_select_resolve(
+            self.h, batch, _ptr(q, torch.bfloat16, "q"), _ptr(summaries), _ptr(chan_idx, torch.int32, "chan_idx"),
+            _ptr(part_offsets, torch.int32, "part_offsets"), _ptr(seq_lens, torch.int32, "seq_lens"),
+            _ptr(scores, torch.float32, "scores"), _ptr(sel, torch.int32, "sel"), _ptr(nsel, torch.int32, "nsel"),
+            _ptr(dir_, torch.int32, "dir"), _ptr(leaf_pool, torch.int32, "leaf_pool"), leaf_pool.shape[0],
+            _ptr(slots, torch.int32, "slots"), _ptr(page_ids, torch.int32, "page_ids"),
+            _ptr(valid_mask, torch.int16, "valid_mask"), _ptr(npages, torch.int32, "npages"), _ptr(ws), _stream()),
+            "spin_score_select_resolve")
 
     def copy_misses_host(self, batch, host_kv, host_row_base, nmiss, miss_pages, miss_slots, kv_pool,
                          copy_stream) -> int:

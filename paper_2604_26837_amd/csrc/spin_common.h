@@ -80,9 +80,19 @@ static inline int spin_launch_status() {
 int spin_score_impl(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries, const int32_t *chan_idx,
                     const int32_t *part_offsets, const int32_t *seq_lens, float *scores, void *workspace,
                     void *stream, int32_t *hist);
+// `res` != NULL (all-resident mode, rows of 16385 - 131072 partitions only): the launch that finishes
+// stage 2 also runs stage 3 for its row and stores the results there; SPIN_ERR_UNSUPPORTED elsewhere.
+struct spin_resolve_args {
+  const int32_t *dir;
+  const int32_t *leaf_pool;
+  int64_t leaf_chunks;
+  int32_t *slots, *page_ids;
+  uint16_t *valid_mask;
+  int32_t *npages;
+};
 int spin_select_impl(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
                      const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace, void *stream,
-                     bool hist_ready);
+                     bool hist_ready, const spin_resolve_args *res);
 
 #ifdef __HIPCC__
 // Launch `kernel` on `st`; when timing is enabled the launch carries a start

@@ -9,6 +9,7 @@
 // every candidate with key > T and the lowest-index candidates with key == T
 // that are still needed.  Because emission is in index order the output is
 // ascending and ties go to the lower id without any sort.
+#include "spin_resolve_dev.h"
 #include "spin_select_dev.h"
 
 #define SEL_BLOCK 512
@@ -232,11 +233,13 @@ __device__ __attribute__((noinline)) void select_big_fallback(
   }
 }
 
+// RESOLVE: the workgroup goes on to stage 3 for its row (same device function as the stage call).
+template <bool RESOLVE>
 __global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
     const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
     const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
-    int recent_pages, int sel_stride, int32_t *__restrict__ sel, int32_t *__restrict__ nsel, int32_t *hist,
-    int words_max) {
+    int recent_pages, int sel_stride, int32_t *sel, int32_t *__restrict__ nsel, int32_t *hist,
+    int words_max, spin_resolve_args ra, int page_stride, int dir_stride, int leaf_entries, int32_t *status) {
   extern __shared__ uint32_t s_dyn[];
   uint32_t *s_main = s_dyn;                              // [words_max] bit p: partition p is selected
   uint32_t *s_eq = s_dyn + words_max;                    // [words_max] bit p: candidate p has the threshold key
@@ -286,6 +289,12 @@ __global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
     // heavy ties in the threshold bin (or a histogram that does not cover the row): multi-pass algorithms
     select_big_fallback(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced, sink_pages, recent_pages,
                         sel_stride, sel, nsel, row, P);
+    if (RESOLVE) {
+      __syncthreads();   // the selection was written by this workgroup: visible to all its threads from here
+      resolve_row<BIG_BLOCK>(row, pl.take, sel, seq_lens, ra.dir, ra.leaf_pool, ra.leaf_chunks, Hkv, tp, sink_pages,
+                             recent_pages, sel_stride, page_stride, dir_stride, leaf_entries, ra.slots, ra.page_ids,
+                             ra.valid_mask, ra.npages, status, spin_var{});
+    }
     return;
   }
 
@@ -448,16 +457,24 @@ __global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
   }
   for (int i = pl.take + tid; i < sel_stride; i += BIG_BLOCK) rsel[i] = -1;
   if (tid == 0) nsel[row] = pl.take;
+  if (RESOLVE) {
+    __syncthreads();
+    resolve_row<BIG_BLOCK>(row, pl.take, sel, seq_lens, ra.dir, ra.leaf_pool, ra.leaf_chunks, Hkv, tp, sink_pages,
+                           recent_pages, sel_stride, page_stride, dir_stride, leaf_entries, ra.slots, ra.page_ids,
+                           ra.valid_mask, ra.npages, status, spin_var{});
+  }
 }
 
 int spin_select_impl(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
                      const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace, void *stream,
-                     bool hist_ready) {
+                     bool hist_ready, const spin_resolve_args *res) {
   if (!ctx || batch < 0 || batch > ctx->cfg.max_batch) return SPIN_ERR_INVALID;
   if (batch == 0) return SPIN_OK;
   if (!scores || !part_offsets || !seq_lens || !sel || !nsel) return SPIN_ERR_INVALID;
   const spin_config &c = ctx->cfg;
   const int rows = batch * c.num_kv_heads;
+  // stage 3 in the same launch exists for the long-row path below only
+  if (res && !(ctx->max_parts > 16384 && ctx->ws_hist_off && workspace && rows <= 65535)) return SPIN_ERR_UNSUPPORTED;
 #define SPIN_SELECT_ARGS                                                                                      \
   0, (hipStream_t)stream, scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk,         \
       c.topk_includes_forced, c.sink_pages, c.recent_pages, ctx->sel_stride, sel, nsel
@@ -478,9 +495,18 @@ int spin_select_impl(spin_ctx *ctx, int32_t batch, const float *scores, const in
                   dim3((unsigned)((ctx->max_parts + BIG_CHUNK - 1) / BIG_CHUNK), (unsigned)rows), dim3(256), 0,
                   (hipStream_t)stream, scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk,
                   c.topk_includes_forced, c.sink_pages, c.recent_pages, ctx->sel_stride, hist);
-    spin_launch(ctx, SPIN_K_SELECT, spin_select_big_kernel, dim3((unsigned)rows), dim3(BIG_BLOCK), lds, (hipStream_t)stream,
-                scores, part_offsets, seq_lens, c.num_kv_heads, c.partition_tokens, c.topk, c.topk_includes_forced,
-                c.sink_pages, c.recent_pages, ctx->sel_stride, sel, nsel, hist, words_max);
+#define SPIN_BIG_ARGS                                                                                         \
+  dim3((unsigned)rows), dim3(BIG_BLOCK), lds, (hipStream_t)stream, scores, part_offsets, seq_lens, c.num_kv_heads, \
+      c.partition_tokens, c.topk, c.topk_includes_forced, c.sink_pages, c.recent_pages, ctx->sel_stride, sel, nsel,  \
+      hist, words_max
+    if (res)
+      spin_launch(ctx, SPIN_K_SELECT, spin_select_big_kernel<true>, SPIN_BIG_ARGS, *res, ctx->page_stride,
+                  ctx->dir_stride, c.leaf_entries, (int32_t *)workspace);
+    else
+      spin_launch(ctx, SPIN_K_SELECT, spin_select_big_kernel<false>, SPIN_BIG_ARGS, spin_resolve_args{}, 0, 0, 0,
+                  (int32_t *)nullptr);
+#undef SPIN_BIG_ARGS
+    return spin_launch_status();
   } else if (ctx->max_parts <= 65536)
     spin_launch(ctx, SPIN_K_SELECT, spin_select_reg_kernel<1024, 64>, dim3((unsigned)rows), dim3(1024),
                 SPIN_SELECT_ARGS, ctx->var);
@@ -495,7 +521,7 @@ int spin_select_impl(spin_ctx *ctx, int32_t batch, const float *scores, const in
 extern "C" int spin_select_topk(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
                                 const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace,
                                 void *stream) {
-  return spin_select_impl(ctx, batch, scores, part_offsets, seq_lens, sel, nsel, workspace, stream, false);
+  return spin_select_impl(ctx, batch, scores, part_offsets, seq_lens, sel, nsel, workspace, stream, false, nullptr);
 }
 
 // Stages 1 and 2 in one call.  Where stage 2 takes two launches and stage 1 can count the leading
@@ -515,5 +541,5 @@ extern "C" int spin_score_select_topk(spin_ctx *ctx, int32_t batch, const void *
   const int st = spin_score_impl(ctx, batch, q, summaries, chan_idx, part_offsets, seq_lens, scores, workspace, stream,
                                  hist);
   if (st != SPIN_OK) return st;
-  return spin_select_impl(ctx, batch, scores, part_offsets, seq_lens, sel, nsel, workspace, stream, fuse);
+  return spin_select_impl(ctx, batch, scores, part_offsets, seq_lens, sel, nsel, workspace, stream, fuse, nullptr);
 }

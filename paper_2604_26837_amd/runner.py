@@ -119,6 +119,17 @@ class LayerState:
         sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
                          self.ws)
 
+    def step123(self, q: torch.Tensor, summaries: Optional[torch.Tensor] = None):
+        """The step in three launches for rows of any supported length: stages 1-3 in one call
+        (two launches), then attention (same results as :meth:`step`)."""
+        sp, w = self.spin, self.w
+        summ = self.summaries if summaries is None else summaries
+        sp.score_select_resolve(w.batch, q, summ, self.chan, self.part_offsets, self.seq_lens, self.scores, self.sel,
+                                self.nsel, self.dir, self.leaf_pool, self.slots, self.page_ids, self.valid_mask,
+                                self.npages, self.ws)
+        sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
+                         self.ws)
+
     def row_base(self, b: int, h: int) -> int:
         return tables.row_base(self.part_offsets_np, b, h, self.w.num_kv_heads)
 

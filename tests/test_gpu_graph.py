@@ -26,6 +26,10 @@ def _workloads():
         "long_token_rows_stage12_call": (c0.with_(seq_lens=(20000, 17001), num_q_heads=8, num_kv_heads=2,
                                                   partition_tokens=1, score_kind=synth.SCORE_SKETCH, topk=300,
                                                   sink_pages=1, recent_pages=1, name="graph_tokens12"), "step12"),
+        # and with stages 1-3 in one call (the launch that finishes stage 2 resolves)
+        "long_token_rows_stage123_call": (c0.with_(seq_lens=(20000, 17001), num_q_heads=8, num_kv_heads=2,
+                                                   partition_tokens=1, score_kind=synth.SCORE_SKETCH, topk=300,
+                                                   sink_pages=1, recent_pages=1, name="graph_tokens123"), "step123"),
     }
 
 

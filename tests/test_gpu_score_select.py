@@ -78,3 +78,81 @@ def test_combined_call_equals_the_two_stage_calls(name):
                                        w.partition_tokens, w.topk, w.topk_includes_forced, w.sink_pages,
                                        w.recent_pages)
             assert sel[r, :nsel[r]].tolist() == list(want), (b, h)
+
+
+def _heavy_ties(layer, w):
+    """Scores that send a long row down the multi-pass fallback: a handful of distinct values."""
+    rng = np.random.default_rng(11)
+    vals = rng.choice(np.array([0.5, 0.5, 0.25, 1.0], dtype=np.float32), size=layer.scores.numel())
+    return torch.from_numpy(vals).to(DEV)
+
+
+@pytest.mark.parametrize("name", list(_workloads()))
+def test_stages_1_to_3_in_one_call_equal_the_stage_calls(name):
+    """spin_score_select_resolve (and spin_select_resolve on its own, also for long rows and for rows that take
+    stage 2's multi-pass fallback) against the separate stage calls: every output identical."""
+    w = _workloads()[name]
+    data = synth.generate(w)
+    natural = torch.from_numpy(data.pool_bits.view(np.int16).copy()).to(DEV).view(torch.bfloat16)
+    layer = runner.LayerState.from_natural_pool(w, data.slot_of, natural)
+    if w.score_kind == synth.SCORE_SKETCH:
+        layer.set_channels(synth.sketch_channels(data))
+    layer.build_summaries()
+    sp = layer.spin
+    qs = [torch.from_numpy(synth.make_queries(w, 400 + i).view(np.int16)).to(DEV).view(torch.bfloat16) for i in range(3)]
+    names = ("scores", "sel", "nsel", "slots", "page_ids", "valid_mask", "npages")
+    twin = {n: torch.zeros_like(getattr(layer, n)) for n in names}
+
+    def stage_calls(q, scores=None):
+        if scores is None:
+            sp.score_partitions(w.batch, q, layer.summaries, layer.chan, layer.part_offsets, layer.seq_lens,
+                                layer.scores, layer.ws)
+            scores = layer.scores
+        sp.select_topk(w.batch, scores, layer.part_offsets, layer.seq_lens, layer.sel, layer.nsel, layer.ws)
+        sp.resolve_slots(w.batch, 0, layer.sel, layer.nsel, layer.seq_lens, layer.dir, layer.leaf_pool, layer.slots,
+                         layer.page_ids, layer.valid_mask, layer.npages, layer.ws)
+
+    def same(what, skip=()):
+        torch.cuda.synchronize()
+        assert layer.status() == 0
+        rows_n = layer.npages.cpu().numpy()
+        for n in names:
+            if n in skip:
+                continue
+            a, b = getattr(layer, n), twin[n]
+            if n in ("slots", "page_ids", "valid_mask"):       # entries past a row's page count are unspecified
+                keep = torch.arange(a.shape[1], device=DEV)[None, :] < layer.npages[:, None]
+                assert torch.equal(a[keep], b[keep]), f"{what}: {n}"
+            elif n == "scores":
+                s1, s2 = a.cpu().numpy().view(np.uint32), b.cpu().numpy().view(np.uint32)
+                for bb in range(w.batch):
+                    for h in range(w.num_kv_heads):
+                        base = tables.row_base(layer.part_offsets_np, bb, h, w.num_kv_heads)
+                        assert np.array_equal(s1[base:base + w.partitions(bb)], s2[base:base + w.partitions(bb)]), what
+            else:
+                assert torch.equal(a, b), f"{what}: {n}"
+        assert rows_n.sum() > 0
+
+    for rep in range(4):
+        q = qs[rep % 3]
+        stage_calls(q)
+        for t in twin.values():
+            t.fill_(-3)
+        sp.score_select_resolve(w.batch, q, layer.summaries, layer.chan, layer.part_offsets, layer.seq_lens,
+                                twin["scores"], twin["sel"], twin["nsel"], layer.dir, layer.leaf_pool, twin["slots"],
+                                twin["page_ids"], twin["valid_mask"], twin["npages"], layer.ws)
+        same(f"three stages, rep {rep}")
+        for n in names[1:]:
+            twin[n].fill_(-4)
+        sp.select_resolve(w.batch, layer.scores, layer.part_offsets, layer.seq_lens, twin["sel"], twin["nsel"],
+                          layer.dir, layer.leaf_pool, twin["slots"], twin["page_ids"], twin["valid_mask"],
+                          twin["npages"], layer.ws)
+        same(f"stages 2+3, rep {rep}", skip=("scores",))
+    # heavy ties: the long rows leave the one-walk path inside the launch
+    tied = _heavy_ties(layer, w)
+    stage_calls(None, scores=tied)
+    for n in names[1:]:
+        twin[n].fill_(-6)
+    sp.select_resolve(w.batch, tied, layer.part_offsets, layer.seq_lens, twin["sel"], twin["nsel"], layer.dir,
+                      layer.leaf_pool, twin["slots"], twin["page_ids"], twin["valid_mask"], twin["npages"], layer.ws)
+    same("heavy ties", skip=("scores",))

@@ -62,10 +62,15 @@ def test_headline_size_and_unsupported_shape():
     w = synth.config1()
     layer, _ = runner.build_device_layer(w)
     _compare(layer, layer.q0)
-    w2 = synth.config0().with_(seq_lens=(65536,), partition_tokens=1, score_kind=synth.SCORE_SKETCH, topk=16,
+    # refused before anything is launched (the pointers are never used): rows beyond 131072 partitions, budget mode
+    w2 = synth.config0().with_(seq_lens=(200000,), partition_tokens=1, score_kind=synth.SCORE_SKETCH, topk=16,
                                sink_pages=0, recent_pages=0, name="sk")
     sp = binding.Spin.for_workload(w2)
     assert sp.lib.spin_select_resolve(sp.h, 1, *([8] * 7), 1, *([8] * 6), 8, None) == -2
+    assert sp.lib.spin_score_select_resolve(sp.h, 1, *([8] * 10), 1, *([8] * 6), 8, None) == -2
+    sp3 = binding.Spin.for_workload(synth.config0(), lru_timestamps=64)
+    assert sp3.lib.spin_select_resolve(sp3.h, 1, *([8] * 7), 1, *([8] * 6), 8, None) == -2
+    assert sp3.lib.spin_score_select_resolve(sp3.h, 1, *([8] * 10), 1, *([8] * 6), 8, None) == -2
 
 
 @pytest.mark.parametrize("seed", range(24))
