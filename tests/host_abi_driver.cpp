@@ -50,6 +50,9 @@ static void poke(spin_ctx *x, const spin_config &c) {
     st = spin_select_resolve(x, batch, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 1, nullptr,
                              nullptr, nullptr, nullptr, ws, n);
     EXPECT(want_ok ? st == SPIN_OK : st < 0);
+    st = spin_score_select_resolve(x, batch, n, n, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                   nullptr, 1, nullptr, nullptr, nullptr, nullptr, ws, n);
+    EXPECT(want_ok ? st == SPIN_OK : st < 0);
     st = spin_sparse_decode(x, batch, n, n, 1, nullptr, nullptr, nullptr, n, nullptr, ws, n);
     EXPECT(want_ok ? st == SPIN_OK : st == SPIN_ERR_INVALID);
     st = spin_build_summaries(x, batch, n, 1, nullptr, nullptr, 1, nullptr, nullptr, nullptr, n, ws, n);
