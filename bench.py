@@ -403,15 +403,13 @@ def main():
     def run_four(i):
         layer.step(qsets[i % len(qsets)], summ_copies[i % len(summ_copies)])
 
-    def run_three(i):
-        layer.step3(qsets[i % len(qsets)], summ_copies[i % len(summ_copies)])
+    # the step as timed: three launches whatever the row length (score, select+resolve, attention; for long
+    # rows stages 1-3 are one call), same results bit for bit; the four separate calls are timed beside it
+    def run_fused(i):
+        layer.step_fused(qsets[i % len(qsets)], summ_copies[i % len(summ_copies)])
 
-    # the step as timed: score, select+resolve in one launch, attention (three
-    # launches, same results bit for bit); the four separate calls are timed beside it
-    def run_12(i):
-        layer.step123(qsets[i % len(qsets)], summ_copies[i % len(summ_copies)])
-
-    run = run_four if args.four_calls else (run_12 if fused_12 else run_three)
+    run_three = run_12 = run_fused
+    run = run_four if args.four_calls else run_fused
 
     for i in range(args.warmup):
         run(i)

@@ -130,6 +130,14 @@ class LayerState:
         sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
                          self.ws)
 
+    def step_fused(self, q: torch.Tensor, summaries: Optional[torch.Tensor] = None):
+        """The step in the fewest launches the row length allows (what ``bench.py`` times): stages 2+3 in one
+        launch for rows of at most 16384 partitions, stages 1-3 in one call for longer ones."""
+        if max(self.w.partitions(b) for b in range(self.w.batch)) <= 16384:
+            self.step3(q, summaries)
+        else:
+            self.step123(q, summaries)
+
     def row_base(self, b: int, h: int) -> int:
         return tables.row_base(self.part_offsets_np, b, h, self.w.num_kv_heads)
 
