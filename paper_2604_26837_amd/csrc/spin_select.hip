@@ -259,14 +259,11 @@ __global__ __launch_bounds__(BIG_BLOCK) void spin_select_big_kernel(
   const int W = (P + 31) >> 5;
 
   // bin of the k'-th candidate: thread t owns bins 4095-4t .. 4092-4t, highest first
-  int hv[4], local = 0;
-  int32_t *rh = hist + (size_t)row * BIG_BINS;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    hv[j] = rh[BIG_BINS - 1 - 4 * tid - j];
-    rh[BIG_BINS - 1 - 4 * tid - j] = 0;                  // ready for the next launch
-    local += hv[j];
-  }
+  int4 *rh4 = (int4 *)(hist + (size_t)row * BIG_BINS) + (BIG_BINS / 4 - 1 - tid);   // one 16-byte load and store
+  const int4 h4 = *rh4;
+  *rh4 = make_int4(0, 0, 0, 0);                            // ready for the next launch
+  const int hv[4] = {h4.w, h4.z, h4.y, h4.x};
+  const int local = h4.x + h4.y + h4.z + h4.w;
   if (tid == 0) { s_D = BIG_BINS; s_r = 0; s_cntD = 0; s_n = 0; }
   int total;
   int running = block_exclusive_scan<BIG_BLOCK>(local, s_wave, total);   // its barriers order the lines above
