@@ -49,6 +49,26 @@ MISTAKES = [
      "        for t in reversed(range(n)):\n            if cum + hist[t] >= net:", ["test_oracle_lru.py"]),
     ("lru", "for p, s in zip(misses, free_slots):", "for p, s in zip(misses, reversed(free_slots)):",
      ["test_oracle_lru.py"]),
+    ("lru", "    for s in range(keep, S):\n        p = cache.page[s]", "    for s in range(keep + 1, S):\n        p = cache.page[s]",
+     ["test_oracle_lru.py"]),
+    ("lru", "far = max(victims, key=lambda r: (resident[r], r))", "far = min(victims, key=lambda r: (resident[r], r))",
+     ["test_oracle_lru.py"]),
+    ("lru", "if best is None or cache.ts[base + w] < best:", "if best is None or cache.ts[base + w] > best:",
+     ["test_oracle_lru_setassoc.py"]),
+    ("lru", "            if any(cache.page[base + w] not in selected for w in range(ways)):\n                break",
+     "            if True:\n                break", ["test_oracle_lru_setassoc.py"]),
+    ("lru", "st = mix32(row, p) % sets", "st = p % sets", ["test_oracle_lru_setassoc.py"]),
+    # variable-length partitions, pinned partitions
+    ("varpart", "n = min(max(tokens[p] - page_tokens * k, 0), page_tokens)", "n = page_tokens", ["test_oracle_varpart.py"]),
+    ("varpart", "if all(x in fp for x in partition_page_list(first_page, tokens, p, page_tokens))] if fp else []",
+     "if any(x in fp for x in partition_page_list(first_page, tokens, p, page_tokens))] if fp else []",
+     ["test_oracle_varpart.py"]),
+    ("varpart", "mins[p], maxs[p] = blk.min(axis=0), blk.max(axis=0)", "mins[p], maxs[p] = blk.max(axis=0), blk.min(axis=0)",
+     ["test_oracle_varpart.py"]),
+    ("select", "out[p] = math.inf", "out[p] = -math.inf", ["test_oracle_select.py"]),
+    # byte model
+    ("envelope", "return 2 * B * L * H * d * e * beta * N", "return B * L * H * d * e * beta * N", ["test_oracle_envelope.py"]),
+    ("envelope", "rho * topk_bytes / bw_pcie", "rho * score_bytes / bw_pcie", ["test_oracle_envelope.py"]),
     # stage 4
     ("attend", "logits = scale * (q @ K_S.T)", "logits = q @ K_S.T", ["test_oracle_attend.py"]),
     ("attend", "out = (w @ V_S) / l", "out = (w @ K_S) / l", ["test_oracle_attend.py"]),
@@ -72,12 +92,25 @@ def _run(files, spec):
 
 
 CASES = [m for m in MISTAKES if m[1] is not None]
+_results = {}
+
+
+def _result(case):
+    """The child runs of all cases, started together on first use (a few at a time)."""
+    if not _results:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=max(1, min(6, (os.cpu_count() or 2) - 1))) as pool:
+            futures = {i: pool.submit(_run, files, json.dumps([module, old, new]))
+                       for i, (module, old, new, files) in enumerate(CASES)}
+            for i, f in futures.items():
+                _results[i] = f.result()
+    return _results[case]
 
 
 @pytest.mark.parametrize("case", range(len(CASES)))
 def test_a_planted_mistake_fails_the_pins(case):
     module, old, new, files = CASES[case]
-    r = _run(files, json.dumps([module, old, new]))
+    r = _result(case)
     # 1 = tests failed (what is wanted); anything else (0 = the pins did not notice, 2+ = the mistake did not apply)
     assert r.returncode == 1, f"oracle/{module}.py with {old!r} -> {new!r}: exit {r.returncode}\n{r.stdout[-1500:]}\n{r.stderr[-500:]}"
     assert "planted mistake does not apply" not in r.stdout + r.stderr
