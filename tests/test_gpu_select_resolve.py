@@ -75,8 +75,8 @@ def test_headline_size_and_unsupported_shape():
 
 @pytest.mark.parametrize("seed", range(24))
 def test_random_workloads_both_combined_calls(seed):
-    """Random workloads (the draw of the stage tests): the stages 2+3 launch and the stages 1+2 call
-    must each reproduce the separate stage calls bit for bit."""
+    """Random workloads (the draw of the stage tests): the stages 2+3 launch, the stages 1+2 call and the
+    stages 1-3 call must each reproduce the separate stage calls bit for bit."""
     from test_gpu_stages import _random_workload
     w = _random_workload(200 + seed)
     print(f"seed {seed}: kind {w.score_kind} tp {w.partition_tokens} reps {w.reps_per_partition} group {w.group} "
@@ -93,8 +93,12 @@ def test_random_workloads_both_combined_calls(seed):
     for t in (layer.sel, layer.nsel, layer.slots, layer.page_ids, layer.valid_mask, layer.npages):
         t.fill_(-7)
     layer.out.fill_(3.0)
-    layer.step12(q)                          # stages 1+2 in one call
-    torch.cuda.synchronize()
-    assert layer.status() == 0
-    for a, b in zip(ref, _snapshot(layer)):
-        assert np.array_equal(a, b)
+    for step in (layer.step12, layer.step123):      # stages 1+2 in one call; stages 1-3 in one call
+        for t in (layer.sel, layer.nsel, layer.slots, layer.page_ids, layer.valid_mask, layer.npages):
+            t.fill_(-7)
+        layer.out.fill_(3.0)
+        step(q)
+        torch.cuda.synchronize()
+        assert layer.status() == 0
+        for a, b in zip(ref, _snapshot(layer)):
+            assert np.array_equal(a, b)
