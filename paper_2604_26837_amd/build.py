@@ -42,5 +42,22 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+EXAMPLE_SRC = os.path.join(PKG_DIR, "examples", "one_step.cpp")
+EXAMPLE_BIN = os.path.join(PKG_DIR, "examples", "one_step")
+
+
+def build_example() -> str:
+    """The C++ caller of the C ABI (no Python involved at run time), linked against libspin.so beside it."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", EXAMPLE_SRC, "-I", os.path.join(ROOT, "include"),
+           "-L", PKG_DIR, "-lspin", "-Wl,-rpath,$ORIGIN/..", "-o", EXAMPLE_BIN + ".tmp"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stderr)
+    os.replace(EXAMPLE_BIN + ".tmp", EXAMPLE_BIN)
+    return EXAMPLE_BIN
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_example())
