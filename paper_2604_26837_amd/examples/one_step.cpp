@@ -1,6 +1,7 @@
 // One decode step of one layer through the C ABI alone (no Python, no torch): the caller owns every
 // buffer (hipMalloc), lays the pages out with spin_pack_kv_pages, fills the two-level page table,
-// builds the summaries (Index), then runs score -> select -> resolve -> attention and checks the
+// builds the summaries (Index), then runs score -> select -> resolve -> attention (and the same step as
+// stages 1-3 in one call + attention, which must give the same bits) and checks the
 // output against dense attention restricted to the pages the library reports (Section 4.1: the
 // attention stage is exact on the selected set).  Exit status 0 and a line "one_step: ok" on success.
 //
@@ -135,6 +136,23 @@ int main() {
   HIP_OK(hipMemcpy(slots.data(), d_slots, slots.size() * 4, hipMemcpyDeviceToHost));
   HIP_OK(hipMemcpy(mask.data(), d_mask, mask.size() * 2, hipMemcpyDeviceToHost));
   HIP_OK(hipMemcpy(out.data(), d_out, out.size() * 2, hipMemcpyDeviceToHost));
+
+  // the same step in three launches (stages 1-3 in one call, then attention) must give the same bits
+  {
+    uint16_t *d_out2;
+    HIP_OK(hipMalloc((void **)&d_out2, (size_t)Hq * D * 2));
+    HIP_OK(hipMemset(d_np, 0xff, rows * 4));
+    SPIN_OK_OR_DIE(spin_score_select_resolve(ctx, 1, d_q, d_summ, nullptr, d_off, d_len, d_scores, d_sel, d_nsel, d_dir, d_leaf,
+                                             rows, d_slots, d_pids, d_mask, d_np, d_ws, st));
+    SPIN_OK_OR_DIE(spin_sparse_decode(ctx, 1, d_q, d_pool, pool_slots, d_slots, d_mask, d_np, d_out2, d_lse, d_ws, st));
+    SPIN_OK_OR_DIE(spin_poll_status(ctx, d_ws, st));
+    std::vector<uint16_t> out2(out.size());
+    HIP_OK(hipMemcpy(out2.data(), d_out2, out2.size() * 2, hipMemcpyDeviceToHost));
+    if (std::memcmp(out.data(), out2.data(), out.size() * 2) != 0) {
+      std::fprintf(stderr, "one_step: the three-launch step differs from the four stage calls\n");
+      return 1;
+    }
+  }
 
   // checks: 32 pages per row with the first and the last page among them, slots as in the table, and the
   // output equal to dense attention over exactly those tokens (double precision on the bf16 inputs)
