@@ -89,13 +89,15 @@ enum spin_status {
   SPIN_ERR_BUDGET = -5,       /* device: a row's slot budget cannot hold its selection */
   SPIN_ERR_NOT_RESIDENT = -6, /* device: a selected page has no leaf or no slot */
   SPIN_ERR_SLOT_RANGE = -7,   /* device: a slot id lies outside the pool */
-  SPIN_ERR_LEAF_POOL = -8     /* device: no free leaf chunk left in the segment pool */
+  SPIN_ERR_LEAF_POOL = -8,    /* device: no free leaf chunk left in the segment pool */
+  SPIN_ERR_STATIC_LIMIT = -9  /* spin_sparse_decode_static: the shape needs more than SPIN_STATIC_SCRATCH_BYTES */
 };
 
 enum spin_score_kind { SPIN_SCORE_MINMAX = 0, SPIN_SCORE_SKETCH = 1, SPIN_SCORE_REPMAX = 2 };
 
 #define SPIN_PART_ALIGN 16
 #define SPIN_SLOT_BYTES 8192
+#define SPIN_STATIC_SCRATCH_BYTES (2u << 20) /* device array behind spin_sparse_decode_static, per GPU */
 
 typedef struct spin_config {
   int32_t max_batch;
@@ -436,6 +438,25 @@ int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, const void *
                        int64_t pool_slots, const int32_t *slots, const uint16_t *valid_mask,
                        const int32_t *npages, void *out, float *lse, void *workspace,
                        void *stream);
+
+/* Stage 4 for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc and so cannot provide the workspace of
+ * spin_sparse_decode.  Same inputs, outputs and output bits as spin_sparse_decode (the same
+ * kernels run); the split-K scratch (row tickets and workgroup partials) lives in a device array
+ * of SPIN_STATIC_SCRATCH_BYTES that is part of the library image: each GPU the library runs on
+ * holds it until the process ends.  The call allocates and frees nothing and enqueues a small
+ * clearing kernel plus the attention kernel on `stream`.
+ * A call needs 256 + 4 * rows + 8 * P + 512 * P bytes of it (each term rounded up to 256), with
+ * rows = batch * num_kv_heads and P = rows * spin_decode_splits(ctx) * (num_q_heads /
+ * num_kv_heads); a larger shape returns SPIN_ERR_STATIC_LIMIT before anything is launched.
+ * status (DEVICE int32, may be NULL): receives the first device-detected fault (a slot id
+ * outside the pool: SPIN_ERR_SLOT_RANGE) if it held 0 before; the caller clears and reads it.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams, or different host threads) race and must be serialised by the caller. */
+int spin_sparse_decode_static(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool,
+                              int64_t pool_slots, const int32_t *slots, const uint16_t *valid_mask,
+                              const int32_t *npages, void *out, float *lse, int32_t *status,
+                              void *stream);
 
 #ifdef __cplusplus
 }

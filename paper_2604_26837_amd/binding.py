@@ -15,7 +15,7 @@ _LIB: Optional[C.CDLL] = None
 SPIN_OK = 0
 STATUS_NAMES = {0: "SPIN_OK", -1: "SPIN_ERR_INVALID", -2: "SPIN_ERR_UNSUPPORTED", -3: "SPIN_ERR_WORKSPACE",
                 -4: "SPIN_ERR_HIP", -5: "SPIN_ERR_BUDGET", -6: "SPIN_ERR_NOT_RESIDENT",
-                -7: "SPIN_ERR_SLOT_RANGE", -8: "SPIN_ERR_LEAF_POOL"}
+                -7: "SPIN_ERR_SLOT_RANGE", -8: "SPIN_ERR_LEAF_POOL", -9: "SPIN_ERR_STATIC_LIMIT"}
 
 EXPORTS = [
     "spin_create", "spin_destroy", "spin_status_string", "spin_workspace_bytes", "spin_sel_stride",
@@ -24,7 +24,7 @@ EXPORTS = [
     "spin_score_partitions", "spin_select_topk", "spin_resolve_slots", "spin_sparse_decode",
     "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv", "spin_reclaim_tail", "spin_alloc_leaves", "spin_free_leaves",
     "spin_set_partition_tables", "spin_probe_stream_read", "spin_offload_pages", "spin_score_select_topk", "spin_score_select_resolve", "spin_pin_partitions",
-    "spin_set_host_page_table", "spin_set_step", "spin_advance_step",
+    "spin_set_host_page_table", "spin_set_step", "spin_advance_step", "spin_sparse_decode_static",
 ]
 
 
@@ -81,6 +81,7 @@ def load_library() -> C.CDLL:
     lib.spin_advance_step.argtypes = [vp, vp, vp]
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
+    lib.spin_sparse_decode_static.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_probe_stream_read.argtypes = [vp, vp, C.c_size_t, vp, vp]
     lib.spin_set_partition_tables.argtypes = [vp, vp, vp, vp, vp]
     lib.spin_reclaim_tail.argtypes = [vp, i32, vp, vp, vp, vp, i64, vp, vp, vp]
@@ -370,3 +371,13 @@ class Spin:
             _ptr(slots, torch.int32, "slots"), _ptr(valid_mask, torch.int16, "valid_mask"),
             _ptr(npages, torch.int32, "npages"), _ptr(out, torch.bfloat16, "out"),
             _ptr(lse, torch.float32, "lse"), _ptr(ws), _stream()), "spin_sparse_decode")
+
+    def sparse_decode_static(self, batch, q, kv_pool, slots, valid_mask, npages, out, lse, status=None):
+        """Stage 4 with the split-K scratch in the library's own device array (no workspace argument)."""
+        pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192
+        self._check(self.lib.spin_sparse_decode_static(
+            self.h, batch, _ptr(q, torch.bfloat16, "q"), _ptr(kv_pool), pool_slots,
+            _ptr(slots, torch.int32, "slots"), _ptr(valid_mask, torch.int16, "valid_mask"),
+            _ptr(npages, torch.int32, "npages"), _ptr(out, torch.bfloat16, "out"),
+            _ptr(lse, torch.float32, "lse"), _ptr(status, torch.int32, "status"), _stream()),
+            "spin_sparse_decode_static")

@@ -182,6 +182,7 @@ extern "C" const char *spin_status_string(int s) {
     case SPIN_ERR_NOT_RESIDENT: return "selected page not resident";
     case SPIN_ERR_SLOT_RANGE: return "slot id outside the pool";
     case SPIN_ERR_LEAF_POOL: return "leaf segment pool exhausted";
+    case SPIN_ERR_STATIC_LIMIT: return "shape needs more scratch than the library's static device array holds";
     default: return "unknown status";
   }
 }

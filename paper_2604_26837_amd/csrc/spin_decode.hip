@@ -18,6 +18,8 @@
 // more than one split the workgroup partials go to the workspace and the
 // last workgroup of the row to arrive (a ticket counter in the workspace
 // header) merges them in split order, so results are reproducible.
+#include <mutex>
+
 #include "spin_common.h"
 
 #define NEG_INF (-__builtin_inff())
@@ -476,20 +478,14 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_tokens_kernel(
   decode_finish<WAVES>(st, row, split, b, h, lane, wave, n, c, G, Hq, nsplit, part_ml, part_acc, tickets, out, lse);
 }
 
-extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool,
-                                  int64_t pool_slots, const int32_t *slots, const uint16_t *valid_mask,
-                                  const int32_t *npages, void *out, float *lse, void *workspace,
-                                  void *stream) {
-  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || pool_slots <= 0) return SPIN_ERR_INVALID;
-  if (batch == 0) return SPIN_OK;
-  if (!q || !kv_pool || !slots || !valid_mask || !npages || !out) return SPIN_ERR_INVALID;
-  if (!workspace) return SPIN_ERR_WORKSPACE;
+// Host side of stage 4: checks, then the launch; the split-K scratch (row tickets, (m, l) pairs and
+// accumulators of the workgroup partials) and the status word are handed in by the two entry points.
+static int decode_launch(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool, int64_t pool_slots,
+                         const int32_t *slots, const uint16_t *valid_mask, const int32_t *npages, void *out,
+                         float *lse, float *part_ml, float *part_acc, int32_t *tickets, int32_t *status,
+                         void *stream) {
   const int rows = batch * ctx->cfg.num_kv_heads;
   const int G = ctx->group, nsplit = ctx->splits;
-  char *ws = (char *)workspace;
-  float *part_ml = (float *)(ws + ctx->ws_ml_off);
-  float *part_acc = (float *)(ws + ctx->ws_acc_off);
-  int32_t *tickets = (int32_t *)(ws + ctx->ws_ticket_off);
   const float scale_log2e = ctx->scale * 1.4426950408889634f;
   const int W = ctx->waves;
   const size_t lds = (size_t)W * G * (SPIN_HEAD_DIM + 2) * sizeof(float);
@@ -500,14 +496,14 @@ extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, c
     spin_launch(ctx, SPIN_K_DECODE, spin_decode_tokens_kernel<8>, dim3((unsigned)(rows * nsplit)), dim3(512), lds_tok,
                 (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, slots, valid_mask, npages,
                 ctx->page_stride, G, ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, scale_log2e, part_ml,
-                part_acc, tickets, (uint16_t *)out, lse, (int32_t *)workspace);
+                part_acc, tickets, (uint16_t *)out, lse, status);
     return spin_launch_status();
   }
 #define SPIN_DECODE_LAUNCH2(WV, DP)                                                                              \
   spin_launch(ctx, SPIN_K_DECODE, spin_decode_kernel<WV, DP>, dim3((unsigned)(rows * nsplit)), dim3(WV * 64), lds, \
               (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, slots, valid_mask,   \
               npages, ctx->page_stride, G, ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, scale_log2e,     \
-              part_ml, part_acc, tickets, (uint16_t *)out, lse, (int32_t *)workspace)
+              part_ml, part_acc, tickets, (uint16_t *)out, lse, status)
 #define SPIN_DECODE_LAUNCH(WV)                          \
   do {                                                  \
     if (ctx->depth == 2) SPIN_DECODE_LAUNCH2(WV, 2);    \
@@ -520,4 +516,81 @@ extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, c
 #undef SPIN_DECODE_LAUNCH
 #undef SPIN_DECODE_LAUNCH2
   return spin_launch_status();
+}
+
+extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool,
+                                  int64_t pool_slots, const int32_t *slots, const uint16_t *valid_mask,
+                                  const int32_t *npages, void *out, float *lse, void *workspace,
+                                  void *stream) {
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || pool_slots <= 0) return SPIN_ERR_INVALID;
+  if (batch == 0) return SPIN_OK;
+  if (!q || !kv_pool || !slots || !valid_mask || !npages || !out) return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  char *ws = (char *)workspace;
+  return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
+                       (float *)(ws + ctx->ws_ml_off), (float *)(ws + ctx->ws_acc_off),
+                       (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace, stream);
+}
+
+// ---------------------------------------------------------------------------
+// Stage 4 for callers that cannot hand over (or allocate) a workspace: the split-K scratch lives in
+// a device array of the library itself.  Every GPU the library runs on holds its own copy of the
+// array, at its own address, until the process ends.
+#define SPIN_STATIC_SCRATCH_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[SPIN_STATIC_SCRATCH_BYTES];
+
+// `scratch` above is only a host-side handle in host code: the device address is asked for once per
+// device (with that device current) and kept; host code uses that address and never the symbol's name.
+static void *g_scratch_ptr[SPIN_STATIC_SCRATCH_DEVICES];
+static std::mutex g_scratch_mutex;
+
+static int static_scratch(void **ptr) {
+  int dev = -1;
+  SPIN_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= SPIN_STATIC_SCRATCH_DEVICES) return SPIN_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    SPIN_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return SPIN_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return SPIN_OK;
+}
+
+// clears the words that must be zero when the attention kernel starts (a kernel, not a memset, so
+// that a caller may record the call into a HIP graph)
+__global__ void spin_static_clear_kernel(int32_t *p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+extern "C" int spin_sparse_decode_static(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool,
+                                         int64_t pool_slots, const int32_t *slots, const uint16_t *valid_mask,
+                                         const int32_t *npages, void *out, float *lse, int32_t *status,
+                                         void *stream) {
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || pool_slots <= 0) return SPIN_ERR_INVALID;
+  if (batch == 0) return SPIN_OK;
+  if (!q || !kv_pool || !slots || !valid_mask || !npages || !out) return SPIN_ERR_INVALID;
+  // layout inside the array, sized for this call's rows: [status word, 256 B][tickets][(m, l)][accumulators]
+  const size_t rows = (size_t)batch * ctx->cfg.num_kv_heads;
+  const size_t partials = rows * ctx->splits * ctx->group;
+  const size_t ticket_off = SPIN_WS_HEADER;
+  const size_t ml_off = (ticket_off + rows * sizeof(int32_t) + 255) & ~(size_t)255;
+  const size_t acc_off = (ml_off + partials * 2 * sizeof(float) + 255) & ~(size_t)255;
+  const size_t need = acc_off + partials * SPIN_HEAD_DIM * sizeof(float);
+  if (need > SPIN_STATIC_SCRATCH_BYTES) return SPIN_ERR_STATIC_LIMIT;
+  void *base = nullptr;
+  const int rc = static_scratch(&base);
+  if (rc != SPIN_OK) return rc;
+  char *sc = (char *)base;
+  // the array keeps the last call's contents: the status word and the row tickets start at zero
+  const int nclear = (int)(ml_off / sizeof(int32_t));
+  hipLaunchKernelGGL(spin_static_clear_kernel, dim3((nclear + 255) / 256), dim3(256), 0, (hipStream_t)stream,
+                     (int32_t *)sc, nclear);
+  if (hipGetLastError() != hipSuccess) return SPIN_ERR_HIP;
+  return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
+                       (float *)(sc + ml_off), (float *)(sc + acc_off), (int32_t *)(sc + ticket_off),
+                       status ? status : (int32_t *)sc, stream);
 }

@@ -65,6 +65,17 @@ def test_stage_calls_reject_bad_arguments_before_launching(lib):
     assert lib.spin_profile_enable(h, -1) == -1
 
 
+def test_static_scratch_entry_point_refuses_shapes_beyond_its_array(lib):
+    """spin_sparse_decode_static checks the scratch it needs against the fixed device array before any HIP call."""
+    sp = binding.Spin(max_batch=64, num_q_heads=32, num_kv_heads=8, topk=128, max_context=32768, decode_splits=8)
+    fake = 4096   # never dereferenced: the call returns before anything is launched
+    big = lib.spin_sparse_decode_static(sp.h, 64, fake, fake, 1, fake, fake, fake, fake, None, None, None)
+    assert big == -9 and lib.spin_status_string(big).startswith(b"shape needs more scratch")
+    assert lib.spin_sparse_decode_static(sp.h, 65, fake, fake, 1, fake, fake, fake, fake, None, None, None) == -1
+    assert lib.spin_sparse_decode_static(sp.h, 0, None, None, 1, None, None, None, None, None, None, None) == 0
+    assert lib.spin_sparse_decode_static(sp.h, 1, None, fake, 1, fake, fake, fake, fake, None, None, None) == -1
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB", None)
     monkeypatch.setattr(build, "LIB_PATH", str(tmp_path / "missing.so"))
