@@ -24,6 +24,8 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   if (c->lru_policy != 0 && c->lru_policy != 1) return SPIN_ERR_INVALID;
   if (c->decode_depth != 0 && (c->decode_depth < 2 || c->decode_depth > 4)) return SPIN_ERR_INVALID;
   if (c->variable_partitions && tp < 16) return SPIN_ERR_UNSUPPORTED;
+  // the key sketch is one row per token: every SKETCH kernel takes summary row == token
+  if (c->score_kind == SPIN_SCORE_SKETCH && tp != 1) return SPIN_ERR_UNSUPPORTED;
   if (c->score_tiles_per_wg < 0 || (c->score_waves != 0 && c->score_waves != 1 && c->score_waves != 2 && c->score_waves != 4 && c->score_waves != 8))
     return SPIN_ERR_INVALID;
 
@@ -196,6 +198,8 @@ extern "C" int spin_set_partition_tables(spin_ctx *ctx, const int32_t *part_offs
   }
   if (!part_offsets || !part_count || !part_first_page || !part_tokens) return SPIN_ERR_INVALID;
   const spin_config &c = ctx->cfg;
+  // strides and the stage-2 path are sized for uniform partitions unless the context was created for tables
+  if (!c.variable_partitions) return SPIN_ERR_UNSUPPORTED;
   // summaries that exist for partitions of any length: min / max keys, or one mean key (centroid)
   const bool kind_ok = c.score_kind == SPIN_SCORE_MINMAX ||
                        (c.score_kind == SPIN_SCORE_REPMAX && c.reps_per_partition == 1);

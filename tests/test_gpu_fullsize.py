@@ -1,7 +1,8 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py
 times (same set-up code, default splits/waves): the whole four-call step runs
-on the device-generated workload and sampled rows are checked one by one
-against the oracle (summaries bit-exact, scores within the fp32 bound, top-k on
+on the device-generated workload and its rows are checked one by one
+against the oracle (every row of configs 1-3; sampled rows over 40 steps for
+the budget workload) (summaries bit-exact, scores within the fp32 bound, top-k on
 the device's own fp32 scores bit-exact, slots bit-exact, attention within
 2e-2 + 1e-2 |ref|).  Properties that hold at any size are checked on all rows."""
 import numpy as np
@@ -108,11 +109,11 @@ def _check_sampled_rows(w, layer, natural, sample):
     return band
 
 
-def test_config1_headline_sampled_rows():
+def test_config1_headline_all_rows():
     w = synth.config1()
     layer, natural = runner.build_device_layer(w, keep_natural=True)
     assert layer.spin.decode_splits == 2
-    band = _check_sampled_rows(w, layer, natural, [0, 37, 70, 127])
+    band = _check_sampled_rows(w, layer, natural, list(range(w.rows)))      # every row against the oracle
     # bits identical run to run in this launch configuration
     a = layer.out.clone()
     layer.step_fused(layer.q0)
@@ -124,10 +125,10 @@ def test_config1_headline_sampled_rows():
     print("cfg1 rows in the rounding band:", band)
 
 
-def test_config2_token_sketch_sampled_rows():
+def test_config2_token_sketch_all_rows():
     w = synth.config2()
     layer, natural = runner.build_device_layer(w, keep_natural=True)
-    band = _check_sampled_rows(w, layer, natural, [0, 29, 63])
+    band = _check_sampled_rows(w, layer, natural, list(range(w.rows)))      # every row against the oracle
     npages = layer.npages.cpu().numpy()
     masks = layer.valid_mask.cpu().numpy().view(np.uint16)
     # 1024 selected tokens per row, spread over at most 1024 pages
@@ -136,34 +137,39 @@ def test_config2_token_sketch_sampled_rows():
     print("cfg2 rows in the rounding band:", band, "mean pages/row", npages.mean())
 
 
-def test_config3_block_repmax_sampled_rows():
+def test_config3_block_repmax_all_rows():
     w = synth.config3()
     layer, natural = runner.build_device_layer(w, keep_natural=True)
-    band = _check_sampled_rows(w, layer, natural, [0, 31])
+    band = _check_sampled_rows(w, layer, natural, list(range(w.rows)))      # every row against the oracle
     npages = layer.npages.cpu().numpy()
     assert (npages <= 32 * 8 + 64 + 4).all() and (npages >= 32 * 8 + 64).all()
     print("cfg3 rows in the rounding band:", band)
 
 
-@pytest.mark.parametrize("policy", [0, 1])
-def test_config4_budget_sampled_rows(policy):
+@pytest.mark.parametrize("policy,evict_exact,n_ts", [(0, False, 64), (0, True, 16), (1, False, 64)])
+def test_config4_budget_sampled_rows(policy, evict_exact, n_ts):
     """The hierarchical-budget workload at full size (32 ragged requests, 7.85 GiB of KV in
     pinned host memory, 25 % of the pages as slots), as `bench.py --workload cfg4` runs it with
-    the copy kernel: over the first steps, sampled rows are checked against the oracle
+    the copy kernel: over the first 40 steps, sampled rows are checked against the oracle
     (selection on the device's fp32 scores, replacement state and miss list bit-exact,
-    attention over the logical pages); tables of all rows stay consistent."""
+    attention over the logical pages); tables of all rows stay consistent.  40 steps fill the
+    budgets of requests of up to the median length, so their rows evict at full size; the case
+    with 16 timestamp values also reaches the demotion of Section 5.3 step 2 (step > n - 1)."""
     from oracle import lru
     from paper_2604_26837_amd import hier
     w = synth.config4()
-    n_ts = 64
-    layer = hier.HierLayer(w, budget_frac=0.25, n_ts=n_ts, copy_mode="gather", keep_natural=True, lru_policy=policy)
+    layer = hier.HierLayer(w, budget_frac=0.25, n_ts=n_ts, copy_mode="gather", keep_natural=True, lru_policy=policy,
+                           evict_exact=evict_exact)
     g, hkv = w.group, w.num_kv_heads
     longest = int(np.argmax(w.seq_lens)) * hkv
     shortest = int(np.argmin(w.seq_lens)) * hkv + hkv - 1
-    sample = sorted({0, 13, 100, 255, longest, shortest})
+    by_len = np.argsort(w.seq_lens)
+    median = [int(by_len[len(by_len) // 2]) * hkv + 3, int(by_len[len(by_len) // 2 - 1]) * hkv + 6]
+    sample = sorted({0, 13, 100, 255, longest, shortest, *median})
     caches = {r: lru.RowCache(layer.budgets[r]) for r in sample}
+    evicted = {r: 0 for r in sample}
     q = layer.q0
-    for step in range(4):
+    for step in range(40):
         layer.step(q, step)
         torch.cuda.synchronize()
         assert layer.status() == 0
@@ -182,10 +188,12 @@ def test_config4_budget_sampled_rows(policy):
             base = layer.part_offsets_np[b] * hkv + h * int(layer.part_offsets_np[b + 1] - layer.part_offsets_np[b])
             want_sel = select.select_topk(scores[base:base + P], n, 16, 16, w.topk, True, w.sink_pages, w.recent_pages)
             assert sel[r, :nsel[r]].tolist() == want_sel, f"step {step} row {r}"
+            held_before = len(caches[r].where)
             if policy == 1:
                 want_slots, want_miss, _ = lru.setassoc_step(caches[r], want_sel, step, n_ts, row=r)
             else:
-                want_slots, want_miss, _ = lru.lru_step(caches[r], want_sel, step, n_ts)
+                want_slots, want_miss, _ = lru.lru_step(caches[r], want_sel, step, n_ts, evict_exact=evict_exact)
+            evicted[r] += held_before + len(want_miss) - len(caches[r].where)
             sb = int(layer.slot_base_np[r])
             assert slots[r, :npages[r]].tolist() == [sb + s for s in want_slots], f"step {step} row {r}"
             assert mp[r, :nm[r]].tolist() == [p for p, _ in want_miss]
@@ -198,6 +206,8 @@ def test_config4_budget_sampled_rows(policy):
             o = out[b, h * g:(h + 1) * g]
             assert np.all(np.abs(o - ref) <= ATOL + RTOL * np.abs(ref)), f"step {step} row {r}"
         q = torch.from_numpy(synth.next_query_ar1(q_bits, 0.9, w.seed + 7000 + step).view(np.int16)).to(q.device).view(torch.bfloat16)
+    # the steps reached eviction on the rows of short and median requests
+    assert evicted[shortest] > 0 and all(evicted[r] > 0 for r in median), evicted
     # every row: the reverse table holds each page at most once, inside the row's own slot range
     rev = layer.rev.cpu().numpy()
     for r in range(0, w.rows, 7):
