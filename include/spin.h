@@ -106,7 +106,7 @@ typedef struct spin_config {
   int32_t head_dim;             /* 128 */
   int32_t page_tokens;          /* 16 */
   int32_t partition_tokens;     /* divides 16, or a multiple of 16 */
-  int32_t score_kind;           /* spin_score_kind */
+  int32_t score_kind;           /* spin_score_kind; SKETCH needs partition_tokens == 1 */
   int32_t sketch_channels;      /* 16 (SKETCH) */
   int32_t reps_per_partition;   /* REPMAX: 1 (one mean key per partition: a landmark or centroid), 2 or 4 */
   int32_t topk;                 /* partitions per row (tokens when partition_tokens == 1) */
@@ -188,7 +188,10 @@ int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_
  * tokens: a cluster's centroid), in all-resident and in budget mode, rows of at most
  * 65536 partitions.  Passing
  * NULL for the three tables returns to uniform partitions.  The pointers are kept,
- * not copied: the tables must outlive the calls that use them. */
+ * not copied: the tables must outlive the calls that use them.
+ * SPIN_ERR_UNSUPPORTED unless the context was created with variable_partitions = 1.  While
+ * tables are registered, spin_append_kv and spin_alloc_leaves (which find a partition's
+ * pages from its id alone) return SPIN_ERR_UNSUPPORTED. */
 int spin_set_partition_tables(spin_ctx *ctx, const int32_t *part_offsets, const int32_t *part_count,
                               const int32_t *part_first_page, const int32_t *part_tokens);
 
@@ -200,7 +203,8 @@ int spin_probe_stream_read(spin_ctx *ctx, const void *buf, size_t bytes, void *w
 
 /* Offload, layout half: write `n_pages` pages given in plain token-major order
  * (src_k, src_v: DEVICE bf16 [n_pages][16][128]) into pool slots `slots[i]`
- * (DEVICE int32 [n_pages], each in [0, pool_slots)) in the slot layout above. */
+ * (DEVICE int32 [n_pages], each in [0, pool_slots)) in the slot layout above.  A page whose
+ * slot lies outside the pool is skipped without a report (the call takes no workspace). */
 int spin_pack_kv_pages(spin_ctx *ctx, int64_t n_pages, const void *src_k, const void *src_v,
                        const int32_t *slots, void *kv_pool, int64_t pool_slots, void *stream);
 
@@ -240,9 +244,12 @@ int spin_append_kv(spin_ctx *ctx, int32_t batch, const void *k_new, const void *
  * over the G query heads of the row's group; bf16 inputs, exact products, fp32
  * accumulation on the matrix cores.  Entries beyond a row's partition count are
  * unspecified.  Summaries must be finite: the kernels pair some summary values
- * with exact zeros of the query-side operand, and 0 x inf would turn the scores
- * of the partition (SKETCH with groups of up to four heads: of the up to 64
- * tokens scored together) into NaN, which stage 2 ranks lowest. */
+ * with exact zeros of the query-side operand (MINMAX: max[d] with max(q[d], 0),
+ * min[d] with min(q[d], 0)), and 0 x inf makes the sum of that head NaN where
+ * the definition has a finite term.  The maximum over the group's heads drops
+ * NaN operands, so such a partition (SKETCH with groups of up to four heads:
+ * each of the up to 64 tokens scored together) scores as the best of its other
+ * heads, -inf when none is left, and stage 2 ranks it accordingly. */
 int spin_score_partitions(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries,
                           const int32_t *chan_idx, const int32_t *part_offsets,
                           const int32_t *seq_lens, float *scores, void *workspace, void *stream);
@@ -387,8 +394,11 @@ int spin_free_leaves(spin_ctx *ctx, int32_t batch, int32_t *dir, int64_t leaf_ch
  * as they were allocated while its context grew.  Applies to
  * spin_gather_misses, spin_offload_pages and spin_copy_misses_host; an offset or
  * entry out of range raises SPIN_ERR_SLOT_RANGE (SPIN_ERR_INVALID from the
- * host-driven copier) and skips the page.  NULL returns to the identity.  The
- * pointer is kept, not copied. */
+ * host-driven copier) and skips the page.  NULL returns to the identity; host_pages > 0
+ * then still registers the size of the host pool, so that both copiers refuse a page
+ * outside it in the same way (with host_pages == 0 the identity mapping is unchecked and
+ * host_row_base / the page lists are the caller's responsibility).  The pointer is kept,
+ * not copied. */
 int spin_set_host_page_table(spin_ctx *ctx, const int32_t *cpu_pages, int64_t entries, int64_t host_pages);
 
 /* Retrieve steps 3-4 (Section 5.2), after budget-mode stage 3: copy every missed

@@ -236,7 +236,7 @@ class Spin:
         """cpu_pages: pinned int32 CPU tensor (kept alive here: the library stores its address)."""
         self._cpu_table = cpu_pages
         if cpu_pages is None:
-            self._check(self.lib.spin_set_host_page_table(self.h, None, 0, 0), "spin_set_host_page_table")
+            self._check(self.lib.spin_set_host_page_table(self.h, None, 0, host_pages), "spin_set_host_page_table")
             return
         if not cpu_pages.is_pinned() or cpu_pages.dtype != torch.int32 or not cpu_pages.is_contiguous():
             raise ValueError("cpu_pages must be a contiguous pinned int32 host tensor")

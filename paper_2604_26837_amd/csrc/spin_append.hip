@@ -92,6 +92,8 @@ extern "C" int spin_append_kv(spin_ctx *ctx, int32_t batch, const void *k_new, c
   if (!k_new || !v_new || !seq_lens || !kv_pool || !dir || !leaf_pool || !part_offsets || !summaries)
     return SPIN_ERR_INVALID;
   if (!workspace) return SPIN_ERR_WORKSPACE;
+  // the kernel finds the token's partition by division: not with registered partition tables
+  if (ctx->var.count) return SPIN_ERR_UNSUPPORTED;
   const spin_config &c = ctx->cfg;
   if (c.score_kind == SPIN_SCORE_SKETCH && (!chan_idx || c.partition_tokens != 1)) return SPIN_ERR_INVALID;
   const int rows = batch * c.num_kv_heads;

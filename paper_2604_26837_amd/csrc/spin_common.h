@@ -145,6 +145,7 @@ __device__ inline uint16_t spin_f32_to_bf16(float f) {
 // entry is missing
 __device__ inline int32_t spin_walk(const int32_t *__restrict__ dir, const int32_t *__restrict__ leaf_pool,
                                     int64_t leaf_chunks, int row, int dir_stride, int leaf_entries, int page) {
+  if (page < 0) return -1;
   const int ci = page / leaf_entries;
   if (ci >= dir_stride) return -1;
   const int32_t chunk = dir[(size_t)row * dir_stride + ci];

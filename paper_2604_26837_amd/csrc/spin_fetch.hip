@@ -31,8 +31,9 @@ extern "C" int spin_copy_misses_host(spin_ctx *ctx, int32_t batch, const void *h
       if (ctx->cpu_table) {                 // pinned host memory: readable from here as well
         if (hp < 0 || hp >= ctx->cpu_table_entries) return SPIN_ERR_INVALID;
         hp = ctx->cpu_table[hp];
-        if (hp < 0 || hp >= ctx->cpu_pages) return SPIN_ERR_INVALID;
       }
+      // the host pool's size, when one was registered (with or without a table), bounds the page
+      if (hp < 0 || (ctx->cpu_pages > 0 && hp >= ctx->cpu_pages)) return SPIN_ERR_INVALID;
       const char *src = (const char *)host_kv + (size_t)hp * SPIN_SLOT_BYTES;
       char *dst = (char *)kv_pool + (size_t)slot * SPIN_SLOT_BYTES;
       SPIN_HIP_CHECK(hipMemcpyAsync(dst, src, SPIN_SLOT_BYTES, hipMemcpyHostToDevice, (hipStream_t)copy_stream));
@@ -76,10 +77,11 @@ __global__ __launch_bounds__(GATHER_WAVES * 64) void spin_gather_kernel(
     if (hm.table) {                         // CPU page table: offset of the page in the row's list -> physical host page
       const bool in_table = hpage >= 0 && hpage < hm.entries;
       hpage = in_table ? hm.table[hpage] : -1;
-      if (hpage < 0 || hpage >= hm.pages) {
-        if (lane == 0) spin_raise(status, SPIN_ERR_SLOT_RANGE);
-        continue;
-      }
+    }
+    // the host pool's size, when one was registered (with or without a table), bounds the page
+    if (hpage < 0 || (hm.pages > 0 && hpage >= hm.pages)) {
+      if (lane == 0) spin_raise(status, SPIN_ERR_SLOT_RANGE);
+      continue;
     }
     uint4 *hp = host_kv + (size_t)hpage * SPIN_SLOT_U4 + lane;
     uint4 *dp = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
@@ -127,8 +129,9 @@ extern "C" int spin_offload_pages(spin_ctx *ctx, int32_t batch, const void *kv_p
 
 extern "C" int spin_set_host_page_table(spin_ctx *ctx, const int32_t *cpu_pages, int64_t entries, int64_t host_pages) {
   if (!ctx) return SPIN_ERR_INVALID;
-  if (!cpu_pages) {
-    ctx->cpu_table = nullptr; ctx->cpu_table_entries = 0; ctx->cpu_pages = 0;
+  if (!cpu_pages) {   // identity mapping; host_pages > 0 still bounds the pages the copiers touch
+    if (host_pages < 0) return SPIN_ERR_INVALID;
+    ctx->cpu_table = nullptr; ctx->cpu_table_entries = 0; ctx->cpu_pages = host_pages;
     return SPIN_OK;
   }
   if (entries <= 0 || host_pages <= 0) return SPIN_ERR_INVALID;

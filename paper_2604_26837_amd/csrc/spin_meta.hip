@@ -130,6 +130,8 @@ extern "C" int spin_alloc_leaves(spin_ctx *ctx, int32_t batch, const int32_t *se
   if (!sel || !nsel || !seq_lens || !dir || !leaf_pool || !leaf_bitmap) return SPIN_ERR_INVALID;
   if (!workspace) return SPIN_ERR_WORKSPACE;
   if (ctx->dir_stride > META_DIR_LDS) return SPIN_ERR_UNSUPPORTED;
+  // the kernel takes a partition's page range from its id alone: not with registered partition tables
+  if (ctx->var.count) return SPIN_ERR_UNSUPPORTED;
   const spin_config &c = ctx->cfg;
   const int rows = batch * c.num_kv_heads;
   spin_launch(ctx, SPIN_K_META, spin_alloc_leaves_kernel, dim3((unsigned)rows), dim3(META_BLOCK), 0, (hipStream_t)stream, sel, nsel,

@@ -16,7 +16,8 @@ __global__ __launch_bounds__(256) void spin_pack_kernel(const uint16_t *__restri
   const int64_t page = blockIdx.x;
   if (page >= n_pages) return;
   const int32_t slot = slots[page];
-  if (slot < 0 || (int64_t)slot >= pool_slots) return;  // checked again on the host side of the ABI
+  if (slot < 0 || (int64_t)slot >= pool_slots) return;  // a slot outside the pool: the page is skipped (this call
+                                                        // has no workspace, hence no status word to raise)
   const int u = threadIdx.x;                             // 16-byte unit of the tile
   const int j = u >> 6, c = (u >> 4) & 3, x = u & 15;
   // K unit: token x, dims 32j + 8c .. +8 (contiguous in the source)

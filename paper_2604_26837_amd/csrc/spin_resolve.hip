@@ -37,6 +37,8 @@ __global__ __launch_bounds__(RES_BLOCK) void spin_resolve_kernel(
 #define LRU_BLOCK 512
 #define LRU_WAVES (LRU_BLOCK / 64)
 #define LRU_MAX_TS 256
+#define LRU_LDS_LIMIT (64 * 1024)   // LDS a workgroup may use without raising the kernel's limit
+#define LRU_LDS_STATIC 4096         // reserve for the static arrays of the budget-mode kernels
 
 __device__ inline int lru_scan(int v, int *s_wave, int &total) {   // exclusive prefix sum over the workgroup
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -543,10 +545,15 @@ extern "C" int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, co
     const bool expand = c.partition_tokens != 16 || ctx->var.count;
     const lru_expand ex = {c.partition_tokens, c.sink_pages, c.recent_pages, ctx->var};
     if (c.lru_policy == 1) {
-      // LDS: four int32 per output entry; per set a counter and a byte; one flag byte per slot of the row
-      const int max_slots_lds = 32 * 1024;
+      // LDS: four int32 per output entry; per set a counter and a byte; one flag byte per slot of the row.
+      // The kernels' own static arrays (histogram, directory copy, scan cells: under 3 KiB) come on top of
+      // the dynamic part, so the slot capacity is what is left of 64 KiB after a 4 KiB reserve.
+      const int64_t avail_sa = LRU_LDS_LIMIT - LRU_LDS_STATIC - (int64_t)ctx->page_stride * 16;
+      int64_t cap_sa = avail_sa > 0 ? (avail_sa * 8 / 13) & ~(int64_t)63 : 0;
+      if (cap_sa > 32 * 1024) cap_sa = 32 * 1024;
+      if (cap_sa < ctx->page_stride || cap_sa < SA_WAYS) return SPIN_ERR_UNSUPPORTED;
+      const int max_slots_lds = (int)cap_sa;
       const size_t lds = (size_t)ctx->page_stride * 16 + (size_t)(max_slots_lds / SA_WAYS) * 5 + max_slots_lds;
-      if (lds > 64 * 1024) return SPIN_ERR_UNSUPPORTED;
 #define SPIN_SA_ARGS                                                                                            \
   dim3((unsigned)rows), dim3(LRU_BLOCK), lds, (hipStream_t)stream, sel, nsel, seq_lens, dir, leaf_pool, leaf_chunks, \
       rev_table, slot_base, c.num_kv_heads, ctx->sel_stride, ctx->page_stride, ctx->dir_stride, c.leaf_entries,   \
@@ -557,10 +564,12 @@ extern "C" int spin_resolve_slots(spin_ctx *ctx, int32_t batch, int32_t step, co
 #undef SPIN_SA_ARGS
       return spin_launch_status();
     }
-    // LDS: two int32 per output entry plus one flag byte per slot of the row
-    const int max_slots_lds = 48 * 1024;
+    // LDS: two int32 per output entry plus one flag byte per slot of the row (static arrays: see above)
+    int64_t cap = (LRU_LDS_LIMIT - LRU_LDS_STATIC - (int64_t)ctx->page_stride * 8) & ~(int64_t)63;
+    if (cap > 48 * 1024) cap = 48 * 1024;
+    if (cap < ctx->page_stride) return SPIN_ERR_UNSUPPORTED;
+    const int max_slots_lds = (int)cap;
     const size_t lds = (size_t)ctx->page_stride * 8 + max_slots_lds;
-    if (lds > 64 * 1024) return SPIN_ERR_UNSUPPORTED;
 #define SPIN_LRU_ARGS                                                                                           \
   dim3((unsigned)rows), dim3(LRU_BLOCK), lds, (hipStream_t)stream, sel, nsel, seq_lens, dir, leaf_pool, leaf_chunks, \
       rev_table, slot_base, c.num_kv_heads, ctx->sel_stride, ctx->page_stride, ctx->dir_stride, c.leaf_entries,   \

@@ -56,6 +56,16 @@ __device__ inline void emit_page(const res_out &o, int pos, int page_stride, int
   o.mask[pos] = (uint16_t)mask;
 }
 
+// A selection entry outside the row: its output position holds no page (nothing of a previous
+// step stays there for stage 4 to attend) and the fault is reported.
+__device__ inline void emit_invalid(const res_out &o, int pos, int page_stride, int32_t *status) {
+  spin_raise(status, SPIN_ERR_INVALID);
+  if (pos < 0 || pos >= page_stride) return;
+  o.slots[pos] = -1;
+  o.page_ids[pos] = -1;
+  o.mask[pos] = 0;
+}
+
 // Resolves one row with the calling workgroup of RES_BLOCK threads; `ns` = the
 // row's selection count.
 template <int RES_BLOCK, bool LOOKUP = true>
@@ -118,7 +128,7 @@ __device__ inline void resolve_row(
     __syncthreads();
     for (int i = tid; i < ns; i += RES_BLOCK) {
       const int s = rsel[i];
-      if (s < 0 || s >= P) continue;
+      if (s < 0 || s >= P) { spin_raise(status, SPIN_ERR_INVALID); continue; }   // takes no output position
       const int n = spin_var_npages(var, vb, s);
       if (s == A) s_flagA = 1;
       if (s == B) s_flagB = 1;
@@ -169,9 +179,13 @@ __device__ inline void resolve_row(
     for (int i0 = 0; i0 < sel_stride; i0 += RES_BLOCK) {
       const int i = i0 + tid;
       const int s = i < sel_stride ? rsel[i] : -1;
-      if (i < ns && s >= 0 && s < pages)
-        emit_page<LOOKUP>(o, i, page_stride, s, page_mask(s, N), dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries,
-                  status);
+      if (i < ns) {
+        if (s >= 0 && s < pages)
+          emit_page<LOOKUP>(o, i, page_stride, s, page_mask(s, N), dir, leaf_pool, leaf_chunks, row, dir_stride,
+                            leaf_entries, status);
+        else
+          emit_invalid(o, i, page_stride, status);   // an entry that names no page of the row
+      }
       if (i0 + RES_BLOCK >= ns) break;
     }
     const int total = min(ns, page_stride);
@@ -211,10 +225,14 @@ __device__ inline void resolve_row(
       const int i = idx / m, k = idx - i * m;
       const int s = rsel[i];
       const int pg = s * m + k;
-      if (s < 0 || pg >= pages) continue;
       int pos = i * m + k;
       if (extraA && s > A) pos += extraA;
       if (extraB && s > B) pos += extraB;
+      if (s < 0 || (int64_t)s * m >= pages) {        // an entry that names no partition of the row
+        emit_invalid(o, pos, page_stride, status);
+        continue;
+      }
+      if (pg >= pages) continue;                     // the ragged end of the context's last partition
       emit_page<LOOKUP>(o, pos, page_stride, pg, page_mask(pg, N), dir, leaf_pool, leaf_chunks, row, dir_stride,
                 leaf_entries, status);
     }
@@ -252,7 +270,8 @@ __device__ inline void resolve_row(
           const int s = rsel[j];
           if (s / ppp != pg) break;
           const int t0 = s * tp, cnt = min(tp, N - t0);
-          if (cnt > 0) mk |= ((1u << cnt) - 1u) << (t0 & 15);
+          if (s < 0 || cnt <= 0) { spin_raise(status, SPIN_ERR_INVALID); continue; }   // names no token of the row
+          mk |= ((1u << cnt) - 1u) << (t0 & 15);
         }
         emit_page<LOOKUP>(o, carry + before, page_stride, pg, mk, dir, leaf_pool, leaf_chunks, row, dir_stride,
                   leaf_entries, status);

@@ -58,6 +58,8 @@ class HierLayer:
             self.cpu_table = torch.from_numpy(perm.astype(np.int32)).pin_memory()
             self.spin.set_host_page_table(self.cpu_table, pool_pages)
             n_host = pool_pages
+        else:
+            self.spin.set_host_page_table(None, n_host)      # identity mapping, bounded by the pool's size
         self.host_kv = torch.empty((n_host, 4096), dtype=torch.bfloat16, pin_memory=True)
         # metadata: leaves for every page range inside a row's context, nothing resident yet
         empty = [np.full((hkv, w.pages(b)), -1, dtype=np.int32) for b in range(w.batch)]

@@ -76,6 +76,35 @@ def test_static_scratch_entry_point_refuses_shapes_beyond_its_array(lib):
     assert lib.spin_sparse_decode_static(sp.h, 1, None, fake, 1, fake, fake, fake, fake, None, None, None) == -1
 
 
+def test_unsupported_combinations_are_refused_on_the_host(lib):
+    """Refusals that need no GPU: partition tables on a context not sized for them, the calls that cannot follow
+    tables, a key sketch with partitions other than one token, budget-mode shapes whose LDS need is too large."""
+    fake = 4096   # never dereferenced: every call below returns before anything is launched
+    base = dict(max_batch=2, num_q_heads=8, num_kv_heads=2, topk=8, max_context=4096, partition_tokens=64)
+    uniform = binding.Spin(**base)
+    assert lib.spin_set_partition_tables(uniform.h, fake, fake, fake, fake) == -2
+    var = binding.Spin(variable_partitions=1, **base)
+    assert lib.spin_set_partition_tables(var.h, fake, fake, fake, fake) == 0
+    i64 = C.c_int64
+    assert lib.spin_append_kv(var.h, 1, fake, fake, fake, fake, i64(8), fake, fake, i64(1), fake, None, fake, fake, None) == -2
+    assert lib.spin_alloc_leaves(var.h, 1, fake, fake, fake, fake, fake, i64(4), fake, fake, None) == -2
+    assert lib.spin_set_partition_tables(var.h, None, None, None, None) == 0
+    with pytest.raises(binding.SpinError, match="UNSUPPORTED"):
+        binding.Spin(max_batch=1, num_q_heads=8, num_kv_heads=2, topk=8, max_context=1024, score_kind=1,
+                     partition_tokens=16)
+    binding.Spin(max_batch=1, num_q_heads=8, num_kv_heads=2, topk=8, max_context=1024, score_kind=1, partition_tokens=1)
+
+    def budget_call(sp):
+        return lib.spin_resolve_slots(sp.h, 1, 0, fake, fake, fake, fake, fake, i64(4), fake, fake, fake, fake, fake,
+                                      fake, fake, fake, fake, fake, None)
+    big = dict(max_batch=1, num_q_heads=8, num_kv_heads=2, max_context=1 << 20, lru_timestamps=64)
+    # bucketed LRU: 8 bytes per output entry + one byte per slot must fit in 60 KiB with slots >= entries
+    assert binding.Spin(topk=7000, **big).page_stride == 7000
+    assert budget_call(binding.Spin(topk=7000, **big)) == -2
+    # set-associative: 16 bytes per output entry + 13/8 bytes per slot
+    assert budget_call(binding.Spin(topk=3500, lru_policy=1, **big)) == -2
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB", None)
     monkeypatch.setattr(build, "LIB_PATH", str(tmp_path / "missing.so"))
