@@ -48,24 +48,135 @@ def parse_args():
     ap.add_argument("--decode-depth", type=int, default=0, help="page buffers per attention wavefront (0: library default)")
     ap.add_argument("--score-waves", type=int, default=0, help="wavefronts per stage-1 workgroup (0: library default)")
     ap.add_argument("--score-tiles", type=int, default=0, help="summary tiles per stage-1 workgroup (0: library default)")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
+    ap.add_argument("--print-source-hash", action="store_true",
+                    help="print the hash of the library's sources that counter summaries under profiles/ record, and exit")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket kernels with HIP events during the timed region")
     return ap.parse_args()
 
 
-def read_traffic(path):
-    """HBM bytes per launch of the decode kernel from the committed counter summary, or None."""
+def source_hash():
+    """sha256 over the library's sources (csrc/* and include/spin.h, sorted by name): what a counter summary
+    under profiles/ must have been taken from for its figures to describe the library that runs now."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(ROOT, "paper_2604_26837_amd", "csrc", "*"))) + \
+        [os.path.join(ROOT, "include", "spin.h")]
+    for f in files:
+        h.update(os.path.basename(f).encode() + b"\0")
+        h.update(open(f, "rb").read())
+    return h.hexdigest()
+
+
+def read_traffic(path, kernel):
+    """(HBM bytes per launch of the attention kernel, note) from the committed counter summary.  The figure is
+    a recorded one (an earlier rocprofv3 session), so it is only passed on when the summary names the same
+    kernel instantiation and the same source hash as the library in the tree; otherwise (None, reason)."""
+    name = os.path.relpath(path, ROOT)
     try:
         txt = open(path).read()
     except OSError:
-        return None
+        return None, f"{name} not found"
     m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", txt, re.M)
-    return float(m.group(1)) if m else None
+    k = re.search(r"^traffic_kernel:\s*(.+?)\s*$", txt, re.M)
+    hs = re.search(r"^csrc_sha256:\s*([0-9a-f]+)", txt, re.M)
+    if not m:
+        return None, f"{name} holds no traffic_bytes_per_launch"
+    if not k or not hs:
+        return None, f"{name} does not say which kernel and sources it was taken from"
+    if k.group(1).replace(" ", "") != kernel.replace(" ", ""):
+        return None, f"{name} was taken from {k.group(1)}, this run launches {kernel}"
+    if hs.group(1) != source_hash():
+        return None, f"{name} was taken from other sources (csrc_sha256 differs): regenerate it"
+    return float(m.group(1)), f"recorded in {name} (rocprofv3 FETCH_SIZE + WRITE_SIZE, same kernel and sources)"
 
 
-def cpu_oracle_leg(layer, natural, q_bits, rows, reps):
-    """Times the fp64 oracle (as it stands) on `rows` rows of the same workload
-    and checks the GPU's output for those rows against it."""
+def _oracle_worker(conn):
+    """Child process of the all-cores leg: receives rows of the workload, then runs the oracle's decode step
+    over them when told to and reports the time it took.  Single-threaded numpy; no GPU, no torch."""
+    for v in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS"):
+        os.environ[v] = "1"
+    from oracle import step as ostep
+    try:
+        from threadpoolctl import threadpool_limits
+        threadpool_limits(limits=1)
+    except Exception:
+        pass
+    rows = []
+    while True:
+        msg = conn.recv()
+        if msg[0] == "row":
+            rows.append(msg[1])
+        elif msg[0] == "run":
+            t0 = time.perf_counter()
+            for _ in range(msg[1]):
+                for a in rows:
+                    ostep.decode_row(*a[:-1], channels=a[-1])
+            conn.send(time.perf_counter() - t0)
+        else:
+            return
+
+
+class OraclePool:
+    """Worker processes for the all-cores leg of `cpu_baseline`.  They are forked before the first GPU call of
+    this program (a process that has initialised the GPU must not be forked), sit idle during the GPU part and
+    hold nothing but the interpreter."""
+
+    def __init__(self):
+        import multiprocessing as mp
+        try:
+            avail = len(os.sched_getaffinity(0))
+        except AttributeError:
+            avail = os.cpu_count() or 1
+        self.n = max(1, min(avail, 16))          # the GPU box's CPU share for one GPU is 16
+        ctx = mp.get_context("fork")
+        self.conns, self.procs = [], []
+        for _ in range(self.n):
+            a, b = ctx.Pipe()
+            p = ctx.Process(target=_oracle_worker, args=(b,), daemon=True)
+            p.start()
+            b.close()
+            self.conns.append(a)
+            self.procs.append(p)
+
+    def run(self, row_args, reps):
+        """Deals the rows round-robin, then times `reps` passes of all workers over their rows (wall clock of
+        the parent from the start signal to the last report)."""
+        used = min(self.n, len(row_args))
+        for i, a in enumerate(row_args):
+            self.conns[i % used].send(("row", a))
+        t0 = time.perf_counter()
+        for c in self.conns[:used]:
+            c.send(("run", reps))
+        busy = [c.recv() for c in self.conns[:used]]
+        wall = time.perf_counter() - t0
+        return wall / reps, used, max(busy) / reps
+
+    def close(self):
+        for c in self.conns:
+            try:
+                c.send(("quit",))
+            except Exception:
+                pass
+        for p in self.procs:
+            p.join(timeout=5)
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_oracle_leg(layer, natural, q_bits, rows, reps, pool=None):
+    """Times the fp64 oracle (as it stands) on `rows` rows of the same workload, on one core and, with `pool`,
+    fanned out over the host's cores; the caller checks the GPU's output for those rows against the results."""
     import numpy as np
     import torch
     from oracle import bf16, index, step as ostep
@@ -97,18 +208,27 @@ def cpu_oracle_leg(layer, natural, q_bits, rows, reps):
         page_map = {(r, pg): pg for pg in range(pages.shape[0])}      # local pool: slot == logical page
         q = bf16.decode(q_bits[b, h * g:(h + 1) * g])
         prepared.append((r, b, h, q, summ, page_map, pages, chan))
+
+    def row_args(p):
+        r, b, h, q, summ, page_map, pages, chan = p
+        return (q, summ, w.score_kind, w.seq_lens[b], w.page_tokens, w.partition_tokens, w.topk,
+                w.topk_includes_forced, w.sink_pages, w.recent_pages, page_map, r, pages, layer.scale, chan)
+
     t0 = time.perf_counter()
     results = None
     for _ in range(reps):
-        results = [ostep.decode_row(q, summ, w.score_kind, w.seq_lens[b], w.page_tokens,
-                                    w.partition_tokens, w.topk, w.topk_includes_forced, w.sink_pages,
-                                    w.recent_pages, page_map, r, pages, layer.scale, channels=chan)
-                   for (r, b, h, q, summ, page_map, pages, chan) in prepared]
+        results = [ostep.decode_row(*a[:-1], channels=a[-1]) for a in map(row_args, prepared)]
     dt = (time.perf_counter() - t0) / reps
     if limiter is not None:
         limiter.restore_original_limits() if hasattr(limiter, "restore_original_limits") else None
-    us_per_layer = dt * 1e6 * (w.rows / len(picked))
-    return picked, prepared, results, us_per_layer
+    scale = w.rows / len(picked)
+    us_per_layer = dt * 1e6 * scale
+    all_cores = None
+    if pool is not None:
+        wall, used, busiest = pool.run([row_args(p) for p in prepared], reps)
+        all_cores = dict(value=round(wall * 1e6 * scale, 1), unit="us/layer", cores=used,
+                         busiest_worker_us=round(busiest * 1e6, 1))
+    return picked, prepared, results, us_per_layer, all_cores
 
 
 def run_cfg4(args):
@@ -356,10 +476,19 @@ def run_setup(args):
 
 def main():
     args = parse_args()
+    if args.print_source_hash:
+        print(source_hash())
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (every stage is independent per (request, KV head) "
               "row and no collective is involved); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    # the all-cores leg of the CPU baseline runs in worker processes; they are created here, before anything
+    # touches the GPU (only the workloads that have a CPU leg need them)
+    pool = None
+    if not args.no_cpu and args.workload in ("cfg1", "cfg2", "cfg3", "cfg1_mean"):
+        pool = OraclePool()
 
     import numpy as np
     import torch
@@ -416,7 +545,9 @@ def main():
     torch.cuda.synchronize()
     assert layer.status() == 0, "device fault during warm-up"
 
-    # --- timed region: exactly K steps of the four-call sequence
+    # --- timed region: exactly K steps of the decode step as `run` issues it (by default the three-launch form:
+    # score, select+resolve in one launch, attention; --four-calls times the four separate stage calls instead;
+    # `step_launches` in the output says which, and the other form is timed right after for reference)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -425,6 +556,15 @@ def main():
     dt = time.perf_counter() - t0
     us_per_step = dt * 1e6 / args.steps
     assert layer.status() == 0, "device fault during the timed region"
+    # mean of three more runs of the same K steps, as a steadier figure beside `value` (which stays the first run)
+    more = []
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            run(i)
+        torch.cuda.synchronize()
+        more.append((time.perf_counter() - t0) * 1e6 / args.steps)
 
     # --- the other launch shape of the same step, for reference
     other = (run_three if one_launch_23 else run_12) if args.four_calls else run_four
@@ -438,6 +578,60 @@ def main():
             other(i)
         torch.cuda.synchronize()
         us_per_step_other = (time.perf_counter() - t0) * 1e6 / args.steps
+
+    # --- the same step recorded once per (query set, summary copy) pair in a HIP graph and replayed: the launch
+    # gaps of the host-issued step are replaced by the graph's own dispatch.  Checked against the eager bits.
+    us_per_step_graph = us_per_step_graph_many = graph_steps = None
+    if not args.no_graph:
+        import math as _m
+        ncomb = len(qsets) * len(summ_copies) // _m.gcd(len(qsets), len(summ_copies))
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            run(0)                                      # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graphs = []
+        for i in range(ncomb):
+            gph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gph):
+                run(i)
+            graphs.append(gph)
+        run(1)
+        torch.cuda.synchronize()
+        eager_bits = layer.out.view(torch.int16).clone()
+        layer.out.fill_(5.0)
+        graphs[1 % ncomb].replay()
+        torch.cuda.synchronize()
+        assert torch.equal(layer.out.view(torch.int16), eager_bits), "graph replay differs from the eager step"
+        for i in range(args.warmup):
+            graphs[i % ncomb].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[i % ncomb].replay()
+        torch.cuda.synchronize()
+        us_per_step_graph = (time.perf_counter() - t0) * 1e6 / args.steps
+        assert layer.status() == 0, "device fault during the graph replays"
+        del graphs
+        # one graph holding `ncomb` consecutive steps (as the layers of a model share one graph): the replay cost
+        # is paid once per `ncomb` steps
+        many = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(many):
+            for i in range(ncomb):
+                run(i)
+        nrep = max(1, args.steps // ncomb)
+        for _ in range(2):
+            many.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(nrep):
+            many.replay()
+        torch.cuda.synchronize()
+        us_per_step_graph_many = (time.perf_counter() - t0) * 1e6 / (nrep * ncomb)
+        graph_steps = ncomb
+        assert layer.status() == 0, "device fault during the graph replays"
+        del many
 
     # --- spread of the step time: the same K steps with a stream event between consecutive steps
     # (no host synchronisation inside; the event records cost a little, so `value` stays the
@@ -473,6 +667,25 @@ def main():
         sp.profile_enable(0)
         assert layer.status() == 0, "device fault during the event-bracketed pass"
 
+    # --- when the timed step attends the sink / recent pages beside stages 2+3: the plain three-launch step with
+    # the same event bracketing, to say what that side work costs the launch of stages 2+3 and what stage 4 takes
+    # over all pages
+    forced_split = (not args.four_calls) and sp.forced_split_supported
+    plain_kernels = {}
+    if forced_split and not args.no_kernel_events:
+        sp.profile_enable(args.steps)
+        for i in range(args.steps):
+            layer.step3(qsets[i % len(qsets)], summ_copies[i % len(summ_copies)])
+        torch.cuda.synchronize()
+        for name, label in (("select", "select+resolve"), ("decode", "decode")):
+            n, mean, mn = sp.profile_read(name)
+            if n:
+                plain_kernels[label] = dict(launches=n, mean_us=round(mean, 3), min_us=round(mn, 3))
+        sp.profile_read("score")
+        sp.profile_enable(0)
+        run(0)                                                         # leave the timed step's results in the buffers
+        torch.cuda.synchronize()
+
     # --- yardstick: a plain streaming read of 128 MiB per launch from the same pool (cold: the
     # launches walk through 2 GiB), timed with the same kernel events
     stream_gbps = None
@@ -499,13 +712,39 @@ def main():
     score_bytes = int(layer.summaries.numel())                         # summary bytes of the (padded) rows
     dec_us = kernels.get("decode", {}).get("mean_us") or None
     sc_us = kernels.get("score", {}).get("mean_us") or None
+    # bytes stage 4's launch itself moves: with the forced split, the sink / recent pages (whole pages: one-page
+    # partitions) were attended by the launch of stages 2+3
+    dec_bytes, side_bytes, side_us = kv_bytes, 0, 0.0
+    if forced_split:
+        for b in range(w.batch):
+            pages = w.pages(b)
+            lo, hi = min(w.sink_pages, pages), max(pages - w.recent_pages, 0)
+            forced_tokens = w.seq_lens[b] if lo >= hi else 16 * lo + (w.seq_lens[b] - 16 * hi)
+            side_bytes += forced_tokens * w.num_kv_heads * 2 * w.head_dim * 2
+        dec_bytes = kv_bytes - side_bytes
+        if plain_kernels.get("select+resolve") and kernels.get("select+resolve"):
+            side_us = max(0.0, kernels["select+resolve"]["mean_us"] - plain_kernels["select+resolve"]["mean_us"])
     roofline = None
+    attended = None
     if dec_us:
-        ach = kv_bytes / dec_us / 1e3                                  # GB/s
-        traffic = read_traffic(os.path.join(ROOT, "profiles", f"{args.workload}_stage_kernels_pmc.txt"))
-        roofline = dict(bound="hbm", kernel="spin_decode_tokens_kernel" if w.partition_tokens < 16 else "spin_decode_kernel", achieved=round(ach, 1), peak=PEAK_HBM_GBPS,
-                        unit="GB/s", frac=round(ach / PEAK_HBM_GBPS, 4), traffic=traffic,
-                        algorithmic_bytes=kv_bytes, whole_page_bytes=page_bytes, mean_us=dec_us)
+        # the metric's figure: all attended K/V bytes of the step over the time spent attending them (stage 4's
+        # launch plus what the side work adds to the launch of stages 2+3)
+        attended = dict(bytes=kv_bytes, us=round(dec_us + side_us, 3), gbps=round(kv_bytes / (dec_us + side_us) / 1e3, 1),
+                        pct_peak=round(100 * kv_bytes / (dec_us + side_us) / 1e3 / PEAK_HBM_GBPS, 2),
+                        side_bytes=side_bytes, side_us=round(side_us, 3))
+        ach = dec_bytes / dec_us / 1e3                                 # GB/s
+        kernel = "spin_decode_tokens_kernel<8>" if w.partition_tokens < 16 else \
+            f"spin_decode_kernel<{args.decode_waves or 8}, {args.decode_depth or 2}>"
+        traffic, traffic_note = read_traffic(os.path.join(ROOT, "profiles", f"{args.workload}_stage_kernels_pmc.txt"),
+                                             kernel)
+        roofline = dict(bound="hbm", kernel=kernel, achieved=round(ach, 1), peak=PEAK_HBM_GBPS,
+                        unit="GB/s", frac=round(ach / PEAK_HBM_GBPS, 4), traffic=traffic, traffic_note=traffic_note,
+                        algorithmic_bytes=dec_bytes, whole_page_bytes=page_bytes - side_bytes, mean_us=dec_us)
+        if plain_kernels.get("decode"):
+            pd = plain_kernels["decode"]["mean_us"]
+            roofline["all_pages_in_stage_4"] = dict(mean_us=pd, algorithmic_bytes=kv_bytes,
+                                                    achieved=round(kv_bytes / pd / 1e3, 1),
+                                                    frac=round(kv_bytes / pd / 1e3 / PEAK_HBM_GBPS, 4))
 
     # --- CPU oracle on a bounded sample of the same workload, same run
     cpu = None
@@ -514,7 +753,10 @@ def main():
         run(0)                                                         # query set 0, summary copy 0
         torch.cuda.synchronize()
         q_bits = qsets[0].view(torch.int16).cpu().numpy().view(np.uint16)
-        picked, prepared, results, cpu_us = cpu_oracle_leg(layer, natural, q_bits, args.cpu_rows, args.cpu_reps)
+        picked, prepared, results, cpu_us, cpu_all = cpu_oracle_leg(layer, natural, q_bits, args.cpu_rows,
+                                                                     args.cpu_reps, pool)
+        if pool is not None:
+            pool.close()
         from oracle import attend as oattend, bf16 as obf16
         out = obf16.decode(layer.out.view(torch.int16).cpu().numpy().view(np.uint16))
         page_ids = layer.page_ids.cpu().numpy()
@@ -535,7 +777,10 @@ def main():
                       ok=bool(worst <= 0.0))
         cpu = dict(value=round(cpu_us, 1), unit="us/layer", cores=1, kind="oracle",
                    sample=f"{len(picked)} of {w.rows} rows of the same step, {args.cpu_reps} repetitions, "
-                          f"scaled by {w.rows / len(picked):.0f}; host has {os.cpu_count()} logical CPUs")
+                          f"scaled by {w.rows / len(picked):.0f}; host has {os.cpu_count()} logical CPUs",
+                   all_cores=cpu_all, cpu_model=cpu_model(),
+                   note="all_cores: the same rows dealt to worker processes (one single-threaded oracle each), "
+                        "wall clock of the slowest, same scaling")
 
     line = {
         "metric": METRIC if args.workload == "cfg1" else f"sparse decode µs/layer + attended-KV HBM GB/s (% peak), {w.name}",
@@ -548,12 +793,19 @@ def main():
                    "partition_tokens": w.partition_tokens, "score": ["minmax", "sketch", "repmax"][w.score_kind],
                    "topk_partitions": w.topk, "decode_splits": sp.decode_splits, "decode_waves": args.decode_waves or 8, "query_sets": len(qsets),
                    "summary_copies": len(summ_copies)},
-        "attended_kv_gbps": roofline["achieved"] if roofline else None,
-        "attended_kv_pct_peak": round(100 * roofline["frac"], 2) if roofline else None,
+        "attended_kv_gbps": attended["gbps"] if attended else None,
+        "attended_kv_pct_peak": attended["pct_peak"] if attended else None,
+        "attended_kv": attended,
         "step_launches": "four stage calls" if args.four_calls else (
             "stages 1-3 in one call (stage 1 counts stage 2's histogram, stage 2's launch resolves), attention (3 launches)" if fused_12
-            else "score, select+resolve, attention (3 launches)"),
+            else ("score, select+resolve with the sink / recent pages attended on the side, attention over the "
+                  "other pages (3 launches)" if forced_split else "score, select+resolve, attention (3 launches)")),
+        "kernels_plain_three_launch_step": plain_kernels or None,
         ("us_per_layer_fused_calls" if args.four_calls else "us_per_layer_four_calls"): round(us_per_step_other, 2) if us_per_step_other else None,
+        "us_per_layer_repeats": [round(x, 2) for x in more],
+        "us_per_layer_graph_replay": round(us_per_step_graph, 2) if us_per_step_graph else None,
+        "us_per_layer_graph_replay_many": dict(value=round(us_per_step_graph_many, 2), steps_per_graph=graph_steps)
+        if us_per_step_graph_many else None,
         "us_per_layer_with_kernel_events": round(us_per_step_events, 2) if us_per_step_events else None,
         "us_per_layer_spread": step_spread,
         "kernel_us_sum": round(sum(k["mean_us"] for k in kernels.values()), 2) if kernels else None,

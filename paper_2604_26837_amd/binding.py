@@ -25,6 +25,7 @@ EXPORTS = [
     "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv", "spin_reclaim_tail", "spin_alloc_leaves", "spin_free_leaves",
     "spin_set_partition_tables", "spin_probe_stream_read", "spin_offload_pages", "spin_score_select_topk", "spin_score_select_resolve", "spin_pin_partitions",
     "spin_set_host_page_table", "spin_set_step", "spin_advance_step", "spin_sparse_decode_static",
+    "spin_select_resolve_forced", "spin_sparse_decode_rest",
 ]
 
 
@@ -82,6 +83,8 @@ def load_library() -> C.CDLL:
     lib.spin_resolve_slots.argtypes = [vp, i32, i32] + [vp] * 5 + [i64] + [vp] * 11
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_sparse_decode_static.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
+    lib.spin_select_resolve_forced.argtypes = [vp, i32] + [vp] * 7 + [i64] + [vp] * 6 + [i64, vp, vp]
+    lib.spin_sparse_decode_rest.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_probe_stream_read.argtypes = [vp, vp, C.c_size_t, vp, vp]
     lib.spin_set_partition_tables.argtypes = [vp, vp, vp, vp, vp]
     lib.spin_reclaim_tail.argtypes = [vp, i32, vp, vp, vp, vp, i64, vp, vp, vp]
@@ -381,3 +384,32 @@ class Spin:
             _ptr(npages, torch.int32, "npages"), _ptr(out, torch.bfloat16, "out"),
             _ptr(lse, torch.float32, "lse"), _ptr(status, torch.int32, "status"), _stream()),
             "spin_sparse_decode_static")
+
+    def select_resolve_forced(self, batch, scores, part_offsets, seq_lens, sel, nsel, dir_, leaf_pool, slots, page_ids,
+                              valid_mask, npages, q, kv_pool, ws):
+        pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192
+        self._check(self.lib.spin_select_resolve_forced(
+            self.h, batch, _ptr(scores, torch.float32, "scores"), _ptr(part_offsets, torch.int32, "part_offsets"),
+            _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(sel, torch.int32, "sel"), _ptr(nsel, torch.int32, "nsel"),
+            _ptr(dir_, torch.int32, "dir"), _ptr(leaf_pool, torch.int32, "leaf_pool"), leaf_pool.shape[0],
+            _ptr(slots, torch.int32, "slots"), _ptr(page_ids, torch.int32, "page_ids"),
+            _ptr(valid_mask, torch.int16, "valid_mask"), _ptr(npages, torch.int32, "npages"),
+            _ptr(q, torch.bfloat16, "q"), _ptr(kv_pool), pool_slots, _ptr(ws), _stream()),
+            "spin_select_resolve_forced")
+
+    def sparse_decode_rest(self, batch, q, kv_pool, slots, valid_mask, npages, out, lse, ws):
+        pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192
+        self._check(self.lib.spin_sparse_decode_rest(
+            self.h, batch, _ptr(q, torch.bfloat16, "q"), _ptr(kv_pool), pool_slots,
+            _ptr(slots, torch.int32, "slots"), _ptr(valid_mask, torch.int16, "valid_mask"),
+            _ptr(npages, torch.int32, "npages"), _ptr(out, torch.bfloat16, "out"),
+            _ptr(lse, torch.float32, "lse"), _ptr(ws), _stream()), "spin_sparse_decode_rest")
+
+    @property
+    def forced_split_supported(self) -> bool:
+        """Whether spin_select_resolve_forced / spin_sparse_decode_rest apply to this context (the library
+        decides; this mirrors its documented conditions so that a caller can choose its step up front)."""
+        c = self.cfg
+        pages = -(-c.max_context // 16)
+        return (c.lru_timestamps == 0 and c.partition_tokens == 16 and not c.variable_partitions and pages <= 4096
+                and 1 <= c.sink_pages + c.recent_pages <= 64)

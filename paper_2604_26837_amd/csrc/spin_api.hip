@@ -110,11 +110,16 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
     off += (size_t)x->max_rows * 4096 * sizeof(int32_t);
   }
   x->ws_zero_bytes = off;
+  x->ws_skip_off = off;
+  off += (size_t)x->max_rows * 2 * sizeof(int32_t);
+  off = (off + 255) & ~(size_t)255;
+  // workgroup partials of stage 4: one per split, plus one for the always-attended pages when the launch of
+  // stages 2+3 attends them
   x->ws_ml_off = off;
-  off += (size_t)x->max_rows * splits * group * 2 * sizeof(float);
+  off += (size_t)x->max_rows * (splits + 1) * group * 2 * sizeof(float);
   off = (off + 255) & ~(size_t)255;
   x->ws_acc_off = off;
-  off += (size_t)x->max_rows * splits * group * SPIN_HEAD_DIM * sizeof(float);
+  off += (size_t)x->max_rows * (splits + 1) * group * SPIN_HEAD_DIM * sizeof(float);
   x->ws_bytes = (off + 255) & ~(size_t)255;
   *out = x;
   return SPIN_OK;

@@ -47,6 +47,7 @@ struct spin_ctx {
   size_t ws_ticket_off, ws_ml_off, ws_acc_off;
   size_t ws_hist_off;     // per-row first-digit histograms of stage 2 for long rows; 0 = not used
   size_t ws_zero_bytes;   // leading part of the workspace that spin_workspace_init clears
+  size_t ws_skip_off;     // [max_rows][2] list positions attended by the launch of stages 2+3 (always-attended pages)
   spin_var var;           // registered partition tables (all NULL: uniform partitions)
   // CPU page table (Section 5.2): entry host_row_base[row] + logical page -> physical page of the pinned
   // host pool; table == NULL: the identity
@@ -69,6 +70,15 @@ typedef __attribute__((ext_vector_type(4))) short spin_s16x4;
     hipError_t e_ = (expr);                  \
     if (e_ != hipSuccess) return SPIN_ERR_HIP; \
   } while (0)
+
+// attention over a row's always-attended pages beside stages 2+3, the rest in stage 4: all-resident mode,
+// uniform one-page partitions, rows short enough for the 512-thread selection, few enough such pages for one
+// wavefront to look them up
+static inline bool spin_forced_split_supported(const spin_ctx *ctx) {
+  const spin_config &c = ctx->cfg;
+  return c.lru_timestamps == 0 && c.partition_tokens == SPIN_PAGE_TOKENS && !c.variable_partitions &&
+         ctx->max_parts <= 4096 && c.sink_pages + c.recent_pages >= 1 && c.sink_pages + c.recent_pages <= 64;
+}
 
 static inline int spin_launch_status() {
   return hipGetLastError() == hipSuccess ? SPIN_OK : SPIN_ERR_HIP;

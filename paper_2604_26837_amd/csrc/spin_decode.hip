@@ -20,242 +20,15 @@
 // header) merges them in split order, so results are reproducible.
 #include <mutex>
 
-#include "spin_common.h"
-
-#define NEG_INF (-__builtin_inff())
-
-struct page_regs {
-  uint4 k[4], v[4];
-};
-
-// Loads of a page.  A page whose mask is not full (token partitions, the ragged last page) only
-// fetches what its attended tokens need: in the K tile a lane holds 16 bytes of ONE token, in
-// the V tile 16 bytes of ONE token quad, so lanes of unattended tokens / quads issue no load
-// and hold zeros (their logits are masked and their probabilities are exactly zero, so the
-// result has the same bits as with the whole page loaded).
-__device__ inline void load_page(page_regs &r, const uint4 *__restrict__ pool, int slot, int lane, unsigned mask) {
-  const uint4 *kp = pool + (size_t)slot * SPIN_SLOT_U4 + lane;
-  if (mask == 0xffffu) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) r.k[j] = spin_nt_load(kp + j * 64);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) r.v[j] = spin_nt_load(kp + SPIN_KTILE_U4 + j * 64);
-  } else {
-    const bool kneed = (mask >> (lane & 15)) & 1u;
-    const bool vneed = ((mask >> (4 * (lane >> 4))) & 0xfu) != 0u;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) r.k[j] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) r.v[j] = make_uint4(0, 0, 0, 0);
-    if (kneed) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) r.k[j] = spin_nt_load(kp + j * 64);
-    }
-    if (vneed) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) r.v[j] = spin_nt_load(kp + SPIN_KTILE_U4 + j * 64);
-    }
-  }
-}
-
-struct softmax_state {
-  float m, l;
-  spin_f32x4 acc[8];
-};
-
-__device__ inline void consume_page(softmax_state &st, const page_regs &r, const spin_bf16x8 (&qf)[4],
-                                    unsigned mask, int c, float scale_log2e) {
-  // S[token 4c+i][head n]
-  spin_f32x4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(spin_bf16x8, r.k[j]), qf[j], s, 0, 0, 0);
-
-  const unsigned mbits = (mask >> (4 * c)) & 0xFu;
-  float sv[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) sv[i] = ((mbits >> i) & 1u) ? s[i] * scale_log2e : NEG_INF;
-  float pm = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-  pm = fmaxf(pm, __shfl_xor(pm, 16));
-  pm = fmaxf(pm, __shfl_xor(pm, 32));
-  const float m_new = fmaxf(st.m, pm);
-  const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
-  const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
-  float pr[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) pr[i] = __builtin_amdgcn_exp2f(sv[i] - m_safe);
-  st.l = st.l * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
-  st.m = m_new;
-
-  // rescale the accumulator rows (head 4c+i) by that head's alpha, only when some maximum moved
-  if (__any(alpha != 1.0f)) {
-    float ar[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) ar[i] = __shfl(alpha, 4 * c + i);
-#pragma unroll
-    for (int jn = 0; jn < 8; ++jn)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) st.acc[jn][i] *= ar[i];
-  }
-
-  // P as the A operand: row n = head, k = tokens 4c..4c+3
-  spin_bf16x2 p01 = {(__bf16)pr[0], (__bf16)pr[1]};
-  spin_bf16x2 p23 = {(__bf16)pr[2], (__bf16)pr[3]};
-  uint2 pk = {__builtin_bit_cast(uint32_t, p01), __builtin_bit_cast(uint32_t, p23)};
-  const spin_s16x4 pa = __builtin_bit_cast(spin_s16x4, pk);
-#pragma unroll
-  for (int jv = 0; jv < 4; ++jv) {
-    uint2 lo = {r.v[jv].x, r.v[jv].y}, hi = {r.v[jv].z, r.v[jv].w};
-    st.acc[2 * jv] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(spin_s16x4, lo),
-                                                               st.acc[2 * jv], 0, 0, 0);
-    st.acc[2 * jv + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(spin_s16x4, hi),
-                                                                   st.acc[2 * jv + 1], 0, 0, 0);
-  }
-}
-
-__device__ inline void write_out(uint16_t *__restrict__ out, float *__restrict__ lse, int qhead, int d, float M,
-                                 float L, float O) {
-  const float r = L > 0.f ? O / L : 0.f;
-  out[(size_t)qhead * SPIN_HEAD_DIM + d] = __builtin_bit_cast(uint16_t, (__bf16)r);
-  if (lse && d == 0) lse[qhead] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f : NEG_INF;
-}
-
-// After a workgroup's wavefronts have consumed their tiles: merge the wavefront partials through
-// LDS and, with several splits, the workgroup partials through the workspace (see the header).
-template <int WAVES>
-__device__ __forceinline__ void decode_finish(softmax_state &st, int row, int split, int b, int h, int lane, int wave,
-                                              int n, int c, int G, int Hq, int nsplit, float *part_ml, float *part_acc,
-                                              int32_t *tickets, uint16_t *__restrict__ out, float *__restrict__ lse) {
-  extern __shared__ float smem[];
-  float *s_acc = smem;                                  // [WAVES][G][128]
-  float *s_m = smem + WAVES * G * SPIN_HEAD_DIM;        // [WAVES][G]
-  float *s_l = s_m + WAVES * G;                         // [WAVES][G]
-  __shared__ int s_last;
-  // denominators: sum the four token-quad lanes of each head
-  float l = st.l;
-  l += __shfl_xor(l, 16);
-  l += __shfl_xor(l, 32);
-
-  // wavefront partials -> LDS
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int head = 4 * c + i;
-    if (head < G) {
-#pragma unroll
-      for (int jn = 0; jn < 8; ++jn) s_acc[(wave * G + head) * SPIN_HEAD_DIM + 16 * jn + n] = st.acc[jn][i];
-    }
-  }
-  if (c == 0 && n < G) {
-    s_m[wave * G + n] = st.m;
-    s_l[wave * G + n] = l;
-  }
-  __syncthreads();
-
-  for (int idx = threadIdx.x; idx < G * SPIN_HEAD_DIM; idx += WAVES * 64) {
-    const int g = idx >> 7, d = idx & 127;
-    float M = NEG_INF;
-#pragma unroll
-    for (int w = 0; w < WAVES; ++w) M = fmaxf(M, s_m[w * G + g]);
-    const float Ms = (M == NEG_INF) ? 0.f : M;
-    float L = 0.f, O = 0.f;
-#pragma unroll
-    for (int w = 0; w < WAVES; ++w) {
-      const float wgt = __builtin_amdgcn_exp2f(s_m[w * G + g] - Ms);
-      L += s_l[w * G + g] * wgt;
-      O += s_acc[(w * G + g) * SPIN_HEAD_DIM + d] * wgt;
-    }
-    if (nsplit == 1) {
-      write_out(out, lse, b * Hq + h * G + g, d, M, L, O);
-    } else {
-      // device-scope stores: written through to where every compute die sees them
-      const size_t pi = ((size_t)row * nsplit + split) * G + g;
-      spin_dev_store(&part_acc[pi * SPIN_HEAD_DIM + d], O);
-      if (d == 0) {
-        spin_dev_store(&part_ml[pi * 2 + 0], M);
-        spin_dev_store(&part_ml[pi * 2 + 1], L);
-      }
-    }
-  }
-  if (nsplit == 1) return;
-
-  // Ticket: the last workgroup of the row to arrive merges all splits in split
-  // order.  Partials travel through device-scope atomic stores and loads (no
-  // cache-wide write-back or invalidate); each thread waits for its own stores
-  // to be acknowledged, the barrier orders them before thread 0's ticket.
-  __builtin_amdgcn_s_waitcnt(0);
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __syncthreads();
-  if (threadIdx.x == 0)
-    s_last = (__hip_atomic_fetch_add(&tickets[row], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nsplit - 1);
-  __syncthreads();
-  if (!s_last) return;
-  // All loads of the merge are independent of each other: the (m, l) pairs are
-  // staged through LDS by one thread each, and every thread issues its
-  // accumulator loads eight splits at a time, the first batch before the
-  // barrier, so the merge costs about one memory round trip.
-  const size_t pbase = (size_t)row * nsplit * G;
-  float *t_m = s_acc, *t_l = s_acc + nsplit * G;   // s_acc is free: the wave partials were consumed above
-  constexpr int CH = 8;        // splits whose accumulators a thread requests at a time
-  constexpr int KPRE = 4;      // output elements per thread requested before the barrier (groups of up to
-                               // 16 heads with 8 wavefronts; further ones are requested in the loop)
-  constexpr int NT = WAVES * 64;
-  const int GD = G * SPIN_HEAD_DIM;
-  float a0[KPRE][CH];
-#pragma unroll
-  for (int k = 0; k < KPRE; ++k) {
-    const int idx = threadIdx.x + k * NT;
-    const int g = idx >> 7, d = idx & 127;
-#pragma unroll
-    for (int s = 0; s < CH; ++s)
-      a0[k][s] = (idx < GD && s < nsplit) ? spin_dev_load(&part_acc[(pbase + (size_t)s * G + g) * SPIN_HEAD_DIM + d]) : 0.f;
-  }
-  for (int i = threadIdx.x; i < nsplit * G; i += NT) {
-    t_m[i] = spin_dev_load(&part_ml[(pbase + i) * 2]);
-    t_l[i] = spin_dev_load(&part_ml[(pbase + i) * 2 + 1]);
-  }
-  __syncthreads();
-  // output element idx = (head g, channel d): the splits merged in split order
-  auto merge_one = [&](int idx, const float (&first)[CH], bool have_first) {
-    const int g = idx >> 7, d = idx & 127;
-    float M = NEG_INF;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, t_m[s * G + g]);
-    const float Ms = (M == NEG_INF) ? 0.f : M;
-    float L = 0.f, O = 0.f;
-    for (int s0 = 0; s0 < nsplit; s0 += CH) {
-      float a[CH];
-#pragma unroll
-      for (int s = 0; s < CH; ++s) {
-        if (have_first && s0 == 0) a[s] = first[s];
-        else a[s] = (s0 + s < nsplit) ? spin_dev_load(&part_acc[(pbase + (size_t)(s0 + s) * G + g) * SPIN_HEAD_DIM + d]) : 0.f;
-      }
-#pragma unroll
-      for (int s = 0; s < CH; ++s) {
-        if (s0 + s < nsplit) {
-          const float wgt = __builtin_amdgcn_exp2f(t_m[(s0 + s) * G + g] - Ms);
-          L += t_l[(s0 + s) * G + g] * wgt;
-          O += a[s] * wgt;
-        }
-      }
-    }
-    write_out(out, lse, b * Hq + h * G + g, d, M, L, O);
-  };
-#pragma unroll
-  for (int k = 0; k < KPRE; ++k) {
-    const int idx = threadIdx.x + k * NT;
-    if (idx < GD) merge_one(idx, a0[k], true);
-  }
-  for (int idx = threadIdx.x + KPRE * NT; idx < GD; idx += NT) merge_one(idx, a0[0], false);
-  if (threadIdx.x == 0)   // ready for the next launch
-    __hip_atomic_store(&tickets[row], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+#include "spin_decode_dev.h"
 
 template <int WAVES, int DEPTH>
 __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
     const uint16_t *__restrict__ q, const uint4 *__restrict__ pool, int64_t pool_slots,
     const int32_t *__restrict__ slots, const uint16_t *__restrict__ masks,
-    const int32_t *__restrict__ npages, int page_stride, int G, int Hq, int Hkv, int nsplit,
-    float scale_log2e, float *part_ml, float *part_acc, int32_t *tickets, uint16_t *__restrict__ out,
-    float *__restrict__ lse, int32_t *status) {
+    const int32_t *__restrict__ npages, int page_stride, int G, int Hq, int Hkv, int nsplit, int pstride,
+    const int32_t *__restrict__ skip, float scale_log2e, float *part_ml, float *part_acc, int32_t *tickets,
+    uint16_t *__restrict__ out, float *__restrict__ lse, int32_t *status) {
   const int row = blockIdx.x / nsplit;
   const int split = blockIdx.x - row * nsplit;
   const int lane = threadIdx.x & 63;
@@ -274,24 +47,35 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
   const int first = wave * nsplit + split, stride = WAVES * nsplit;
   int np = npages[row];
   np = np < 0 ? 0 : (np > page_stride ? page_stride : np);
-
-  // the group's queries as the B operand: column n = head, k = channels 32j+8c..+8
-  spin_bf16x8 qf[4];
-  {
-    const uint4 *qrow = (const uint4 *)(q + ((size_t)(b * Hq + h * G + (n < G ? n : 0))) * SPIN_HEAD_DIM);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      uint4 v = qrow[j * 4 + c];
-      if (n >= G) v = make_uint4(0, 0, 0, 0);
-      qf[j] = __builtin_bit_cast(spin_bf16x8, v);
-    }
+  // list positions [0, skip_lo) and [np - skip_hi, np) were attended by an earlier launch (the row's
+  // always-attended pages): they keep their place in the dealing but are not fetched or attended here
+  int skip_lo = 0, skip_hi = 0;
+  if (skip) {
+    skip_lo = skip[2 * row];
+    skip_hi = skip[2 * row + 1];
   }
+  const int keep_end = np - (skip_hi > 0 ? skip_hi : 0);
 
+  spin_bf16x8 qf[4];
+  load_queries(qf, q, b, h, G, Hq, n, c);
   softmax_state st;
-  st.m = NEG_INF;
-  st.l = 0.f;
+  softmax_reset(st);
+
+  // The first wavefront of a row starts from the partial (m, l, O) the earlier launch left for the row's
+  // always-attended pages instead of from the empty state: it then is part of the ordinary merge.
+  if (skip && split == 0 && wave == 0) {
+    const size_t pf = ((size_t)row * pstride + nsplit) * G;
+    if (n < G) {
+      st.m = part_ml[(pf + n) * 2];
+      if (c == 0) st.l = part_ml[(pf + n) * 2 + 1];   // the lanes' denominators are summed over c at the end
+    }
 #pragma unroll
-  for (int i = 0; i < 8; ++i) st.acc[i] = (spin_f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < 4; ++i)
+      if (4 * c + i < G) {
+#pragma unroll
+        for (int jn = 0; jn < 8; ++jn) st.acc[jn][i] = part_acc[(pf + 4 * c + i) * SPIN_HEAD_DIM + 16 * jn + n];
+      }
+  }
 
   // this wavefront's pages: first + i * stride, i < nw
   const int nw_max = (page_stride - first + stride - 1) / stride;   // entries that exist in the buffer
@@ -307,31 +91,20 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
     if (base >= nw) break;
     const int cnt = (nw - base) < 64 ? (nw - base) : 64;
     if (lane < cnt) {
-      if (myslot < 0 || (int64_t)myslot >= pool_slots) {
+      if (p < skip_lo || p >= keep_end) {
+        myslot = 0;   // attended elsewhere: nothing is fetched for an empty mask
+        mymask = 0;
+      } else if (myslot < 0 || (int64_t)myslot >= pool_slots) {
         spin_raise(status, SPIN_ERR_SLOT_RANGE);
         myslot = 0;   // read a valid slot, attend to none of it
         mymask = 0;
       }
     }
-    // ring of DEPTH register buffers: DEPTH-1 pages are in flight while one is consumed
-    page_regs r[DEPTH];
-#pragma unroll
-    for (int d = 0; d < DEPTH - 1; ++d)
-      if (d < cnt) load_page(r[d], pool, __builtin_amdgcn_readlane(myslot, d), lane,
-                             (unsigned)__builtin_amdgcn_readlane((int)mymask, d));
-    for (int i = 0; i < cnt; i += DEPTH) {
-#pragma unroll
-      for (int d = 0; d < DEPTH; ++d) {
-        const int ahead = i + d + DEPTH - 1;
-        if (ahead < cnt) load_page(r[(d + DEPTH - 1) % DEPTH], pool, __builtin_amdgcn_readlane(myslot, ahead), lane,
-                                   (unsigned)__builtin_amdgcn_readlane((int)mymask, ahead));
-        if (i + d < cnt)
-          consume_page(st, r[d], qf, (unsigned)__builtin_amdgcn_readlane((int)mymask, i + d), c, scale_log2e);
-      }
-    }
+    attend_lane_pages<DEPTH>(st, pool, myslot, mymask, cnt, lane, c, qf, scale_log2e);
   }
 
-  decode_finish<WAVES>(st, row, split, b, h, lane, wave, n, c, G, Hq, nsplit, part_ml, part_acc, tickets, out, lse);
+  decode_finish<WAVES>(st, row, split, b, h, lane, wave, n, c, G, Hq, nsplit, pstride, part_ml, part_acc, tickets, out,
+                       lse);
 }
 
 // ---------------------------------------------------------------------------
@@ -390,9 +163,9 @@ template <int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void spin_decode_tokens_kernel(
     const uint16_t *__restrict__ q, const uint4 *__restrict__ pool, int64_t pool_slots,
     const int32_t *__restrict__ slots, const uint16_t *__restrict__ masks,
-    const int32_t *__restrict__ npages, int page_stride, int G, int Hq, int Hkv, int nsplit,
-    float scale_log2e, float *part_ml, float *part_acc, int32_t *tickets, uint16_t *__restrict__ out,
-    float *__restrict__ lse, int32_t *status) {
+    const int32_t *__restrict__ npages, int page_stride, int G, int Hq, int Hkv, int nsplit, int pstride,
+    const int32_t *__restrict__ skip, float scale_log2e, float *part_ml, float *part_acc, int32_t *tickets,
+    uint16_t *__restrict__ out, float *__restrict__ lse, int32_t *status) {
   extern __shared__ float smem[];
   // the token lists live behind the merge buffers of decode_finish
   uint32_t *tok = (uint32_t *)(smem + WAVES * G * (SPIN_HEAD_DIM + 2)) + (threadIdx.x >> 6) * TOK_LIST;
@@ -475,17 +248,21 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_tokens_kernel(
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // before the next batch overwrites the list
   }
   __syncthreads();   // the merge buffers are separate from the lists, but keep the phases apart
-  decode_finish<WAVES>(st, row, split, b, h, lane, wave, n, c, G, Hq, nsplit, part_ml, part_acc, tickets, out, lse);
+  decode_finish<WAVES>(st, row, split, b, h, lane, wave, n, c, G, Hq, nsplit, pstride, part_ml, part_acc, tickets, out,
+                       lse);
 }
 
 // Host side of stage 4: checks, then the launch; the split-K scratch (row tickets, (m, l) pairs and
 // accumulators of the workgroup partials) and the status word are handed in by the two entry points.
+// skip != NULL: the row's always-attended pages were attended by the launch of stages 2+3, whose partial sits
+// behind the splits' partials and whose list positions are named in skip[row][2].
 static int decode_launch(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool, int64_t pool_slots,
                          const int32_t *slots, const uint16_t *valid_mask, const int32_t *npages, void *out,
                          float *lse, float *part_ml, float *part_acc, int32_t *tickets, int32_t *status,
-                         void *stream) {
+                         const int32_t *skip, void *stream) {
   const int rows = batch * ctx->cfg.num_kv_heads;
   const int G = ctx->group, nsplit = ctx->splits;
+  const int pstride = ctx->splits + 1;
   const float scale_log2e = ctx->scale * 1.4426950408889634f;
   const int W = ctx->waves;
   const size_t lds = (size_t)W * G * (SPIN_HEAD_DIM + 2) * sizeof(float);
@@ -495,15 +272,15 @@ static int decode_launch(spin_ctx *ctx, int32_t batch, const void *q, const void
     const size_t lds_tok = (size_t)8 * G * (SPIN_HEAD_DIM + 2) * sizeof(float) + (size_t)8 * TOK_LIST * sizeof(uint32_t);
     spin_launch(ctx, SPIN_K_DECODE, spin_decode_tokens_kernel<8>, dim3((unsigned)(rows * nsplit)), dim3(512), lds_tok,
                 (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, slots, valid_mask, npages,
-                ctx->page_stride, G, ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, scale_log2e, part_ml,
-                part_acc, tickets, (uint16_t *)out, lse, status);
+                ctx->page_stride, G, ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, pstride, skip, scale_log2e,
+                part_ml, part_acc, tickets, (uint16_t *)out, lse, status);
     return spin_launch_status();
   }
 #define SPIN_DECODE_LAUNCH2(WV, DP)                                                                              \
   spin_launch(ctx, SPIN_K_DECODE, spin_decode_kernel<WV, DP>, dim3((unsigned)(rows * nsplit)), dim3(WV * 64), lds, \
               (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, slots, valid_mask,   \
-              npages, ctx->page_stride, G, ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, scale_log2e,     \
-              part_ml, part_acc, tickets, (uint16_t *)out, lse, status)
+              npages, ctx->page_stride, G, ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, pstride, skip,   \
+              scale_log2e, part_ml, part_acc, tickets, (uint16_t *)out, lse, status)
 #define SPIN_DECODE_LAUNCH(WV)                          \
   do {                                                  \
     if (ctx->depth == 2) SPIN_DECODE_LAUNCH2(WV, 2);    \
@@ -529,7 +306,25 @@ extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, c
   char *ws = (char *)workspace;
   return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
                        (float *)(ws + ctx->ws_ml_off), (float *)(ws + ctx->ws_acc_off),
-                       (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace, stream);
+                       (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace, nullptr, stream);
+}
+
+// Stage 4 over what spin_select_resolve_forced left: the pages other than the always-attended ones, merged
+// with the partial that launch stored for them.
+extern "C" int spin_sparse_decode_rest(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool,
+                                       int64_t pool_slots, const int32_t *slots, const uint16_t *valid_mask,
+                                       const int32_t *npages, void *out, float *lse, void *workspace,
+                                       void *stream) {
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || pool_slots <= 0) return SPIN_ERR_INVALID;
+  if (!spin_forced_split_supported(ctx)) return SPIN_ERR_UNSUPPORTED;
+  if (batch == 0) return SPIN_OK;
+  if (!q || !kv_pool || !slots || !valid_mask || !npages || !out) return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  char *ws = (char *)workspace;
+  return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
+                       (float *)(ws + ctx->ws_ml_off), (float *)(ws + ctx->ws_acc_off),
+                       (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace,
+                       (const int32_t *)(ws + ctx->ws_skip_off), stream);
 }
 
 // ---------------------------------------------------------------------------
@@ -575,7 +370,7 @@ extern "C" int spin_sparse_decode_static(spin_ctx *ctx, int32_t batch, const voi
   if (!q || !kv_pool || !slots || !valid_mask || !npages || !out) return SPIN_ERR_INVALID;
   // layout inside the array, sized for this call's rows: [status word, 256 B][tickets][(m, l)][accumulators]
   const size_t rows = (size_t)batch * ctx->cfg.num_kv_heads;
-  const size_t partials = rows * ctx->splits * ctx->group;
+  const size_t partials = rows * (ctx->splits + 1) * ctx->group;   // one spare partial per row (not used here)
   const size_t ticket_off = SPIN_WS_HEADER;
   const size_t ml_off = (ticket_off + rows * sizeof(int32_t) + 255) & ~(size_t)255;
   const size_t acc_off = (ml_off + partials * 2 * sizeof(float) + 255) & ~(size_t)255;
@@ -592,5 +387,5 @@ extern "C" int spin_sparse_decode_static(spin_ctx *ctx, int32_t batch, const voi
   if (hipGetLastError() != hipSuccess) return SPIN_ERR_HIP;
   return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
                        (float *)(sc + ml_off), (float *)(sc + acc_off), (int32_t *)(sc + ticket_off),
-                       status ? status : (int32_t *)sc, stream);
+                       status ? status : (int32_t *)sc, nullptr, stream);
 }

@@ -32,6 +32,12 @@ struct res_out {
   uint16_t *mask;
 };
 
+__device__ inline void res_put(const res_out &o, int pos, int32_t slot, int32_t page, uint32_t mask) {
+  o.slots[pos] = slot;
+  o.page_ids[pos] = page;
+  o.mask[pos] = (uint16_t)mask;
+}
+
 #define RES_DIR_LDS 256
 
 // `dir` points at the row's directory entries (a copy in LDS when it fits)
@@ -51,9 +57,7 @@ __device__ inline void emit_page(const res_out &o, int pos, int page_stride, int
       mask = 0;
     }
   }
-  o.slots[pos] = slot;
-  o.page_ids[pos] = page;
-  o.mask[pos] = (uint16_t)mask;
+  res_put(o, pos, slot, page, mask);
 }
 
 // A selection entry outside the row: its output position holds no page (nothing of a previous
@@ -61,9 +65,7 @@ __device__ inline void emit_page(const res_out &o, int pos, int page_stride, int
 __device__ inline void emit_invalid(const res_out &o, int pos, int page_stride, int32_t *status) {
   spin_raise(status, SPIN_ERR_INVALID);
   if (pos < 0 || pos >= page_stride) return;
-  o.slots[pos] = -1;
-  o.page_ids[pos] = -1;
-  o.mask[pos] = 0;
+  res_put(o, pos, -1, -1, 0);
 }
 
 // Resolves one row with the calling workgroup of RES_BLOCK threads; `ns` = the
@@ -170,7 +172,7 @@ __device__ inline void resolve_row(
                 leaf_chunks, row, dir_stride, leaf_entries, status);
     }
     const int total = min(carry + extraA + extraB, page_stride);
-    for (int i = total + tid; i < page_stride; i += RES_BLOCK) { o.slots[i] = -1; o.page_ids[i] = -1; o.mask[i] = 0; }
+    for (int i = total + tid; i < page_stride; i += RES_BLOCK) res_put(o, i, -1, -1, 0);
     if (tid == 0) npages[row] = total;
   } else if (tp == 16) {
     // partition == page: the selection is the page list.  The entry is loaded
@@ -189,7 +191,7 @@ __device__ inline void resolve_row(
       if (i0 + RES_BLOCK >= ns) break;
     }
     const int total = min(ns, page_stride);
-    for (int i = total + tid; i < page_stride; i += RES_BLOCK) { o.slots[i] = -1; o.page_ids[i] = -1; o.mask[i] = 0; }
+    for (int i = total + tid; i < page_stride; i += RES_BLOCK) res_put(o, i, -1, -1, 0);
     if (tid == 0) npages[row] = total;
   } else if (tp > 16) {
     const int m = tp >> 4;
@@ -250,7 +252,7 @@ __device__ inline void resolve_row(
       total -= max((last + 1) * m - pages, 0);
     }
     total = min(total, page_stride);
-    for (int i = total + tid; i < page_stride; i += RES_BLOCK) { o.slots[i] = -1; o.page_ids[i] = -1; o.mask[i] = 0; }
+    for (int i = total + tid; i < page_stride; i += RES_BLOCK) res_put(o, i, -1, -1, 0);
     if (tid == 0) npages[row] = total;
   } else {
     const int ppp = 16 / tp;   // partitions per page
@@ -279,7 +281,7 @@ __device__ inline void resolve_row(
       carry += tot;
     }
     const int total = min(carry, page_stride);
-    for (int i = total + tid; i < page_stride; i += RES_BLOCK) { o.slots[i] = -1; o.page_ids[i] = -1; o.mask[i] = 0; }
+    for (int i = total + tid; i < page_stride; i += RES_BLOCK) res_put(o, i, -1, -1, 0);
     if (tid == 0) npages[row] = total;
   }
 }

@@ -3,6 +3,7 @@
 // that selected a row resolves it straight away: the same device functions run
 // as in the two stage calls, the results are the same bits, and one launch with
 // its start-up latency chain is saved.
+#include "spin_decode_dev.h"
 #include "spin_resolve_dev.h"
 #include "spin_select_dev.h"
 
@@ -20,6 +21,164 @@ __global__ __launch_bounds__(BLOCK) void spin_select_resolve_kernel(
   __syncthreads();   // the selection was written by this workgroup: visible to all its threads from here
   resolve_row<BLOCK>(row, take, sel, seq_lens, dir, leaf_pool, leaf_chunks, Hkv, tp, sink_pages, recent_pages,
                      sel_stride, page_stride, dir_stride, leaf_entries, slots, page_ids, valid_mask, npages, status, var);
+}
+
+// ---------------------------------------------------------------------------
+// The always-attended pages of a row (its first sink_pages and last recent_pages pages; one-page
+// partitions) do not depend on the selection, so they can be attended while stages 2+3 run: those
+// are latency-bound on one workgroup per row and leave the other half of the chip and the memory
+// system idle.  A second set of workgroups in the same launch, one per row, looks these pages up
+// in the two-level table itself, attends them with stage 4's tile code and stores one partial
+// (m, l, O) per query head behind the row's split partials; it also records how many leading and
+// trailing entries of the row's page list they are (stage 3 lists pages in ascending order, so
+// the sink pages open the list and the recent pages close it).  Stage 4 then skips those entries
+// and its first wavefront of the row starts from that partial instead of from the empty state.
+// The always-attended pages of a row as one list: j < nlo is sink page j, the others are the recent
+// pages from recent_begin on.  Looks entry j up for the calling lane (all lanes of the wavefront call;
+// `active` says whether the lane has an entry): slot and token mask, or an empty mask when the page is
+// not resident (stage 3 reports that).
+__device__ inline void forced_lookup(bool active, int j, int nlo, int recent_begin, int N, int32_t mydir,
+                                     bool dir_in_lanes, const int32_t *__restrict__ dir,
+                                     const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, int row,
+                                     int dir_stride, int leaf_entries, int64_t pool_slots, int &myslot,
+                                     unsigned &mymask) {
+  const int page = j < nlo ? j : recent_begin + (j - nlo);
+  int32_t s = -1;
+  if (dir_in_lanes) {
+    const int ci = active ? page / leaf_entries : 0;
+    const int32_t chunk = __shfl(mydir, ci < dir_stride ? ci : 0);   // every lane takes part in the exchange
+    if (active && ci < dir_stride && chunk >= 0 && (int64_t)chunk < leaf_chunks)
+      s = leaf_pool[(size_t)chunk * leaf_entries + (page - ci * leaf_entries)];
+  } else if (active) {
+    s = spin_walk(dir, leaf_pool, leaf_chunks, row, dir_stride, leaf_entries, page);
+  }
+  myslot = 0;
+  mymask = 0;
+  if (s >= 0 && (int64_t)s < pool_slots) {
+    myslot = s;
+    mymask = page_mask(page, N);
+  }
+}
+
+struct forced_span {
+  int nlo, nhi, recent_begin;
+};
+// the same rule as stages 2 and 3: a context no longer than the two windows is attended whole
+__device__ inline forced_span forced_pages_of(int N, int sink_pages, int recent_pages) {
+  const int pages = (N + 15) >> 4;
+  int sink_end = min(sink_pages, pages);
+  int recent_begin = max(pages - recent_pages, 0);
+  if (sink_end >= recent_begin) { sink_end = pages; recent_begin = pages; }
+  return forced_span{sink_end, pages - recent_begin, recent_begin};
+}
+
+template <int WAVES>
+__device__ inline void attend_forced_row(
+    int row, const uint16_t *__restrict__ q, const uint4 *__restrict__ pool, int64_t pool_slots,
+    const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ dir, const int32_t *__restrict__ leaf_pool,
+    int64_t leaf_chunks, int Hkv, int G, int Hq, int sink_pages, int recent_pages, int dir_stride, int leaf_entries,
+    int nsplit, int pstride, float scale_log2e, float *part_ml, float *part_acc, int32_t *skip) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = lane & 15, c = lane >> 4;
+  const int b = row / Hkv, h = row - b * Hkv;
+
+  spin_bf16x8 qf[4];
+  load_queries(qf, q, b, h, G, Hq, n, c);
+  // the row's directory entries, one per lane, requested together with the context length, so that the leaf
+  // entries are the only dependent table access (directories of more than 64 entries are walked page by page)
+  const bool dir_in_lanes = dir_stride <= 64;
+  int32_t mydir = -1;
+  if (dir_in_lanes && lane < dir_stride) mydir = dir[(size_t)row * dir_stride + lane];
+  const int N = seq_lens[b];
+  const forced_span fs = forced_pages_of(N, sink_pages, recent_pages);
+  const int nlo = fs.nlo, nhi = fs.nhi, recent_begin = fs.recent_begin;
+  const int nf = min(nlo + nhi, 64);            // the host admits at most 64 such pages
+  if (threadIdx.x == 0) {
+    skip[2 * row] = nlo;
+    skip[2 * row + 1] = nhi;
+  }
+  // lane i looks up the i-th page of this wavefront: pages wave, wave + WAVES, ... of the list above
+  const int cnt = nf > wave ? (nf - wave + WAVES - 1) / WAVES : 0;
+  int myslot = 0;
+  unsigned mymask = 0;
+  forced_lookup(lane < cnt, wave + WAVES * lane, nlo, recent_begin, N, mydir, dir_in_lanes, dir, leaf_pool, leaf_chunks, row,
+                dir_stride, leaf_entries, pool_slots, myslot, mymask);
+  softmax_state st;
+  softmax_reset(st);
+  attend_lane_pages<2>(st, pool, myslot, mymask, cnt, lane, c, qf, scale_log2e);
+  decode_finish<WAVES>(st, row, SPIN_ONLY_PARTIAL, b, h, lane, wave, n, c, G, Hq, nsplit, pstride, part_ml,
+                       part_acc, nullptr, nullptr, nullptr);
+}
+
+struct spin_forced_args {
+  const uint16_t *q;
+  const uint4 *pool;
+  int64_t pool_slots;
+  int G, Hq, nsplit, pstride;
+  float scale_log2e;
+  float *part_ml, *part_acc;
+  int32_t *skip;
+};
+
+// workgroups [0, rows): stages 2+3 of a row, exactly as spin_select_resolve_kernel;
+// workgroups [rows, 2 rows): attention over the always-attended pages of row blockIdx.x - rows
+template <int KPT>
+__global__ __launch_bounds__(512) void spin_select_resolve_forced_kernel(
+    int rows, const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
+    const int32_t *__restrict__ seq_lens, int Hkv, int tp, int topk, int includes_forced, int sink_pages,
+    int recent_pages, int sel_stride, int32_t *sel, int32_t *nsel, const int32_t *dir,
+    const int32_t *__restrict__ leaf_pool, int64_t leaf_chunks, int page_stride, int dir_stride, int leaf_entries,
+    int32_t *__restrict__ slots, int32_t *__restrict__ page_ids, uint16_t *__restrict__ valid_mask,
+    int32_t *__restrict__ npages, int32_t *status, spin_forced_args fa) {
+  if ((int)blockIdx.x >= rows) {
+    attend_forced_row<8>((int)blockIdx.x - rows, fa.q, fa.pool, fa.pool_slots, seq_lens, dir, leaf_pool, leaf_chunks, Hkv,
+                         fa.G, fa.Hq, sink_pages, recent_pages, dir_stride, leaf_entries, fa.nsplit, fa.pstride,
+                         fa.scale_log2e, fa.part_ml, fa.part_acc, fa.skip);
+    return;
+  }
+  const int row = blockIdx.x;
+  const int take = select_reg_row<512, KPT>(scores, part_offsets, seq_lens, Hkv, tp, topk, includes_forced,
+                                            sink_pages, recent_pages, sel_stride, sel, nsel, row, spin_var{});
+  __syncthreads();   // the selection was written by this workgroup: visible to all its threads from here
+  resolve_row<512>(row, take, sel, seq_lens, dir, leaf_pool, leaf_chunks, Hkv, tp, sink_pages, recent_pages,
+                   sel_stride, page_stride, dir_stride, leaf_entries, slots, page_ids, valid_mask, npages, status,
+                   spin_var{});
+}
+
+extern "C" int spin_select_resolve_forced(spin_ctx *ctx, int32_t batch, const float *scores,
+                                          const int32_t *part_offsets, const int32_t *seq_lens, int32_t *sel,
+                                          int32_t *nsel, const int32_t *dir, const int32_t *leaf_pool,
+                                          int64_t leaf_chunks, int32_t *slots, int32_t *page_ids,
+                                          uint16_t *valid_mask, int32_t *npages, const void *q, const void *kv_pool,
+                                          int64_t pool_slots, void *workspace, void *stream) {
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || leaf_chunks <= 0 || pool_slots <= 0) return SPIN_ERR_INVALID;
+  if (!spin_forced_split_supported(ctx) || ctx->var.count) return SPIN_ERR_UNSUPPORTED;
+  if (batch == 0) return SPIN_OK;
+  if (!scores || !part_offsets || !seq_lens || !sel || !nsel || !dir || !leaf_pool || !slots || !page_ids ||
+      !valid_mask || !npages || !q || !kv_pool)
+    return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  const spin_config &c = ctx->cfg;
+  const int rows = batch * c.num_kv_heads;
+  char *ws = (char *)workspace;
+  const spin_forced_args fa = {(const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, ctx->group, c.num_q_heads,
+                               ctx->splits, ctx->splits + 1, ctx->scale * 1.4426950408889634f,
+                               (float *)(ws + ctx->ws_ml_off), (float *)(ws + ctx->ws_acc_off),
+                               (int32_t *)(ws + ctx->ws_skip_off)};
+  // dynamic LDS: the merge buffers of the attention workgroups (8 wavefronts)
+  const size_t lds = (size_t)8 * ctx->group * (SPIN_HEAD_DIM + 2) * sizeof(float);
+#define SPIN_SRF_ARGS                                                                                         \
+  dim3((unsigned)(2 * rows)), dim3(512), lds, (hipStream_t)stream, rows, scores, part_offsets, seq_lens,      \
+      c.num_kv_heads, c.partition_tokens, c.topk, c.topk_includes_forced, c.sink_pages, c.recent_pages,       \
+      ctx->sel_stride, sel, nsel, dir, leaf_pool, leaf_chunks, ctx->page_stride, ctx->dir_stride,             \
+      c.leaf_entries, slots, page_ids, valid_mask, npages, (int32_t *)workspace, fa
+  if (ctx->max_parts <= 2048)
+    spin_launch(ctx, SPIN_K_SELECT, spin_select_resolve_forced_kernel<4>, SPIN_SRF_ARGS);
+  else
+    spin_launch(ctx, SPIN_K_SELECT, spin_select_resolve_forced_kernel<8>, SPIN_SRF_ARGS);
+#undef SPIN_SRF_ARGS
+  return spin_launch_status();
 }
 
 // hist_ready: stage 1 of this step has filled the long-row histograms already

@@ -23,6 +23,7 @@ class LayerState:
         workload's ``partition_tokens`` is then the largest partition allowed."""
         self.w = w
         self.device = device
+        self.layouts_none = layouts is None
         if layouts is not None:
             cfg_over = dict(cfg_over, variable_partitions=1)
         self.spin = binding.Spin.for_workload(w, **cfg_over)
@@ -130,10 +131,25 @@ class LayerState:
         sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
                          self.ws)
 
+    def step3f(self, q: torch.Tensor, summaries: Optional[torch.Tensor] = None):
+        """Three launches, and the launch of stages 2+3 also attends the sink / recent pages on the compute
+        units it leaves idle; stage 4 covers the rest of the page list and merges that partial."""
+        sp, w = self.spin, self.w
+        summ = self.summaries if summaries is None else summaries
+        sp.score_partitions(w.batch, q, summ, self.chan, self.part_offsets, self.seq_lens, self.scores, self.ws)
+        sp.select_resolve_forced(w.batch, self.scores, self.part_offsets, self.seq_lens, self.sel, self.nsel, self.dir,
+                                 self.leaf_pool, self.slots, self.page_ids, self.valid_mask, self.npages, q,
+                                 self.kv_pool, self.ws)
+        sp.sparse_decode_rest(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
+                              self.ws)
+
     def step_fused(self, q: torch.Tensor, summaries: Optional[torch.Tensor] = None):
         """The step in the fewest launches the row length allows (what ``bench.py`` times): stages 2+3 in one
-        launch for rows of at most 16384 partitions, stages 1-3 in one call for longer ones."""
-        if max(self.w.partitions(b) for b in range(self.w.batch)) <= 16384:
+        launch for rows of at most 16384 partitions (with the sink / recent pages attended beside them where
+        that applies), stages 1-3 in one call for longer ones."""
+        if self.spin.forced_split_supported and self.layouts_none:
+            self.step3f(q, summaries)
+        elif max(self.w.partitions(b) for b in range(self.w.batch)) <= 16384:
             self.step3(q, summaries)
         else:
             self.step123(q, summaries)

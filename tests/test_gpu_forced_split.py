@@ -1,0 +1,123 @@
+"""spin_select_resolve_forced + spin_sparse_decode_rest: stages 2+3 whose launch also attends the row's sink and
+recent pages, and the stage 4 that covers the rest of the page list and merges that partial.  Stages 2+3 must
+give the bits of spin_select_resolve; the attention output is held to stage 4's tolerance against the oracle on
+the GPU's own page list, and must be the same bits from run to run."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attend, bf16
+from paper_2604_26837_amd import binding, runner, synth
+
+pytestmark = pytest.mark.gpu
+ATOL, RTOL = 2e-2, 1e-2
+
+
+def _layer(w, **over):
+    data = synth.generate(w, spare_slots=2)
+    natural = torch.from_numpy(data.pool_bits.view(np.int16).copy()).to("cuda:0").view(torch.bfloat16)
+    layer = runner.LayerState.from_natural_pool(w, data.slot_of, natural, **over)
+    layer.build_summaries()
+    q = torch.from_numpy(data.q_bits.view(np.int16).copy()).to("cuda:0").view(torch.bfloat16)
+    return data, layer, q
+
+
+def _oracle_out(w, data, layer):
+    """fp64 attention per row over the page list, slots and masks the GPU produced."""
+    slots, npages = layer.slots.cpu().numpy(), layer.npages.cpu().numpy()
+    masks = layer.valid_mask.cpu().numpy().view(np.uint16)
+    g = w.group
+    ref = np.zeros((w.batch, w.num_q_heads, w.head_dim))
+    lse = np.zeros((w.batch, w.num_q_heads))
+    for r in range(w.rows):
+        b, h = divmod(r, w.num_kv_heads)
+        keep = [(int(s), int(m)) for s, m in zip(slots[r, :npages[r]], masks[r, :npages[r]]) if s >= 0]
+        pages = bf16.decode(data.pool_bits[np.asarray([s for s, _ in keep], dtype=np.int64)]) if keep else \
+            np.zeros((0, 2, 16, w.head_dim))
+        ks, vs = attend.gather_tokens(pages[:, 0], pages[:, 1], [m for _, m in keep])
+        o, l = attend.attend(bf16.decode(data.q_bits[b, h * g:(h + 1) * g]), ks, vs, layer.scale)
+        ref[b, h * g:(h + 1) * g], lse[b, h * g:(h + 1) * g] = o, l
+    return ref, lse
+
+
+def _bits(t):
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+CASES = {
+    # name: (workload, config overrides)
+    "cfg0": (synth.config0(), {}),
+    "ragged_4_sinks_8_recents": (synth.config0().with_(
+        seq_lens=(4096, 1000, 2049, 40, 16 * 12, 5, 16 * 13 + 1, 3000), num_q_heads=8, num_kv_heads=2, topk=40,
+        sink_pages=4, recent_pages=8, name="forced_ragged"), {}),
+    "one_split": (synth.config0().with_(seq_lens=(4096, 700), topk=24, sink_pages=2, recent_pages=3,
+                                        name="forced_1split"), dict(decode_splits=1)),
+    "three_splits_group8": (synth.config0().with_(seq_lens=(3000, 4096, 17), num_q_heads=16, num_kv_heads=2, topk=50,
+                                                  sink_pages=3, recent_pages=5, name="forced_g8"),
+                            dict(decode_splits=3)),
+    "group1_recent_only": (synth.config0().with_(seq_lens=(2500, 1300), num_q_heads=2, num_kv_heads=2, topk=20,
+                                                 sink_pages=0, recent_pages=6, name="forced_g1"),
+                           dict(decode_splits=2, decode_waves=4)),
+    "rows_up_to_4096_pages": (synth.config0().with_(seq_lens=(65536, 40000), num_q_heads=8, num_kv_heads=2, topk=64,
+                                                    sink_pages=8, recent_pages=56, name="forced_long"), {}),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_forced_pages_attended_beside_stages_2_and_3(name):
+    w, over = CASES[name]
+    data, layer, q = _layer(w, **over)
+    assert layer.spin.forced_split_supported
+    layer.step3(q)
+    torch.cuda.synchronize()
+    assert layer.status() == 0
+    plain = dict(sel=layer.sel.clone(), nsel=layer.nsel.clone(), slots=layer.slots.clone(),
+                 page_ids=layer.page_ids.clone(), mask=layer.valid_mask.clone(), npages=layer.npages.clone())
+    plain_out = bf16.decode(_bits(layer.out))
+    for t in (layer.sel, layer.slots, layer.page_ids):
+        t.fill_(-7)
+    layer.out.fill_(3.0)
+    layer.step3f(q)
+    torch.cuda.synchronize()
+    assert layer.status() == 0
+    # stages 2+3: the same bits as the plain launch
+    for k, t in (("sel", layer.sel), ("nsel", layer.nsel), ("slots", layer.slots), ("page_ids", layer.page_ids),
+                 ("mask", layer.valid_mask), ("npages", layer.npages)):
+        assert torch.equal(t, plain[k]), k
+    # stage 4 against the oracle on the GPU's own page list
+    ref, lref = _oracle_out(w, data, layer)
+    out = bf16.decode(_bits(layer.out))
+    err = np.abs(out - ref)
+    assert (err <= ATOL + RTOL * np.abs(ref)).all(), f"max err {err.max()}"
+    assert (np.abs(out - plain_out) <= 2 * (ATOL + RTOL * np.abs(ref))).all()
+    lse = layer.lse.cpu().numpy().astype(np.float64)
+    fin = np.isfinite(lref)
+    assert np.array_equal(np.isfinite(lse), fin) and np.allclose(lse[fin], lref[fin], rtol=2e-3, atol=2e-3)
+    # the same bits from run to run, also after other work has used the workspace
+    first = _bits(layer.out).copy()
+    layer.step(q)
+    for _ in range(3):
+        layer.out.fill_(1.0)
+        layer.step3f(q)
+        torch.cuda.synchronize()
+        assert np.array_equal(_bits(layer.out), first)
+
+
+def test_forced_page_that_is_not_resident_is_reported_and_skipped():
+    w = synth.config0().with_(seq_lens=(4096, 2000), topk=24, sink_pages=2, recent_pages=3, name="forced_missing")
+    data, layer, q = _layer(w, decode_splits=2)
+    # drop the mapping of sink page 1 of row 0 and of the last page of row 3
+    d = layer.dir.cpu().numpy()
+    leaf = layer.leaf_pool.cpu().numpy().copy()
+    leaf[d[0, 0], 1] = -1
+    last = w.pages(1) - 1
+    leaf[d[3, last // w.leaf_entries], last % w.leaf_entries] = -1
+    layer.leaf_pool.copy_(torch.from_numpy(leaf))
+    layer.step3f(q)
+    torch.cuda.synchronize()
+    assert binding.STATUS_NAMES[layer.status()] == "SPIN_ERR_NOT_RESIDENT"
+    slots, npages = layer.slots.cpu().numpy(), layer.npages.cpu().numpy()
+    assert slots[0, 1] == -1 and slots[3, npages[3] - 1] == -1
+    ref, _ = _oracle_out(w, data, layer)          # over the pages that are resident
+    out = bf16.decode(_bits(layer.out))
+    assert (np.abs(out - ref) <= ATOL + RTOL * np.abs(ref)).all()

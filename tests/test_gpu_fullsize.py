@@ -119,9 +119,17 @@ def test_config1_headline_all_rows():
     layer.step_fused(layer.q0)
     torch.cuda.synchronize()
     assert torch.equal(a.view(torch.int16), layer.out.view(torch.int16))
-    layer.step(layer.q0)                       # and the four stage calls give the same bits
+    # the four stage calls and the plain three-launch step agree bit for bit; the timed step attends the sink and
+    # recent pages beside stages 2+3 and merges them in another order, so it agrees to stage 4's tolerance
+    layer.step(layer.q0)
     torch.cuda.synchronize()
-    assert torch.equal(a.view(torch.int16), layer.out.view(torch.int16))
+    four = layer.out.clone()
+    sel4, slots4 = layer.sel.clone(), layer.slots.clone()
+    layer.step3(layer.q0)
+    torch.cuda.synchronize()
+    assert torch.equal(four.view(torch.int16), layer.out.view(torch.int16))
+    assert torch.equal(sel4, layer.sel) and torch.equal(slots4, layer.slots)
+    assert (a.float() - four.float()).abs().max().item() <= 2 * ATOL
     print("cfg1 rows in the rounding band:", band)
 
 
