@@ -131,6 +131,23 @@ def test_config1_headline_all_rows():
     assert torch.equal(sel4, layer.sel) and torch.equal(slots4, layer.slots)
     assert (a.float() - four.float()).abs().max().item() <= 2 * ATOL
     print("cfg1 rows in the rounding band:", band)
+    # The split-K merge hands partials from one workgroup to another inside a launch (device-scope stores, a
+    # ticket, device-scope loads): 500 launches over 8 query sets, in both forms of stage 4, must reproduce the
+    # bits of the first pass over each set.
+    qsets = [layer.q0] + [synth.make_queries_on_device(w, w.seed + 1000 + i, "cuda:0") for i in range(1, 8)]
+    for step_fn in (layer.step_fused, layer.step):
+        first = []
+        for q in qsets:
+            step_fn(q)
+            first.append(layer.out.clone())
+        bad = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+        for i in range(500):
+            step_fn(qsets[i % 8])
+            bad += (layer.out.view(torch.int16) != first[i % 8].view(torch.int16)).any().to(torch.int32)
+            if i % 50 == 49 and int(bad.item()):
+                break
+        assert int(bad.item()) == 0, f"{step_fn.__name__}: output bits changed between launches"
+    assert layer.status() == 0
 
 
 def test_config2_token_sketch_all_rows():
