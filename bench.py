@@ -245,17 +245,21 @@ def run_cfg4(args):
     results = {}
     modes = ["memcpy", "gather"] if args.copy_mode == "both" else [args.copy_mode]
     # the paper's bucketed policy (whole buckets, then exact), then the 8-way set-associative variant
-    for exact, policy in ((False, 0), (True, 0), (False, 1)):
+    # (and, with the copy kernel, the step whose attention over the hits runs beside the copy)
+    for exact, policy, overlap in ((False, 0, False), (False, 0, True), (True, 0, False), (False, 1, False)):
         for mode in modes:
-            if (exact or policy) and mode != modes[-1]:
+            if (exact or policy or overlap) and mode != modes[-1]:
+                continue
+            if overlap and mode != "gather":
                 continue
             layer = hier.HierLayer(w, budget_frac=args.budget_frac, n_ts=64, evict_exact=exact, copy_mode=mode,
-                                   lru_policy=policy, decode_splits=args.decode_splits,
+                                   overlap_hits=overlap, lru_policy=policy, decode_splits=args.decode_splits,
                                    decode_waves=args.decode_waves, decode_depth=args.decode_depth)
             q = layer.q0
             lat, persist, prev = [], [], None
             layer.spin.profile_enable(steps)          # kernels bracketed by HIP events on the launch stream
-            trace = [[] for _ in range(w.rows)] if (mode == modes[-1] and not exact and not policy and not args.no_cpu) else None
+            trace = [[] for _ in range(w.rows)] if (mode == modes[-1] and not exact and not policy and not overlap
+                                                     and not args.no_cpu) else None
             for s in range(steps):
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
@@ -282,7 +286,7 @@ def run_cfg4(args):
             layer.spin.profile_enable(0)
             overall, warm = layer.hit_rates()
             lat_w = sorted(lat[1:])
-            key = f"{mode}{'_evict_exact' if exact else ''}{'_set_assoc8' if policy else ''}"
+            key = f"{mode}{'_overlap_hits' if overlap else ''}{'_evict_exact' if exact else ''}{'_set_assoc8' if policy else ''}"
             results[key] = dict(hit_rate=round(overall, 4), hit_rate_after_step0=round(warm, 4),
                                 misses_per_step=round(layer.stats["misses_after_first"] / (steps - 1), 1),
                                 selected_per_step=round(layer.stats["selected"] / steps, 1),

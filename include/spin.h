@@ -476,6 +476,27 @@ int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, const void *
                        const int32_t *npages, void *out, float *lse, void *workspace,
                        void *stream);
 
+/* Stage 4 in two passes, for a step whose missed pages are still being copied (Section 5.2,
+ * Retrieve: pages that hit are in HBM already; Section 3.1, Eq. 3: the copy is the long term of a
+ * step under a budget).  spin_split_hits_misses splits the token masks of stage 3b's page list
+ * into two of the same shape (DEVICE uint16 [rows][page_stride]): mask_hits keeps the mask of every
+ * page that is not in the row's miss list, mask_misses that of every page that is.
+ * spin_sparse_decode_begin attends what its masks name and leaves one partial result per query
+ * head in `workspace`; spin_sparse_decode_finish, later on the same stream and workspace, attends
+ * what ITS masks name starting from that partial and writes out / lse as spin_sparse_decode does
+ * (same tolerance; the summation order differs, the bits are the same from run to run).  Between
+ * the two the caller makes its stream wait for the copy.  Slots of whole pages only
+ * (partition_tokens >= 16); SPIN_ERR_UNSUPPORTED otherwise. */
+int spin_split_hits_misses(spin_ctx *ctx, int32_t batch, const int32_t *page_ids, const uint16_t *valid_mask,
+                           const int32_t *npages, const int32_t *miss_pages, const int32_t *nmiss,
+                           uint16_t *mask_hits, uint16_t *mask_misses, void *stream);
+int spin_sparse_decode_begin(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool, int64_t pool_slots,
+                             const int32_t *slots, const uint16_t *valid_mask, const int32_t *npages,
+                             void *workspace, void *stream);
+int spin_sparse_decode_finish(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool, int64_t pool_slots,
+                              const int32_t *slots, const uint16_t *valid_mask, const int32_t *npages, void *out,
+                              float *lse, void *workspace, void *stream);
+
 /* Stage 4 for callers that cannot allocate: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc and so cannot provide the workspace of
  * spin_sparse_decode.  Same inputs, outputs and output bits as spin_sparse_decode (the same

@@ -25,7 +25,8 @@ EXPORTS = [
     "spin_copy_misses_host", "spin_gather_misses", "spin_select_resolve", "spin_append_kv", "spin_reclaim_tail", "spin_alloc_leaves", "spin_free_leaves",
     "spin_set_partition_tables", "spin_probe_stream_read", "spin_offload_pages", "spin_score_select_topk", "spin_score_select_resolve", "spin_pin_partitions",
     "spin_set_host_page_table", "spin_set_step", "spin_advance_step", "spin_sparse_decode_static",
-    "spin_select_resolve_forced", "spin_sparse_decode_rest",
+    "spin_select_resolve_forced", "spin_sparse_decode_rest", "spin_split_hits_misses", "spin_sparse_decode_begin",
+    "spin_sparse_decode_finish",
 ]
 
 
@@ -84,6 +85,9 @@ def load_library() -> C.CDLL:
     lib.spin_sparse_decode.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_sparse_decode_static.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_select_resolve_forced.argtypes = [vp, i32] + [vp] * 7 + [i64] + [vp] * 6 + [i64, vp, vp]
+    lib.spin_split_hits_misses.argtypes = [vp, i32] + [vp] * 8
+    lib.spin_sparse_decode_begin.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp]
+    lib.spin_sparse_decode_finish.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_sparse_decode_rest.argtypes = [vp, i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.spin_probe_stream_read.argtypes = [vp, vp, C.c_size_t, vp, vp]
     lib.spin_set_partition_tables.argtypes = [vp, vp, vp, vp, vp]
@@ -404,6 +408,28 @@ class Spin:
             _ptr(slots, torch.int32, "slots"), _ptr(valid_mask, torch.int16, "valid_mask"),
             _ptr(npages, torch.int32, "npages"), _ptr(out, torch.bfloat16, "out"),
             _ptr(lse, torch.float32, "lse"), _ptr(ws), _stream()), "spin_sparse_decode_rest")
+
+    def split_hits_misses(self, batch, page_ids, valid_mask, npages, miss_pages, nmiss, mask_hits, mask_misses):
+        self._check(self.lib.spin_split_hits_misses(
+            self.h, batch, _ptr(page_ids, torch.int32, "page_ids"), _ptr(valid_mask, torch.int16, "valid_mask"),
+            _ptr(npages, torch.int32, "npages"), _ptr(miss_pages, torch.int32, "miss_pages"),
+            _ptr(nmiss, torch.int32, "nmiss"), _ptr(mask_hits, torch.int16, "mask_hits"),
+            _ptr(mask_misses, torch.int16, "mask_misses"), _stream()), "spin_split_hits_misses")
+
+    def sparse_decode_begin(self, batch, q, kv_pool, slots, valid_mask, npages, ws):
+        pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192
+        self._check(self.lib.spin_sparse_decode_begin(
+            self.h, batch, _ptr(q, torch.bfloat16, "q"), _ptr(kv_pool), pool_slots, _ptr(slots, torch.int32, "slots"),
+            _ptr(valid_mask, torch.int16, "valid_mask"), _ptr(npages, torch.int32, "npages"), _ptr(ws), _stream()),
+            "spin_sparse_decode_begin")
+
+    def sparse_decode_finish(self, batch, q, kv_pool, slots, valid_mask, npages, out, lse, ws):
+        pool_slots = kv_pool.numel() * kv_pool.element_size() // 8192
+        self._check(self.lib.spin_sparse_decode_finish(
+            self.h, batch, _ptr(q, torch.bfloat16, "q"), _ptr(kv_pool), pool_slots, _ptr(slots, torch.int32, "slots"),
+            _ptr(valid_mask, torch.int16, "valid_mask"), _ptr(npages, torch.int32, "npages"),
+            _ptr(out, torch.bfloat16, "out"), _ptr(lse, torch.float32, "lse"), _ptr(ws), _stream()),
+            "spin_sparse_decode_finish")
 
     @property
     def forced_split_supported(self) -> bool:

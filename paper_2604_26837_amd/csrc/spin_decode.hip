@@ -22,12 +22,15 @@
 
 #include "spin_decode_dev.h"
 
+#define SPIN_DECODE_FROM_PARTIAL 1   // the row's first wavefront starts from the partial at index nsplit
+#define SPIN_DECODE_TO_PARTIAL 2     // the row's merged result goes there instead of to `out`
+
 template <int WAVES, int DEPTH>
 __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
     const uint16_t *__restrict__ q, const uint4 *__restrict__ pool, int64_t pool_slots,
     const int32_t *__restrict__ slots, const uint16_t *__restrict__ masks,
     const int32_t *__restrict__ npages, int page_stride, int G, int Hq, int Hkv, int nsplit, int pstride,
-    const int32_t *__restrict__ skip, float scale_log2e, float *part_ml, float *part_acc, int32_t *tickets,
+    const int32_t *__restrict__ skip, int mode, float scale_log2e, float *part_ml, float *part_acc, int32_t *tickets,
     uint16_t *__restrict__ out, float *__restrict__ lse, int32_t *status) {
   const int row = blockIdx.x / nsplit;
   const int split = blockIdx.x - row * nsplit;
@@ -61,9 +64,10 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
   softmax_state st;
   softmax_reset(st);
 
-  // The first wavefront of a row starts from the partial (m, l, O) the earlier launch left for the row's
-  // always-attended pages instead of from the empty state: it then is part of the ordinary merge.
-  if (skip && split == 0 && wave == 0) {
+  // The first wavefront of a row starts from the partial (m, l, O) an earlier launch left for the row (its
+  // always-attended pages, or the first of two passes over the page list) instead of from the empty state:
+  // that partial then is part of the ordinary merge.
+  if ((mode & SPIN_DECODE_FROM_PARTIAL) && split == 0 && wave == 0) {
     const size_t pf = ((size_t)row * pstride + nsplit) * G;
     if (n < G) {
       st.m = part_ml[(pf + n) * 2];
@@ -104,7 +108,7 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
   }
 
   decode_finish<WAVES>(st, row, split, b, h, lane, wave, n, c, G, Hq, nsplit, pstride, part_ml, part_acc, tickets, out,
-                       lse);
+                       lse, (mode & SPIN_DECODE_TO_PARTIAL) != 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -259,7 +263,7 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_tokens_kernel(
 static int decode_launch(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool, int64_t pool_slots,
                          const int32_t *slots, const uint16_t *valid_mask, const int32_t *npages, void *out,
                          float *lse, float *part_ml, float *part_acc, int32_t *tickets, int32_t *status,
-                         const int32_t *skip, void *stream) {
+                         const int32_t *skip, int mode, void *stream) {
   const int rows = batch * ctx->cfg.num_kv_heads;
   const int G = ctx->group, nsplit = ctx->splits;
   const int pstride = ctx->splits + 1;
@@ -267,6 +271,7 @@ static int decode_launch(spin_ctx *ctx, int32_t batch, const void *q, const void
   const int W = ctx->waves;
   const size_t lds = (size_t)W * G * (SPIN_HEAD_DIM + 2) * sizeof(float);
   if (ctx->k_token_major) {
+    if (mode) return SPIN_ERR_UNSUPPORTED;   // the gathered-token kernel runs whole rows only
     // token-major slots: tiles of gathered tokens (always 8 wavefronts: the waves and depth knobs do not
     // apply, and the merge buffers are sized for 8 whatever the waves knob says)
     const size_t lds_tok = (size_t)8 * G * (SPIN_HEAD_DIM + 2) * sizeof(float) + (size_t)8 * TOK_LIST * sizeof(uint32_t);
@@ -280,7 +285,7 @@ static int decode_launch(spin_ctx *ctx, int32_t batch, const void *q, const void
   spin_launch(ctx, SPIN_K_DECODE, spin_decode_kernel<WV, DP>, dim3((unsigned)(rows * nsplit)), dim3(WV * 64), lds, \
               (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, slots, valid_mask,   \
               npages, ctx->page_stride, G, ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, pstride, skip,   \
-              scale_log2e, part_ml, part_acc, tickets, (uint16_t *)out, lse, status)
+              mode, scale_log2e, part_ml, part_acc, tickets, (uint16_t *)out, lse, status)
 #define SPIN_DECODE_LAUNCH(WV)                          \
   do {                                                  \
     if (ctx->depth == 2) SPIN_DECODE_LAUNCH2(WV, 2);    \
@@ -306,7 +311,39 @@ extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, c
   char *ws = (char *)workspace;
   return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
                        (float *)(ws + ctx->ws_ml_off), (float *)(ws + ctx->ws_acc_off),
-                       (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace, nullptr, stream);
+                       (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace, nullptr, 0, stream);
+}
+
+// Attention in two passes over one page list: the first attends the tokens its masks name and leaves
+// the row's merged partial (m, l, O) in the workspace, the second starts from it.
+static int decode_two_pass(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool, int64_t pool_slots,
+                           const int32_t *slots, const uint16_t *valid_mask, const int32_t *npages, void *out,
+                           float *lse, void *workspace, int mode, void *stream) {
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch || pool_slots <= 0) return SPIN_ERR_INVALID;
+  if (ctx->k_token_major) return SPIN_ERR_UNSUPPORTED;
+  if (batch == 0) return SPIN_OK;
+  if (!q || !kv_pool || !slots || !valid_mask || !npages || (!out && !(mode & SPIN_DECODE_TO_PARTIAL)))
+    return SPIN_ERR_INVALID;
+  if (!workspace) return SPIN_ERR_WORKSPACE;
+  char *ws = (char *)workspace;
+  return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
+                       (float *)(ws + ctx->ws_ml_off), (float *)(ws + ctx->ws_acc_off),
+                       (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace, nullptr, mode, stream);
+}
+
+extern "C" int spin_sparse_decode_begin(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool,
+                                        int64_t pool_slots, const int32_t *slots, const uint16_t *valid_mask,
+                                        const int32_t *npages, void *workspace, void *stream) {
+  return decode_two_pass(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, nullptr, nullptr, workspace,
+                         SPIN_DECODE_TO_PARTIAL, stream);
+}
+
+extern "C" int spin_sparse_decode_finish(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool,
+                                         int64_t pool_slots, const int32_t *slots, const uint16_t *valid_mask,
+                                         const int32_t *npages, void *out, float *lse, void *workspace,
+                                         void *stream) {
+  return decode_two_pass(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse, workspace,
+                         SPIN_DECODE_FROM_PARTIAL, stream);
 }
 
 // Stage 4 over what spin_select_resolve_forced left: the pages other than the always-attended ones, merged
@@ -324,7 +361,7 @@ extern "C" int spin_sparse_decode_rest(spin_ctx *ctx, int32_t batch, const void 
   return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
                        (float *)(ws + ctx->ws_ml_off), (float *)(ws + ctx->ws_acc_off),
                        (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace,
-                       (const int32_t *)(ws + ctx->ws_skip_off), stream);
+                       (const int32_t *)(ws + ctx->ws_skip_off), SPIN_DECODE_FROM_PARTIAL, stream);
 }
 
 // ---------------------------------------------------------------------------
@@ -387,5 +424,5 @@ extern "C" int spin_sparse_decode_static(spin_ctx *ctx, int32_t batch, const voi
   if (hipGetLastError() != hipSuccess) return SPIN_ERR_HIP;
   return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
                        (float *)(sc + ml_off), (float *)(sc + acc_off), (int32_t *)(sc + ticket_off),
-                       status ? status : (int32_t *)sc, nullptr, stream);
+                       status ? status : (int32_t *)sc, nullptr, 0, stream);
 }

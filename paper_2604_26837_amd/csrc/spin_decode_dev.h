@@ -150,13 +150,16 @@ __device__ inline void write_out(uint16_t *__restrict__ out, float *__restrict__
 // the merge, in index order, of the partials 0 .. nsplit-1 of the calling launch.
 // split == SPIN_ONLY_PARTIAL: the workgroup only stores its partial, at index nsplit, for a later
 // launch on the same stream to start from (the attention over a row's always-attended pages).
+// to_partial: the merged result of the row is stored there as well, unnormalised, instead of being
+// written to `out` (the first of two attention passes over one page list).
 #define SPIN_ONLY_PARTIAL (-1)
 // Returns true in the workgroup that wrote the row's output.
 template <int WAVES>
 __device__ __forceinline__ bool decode_finish(softmax_state &st, int row, int split, int b, int h, int lane, int wave,
                                               int n, int c, int G, int Hq, int nsplit, int pstride,
                                               float *part_ml, float *part_acc, int32_t *tickets,
-                                              uint16_t *__restrict__ out, float *__restrict__ lse) {
+                                              uint16_t *__restrict__ out, float *__restrict__ lse,
+                                              bool to_partial = false) {
   extern __shared__ float smem[];
   float *s_acc = smem;                                  // [WAVES][G][128]
   float *s_m = smem + WAVES * G * SPIN_HEAD_DIM;        // [WAVES][G]
@@ -195,7 +198,7 @@ __device__ __forceinline__ bool decode_finish(softmax_state &st, int row, int sp
       L += s_l[w * G + g] * wgt;
       O += s_acc[(w * G + g) * SPIN_HEAD_DIM + d] * wgt;
     }
-    if (split == SPIN_ONLY_PARTIAL) {
+    if (split == SPIN_ONLY_PARTIAL || (nsplit == 1 && to_partial)) {
       // read by a later launch on the same stream: plain stores
       const size_t pi = ((size_t)row * pstride + nsplit) * G + g;
       part_acc[pi * SPIN_HEAD_DIM + d] = O;
@@ -277,7 +280,16 @@ __device__ __forceinline__ bool decode_finish(softmax_state &st, int row, int sp
         }
       }
     }
-    write_out(out, lse, b * Hq + h * G + g, d, M, L, O);
+    if (to_partial) {
+      const size_t pi = ((size_t)row * pstride + nsplit) * G + g;
+      part_acc[pi * SPIN_HEAD_DIM + d] = O;
+      if (d == 0) {
+        part_ml[pi * 2 + 0] = M;
+        part_ml[pi * 2 + 1] = L;
+      }
+    } else {
+      write_out(out, lse, b * Hq + h * G + g, d, M, L, O);
+    }
   };
 #pragma unroll
   for (int k = 0; k < KPRE; ++k) {

@@ -4,9 +4,9 @@
 // Two copiers.  The host-driven one issues one 8 KiB hipMemcpyAsync per miss on
 // a side stream (needs the miss list on the host).  The device-driven one is
 // the paper's copy kernel (Section 5.5): one wavefront copies one page with
-// 16-byte lane transactions straight out of pinned host memory; workgroups are
-// dealt (row, chunk of misses) pairs so pages spread over the whole chip
-// whatever row owns them, and the miss list never leaves the device.  The same
+// 16-byte lane transactions straight out of pinned host memory; a fixed, small number of
+// workgroups walks the (row, chunk of misses) pairs with a grid stride, so pages are spread over
+// the wavefronts whatever row owns them, and the miss list never leaves the device.  The same
 // kernel run the other way is Offload's copy (slot -> host page).
 #include "spin_common.h"
 
@@ -46,6 +46,11 @@ extern "C" int spin_copy_misses_host(spin_ctx *ctx, int32_t batch, const void *h
 
 #define GATHER_WAVES 4
 #define GATHER_PAGES_PER_WG 16
+// Workgroups of a copy launch.  The host link is the limit (about 54 GB/s), and it takes about 64 compute units
+// to saturate it (measured per step of the budget workload, 6.4 K pages: 8 / 16 / 32 / 64 / 128 / 512 / 2048
+// workgroups -> 2605 / 1489 / 1092 / 1001 / 1000 / 1032 / 1032 us); more only crowd the units that other
+// launches could use meanwhile.
+#define GATHER_MAX_WGS 64
 
 struct host_map {
   const int32_t *table;     // NULL: identity
@@ -58,9 +63,12 @@ template <bool TO_HOST>
 __global__ __launch_bounds__(GATHER_WAVES * 64) void spin_gather_kernel(
     uint4 *__restrict__ host_kv, const int64_t *__restrict__ row_base, const int32_t *__restrict__ nmiss,
     const int32_t *__restrict__ miss_pages, const int32_t *__restrict__ miss_slots, uint4 *__restrict__ pool,
-    int64_t pool_slots, int page_stride, int chunks_per_row, int32_t *status, host_map hm) {
-  const int row = blockIdx.x / chunks_per_row, chunk = blockIdx.x - row * chunks_per_row;
+    int64_t pool_slots, int page_stride, int chunks_per_row, int total_items, int32_t *status, host_map hm) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // (row, chunk of the row's list) pairs are dealt to the workgroups with a grid stride: the link needs few
+  // pages in flight, so the launch stays small and leaves the compute units to whatever runs beside it
+  for (int item = blockIdx.x; item < total_items; item += gridDim.x) {
+  const int row = item / chunks_per_row, chunk = item - row * chunks_per_row;
   int n = nmiss[row];
   n = n < 0 ? 0 : (n > page_stride ? page_stride : n);
   const int begin = chunk * GATHER_PAGES_PER_WG;
@@ -93,6 +101,7 @@ __global__ __launch_bounds__(GATHER_WAVES * 64) void spin_gather_kernel(
 #pragma unroll
     for (int k = 0; k < 8; ++k) dst[k * 64] = v[k];
   }
+  }
 }
 
 extern "C" int spin_gather_misses(spin_ctx *ctx, int32_t batch, const void *host_kv, const int64_t *row_base,
@@ -104,9 +113,9 @@ extern "C" int spin_gather_misses(spin_ctx *ctx, int32_t batch, const void *host
   if (!workspace) return SPIN_ERR_WORKSPACE;
   const int rows = batch * ctx->cfg.num_kv_heads;
   const int chunks = (ctx->page_stride + GATHER_PAGES_PER_WG - 1) / GATHER_PAGES_PER_WG;
-  spin_launch(ctx, SPIN_K_GATHER, spin_gather_kernel<false>, dim3((unsigned)(rows * chunks)), dim3(GATHER_WAVES * 64), 0,
+  spin_launch(ctx, SPIN_K_GATHER, spin_gather_kernel<false>, dim3((unsigned)min(rows * chunks, GATHER_MAX_WGS)), dim3(GATHER_WAVES * 64), 0,
               (hipStream_t)stream, (uint4 *)const_cast<void *>(host_kv), row_base, nmiss, miss_pages, miss_slots,
-              (uint4 *)kv_pool, pool_slots, ctx->page_stride, chunks, (int32_t *)workspace,
+              (uint4 *)kv_pool, pool_slots, ctx->page_stride, chunks, rows * chunks, (int32_t *)workspace,
               host_map{ctx->cpu_table, ctx->cpu_table_entries, ctx->cpu_pages});
   return spin_launch_status();
 }
@@ -120,9 +129,9 @@ extern "C" int spin_offload_pages(spin_ctx *ctx, int32_t batch, const void *kv_p
   if (!workspace) return SPIN_ERR_WORKSPACE;
   const int rows = batch * ctx->cfg.num_kv_heads;
   const int chunks = (ctx->page_stride + GATHER_PAGES_PER_WG - 1) / GATHER_PAGES_PER_WG;
-  spin_launch(ctx, SPIN_K_OFFLOAD, spin_gather_kernel<true>, dim3((unsigned)(rows * chunks)), dim3(GATHER_WAVES * 64), 0,
+  spin_launch(ctx, SPIN_K_OFFLOAD, spin_gather_kernel<true>, dim3((unsigned)min(rows * chunks, GATHER_MAX_WGS)), dim3(GATHER_WAVES * 64), 0,
               (hipStream_t)stream, (uint4 *)host_kv, row_base, count, pages, slots,
-              (uint4 *)const_cast<void *>(kv_pool), pool_slots, ctx->page_stride, chunks, (int32_t *)workspace,
+              (uint4 *)const_cast<void *>(kv_pool), pool_slots, ctx->page_stride, chunks, rows * chunks, (int32_t *)workspace,
               host_map{ctx->cpu_table, ctx->cpu_table_entries, ctx->cpu_pages});
   return spin_launch_status();
 }
@@ -137,4 +146,50 @@ extern "C" int spin_set_host_page_table(spin_ctx *ctx, const int32_t *cpu_pages,
   if (entries <= 0 || host_pages <= 0) return SPIN_ERR_INVALID;
   ctx->cpu_table = cpu_pages; ctx->cpu_table_entries = entries; ctx->cpu_pages = host_pages;
   return SPIN_OK;
+}
+
+// Splits a row's token masks by whether the page had to be fetched: while the copy of the missed pages is under
+// way, attention can already run over the pages that hit (Section 5.2, Retrieve: only the misses travel).  Both
+// lists ascend by page id, so a page is a miss iff a binary search finds it in the row's miss list.
+__global__ __launch_bounds__(256) void spin_split_kernel(const int32_t *__restrict__ page_ids,
+                                                         const uint16_t *__restrict__ mask,
+                                                         const int32_t *__restrict__ npages,
+                                                         const int32_t *__restrict__ miss_pages,
+                                                         const int32_t *__restrict__ nmiss, int page_stride,
+                                                         uint16_t *__restrict__ mask_hits,
+                                                         uint16_t *__restrict__ mask_misses) {
+  const int row = blockIdx.x;
+  int np = npages[row], nm = nmiss[row];
+  np = np < 0 ? 0 : (np > page_stride ? page_stride : np);
+  nm = nm < 0 ? 0 : (nm > page_stride ? page_stride : nm);
+  const int32_t *mp = miss_pages + (size_t)row * page_stride;
+  for (int i = threadIdx.x; i < page_stride; i += blockDim.x) {
+    uint16_t hit = 0, miss = 0;
+    if (i < np) {
+      const int32_t pg = page_ids[(size_t)row * page_stride + i];
+      int lo = 0, hi = nm;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (mp[mid] < pg) lo = mid + 1; else hi = mid;
+      }
+      const bool is_miss = lo < nm && mp[lo] == pg;
+      const uint16_t m = mask[(size_t)row * page_stride + i];
+      hit = is_miss ? 0 : m;
+      miss = is_miss ? m : 0;
+    }
+    mask_hits[(size_t)row * page_stride + i] = hit;
+    mask_misses[(size_t)row * page_stride + i] = miss;
+  }
+}
+
+extern "C" int spin_split_hits_misses(spin_ctx *ctx, int32_t batch, const int32_t *page_ids, const uint16_t *valid_mask,
+                                      const int32_t *npages, const int32_t *miss_pages, const int32_t *nmiss,
+                                      uint16_t *mask_hits, uint16_t *mask_misses, void *stream) {
+  if (!ctx || batch < 0 || batch > ctx->cfg.max_batch) return SPIN_ERR_INVALID;
+  if (batch == 0) return SPIN_OK;
+  if (!page_ids || !valid_mask || !npages || !miss_pages || !nmiss || !mask_hits || !mask_misses) return SPIN_ERR_INVALID;
+  const int rows = batch * ctx->cfg.num_kv_heads;
+  spin_launch(ctx, SPIN_K_META, spin_split_kernel, dim3((unsigned)rows), dim3(256), 0, (hipStream_t)stream, page_ids,
+              valid_mask, npages, miss_pages, nmiss, ctx->page_stride, mask_hits, mask_misses);
+  return spin_launch_status();
 }

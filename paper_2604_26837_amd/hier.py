@@ -22,11 +22,14 @@ def request_workload(w: synth.Workload, b: int) -> synth.Workload:
 class HierLayer:
     def __init__(self, w: synth.Workload, budget_frac: float = 0.25, n_ts: int = 64, evict_exact: bool = False,
                  device: str = "cuda:0", copy_mode: str = "memcpy", keep_natural: bool = False,
-                 scatter_host_pages: bool = False, **cfg_over):
+                 scatter_host_pages: bool = False, overlap_hits: bool = False, **cfg_over):
+        """``overlap_hits`` (copy kernel only): attention over the pages that hit runs while the copy kernel brings
+        the missed pages in on a side stream; a second pass attends the missed pages and completes the result."""
         # any uniform partition size; scores that need no per-head channel table
         assert w.score_kind in (synth.SCORE_MINMAX, synth.SCORE_REPMAX)
         assert copy_mode in ("memcpy", "gather")
-        self.w, self.device, self.copy_mode = w, device, copy_mode
+        assert not overlap_hits or (copy_mode == "gather" and w.partition_tokens >= 16)
+        self.w, self.device, self.copy_mode, self.overlap_hits = w, device, copy_mode, overlap_hits
         self.spin = binding.Spin.for_workload(w, lru_timestamps=n_ts, lru_evict_exact=int(evict_exact), **cfg_over)
         sp = self.spin
         self.ws = sp.new_workspace(device)
@@ -81,6 +84,7 @@ class HierLayer:
         self.slots, self.page_ids = z(rows, sp.page_stride), z(rows, sp.page_stride)
         self.valid_mask, self.npages = z(rows, sp.page_stride, dt=torch.int16), z(rows)
         self.miss_pages, self.miss_slots, self.nmiss = z(rows, sp.page_stride), z(rows, sp.page_stride), z(rows)
+        self.mask_hits, self.mask_misses = z(rows, sp.page_stride, dt=torch.int16), z(rows, sp.page_stride, dt=torch.int16)
         self.out = torch.zeros((w.batch, w.num_q_heads, w.head_dim), dtype=torch.bfloat16, device=device)
         self.lse = torch.zeros((w.batch, w.num_q_heads), dtype=torch.float32, device=device)
         hp = lambda *s: torch.zeros(s, dtype=torch.int32, pin_memory=True)
@@ -145,12 +149,30 @@ class HierLayer:
             ev = torch.cuda.Event()
             ev.record(self.copy_stream)
             main.wait_event(ev)
+        elif self.overlap_hits:
+            # the copy kernel on the side stream, attention over the hits beside it, then the missed pages
+            sp.split_hits_misses(w.batch, self.page_ids, self.valid_mask, self.npages, self.miss_pages, self.nmiss,
+                                 self.mask_hits, self.mask_misses)
+            resolved = torch.cuda.Event()
+            resolved.record(main)
+            with torch.cuda.stream(self.copy_stream):
+                self.copy_stream.wait_event(resolved)
+                sp.gather_misses(w.batch, self.host_kv, self.host_row_base_dev, self.nmiss, self.miss_pages,
+                                 self.miss_slots, self.kv_pool, self.ws)
+                fetched = torch.cuda.Event()
+                fetched.record(self.copy_stream)
+            sp.sparse_decode_begin(w.batch, q, self.kv_pool, self.slots, self.mask_hits, self.npages, self.ws)
+            main.wait_event(fetched)
+            sp.sparse_decode_finish(w.batch, q, self.kv_pool, self.slots, self.mask_misses, self.npages, self.out,
+                                    self.lse, self.ws)
+            copied = None
         else:
             sp.gather_misses(w.batch, self.host_kv, self.host_row_base_dev, self.nmiss, self.miss_pages,
                              self.miss_slots, self.kv_pool, self.ws)
             copied = None
-        sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
-                         self.ws)
+        if not self.overlap_hits:
+            sp.sparse_decode(w.batch, q, self.kv_pool, self.slots, self.valid_mask, self.npages, self.out, self.lse,
+                             self.ws)
         if device_step:
             sp.advance_step(self.ws)
         if count:

@@ -241,3 +241,53 @@ def test_random_launch_shapes_and_page_lists(seed):
     got, lgot = _run_decode(dw, page_lists, mask_lists)
     # rows that attend to no token at all: zeros, lse = -inf
     _compare(got, np.nan_to_num(ref), lgot, lref)
+
+
+@pytest.mark.parametrize("splits,waves", [(0, 0), (1, 8), (3, 4), (2, 2)])
+def test_two_pass_attention_over_a_split_page_list(splits, waves):
+    """spin_sparse_decode_begin + spin_sparse_decode_finish over any two-way split of the token masks (a page in
+    one pass, the other, both in part, or neither) equal attention over the union: oracle tolerance, and the
+    same bits from run to run."""
+    from gpu_harness import DEV, DeviceWorkload, bf16_to_bits
+    w = synth.config0().with_(seq_lens=(700, 16, 333, 2049), num_q_heads=8, num_kv_heads=2, topk=40, name="two_pass")
+    dw = DeviceWorkload(synth.generate(w, spare_slots=5), decode_splits=splits, decode_waves=waves)
+    sp = dw.spin
+    rng = np.random.default_rng(21 + splits)
+    pl, ml = _random_selection(w, rng, 40, ragged_masks=True)
+    rows = w.rows
+    slots = np.full((rows, sp.page_stride), -1, dtype=np.int32)
+    ma = np.zeros((rows, sp.page_stride), dtype=np.uint16)
+    mb = np.zeros((rows, sp.page_stride), dtype=np.uint16)
+    npg = np.zeros(rows, dtype=np.int32)
+    for r in range(rows):
+        n = len(pl[r])
+        slots[r, :n] = [dw.page_map[(r, p)] for p in pl[r]]
+        npg[r] = n
+        for i, m in enumerate(ml[r]):
+            kind = int(rng.integers(0, 4))
+            a = {0: m, 1: 0, 2: m & int(rng.integers(0, 1 << 16)), 3: 0}[kind]
+            ma[r, i], mb[r, i] = a, (m & ~a) & 0xFFFF
+            if kind == 3:
+                ml[r][i] = 0            # attended in neither pass
+                mb[r, i] = 0
+    if rows > 1:
+        ma[1, :] = 0                    # a row whose first pass is empty, and one whose second pass is
+        mb[1, :npg[1]] = ml[1]
+        mb[rows - 1, :] = 0
+        ma[rows - 1, :npg[rows - 1]] = ml[rows - 1]
+    d_slots = torch.from_numpy(slots).to(DEV)
+    d_a, d_b = torch.from_numpy(ma.view(np.int16)).to(DEV), torch.from_numpy(mb.view(np.int16)).to(DEV)
+    d_np = torch.from_numpy(npg).to(DEV)
+    ref, lref = _oracle_rows(dw, pl, ml)
+    bits = []
+    for _ in range(3):
+        out = torch.full((w.batch, w.num_q_heads, w.head_dim), 7.0, dtype=torch.bfloat16, device=DEV)
+        lse = torch.full((w.batch, w.num_q_heads), 7.0, dtype=torch.float32, device=DEV)
+        sp.sparse_decode_begin(w.batch, dw.q, dw.kv_pool, d_slots, d_a, d_np, dw.ws)
+        sp.sparse_decode_finish(w.batch, dw.q, dw.kv_pool, d_slots, d_b, d_np, out, lse, dw.ws)
+        torch.cuda.synchronize()
+        dw.check_ok()
+        bits.append(bf16_to_bits(out).copy())
+    assert np.array_equal(bits[0], bits[1]) and np.array_equal(bits[0], bits[2])
+    got = bf16.decode(bits[0]).reshape(rows, w.group, w.head_dim)
+    _compare(got, ref, lse.cpu().numpy().astype(np.float64).reshape(rows, w.group), lref)

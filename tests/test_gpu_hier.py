@@ -21,14 +21,16 @@ def _small():
 
 
 # the last two cases: the request's pages scattered over the host pool behind a CPU page table
-@pytest.mark.parametrize("copy_mode,exact,policy,scatter", [("memcpy", False, 0, False), ("gather", False, 0, False),
-                                                            ("gather", True, 0, False), ("gather", False, 1, False),
-                                                            ("gather", False, 0, True), ("memcpy", False, 0, True)])
-def test_steps_match_oracle(copy_mode, exact, policy, scatter):
+# (the case with overlap: attention over the hits runs beside the copy kernel, a second pass takes the misses)
+@pytest.mark.parametrize("copy_mode,exact,policy,scatter,overlap", [
+    ("memcpy", False, 0, False, False), ("gather", False, 0, False, False), ("gather", True, 0, False, False),
+    ("gather", False, 1, False, False), ("gather", False, 0, True, False), ("memcpy", False, 0, True, False),
+    ("gather", False, 0, False, True), ("gather", False, 1, True, True)])
+def test_steps_match_oracle(copy_mode, exact, policy, scatter, overlap):
     w = _small()
     n_ts = 6                      # small range: demotion kicks in within the trace
     layer = hier.HierLayer(w, budget_frac=0.06, n_ts=n_ts, evict_exact=exact, copy_mode=copy_mode, keep_natural=True,
-                           lru_policy=policy, scatter_host_pages=scatter)
+                           lru_policy=policy, scatter_host_pages=scatter, overlap_hits=overlap)
     rows, g = w.rows, w.group
     caches = [lru.RowCache(layer.budgets[r]) for r in range(rows)]
     nat = [n.view(torch.int16).numpy().view(np.uint16) for n in layer.natural]      # per request [slots][2][16][D]
@@ -59,6 +61,13 @@ def test_steps_match_oracle(copy_mode, exact, policy, scatter):
             assert slots[r, :npages[r]].tolist() == [sb + s for s in want_slots], f"step {step} row {r}"
             assert mp[r, :nm[r]].tolist() == [p for p, _ in want_miss]
             assert ms[r, :nm[r]].tolist() == [sb + s for _, s in want_miss]
+            if overlap:       # the masks of the two passes: every page in exactly one of them
+                missed = {p for p, _ in want_miss}
+                full = [(1 << min(16, n - 16 * p)) - 1 for p in want_sel]
+                mh = layer.mask_hits.cpu().numpy().view(np.uint16)[r, :npages[r]].tolist()
+                mm = layer.mask_misses.cpu().numpy().view(np.uint16)[r, :npages[r]].tolist()
+                assert mh == [0 if p in missed else f for p, f in zip(want_sel, full)]
+                assert mm == [f if p in missed else 0 for p, f in zip(want_sel, full)]
             # attention over the logical pages
             pages = bf16.decode(nat[b][layer.natural_slot_of[b][h][np.asarray(want_sel, dtype=np.int64)]])
             masks = [(1 << min(16, n - 16 * p)) - 1 for p in want_sel]
