@@ -152,24 +152,6 @@ int spin_workspace_init(spin_ctx *ctx, void *workspace, void *stream);
  * last init (SPIN_OK if none). */
 int spin_poll_status(spin_ctx *ctx, const void *workspace, void *stream);
 
-/* Per-kernel timing for benchmarks.  spin_profile_enable(ctx, capacity > 0)
- * creates `capacity` HIP event pairs per kernel; from then on each kernel
- * launch of a stage call carries a start and a stop event on its stream (up to
- * `capacity` launches per kernel, later ones are not timed).
- * spin_profile_read() waits for the recorded events of kernel `which`, returns
- * how many launches were timed and their mean and minimum duration in
- * microseconds, and resets that kernel's counter.  capacity == 0 disables and
- * releases the events.  Not for concurrent use with stage calls. */
-enum spin_kernel_id {
-  SPIN_K_SCORE = 0, SPIN_K_SELECT = 1, SPIN_K_RESOLVE = 2, SPIN_K_DECODE = 3, SPIN_K_MERGE = 4,
-  SPIN_K_INDEX = 5, SPIN_K_PACK = 6, SPIN_K_GATHER = 7, SPIN_K_PROBE = 8,
-  SPIN_K_SELECT_HIST = 9, /* first launch of stage 2 for rows of more than 16384 partitions */
-  SPIN_K_OFFLOAD = 10, SPIN_K_APPEND = 11,
-  SPIN_K_META = 12 /* spin_reclaim_tail, spin_alloc_leaves, spin_free_leaves */
-};
-int spin_profile_enable(spin_ctx *ctx, int32_t capacity);
-int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_us, float *min_us);
-
 /* Variable-length partitions (Section 5.2: the Meta-partition table keeps each
  * partition's token count, the Partition Offset table where its page list
  * starts; Section 4.1: a partition may be a block or a cluster of any size).
@@ -195,12 +177,6 @@ int spin_profile_read(spin_ctx *ctx, int32_t which, int32_t *count, float *mean_
  * pages from its id alone) return SPIN_ERR_UNSUPPORTED. */
 int spin_set_partition_tables(spin_ctx *ctx, const int32_t *part_offsets, const int32_t *part_count,
                               const int32_t *part_first_page, const int32_t *part_tokens);
-
-/* Measurement aid: streams `bytes` (a multiple of 16) from the DEVICE buffer `buf`
- * with a plain read-only kernel, timed as SPIN_K_PROBE when profiling is enabled.
- * Gives the bandwidth a single launch of that size can reach on the box at hand,
- * the yardstick the stage kernels are compared with. */
-int spin_probe_stream_read(spin_ctx *ctx, const void *buf, size_t bytes, void *workspace, void *stream);
 
 /* Offload, layout half: write `n_pages` pages given in plain token-major order
  * (src_k, src_v: DEVICE bf16 [n_pages][16][128]) into pool slots `slots[i]`

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "spin.h"
+#include "spin_measure.h"
 
 #define SPIN_HEAD_DIM 128
 #define SPIN_PAGE_TOKENS 16

@@ -3,6 +3,7 @@
 // destroyed.  Address and undefined-behaviour sanitizers watch the host code meanwhile; the program
 // itself only checks return codes.  Built and run by tests/test_host_sanitizers.py.
 #include "spin.h"
+#include "spin_measure.h"
 
 #include <cstdio>
 #include <cstdlib>
@@ -55,6 +56,20 @@ static void poke(spin_ctx *x, const spin_config &c) {
     EXPECT(want_ok ? st == SPIN_OK : st < 0);
     st = spin_sparse_decode(x, batch, n, n, 1, nullptr, nullptr, nullptr, n, nullptr, ws, n);
     EXPECT(want_ok ? st == SPIN_OK : st == SPIN_ERR_INVALID);
+    st = spin_sparse_decode_static(x, batch, n, n, 1, nullptr, nullptr, nullptr, n, nullptr, nullptr, n);
+    EXPECT(want_ok ? st == SPIN_OK : st == SPIN_ERR_INVALID);
+    // the calls below also refuse contexts they do not apply to, before looking at the batch
+    st = spin_select_resolve_forced(x, batch, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 1, nullptr,
+                                    nullptr, nullptr, nullptr, n, n, 1, ws, n);
+    EXPECT(want_ok ? (st == SPIN_OK || st == SPIN_ERR_UNSUPPORTED) : st < 0);
+    st = spin_sparse_decode_rest(x, batch, n, n, 1, nullptr, nullptr, nullptr, n, nullptr, ws, n);
+    EXPECT(want_ok ? (st == SPIN_OK || st == SPIN_ERR_UNSUPPORTED) : st < 0);
+    st = spin_split_hits_misses(x, batch, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, n);
+    EXPECT(want_ok ? st == SPIN_OK : st == SPIN_ERR_INVALID);
+    st = spin_sparse_decode_begin(x, batch, n, n, 1, nullptr, nullptr, nullptr, ws, n);
+    EXPECT(want_ok ? (st == SPIN_OK || st == SPIN_ERR_UNSUPPORTED) : st < 0);
+    st = spin_sparse_decode_finish(x, batch, n, n, 1, nullptr, nullptr, nullptr, n, nullptr, ws, n);
+    EXPECT(want_ok ? (st == SPIN_OK || st == SPIN_ERR_UNSUPPORTED) : st < 0);
     st = spin_build_summaries(x, batch, n, 1, nullptr, nullptr, 1, nullptr, nullptr, nullptr, n, ws, n);
     EXPECT(want_ok ? st == SPIN_OK : st < 0);
     st = spin_append_kv(x, batch, n, n, nullptr, n, 1, nullptr, nullptr, 1, nullptr, nullptr, n, ws, n);
@@ -92,6 +107,8 @@ static void poke(spin_ctx *x, const spin_config &c) {
   EXPECT(spin_set_host_page_table(x, cpu_table, 4, 4) == SPIN_OK);
   EXPECT(spin_set_host_page_table(x, cpu_table, 0, 4) == SPIN_ERR_INVALID);
   EXPECT(spin_set_host_page_table(x, cpu_table, 4, 0) == SPIN_ERR_INVALID);
+  EXPECT(spin_set_host_page_table(x, nullptr, 0, 40) == SPIN_OK);     // identity, bounded by the pool's size
+  EXPECT(spin_set_host_page_table(x, nullptr, 0, -1) == SPIN_ERR_INVALID);
   EXPECT(spin_set_host_page_table(x, nullptr, 0, 0) == SPIN_OK);
   // partition tables: all four or none
   int32_t t[4] = {0, 0, 0, 0};
