@@ -49,6 +49,9 @@ def parse_args():
     ap.add_argument("--score-waves", type=int, default=0, help="wavefronts per stage-1 workgroup (0: library default)")
     ap.add_argument("--score-tiles", type=int, default=0, help="summary tiles per stage-1 workgroup (0: library default)")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step")
+    ap.add_argument("--no-other-form", action="store_true",
+                    help="skip the pass that times the other launch form of the step (under a profiler: every launch of "
+                         "a kernel then belongs to the timed form)")
     ap.add_argument("--print-source-hash", action="store_true",
                     help="print the hash of the library's sources that counter summaries under profiles/ record, and exit")
     ap.add_argument("--no-kernel-events", action="store_true",
@@ -573,7 +576,7 @@ def main():
     # --- the other launch shape of the same step, for reference
     other = (run_three if one_launch_23 else run_12) if args.four_calls else run_four
     us_per_step_other = None
-    if True:
+    if not args.no_other_form:
         for i in range(5):
             other(i)
         torch.cuda.synchronize()
