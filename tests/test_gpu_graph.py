@@ -17,6 +17,9 @@ def _workloads():
         # stages 2+3 in one launch
         "pages": (c0.with_(seq_lens=(4096, 1000, 2049), num_q_heads=8, num_kv_heads=2, topk=24, sink_pages=2,
                            recent_pages=3, name="graph"), "step3"),
+        # the same with the sink / recent pages attended beside stages 2+3 (their partial travels through the workspace)
+        "pages_forced_split": (c0.with_(seq_lens=(4096, 1000, 2049, 30), num_q_heads=8, num_kv_heads=2, topk=24,
+                                        sink_pages=2, recent_pages=3, name="graph_forced"), "step3f"),
         # token partitions, rows long enough for the two-launch selection (its histogram lives in the
         # workspace and must be left cleared by every replay), partial page masks in the attention
         "long_token_rows": (c0.with_(seq_lens=(20000, 17001), num_q_heads=8, num_kv_heads=2, partition_tokens=1,
