@@ -3,7 +3,8 @@
 
 One "step" = one pass of the whole path (score -> select -> resolve -> attend)
 for one layer over one batch of synthetic input, resident in HBM.  Prints ONE
-JSON line; see the design doc for the byte accounting behind `roofline`.
+JSON line.  `roofline` is about the attention kernel: the bytes its launch moves (512 B per token it
+attends) over its mean duration, taken from HIP events on the launch stream, against 8 TB/s.
 """
 from __future__ import annotations
 

@@ -1,4 +1,4 @@
-"""Parity at the benchmark's full sizes, in the launch configuration bench.py
+"""Parity at the full sizes of the five benchmark workloads, in the launch configuration bench.py
 times (same set-up code, default splits/waves): the whole four-call step runs
 on the device-generated workload and its rows are checked one by one
 against the oracle (every row of configs 1-3; sampled rows over 40 steps for
