@@ -338,18 +338,19 @@ int spin_score_select_resolve(spin_ctx *ctx, int32_t batch, const void *q, const
  * windows always take part in attention), and stages 2+3 occupy one workgroup per row and leave
  * the memory system idle.  spin_select_resolve_forced is spin_select_resolve (same arguments,
  * same results, bit for bit) whose launch carries a second set of workgroups: one per row
- * looks the row's sink and recent pages up in the two-level table, attends them (q, kv_pool as
- * in spin_sparse_decode) and leaves one partial result per query head in `workspace`, together
- * with the number of leading and trailing entries of the row's page list these pages are.
+ * or a few per row look the row's sink and recent pages up in the two-level table, attend them
+ * (q, kv_pool as in spin_sparse_decode) and leave their partial results per query head in
+ * `workspace`, together with the number of leading and trailing entries of the row's page list
+ * these pages are.
  * spin_sparse_decode_rest is spin_sparse_decode over the remaining entries of the same page
- * list; the row's first wavefront starts from that partial, so it takes a fixed place in
- * the summation order.  It must follow
+ * list; the first wavefronts of the row's splits start from those partials, so each takes a
+ * fixed place in the summation order.  It must follow
  * spin_select_resolve_forced of the same step, on the same stream and workspace, with the same
  * q and kv_pool.  out and lse are stage 4's results to its tolerance (the summation order
  * differs from spin_sparse_decode's, so the bits may), identical from run to run.
- * Supported in all-resident mode with uniform one-page partitions, contexts of at most 65536
- * tokens and 1 to 64 sink + recent pages; SPIN_ERR_UNSUPPORTED otherwise, before anything is
- * launched (the plain calls then apply). */
+ * Supported in all-resident mode with uniform partitions of whole pages, rows of at most 4096
+ * partitions and 1 to 1024 sink + recent pages; SPIN_ERR_UNSUPPORTED otherwise, before anything
+ * is launched (the plain calls then apply). */
 int spin_select_resolve_forced(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
                                const int32_t *seq_lens, int32_t *sel, int32_t *nsel, const int32_t *dir,
                                const int32_t *leaf_pool, int64_t leaf_chunks, int32_t *slots, int32_t *page_ids,
@@ -481,8 +482,8 @@ int spin_sparse_decode_finish(spin_ctx *ctx, int32_t batch, const void *q, const
  * holds it until the process ends.  The call allocates and frees nothing and enqueues a small
  * clearing kernel plus the attention kernel on `stream`.
  * A call needs 256 + 4 * rows + 8 * P + 512 * P bytes of it (each term rounded up to 256), with
- * rows = batch * num_kv_heads and P = rows * (spin_decode_splits(ctx) + 1) * (num_q_heads /
- * num_kv_heads); a larger shape returns SPIN_ERR_STATIC_LIMIT before anything is launched.
+ * rows = batch * num_kv_heads and P = rows * (2 * spin_decode_splits(ctx)) * (num_q_heads /
+ * num_kv_heads) at most (the workspace's layout of partials is kept); a larger shape returns SPIN_ERR_STATIC_LIMIT before anything is launched.
  * status (DEVICE int32, may be NULL): receives the first device-detected fault (a slot id
  * outside the pool: SPIN_ERR_SLOT_RANGE) if it held 0 before; the caller clears and reads it.
  * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different

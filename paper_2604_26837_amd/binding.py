@@ -436,6 +436,6 @@ class Spin:
         """Whether spin_select_resolve_forced / spin_sparse_decode_rest apply to this context (the library
         decides; this mirrors its documented conditions so that a caller can choose its step up front)."""
         c = self.cfg
-        pages = -(-c.max_context // 16)
-        return (c.lru_timestamps == 0 and c.partition_tokens == 16 and not c.variable_partitions and pages <= 4096
-                and 1 <= c.sink_pages + c.recent_pages <= 64)
+        parts = -(-c.max_context // max(c.partition_tokens, 1))
+        return (c.lru_timestamps == 0 and c.partition_tokens >= 16 and not c.variable_partitions and parts <= 4096
+                and 1 <= c.sink_pages + c.recent_pages <= 1024)

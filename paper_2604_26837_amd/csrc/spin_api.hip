@@ -99,6 +99,16 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   if (splits > 64) splits = 64;
   x->splits = splits;
   x->scale = c->softmax_scale > 0.f ? c->softmax_scale : 1.0f / sqrtf((float)c->head_dim);
+  // the always-attended pages beside stages 2+3: about 16 pages per side workgroup, at most one per split
+  // (each leaves a partial that one split's first wavefront starts from)
+  x->side_wgs = 0;
+  const int32_t forced_pages = c->sink_pages + c->recent_pages;
+  if (c->lru_timestamps == 0 && tp >= SPIN_PAGE_TOKENS && !c->variable_partitions && x->max_parts <= 4096 &&
+      forced_pages >= 1 && forced_pages <= 1024) {
+    int32_t s_wgs = (forced_pages + 15) / 16;
+    x->side_wgs = s_wgs > splits ? splits : s_wgs;
+  }
+  x->pstride = splits + (x->side_wgs > 1 ? x->side_wgs : 1);
 
   size_t off = SPIN_WS_HEADER;
   x->ws_ticket_off = off;                       // one arrival counter per row, zero between launches
@@ -113,13 +123,13 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   x->ws_skip_off = off;
   off += (size_t)x->max_rows * 2 * sizeof(int32_t);
   off = (off + 255) & ~(size_t)255;
-  // workgroup partials of stage 4: one per split, plus one for the always-attended pages when the launch of
-  // stages 2+3 attends them
+  // workgroup partials of stage 4: one per split, plus those of the always-attended pages when the launch of
+  // stages 2+3 attends them (at least one: the first of two passes over a page list leaves its result there)
   x->ws_ml_off = off;
-  off += (size_t)x->max_rows * (splits + 1) * group * 2 * sizeof(float);
+  off += (size_t)x->max_rows * x->pstride * group * 2 * sizeof(float);
   off = (off + 255) & ~(size_t)255;
   x->ws_acc_off = off;
-  off += (size_t)x->max_rows * (splits + 1) * group * SPIN_HEAD_DIM * sizeof(float);
+  off += (size_t)x->max_rows * x->pstride * group * SPIN_HEAD_DIM * sizeof(float);
   x->ws_bytes = (off + 255) & ~(size_t)255;
   *out = x;
   return SPIN_OK;

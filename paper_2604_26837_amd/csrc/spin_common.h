@@ -39,6 +39,8 @@ struct spin_ctx {
   int32_t page_stride;
   int32_t dir_stride;
   int32_t splits;
+  int32_t side_wgs;       // workgroups per row that attend the always-attended pages beside stages 2+3 (0: not supported)
+  int32_t pstride;        // stage 4's partials per row in the workspace: one per split, then one per such workgroup
   int32_t waves;          // wavefronts per decode workgroup
   int32_t depth;          // page buffers per decode wavefront
   int32_t kd;             // contraction length of one summary row
@@ -73,13 +75,8 @@ typedef __attribute__((ext_vector_type(4))) short spin_s16x4;
   } while (0)
 
 // attention over a row's always-attended pages beside stages 2+3, the rest in stage 4: all-resident mode,
-// uniform one-page partitions, rows short enough for the 512-thread selection, few enough such pages for one
-// wavefront to look them up
-static inline bool spin_forced_split_supported(const spin_ctx *ctx) {
-  const spin_config &c = ctx->cfg;
-  return c.lru_timestamps == 0 && c.partition_tokens == SPIN_PAGE_TOKENS && !c.variable_partitions &&
-         ctx->max_parts <= 4096 && c.sink_pages + c.recent_pages >= 1 && c.sink_pages + c.recent_pages <= 64;
-}
+// uniform partitions of whole pages, rows short enough for the 512-thread selection
+static inline bool spin_forced_split_supported(const spin_ctx *ctx) { return ctx->side_wgs > 0; }
 
 static inline int spin_launch_status() {
   return hipGetLastError() == hipSuccess ? SPIN_OK : SPIN_ERR_HIP;

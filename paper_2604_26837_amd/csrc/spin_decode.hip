@@ -30,7 +30,7 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
     const uint16_t *__restrict__ q, const uint4 *__restrict__ pool, int64_t pool_slots,
     const int32_t *__restrict__ slots, const uint16_t *__restrict__ masks,
     const int32_t *__restrict__ npages, int page_stride, int G, int Hq, int Hkv, int nsplit, int pstride,
-    const int32_t *__restrict__ skip, int mode, float scale_log2e, float *part_ml, float *part_acc, int32_t *tickets,
+    const int32_t *__restrict__ skip, int mode, int nside, float scale_log2e, float *part_ml, float *part_acc, int32_t *tickets,
     uint16_t *__restrict__ out, float *__restrict__ lse, int32_t *status) {
   const int row = blockIdx.x / nsplit;
   const int split = blockIdx.x - row * nsplit;
@@ -64,11 +64,11 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_kernel(
   softmax_state st;
   softmax_reset(st);
 
-  // The first wavefront of a row starts from the partial (m, l, O) an earlier launch left for the row (its
-  // always-attended pages, or the first of two passes over the page list) instead of from the empty state:
-  // that partial then is part of the ordinary merge.
-  if ((mode & SPIN_DECODE_FROM_PARTIAL) && split == 0 && wave == 0) {
-    const size_t pf = ((size_t)row * pstride + nsplit) * G;
+  // The first wavefront of split s < nside starts from the s-th partial (m, l, O) an earlier launch left for
+  // the row (its always-attended pages, or the first of two passes over the page list) instead of from the
+  // empty state: that partial then is part of the ordinary merge.
+  if ((mode & SPIN_DECODE_FROM_PARTIAL) && split < nside && wave == 0) {
+    const size_t pf = ((size_t)row * pstride + nsplit + split) * G;
     if (n < G) {
       st.m = part_ml[(pf + n) * 2];
       if (c == 0) st.l = part_ml[(pf + n) * 2 + 1];   // the lanes' denominators are summed over c at the end
@@ -263,10 +263,10 @@ __global__ __launch_bounds__(WAVES * 64) void spin_decode_tokens_kernel(
 static int decode_launch(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool, int64_t pool_slots,
                          const int32_t *slots, const uint16_t *valid_mask, const int32_t *npages, void *out,
                          float *lse, float *part_ml, float *part_acc, int32_t *tickets, int32_t *status,
-                         const int32_t *skip, int mode, void *stream) {
+                         const int32_t *skip, int mode, int nside, void *stream) {
   const int rows = batch * ctx->cfg.num_kv_heads;
   const int G = ctx->group, nsplit = ctx->splits;
-  const int pstride = ctx->splits + 1;
+  const int pstride = ctx->pstride;
   const float scale_log2e = ctx->scale * 1.4426950408889634f;
   const int W = ctx->waves;
   const size_t lds = (size_t)W * G * (SPIN_HEAD_DIM + 2) * sizeof(float);
@@ -285,7 +285,7 @@ static int decode_launch(spin_ctx *ctx, int32_t batch, const void *q, const void
   spin_launch(ctx, SPIN_K_DECODE, spin_decode_kernel<WV, DP>, dim3((unsigned)(rows * nsplit)), dim3(WV * 64), lds, \
               (hipStream_t)stream, (const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, slots, valid_mask,   \
               npages, ctx->page_stride, G, ctx->cfg.num_q_heads, ctx->cfg.num_kv_heads, nsplit, pstride, skip,   \
-              mode, scale_log2e, part_ml, part_acc, tickets, (uint16_t *)out, lse, status)
+              mode, nside, scale_log2e, part_ml, part_acc, tickets, (uint16_t *)out, lse, status)
 #define SPIN_DECODE_LAUNCH(WV)                          \
   do {                                                  \
     if (ctx->depth == 2) SPIN_DECODE_LAUNCH2(WV, 2);    \
@@ -311,7 +311,7 @@ extern "C" int spin_sparse_decode(spin_ctx *ctx, int32_t batch, const void *q, c
   char *ws = (char *)workspace;
   return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
                        (float *)(ws + ctx->ws_ml_off), (float *)(ws + ctx->ws_acc_off),
-                       (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace, nullptr, 0, stream);
+                       (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace, nullptr, 0, 0, stream);
 }
 
 // Attention in two passes over one page list: the first attends the tokens its masks name and leaves
@@ -328,7 +328,7 @@ static int decode_two_pass(spin_ctx *ctx, int32_t batch, const void *q, const vo
   char *ws = (char *)workspace;
   return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
                        (float *)(ws + ctx->ws_ml_off), (float *)(ws + ctx->ws_acc_off),
-                       (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace, nullptr, mode, stream);
+                       (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace, nullptr, mode, 1, stream);
 }
 
 extern "C" int spin_sparse_decode_begin(spin_ctx *ctx, int32_t batch, const void *q, const void *kv_pool,
@@ -361,7 +361,7 @@ extern "C" int spin_sparse_decode_rest(spin_ctx *ctx, int32_t batch, const void 
   return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
                        (float *)(ws + ctx->ws_ml_off), (float *)(ws + ctx->ws_acc_off),
                        (int32_t *)(ws + ctx->ws_ticket_off), (int32_t *)workspace,
-                       (const int32_t *)(ws + ctx->ws_skip_off), SPIN_DECODE_FROM_PARTIAL, stream);
+                       (const int32_t *)(ws + ctx->ws_skip_off), SPIN_DECODE_FROM_PARTIAL, ctx->side_wgs, stream);
 }
 
 // ---------------------------------------------------------------------------
@@ -407,7 +407,7 @@ extern "C" int spin_sparse_decode_static(spin_ctx *ctx, int32_t batch, const voi
   if (!q || !kv_pool || !slots || !valid_mask || !npages || !out) return SPIN_ERR_INVALID;
   // layout inside the array, sized for this call's rows: [status word, 256 B][tickets][(m, l)][accumulators]
   const size_t rows = (size_t)batch * ctx->cfg.num_kv_heads;
-  const size_t partials = rows * (ctx->splits + 1) * ctx->group;   // one spare partial per row (not used here)
+  const size_t partials = rows * ctx->pstride * ctx->group;   // the layout of the workspace (spare partials are not used here)
   const size_t ticket_off = SPIN_WS_HEADER;
   const size_t ml_off = (ticket_off + rows * sizeof(int32_t) + 255) & ~(size_t)255;
   const size_t acc_off = (ml_off + partials * 2 * sizeof(float) + 255) & ~(size_t)255;
@@ -424,5 +424,5 @@ extern "C" int spin_sparse_decode_static(spin_ctx *ctx, int32_t batch, const voi
   if (hipGetLastError() != hipSuccess) return SPIN_ERR_HIP;
   return decode_launch(ctx, batch, q, kv_pool, pool_slots, slots, valid_mask, npages, out, lse,
                        (float *)(sc + ml_off), (float *)(sc + acc_off), (int32_t *)(sc + ticket_off),
-                       status ? status : (int32_t *)sc, nullptr, 0, stream);
+                       status ? status : (int32_t *)sc, nullptr, 0, 0, stream);
 }

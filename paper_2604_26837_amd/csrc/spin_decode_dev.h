@@ -146,15 +146,15 @@ __device__ inline void write_out(uint16_t *__restrict__ out, float *__restrict__
 
 // After a workgroup's wavefronts have consumed their tiles: merge the wavefront partials through
 // LDS and, with several splits, the workgroup partials through the workspace (see the header).
-// Partial `s` of a row lives at index row * pstride + s (pstride = splits + 1); the row's output is
+// Partial `s` of a row lives at index row * pstride + s (pstride = splits + the partials earlier launches may leave); the row's output is
 // the merge, in index order, of the partials 0 .. nsplit-1 of the calling launch.
-// split == SPIN_ONLY_PARTIAL: the workgroup only stores its partial, at index nsplit, for a later
-// launch on the same stream to start from (the attention over a row's always-attended pages).
+// ONLY_PARTIAL (then `split` is the index j of the calling workgroup among those that attend a row's
+// always-attended pages): the workgroup only stores its partial, at index nsplit + j, for a later
+// launch on the same stream to start from.
 // to_partial: the merged result of the row is stored there as well, unnormalised, instead of being
 // written to `out` (the first of two attention passes over one page list).
-#define SPIN_ONLY_PARTIAL (-1)
 // Returns true in the workgroup that wrote the row's output.
-template <int WAVES>
+template <int WAVES, bool ONLY_PARTIAL = false>
 __device__ __forceinline__ bool decode_finish(softmax_state &st, int row, int split, int b, int h, int lane, int wave,
                                               int n, int c, int G, int Hq, int nsplit, int pstride,
                                               float *part_ml, float *part_acc, int32_t *tickets,
@@ -198,9 +198,9 @@ __device__ __forceinline__ bool decode_finish(softmax_state &st, int row, int sp
       L += s_l[w * G + g] * wgt;
       O += s_acc[(w * G + g) * SPIN_HEAD_DIM + d] * wgt;
     }
-    if (split == SPIN_ONLY_PARTIAL || (nsplit == 1 && to_partial)) {
+    if (ONLY_PARTIAL || (nsplit == 1 && to_partial)) {
       // read by a later launch on the same stream: plain stores
-      const size_t pi = ((size_t)row * pstride + nsplit) * G + g;
+      const size_t pi = ((size_t)row * pstride + nsplit + (ONLY_PARTIAL ? split : 0)) * G + g;
       part_acc[pi * SPIN_HEAD_DIM + d] = O;
       if (d == 0) {
         part_ml[pi * 2 + 0] = M;
@@ -218,7 +218,7 @@ __device__ __forceinline__ bool decode_finish(softmax_state &st, int row, int sp
       }
     }
   }
-  if (split == SPIN_ONLY_PARTIAL) return false;
+  if (ONLY_PARTIAL) return false;
   if (nsplit == 1) return true;
 
   // Ticket: the last workgroup of the row to arrive merges all splits in split

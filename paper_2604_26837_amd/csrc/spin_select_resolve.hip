@@ -24,15 +24,18 @@ __global__ __launch_bounds__(BLOCK) void spin_select_resolve_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// The always-attended pages of a row (its first sink_pages and last recent_pages pages; one-page
-// partitions) do not depend on the selection, so they can be attended while stages 2+3 run: those
-// are latency-bound on one workgroup per row and leave the other half of the chip and the memory
-// system idle.  A second set of workgroups in the same launch, one per row, looks these pages up
-// in the two-level table itself, attends them with stage 4's tile code and stores one partial
-// (m, l, O) per query head behind the row's split partials; it also records how many leading and
-// trailing entries of the row's page list they are (stage 3 lists pages in ascending order, so
-// the sink pages open the list and the recent pages close it).  Stage 4 then skips those entries
-// and its first wavefront of the row starts from that partial instead of from the empty state.
+// The always-attended pages of a row (its first sink_pages and last recent_pages pages) do not
+// depend on the selection, so they can be attended while stages 2+3 run: those are latency-bound
+// on one workgroup per row and leave the rest of the chip and the memory system idle.  A second
+// set of workgroups in the same launch (about one per 16 such pages of a row, at most one per
+// split of stage 4) looks these pages up in the two-level table itself, attends them with stage
+// 4's tile code and stores one partial (m, l, O) per query head behind the row's split partials;
+// the first of them also records how many leading and trailing entries of the row's page list
+// these pages are (stage 3 lists pages in ascending order and lists every such page, so the sink
+// pages open the list and the recent pages close it, whatever the partition size).  Stage 4 then
+// skips those entries, and the first wavefront of split j starts from the j-th partial instead of
+// from the empty state.
+
 // The always-attended pages of a row as one list: j < nlo is sink page j, the others are the recent
 // pages from recent_begin on.  Looks entry j up for the calling lane (all lanes of the wavefront call;
 // `active` says whether the lane has an entry): slot and token mask, or an empty mask when the page is
@@ -74,7 +77,7 @@ __device__ inline forced_span forced_pages_of(int N, int sink_pages, int recent_
 
 template <int WAVES>
 __device__ inline void attend_forced_row(
-    int row, const uint16_t *__restrict__ q, const uint4 *__restrict__ pool, int64_t pool_slots,
+    int row, int side, int nside, const uint16_t *__restrict__ q, const uint4 *__restrict__ pool, int64_t pool_slots,
     const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ dir, const int32_t *__restrict__ leaf_pool,
     int64_t leaf_chunks, int Hkv, int G, int Hq, int sink_pages, int recent_pages, int dir_stride, int leaf_entries,
     int nsplit, int pstride, float scale_log2e, float *part_ml, float *part_acc, int32_t *skip) {
@@ -93,21 +96,26 @@ __device__ inline void attend_forced_row(
   const int N = seq_lens[b];
   const forced_span fs = forced_pages_of(N, sink_pages, recent_pages);
   const int nlo = fs.nlo, nhi = fs.nhi, recent_begin = fs.recent_begin;
-  const int nf = min(nlo + nhi, 64);            // the host admits at most 64 such pages
-  if (threadIdx.x == 0) {
+  const int nf = nlo + nhi;
+  if (threadIdx.x == 0 && side == 0) {
     skip[2 * row] = nlo;
     skip[2 * row + 1] = nhi;
   }
-  // lane i looks up the i-th page of this wavefront: pages wave, wave + WAVES, ... of the list above
-  const int cnt = nf > wave ? (nf - wave + WAVES - 1) / WAVES : 0;
-  int myslot = 0;
-  unsigned mymask = 0;
-  forced_lookup(lane < cnt, wave + WAVES * lane, nlo, recent_begin, N, mydir, dir_in_lanes, dir, leaf_pool, leaf_chunks, row,
-                dir_stride, leaf_entries, pool_slots, myslot, mymask);
+  // The list above is dealt round-robin to the row's `nside` workgroups and, inside one, to its wavefronts;
+  // lane i looks up the i-th page of this wavefront (batches of 64).
+  const int first = side + nside * wave, stride = nside * WAVES;
+  const int cnt_all = nf > first ? (nf - first + stride - 1) / stride : 0;
   softmax_state st;
   softmax_reset(st);
-  attend_lane_pages<2>(st, pool, myslot, mymask, cnt, lane, c, qf, scale_log2e);
-  decode_finish<WAVES>(st, row, SPIN_ONLY_PARTIAL, b, h, lane, wave, n, c, G, Hq, nsplit, pstride, part_ml,
+  for (int base = 0; base < cnt_all; base += 64) {
+    const int cnt = min(cnt_all - base, 64);
+    int myslot = 0;
+    unsigned mymask = 0;
+    forced_lookup(lane < cnt, first + stride * (base + lane), nlo, recent_begin, N, mydir, dir_in_lanes, dir, leaf_pool,
+                  leaf_chunks, row, dir_stride, leaf_entries, pool_slots, myslot, mymask);
+    attend_lane_pages<2>(st, pool, myslot, mymask, cnt, lane, c, qf, scale_log2e);
+  }
+  decode_finish<WAVES, true>(st, row, side, b, h, lane, wave, n, c, G, Hq, nsplit, pstride, part_ml,
                        part_acc, nullptr, nullptr, nullptr);
 }
 
@@ -115,14 +123,14 @@ struct spin_forced_args {
   const uint16_t *q;
   const uint4 *pool;
   int64_t pool_slots;
-  int G, Hq, nsplit, pstride;
+  int G, Hq, nsplit, pstride, nside;
   float scale_log2e;
   float *part_ml, *part_acc;
   int32_t *skip;
 };
 
 // workgroups [0, rows): stages 2+3 of a row, exactly as spin_select_resolve_kernel;
-// workgroups [rows, 2 rows): attention over the always-attended pages of row blockIdx.x - rows
+// workgroups [rows, rows + rows * nside): attention over the always-attended pages, nside workgroups per row
 template <int KPT>
 __global__ __launch_bounds__(512) void spin_select_resolve_forced_kernel(
     int rows, const float *__restrict__ scores, const int32_t *__restrict__ part_offsets,
@@ -132,7 +140,8 @@ __global__ __launch_bounds__(512) void spin_select_resolve_forced_kernel(
     int32_t *__restrict__ slots, int32_t *__restrict__ page_ids, uint16_t *__restrict__ valid_mask,
     int32_t *__restrict__ npages, int32_t *status, spin_forced_args fa) {
   if ((int)blockIdx.x >= rows) {
-    attend_forced_row<8>((int)blockIdx.x - rows, fa.q, fa.pool, fa.pool_slots, seq_lens, dir, leaf_pool, leaf_chunks, Hkv,
+    const int idx = (int)blockIdx.x - rows, srow = idx / fa.nside;
+    attend_forced_row<8>(srow, idx - srow * fa.nside, fa.nside, fa.q, fa.pool, fa.pool_slots, seq_lens, dir, leaf_pool, leaf_chunks, Hkv,
                          fa.G, fa.Hq, sink_pages, recent_pages, dir_stride, leaf_entries, fa.nsplit, fa.pstride,
                          fa.scale_log2e, fa.part_ml, fa.part_acc, fa.skip);
     return;
@@ -163,13 +172,13 @@ extern "C" int spin_select_resolve_forced(spin_ctx *ctx, int32_t batch, const fl
   const int rows = batch * c.num_kv_heads;
   char *ws = (char *)workspace;
   const spin_forced_args fa = {(const uint16_t *)q, (const uint4 *)kv_pool, pool_slots, ctx->group, c.num_q_heads,
-                               ctx->splits, ctx->splits + 1, ctx->scale * 1.4426950408889634f,
+                               ctx->splits, ctx->pstride, ctx->side_wgs, ctx->scale * 1.4426950408889634f,
                                (float *)(ws + ctx->ws_ml_off), (float *)(ws + ctx->ws_acc_off),
                                (int32_t *)(ws + ctx->ws_skip_off)};
   // dynamic LDS: the merge buffers of the attention workgroups (8 wavefronts)
   const size_t lds = (size_t)8 * ctx->group * (SPIN_HEAD_DIM + 2) * sizeof(float);
 #define SPIN_SRF_ARGS                                                                                         \
-  dim3((unsigned)(2 * rows)), dim3(512), lds, (hipStream_t)stream, rows, scores, part_offsets, seq_lens,      \
+  dim3((unsigned)(rows * (1 + ctx->side_wgs))), dim3(512), lds, (hipStream_t)stream, rows, scores, part_offsets, seq_lens,      \
       c.num_kv_heads, c.partition_tokens, c.topk, c.topk_includes_forced, c.sink_pages, c.recent_pages,       \
       ctx->sel_stride, sel, nsel, dir, leaf_pool, leaf_chunks, ctx->page_stride, ctx->dir_stride,             \
       c.leaf_entries, slots, page_ids, valid_mask, npages, (int32_t *)workspace, fa

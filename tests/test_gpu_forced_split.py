@@ -58,6 +58,18 @@ CASES = {
     "group1_recent_only": (synth.config0().with_(seq_lens=(2500, 1300), num_q_heads=2, num_kv_heads=2, topk=20,
                                                  sink_pages=0, recent_pages=6, name="forced_g1"),
                            dict(decode_splits=2, decode_waves=4)),
+    # partitions of several pages: the sink / recent pages need not line up with partitions, and there are enough
+    # of them for several side workgroups per row
+    "blocks_of_8_pages": (synth.config0().with_(seq_lens=(20000, 9000, 1500, 300, 16 * 70), num_q_heads=8, num_kv_heads=2,
+                                                partition_tokens=128, score_kind=synth.SCORE_REPMAX, topk=8,
+                                                topk_includes_forced=False, sink_pages=4, recent_pages=64,
+                                                name="forced_blocks"), {}),
+    "blocks_of_4_pages_minmax": (synth.config0().with_(seq_lens=(8000, 3001, 100), num_q_heads=8, num_kv_heads=2,
+                                                       partition_tokens=64, topk=12, sink_pages=3, recent_pages=21,
+                                                       name="forced_blocks4"), dict(decode_splits=2)),
+    "many_recent_pages": (synth.config0().with_(seq_lens=(30000, 12000), num_q_heads=8, num_kv_heads=2, topk=300,
+                                                sink_pages=16, recent_pages=200, name="forced_many"),
+                          dict(decode_splits=3)),
     "rows_up_to_4096_pages": (synth.config0().with_(seq_lens=(65536, 40000), num_q_heads=8, num_kv_heads=2, topk=64,
                                                     sink_pages=8, recent_pages=56, name="forced_long"), {}),
 }
