@@ -1,7 +1,8 @@
 // One decode step of one layer through the C ABI alone (no Python, no torch): the caller owns every
 // buffer (hipMalloc), lays the pages out with spin_pack_kv_pages, fills the two-level page table,
 // builds the summaries (Index), then runs score -> select -> resolve -> attention (and the same step as
-// stages 1-3 in one call + attention, which must give the same bits) and checks the
+// stages 1-3 in one call + attention, which must give the same bits; as stage 4 from the library's own
+// scratch array; and as the step that attends the sink / recent pages beside stages 2+3) and checks the
 // output against dense attention restricted to the pages the library reports (Section 4.1: the
 // attention stage is exact on the selected set).  Exit status 0 and a line "one_step: ok" on success.
 //
@@ -151,6 +152,47 @@ int main() {
     if (std::memcmp(out.data(), out2.data(), out.size() * 2) != 0) {
       std::fprintf(stderr, "one_step: the three-launch step differs from the four stage calls\n");
       return 1;
+    }
+  }
+
+  // stage 4 without a workspace (its scratch in the library's own device array) gives the same bits; and the
+  // step whose launch of stages 2+3 also attends the sink / recent pages gives the same page list and an output
+  // within stage 4's tolerance of the one above (the order of the online-softmax updates differs)
+  std::vector<uint16_t> out_forced(out.size());
+  {
+    uint16_t *d_out3;
+    int32_t *d_status;
+    HIP_OK(hipMalloc((void **)&d_out3, (size_t)Hq * D * 2));
+    HIP_OK(hipMalloc((void **)&d_status, 4));
+    HIP_OK(hipMemset(d_status, 0, 4));
+    SPIN_OK_OR_DIE(spin_sparse_decode_static(ctx, 1, d_q, d_pool, pool_slots, d_slots, d_mask, d_np, d_out3, d_lse, d_status, st));
+    HIP_OK(hipStreamSynchronize(st));
+    std::vector<uint16_t> out3(out.size());
+    int32_t status = -1;
+    HIP_OK(hipMemcpy(out3.data(), d_out3, out3.size() * 2, hipMemcpyDeviceToHost));
+    HIP_OK(hipMemcpy(&status, d_status, 4, hipMemcpyDeviceToHost));
+    if (status != 0 || std::memcmp(out.data(), out3.data(), out.size() * 2) != 0) {
+      std::fprintf(stderr, "one_step: spin_sparse_decode_static differs from spin_sparse_decode (status %d)\n", status);
+      return 1;
+    }
+    std::vector<int32_t> slots_before(slots);
+    SPIN_OK_OR_DIE(spin_score_partitions(ctx, 1, d_q, d_summ, nullptr, d_off, d_len, d_scores, d_ws, st));
+    SPIN_OK_OR_DIE(spin_select_resolve_forced(ctx, 1, d_scores, d_off, d_len, d_sel, d_nsel, d_dir, d_leaf, rows, d_slots, d_pids,
+                                              d_mask, d_np, d_q, d_pool, pool_slots, d_ws, st));
+    SPIN_OK_OR_DIE(spin_sparse_decode_rest(ctx, 1, d_q, d_pool, pool_slots, d_slots, d_mask, d_np, d_out3, d_lse, d_ws, st));
+    SPIN_OK_OR_DIE(spin_poll_status(ctx, d_ws, st));
+    HIP_OK(hipMemcpy(out_forced.data(), d_out3, out_forced.size() * 2, hipMemcpyDeviceToHost));
+    HIP_OK(hipMemcpy(slots.data(), d_slots, slots.size() * 4, hipMemcpyDeviceToHost));
+    if (slots != slots_before) {
+      std::fprintf(stderr, "one_step: spin_select_resolve_forced resolved other slots than the stage calls\n");
+      return 1;
+    }
+    for (size_t i = 0; i < out.size(); ++i) {
+      const double a = from_bf16(out[i]), b = from_bf16(out_forced[i]);
+      if (!(std::fabs(a - b) <= 2e-2 + 1e-2 * std::fabs(a))) {
+        std::fprintf(stderr, "one_step: the step that attends sink / recent pages early differs at %zu: %g vs %g\n", i, b, a);
+        return 1;
+      }
     }
   }
 
