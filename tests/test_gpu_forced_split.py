@@ -75,9 +75,34 @@ CASES = {
 }
 
 
-@pytest.mark.parametrize("name", list(CASES))
+def _random_case(seed):
+    """A workload drawn at random among those the split supports: whole-page partitions of one size, at least
+    one sink or recent page, ragged contexts from a few tokens to several leaves, random launch shape."""
+    rng = np.random.default_rng(4200 + seed)
+    kind = int(rng.choice([synth.SCORE_MINMAX, synth.SCORE_REPMAX]))
+    reps = int(rng.choice([1, 2, 4])) if kind == synth.SCORE_REPMAX else 4
+    tp = int(rng.choice([16, 16, 32, 64, 128]))
+    g, hkv = int(rng.choice([1, 2, 4, 4, 5, 8])), int(rng.choice([1, 2, 3]))
+    lens = []
+    for _ in range(int(rng.integers(1, 5))):
+        style = int(rng.integers(0, 4))
+        lens.append(int({0: rng.integers(1, 60), 1: rng.integers(60, 900), 2: rng.integers(900, 12000),
+                         3: 16 * rng.integers(1, 700)}[style]))
+    sink, recent = int(rng.integers(0, 20)), int(rng.integers(0, 90))
+    if sink + recent == 0:
+        recent = 1
+    w = synth.config0().with_(seq_lens=tuple(lens), num_q_heads=g * hkv, num_kv_heads=hkv, partition_tokens=tp,
+                              score_kind=kind, reps_per_partition=reps, topk=int(rng.integers(1, 80)),
+                              topk_includes_forced=bool(rng.integers(0, 2)), sink_pages=sink, recent_pages=recent,
+                              name=f"forced_random{seed}")
+    over = dict(decode_splits=int(rng.choice([0, 1, 2, 3, 5])), decode_waves=int(rng.choice([0, 2, 4, 8])),
+                decode_depth=int(rng.choice([0, 2, 3])))
+    return w, over
+
+
+@pytest.mark.parametrize("name", list(CASES) + [f"random{i}" for i in range(24)])
 def test_forced_pages_attended_beside_stages_2_and_3(name):
-    w, over = CASES[name]
+    w, over = CASES[name] if name in CASES else _random_case(int(name[6:]))
     data, layer, q = _layer(w, **over)
     assert layer.spin.forced_split_supported
     layer.step3(q)
