@@ -256,8 +256,8 @@ int spin_pin_partitions(spin_ctx *ctx, int32_t batch, float *scores, const int32
 
 /* Stages 1 and 2 in ONE call: arguments and results are exactly those of
  * spin_score_partitions followed by spin_select_topk, bit for bit (the scores
- * are still written).  With SKETCH scores and contexts whose stage 2 takes two
- * launches (rows of 16385 to 131072 partitions) stage 1 counts the leading key
+ * are still written).  With contexts whose stage 2 takes two
+ * launches (rows of 16385 to 131072 uniform partitions) stage 1 counts the leading key
  * bits of its scores while it still holds them, so the histogram launch over
  * the score array is saved; every other configuration simply runs the two
  * stages one after the other.  The workspace is needed as for the two calls.

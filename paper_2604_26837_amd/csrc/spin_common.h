@@ -232,4 +232,15 @@ __device__ inline uint32_t spin_wave_max_u32(uint32_t v) {
              max((uint32_t)__builtin_amdgcn_readlane((int)v, 32), (uint32_t)__builtin_amdgcn_readlane((int)v, 48)));
 }
 __device__ inline uint32_t spin_wave_min_u32(uint32_t v) { return ~spin_wave_max_u32(~v); }
+
+// Order-preserving 32-bit key of a score, the order stage 2 ranks by.
+__device__ inline uint32_t score_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) u = 0xff800000u;  // NaN ranks as -inf
+  if (u == 0x80000000u) u = 0u;                          // -0 ties +0
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// bins of the chip-wide histogram of the leading 12 key bits (stage 2 of long rows)
+#define BIG_BINS 4096
 #endif

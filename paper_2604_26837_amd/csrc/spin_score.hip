@@ -46,6 +46,34 @@ struct score_hist_args {
   int tp, topk, includes_forced, sink_pages, recent_pages, sel_stride;
 };
 
+// MINMAX / REPMAX rows of more than 16384 partitions scored by stretches of `tiles_per_wg` tiles per workgroup,
+// which also counts the leading 12 key bits of its candidates' scores: LDS bins, then one global add per bin the
+// stretch touched.  That is the first launch of stage 2 for long rows; the score bits are those of the kernels above.
+template <int NJ, bool MINMAX, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void spin_score_k32_hist_kernel(
+    const uint16_t *__restrict__ q, const uint4 *__restrict__ summ, const int32_t *__restrict__ part_offsets,
+    int Hq, int Hkv, int G, int rows_per_part, int tiles_per_wg, int wgs_per_row, float *__restrict__ scores,
+    score_hist_args ha) {
+  __shared__ int s_h[BIG_BINS];
+  const int row = blockIdx.x / wgs_per_row, chunk = blockIdx.x - row * wgs_per_row;
+  const int b = row / Hkv;
+  const int PP = part_offsets[b + 1] - part_offsets[b];
+  if (chunk * tiles_per_wg >= PP * rows_per_part / 16) return;   // the whole workgroup: nothing to score or count
+  score_bins hb = {s_h, 0, 0};
+  const sel_plan pl = select_plan(ha.seq_lens[b], PP, ha.tp, ha.topk, ha.includes_forced, ha.sink_pages,
+                                  ha.recent_pages, ha.sel_stride);
+  if (pl.kprime > 0) { hb.cand_lo = pl.nf_lo; hb.cand_hi = pl.first_hi; }
+  for (int i = threadIdx.x; i < BIG_BINS; i += WAVES * 64) s_h[i] = 0;
+  __syncthreads();
+  score_row_tiles<NJ, MINMAX, WAVES, true>(q, summ, part_offsets, Hq, Hkv, G, rows_per_part, tiles_per_wg, row, chunk,
+                                           scores, hb);
+  __syncthreads();
+  for (int i = threadIdx.x; i < BIG_BINS; i += WAVES * 64) {
+    const int cnt = s_h[i];
+    if (cnt) atomicAdd(&ha.hist[(size_t)row * BIG_BINS + i], cnt);
+  }
+}
+
 // SKETCH: one 16x16x16 instruction per tile of 16 tokens (512 bytes).
 // HIST: the workgroup also counts the leading 12 key bits of its candidates' scores (LDS, then one
 // global add per bin it touched), which is the first launch of stage 2 for long rows.
@@ -241,6 +269,25 @@ int spin_score_impl(spin_ctx *ctx, int32_t batch, const void *q, const void *sum
   const int max_pp = ((ctx->max_parts + 15) / 16) * 16;
   hipStream_t st = (hipStream_t)stream;
   const int W = c.score_waves ? c.score_waves : 4;
+  const score_hist_args ha = {seq_lens, hist, c.partition_tokens, c.topk, c.topk_includes_forced, c.sink_pages,
+                              c.recent_pages, ctx->sel_stride};
+  if (hist && c.score_kind != SPIN_SCORE_SKETCH) {
+    // long rows whose stage 2 starts from a histogram: stretches of 64 tiles, so that clearing and adding up the
+    // 4096 LDS bins is small beside the 256 KiB or more of summaries a workgroup reads
+    const bool mm = c.score_kind == SPIN_SCORE_MINMAX;
+    const int R = mm ? 1 : c.reps_per_partition;
+    const int tiles_per_wg = 64, max_tiles = max_pp * R / 16;
+    const int wgs = (max_tiles + tiles_per_wg - 1) / tiles_per_wg;
+    if (mm)
+      spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_hist_kernel<8, true, 4>, dim3((unsigned)rows * wgs), dim3(256), 0, st,
+                  (const uint16_t *)q, (const uint4 *)summaries, part_offsets, c.num_q_heads, c.num_kv_heads, ctx->group,
+                  R, tiles_per_wg, wgs, scores, ha);
+    else
+      spin_launch(ctx, SPIN_K_SCORE, spin_score_k32_hist_kernel<4, false, 4>, dim3((unsigned)rows * wgs), dim3(256), 0, st,
+                  (const uint16_t *)q, (const uint4 *)summaries, part_offsets, c.num_q_heads, c.num_kv_heads, ctx->group,
+                  R, tiles_per_wg, wgs, scores, ha);
+    return spin_launch_status();
+  }
   if (c.score_kind == SPIN_SCORE_MINMAX) {
     // one tile per wavefront measured best: the dispatcher streams the workgroups
     const int tiles_per_wg = c.score_tiles_per_wg ? c.score_tiles_per_wg : W, max_tiles = max_pp / 16;
@@ -284,8 +331,6 @@ int spin_score_impl(spin_ctx *ctx, int32_t batch, const void *q, const void *sum
     const bool four = ctx->group <= 4 && (c.score_tiles_per_wg % 4) == 0;
     const int tiles_per_wg = c.score_tiles_per_wg ? c.score_tiles_per_wg : (four ? 256 : 128), max_tiles = max_pp / 16;
     const int wgs = (max_tiles + tiles_per_wg - 1) / tiles_per_wg;
-    const score_hist_args ha = {seq_lens, hist, c.partition_tokens, c.topk, c.topk_includes_forced, c.sink_pages,
-                                c.recent_pages, ctx->sel_stride};
 #define SPIN_SKETCH_ARGS                                                                                         \
   dim3((unsigned)rows * wgs), dim3(SCORE_WAVES * 64), 0, st, (const uint16_t *)q, (const uint2 *)summaries, chan_idx, \
       part_offsets, c.num_q_heads, c.num_kv_heads, ctx->group, tiles_per_wg, wgs, scores, ha

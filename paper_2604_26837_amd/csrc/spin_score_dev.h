@@ -38,9 +38,16 @@ __device__ inline float spin_head_max(const spin_f32x4 &s, int c, int G) {
   return m;
 }
 
-template <int NJ, bool MINMAX>
+// what a workgroup that also counts stage 2's first histogram needs: the LDS bins and the row's candidate range
+struct score_bins {
+  int *bins;            // [BIG_BINS] in LDS
+  int cand_lo, cand_hi; // partitions [cand_lo, cand_hi) are candidates of stage 2
+};
+
+template <int NJ, bool MINMAX, bool HIST = false>
 __device__ inline void consume_tile(const score_tile<NJ> &r, const spin_bf16x8 (&qf)[NJ], int n, int c, int G,
-                                    int rpp, float *__restrict__ scores, size_t base, int t) {
+                                    int rpp, float *__restrict__ scores, size_t base, int t,
+                                    score_bins hb = score_bins{nullptr, 0, 0}) {
   // the queries are the A operand, the summary rows the B operand: lane (n, c) ends up with
   // S[head 4c+i][summary row n], so the maximum over the group's heads stays inside the lane
   // (plus two exchanges between the lane quarters when the group has more than 4 heads)
@@ -52,6 +59,10 @@ __device__ inline void consume_tile(const score_tile<NJ> &r, const spin_bf16x8 (
   if (MINMAX) {
     if (c == 0) {
       scores[base + (size_t)t * 16 + n] = m;
+      if (HIST) {
+        const int p = t * 16 + n;
+        if (p >= hb.cand_lo && p < hb.cand_hi) atomicAdd(&hb.bins[score_key(m) >> 20], 1);
+      }
     }
   } else {
     // rows rpp*p .. rpp*p + rpp-1 (rpp = 1, 2 or 4) are the representatives of partition (16/rpp) t + p:
@@ -60,16 +71,21 @@ __device__ inline void consume_tile(const score_tile<NJ> &r, const spin_bf16x8 (
     if (rpp == 4) m = fmaxf(m, spin_dpp<SPIN_DPP_XOR2>(m));
     if (c == 0 && (n & (rpp - 1)) == 0) {
       scores[base + (size_t)t * (16 / rpp) + n / rpp] = m;
+      if (HIST) {
+        const int p = t * (16 / rpp) + n / rpp;
+        if (p >= hb.cand_lo && p < hb.cand_hi) atomicAdd(&hb.bins[score_key(m) >> 20], 1);
+      }
     }
   }
 }
 
 // Scores the tiles [chunk*tiles_per_wg, +tiles_per_wg) of one row with the calling
 // workgroup (WAVES wavefronts).
-template <int NJ, bool MINMAX, int WAVES>
+template <int NJ, bool MINMAX, int WAVES, bool HIST = false>
 __device__ inline void score_row_tiles(
     const uint16_t *__restrict__ q, const uint4 *__restrict__ summ, const int32_t *__restrict__ part_offsets,
-    int Hq, int Hkv, int G, int rows_per_part, int tiles_per_wg, int row, int chunk, float *__restrict__ scores) {
+    int Hq, int Hkv, int G, int rows_per_part, int tiles_per_wg, int row, int chunk, float *__restrict__ scores,
+    score_bins hb = score_bins{nullptr, 0, 0}) {
   const int b = row / Hkv, h = row - b * Hkv;
   const int off_b = part_offsets[b];
   const int PP = part_offsets[b + 1] - off_b;
@@ -105,9 +121,9 @@ __device__ inline void score_row_tiles(
   for (; t < t_end; t += 2 * WAVES) {
     const int t1 = t + WAVES, t2 = t + 2 * WAVES;
     if (t1 < t_end) load_tile<NJ>(rb, tiles + (size_t)t1 * (NJ * 64), lane);
-    consume_tile<NJ, MINMAX>(ra, qf, n, c, G, rows_per_part, scores, base, t);
+    consume_tile<NJ, MINMAX, HIST>(ra, qf, n, c, G, rows_per_part, scores, base, t, hb);
     if (t2 < t_end) load_tile<NJ>(ra, tiles + (size_t)t2 * (NJ * 64), lane);
-    if (t1 < t_end) consume_tile<NJ, MINMAX>(rb, qf, n, c, G, rows_per_part, scores, base, t1);
+    if (t1 < t_end) consume_tile<NJ, MINMAX, HIST>(rb, qf, n, c, G, rows_per_part, scores, base, t1, hb);
   }
 }
 

@@ -534,8 +534,7 @@ extern "C" int spin_score_select_topk(spin_ctx *ctx, int32_t batch, const void *
   if (batch == 0) return SPIN_OK;
   if (!sel || !nsel) return SPIN_ERR_INVALID;
   // (same condition as the two-launch path of stage 2: the histogram must be consumed by the launch that follows)
-  const bool fuse = ctx->ws_hist_off && workspace && ctx->cfg.score_kind == SPIN_SCORE_SKETCH &&
-                    batch * ctx->cfg.num_kv_heads <= 65535;
+  const bool fuse = ctx->ws_hist_off && workspace && batch * ctx->cfg.num_kv_heads <= 65535;
   int32_t *hist = fuse ? (int32_t *)((char *)workspace + ctx->ws_hist_off) : nullptr;
   const int st = spin_score_impl(ctx, batch, q, summaries, chan_idx, part_offsets, seq_lens, scores, workspace, stream,
                                  hist);

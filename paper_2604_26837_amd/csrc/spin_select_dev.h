@@ -3,16 +3,6 @@
 #pragma once
 #include "spin_common.h"
 
-__device__ inline uint32_t score_key(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) u = 0xff800000u;  // NaN ranks as -inf
-  if (u == 0x80000000u) u = 0u;                          // -0 ties +0
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// bins of the chip-wide histogram of the leading 12 key bits (stage 2 of long rows)
-#define BIG_BINS 4096
-
 struct sel_plan {
   int P, nf_lo, first_hi, kprime, take;
 };

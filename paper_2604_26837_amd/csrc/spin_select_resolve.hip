@@ -235,8 +235,8 @@ extern "C" int spin_select_resolve(spin_ctx *ctx, int32_t batch, const float *sc
                              page_ids, valid_mask, npages, workspace, stream, false);
 }
 
-// Stages 1, 2 and 3 in two launches: spin_score_partitions (which, for long SKETCH rows, counts stage 2's
-// first histogram as it goes) followed by spin_select_resolve.  Same results as the three stage calls.
+// Stages 1, 2 and 3 in two launches: spin_score_partitions (which, for rows of more than 16384 partitions, counts
+// stage 2's first histogram as it goes) followed by spin_select_resolve.  Same results as the three stage calls.
 extern "C" int spin_score_select_resolve(spin_ctx *ctx, int32_t batch, const void *q, const void *summaries,
                                          const int32_t *chan_idx, const int32_t *part_offsets,
                                          const int32_t *seq_lens, float *scores, int32_t *sel, int32_t *nsel,
@@ -252,7 +252,7 @@ extern "C" int spin_score_select_resolve(spin_ctx *ctx, int32_t batch, const voi
   const bool long_rows = ctx->max_parts > 16384;
   // refuse before stage 1 is issued what the second launch would refuse
   if (c.lru_timestamps > 0 || (long_rows && !(ctx->ws_hist_off && rows <= 65535))) return SPIN_ERR_UNSUPPORTED;
-  const bool fuse = long_rows && c.score_kind == SPIN_SCORE_SKETCH;
+  const bool fuse = long_rows;   // stage 1 of every score kind counts stage 2's first histogram for long rows
   int32_t *hist = fuse ? (int32_t *)((char *)workspace + ctx->ws_hist_off) : nullptr;
   const int st = spin_score_impl(ctx, batch, q, summaries, chan_idx, part_offsets, seq_lens, scores, workspace, stream,
                                  hist);

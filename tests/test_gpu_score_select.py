@@ -1,6 +1,6 @@
 """Stages 1 and 2 in one call must give exactly what the two stage calls give:
-same score bits, same selection.  Long token rows take the path where stage 1
-counts the leading key bits for stage 2 (the histogram in the workspace must be
+same score bits, same selection.  Rows of more than 16384 partitions take the path where
+stage 1 counts the leading key bits for stage 2 (the histogram in the workspace must be
 left cleared, so the calls are repeated and interleaved); every other shape
 simply runs the two stages."""
 import numpy as np
@@ -26,6 +26,13 @@ def _workloads():
         # one short request in a context sized for long rows; k' = 0 for the request that is all forced
         "long_context_short_rows": c0.with_(seq_lens=(100, 32, 17000), topk=40, sink_pages=1, recent_pages=1,
                                             name="ss_mixed", **tok),
+        # long rows of page partitions: stage 1 of the other two score kinds counts the histogram too
+        "long_page_rows_minmax": c0.with_(seq_lens=(16 * 17000 + 5, 300000, 900), num_q_heads=4, num_kv_heads=1,
+                                          topk=200, sink_pages=3, recent_pages=6, name="ss_long_minmax"),
+        "long_page_rows_repmax": c0.with_(seq_lens=(270000, 16 * 16385), num_q_heads=6, num_kv_heads=2,
+                                          score_kind=synth.SCORE_REPMAX, reps_per_partition=2, topk=77,
+                                          topk_includes_forced=False, sink_pages=2, recent_pages=0,
+                                          name="ss_long_repmax"),
         # shapes where the combined call is the two launches
         "short_token_rows": c0.with_(seq_lens=(5000, 900), topk=64, sink_pages=1, recent_pages=1, name="ss_short", **tok),
         "pages_minmax": c0.with_(seq_lens=(4096, 1000, 2049), num_q_heads=8, num_kv_heads=2, topk=24, sink_pages=2,
@@ -78,6 +85,34 @@ def test_combined_call_equals_the_two_stage_calls(name):
                                        w.partition_tokens, w.topk, w.topk_includes_forced, w.sink_pages,
                                        w.recent_pages)
             assert sel[r, :nsel[r]].tolist() == list(want), (b, h)
+
+
+@pytest.mark.parametrize("name", ["long_token_rows", "long_page_rows_minmax", "long_page_rows_repmax"])
+def test_combined_call_saves_the_histogram_launch(name):
+    """For long rows the combined call issues no histogram launch over the score array (stage 1 has counted
+    the bins), the separate stage 2 call issues one."""
+    w = _workloads()[name]
+    data = synth.generate(w)
+    natural = torch.from_numpy(data.pool_bits.view(np.int16).copy()).to(DEV).view(torch.bfloat16)
+    layer = runner.LayerState.from_natural_pool(w, data.slot_of, natural)
+    if w.score_kind == synth.SCORE_SKETCH:
+        layer.set_channels(synth.sketch_channels(data))
+    layer.build_summaries()
+    sp = layer.spin
+    q = torch.from_numpy(synth.make_queries(w, 17).view(np.int16)).to(DEV).view(torch.bfloat16)
+    sp.profile_enable(8)
+    try:
+        sp.score_select_topk(w.batch, q, layer.summaries, layer.chan, layer.part_offsets, layer.seq_lens, layer.scores,
+                             layer.sel, layer.nsel, layer.ws)
+        torch.cuda.synchronize()
+        assert sp.profile_read("select_hist")[0] == 0 and sp.profile_read("score")[0] == 1
+        assert sp.profile_read("select")[0] == 1
+        sp.select_topk(w.batch, layer.scores, layer.part_offsets, layer.seq_lens, layer.sel, layer.nsel, layer.ws)
+        torch.cuda.synchronize()
+        assert sp.profile_read("select_hist")[0] == 1 and sp.profile_read("select")[0] == 1
+    finally:
+        sp.profile_enable(0)
+    assert layer.status() == 0
 
 
 def _heavy_ties(layer, w):
