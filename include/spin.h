@@ -480,7 +480,9 @@ int spin_sparse_decode_finish(spin_ctx *ctx, int32_t batch, const void *q, const
  * kernels run); the split-K scratch (row tickets and workgroup partials) lives in a device array
  * of SPIN_STATIC_SCRATCH_BYTES that is part of the library image: each GPU the library runs on
  * holds it until the process ends.  The call allocates and frees nothing and enqueues a small
- * clearing kernel plus the attention kernel on `stream`.
+ * clearing kernel plus the attention kernel on `stream`.  The array's device address is looked
+ * up once per device: by spin_create for the device that is current then, otherwise by the
+ * first call on that device.
  * A call needs 256 + 4 * rows + 8 * P + 512 * P bytes of it (each term rounded up to 256), with
  * rows = batch * num_kv_heads and P = rows * (2 * spin_decode_splits(ctx)) * (num_q_heads /
  * num_kv_heads) at most (the workspace's layout of partials is kept); a larger shape returns SPIN_ERR_STATIC_LIMIT before anything is launched.

@@ -131,6 +131,10 @@ extern "C" int spin_create(const spin_config *c, spin_ctx **out) {
   x->ws_acc_off = off;
   off += (size_t)x->max_rows * x->pstride * group * SPIN_HEAD_DIM * sizeof(float);
   x->ws_bytes = (off + 255) & ~(size_t)255;
+  // set-up for spin_sparse_decode_static on the device that is current now: its first call then asks the
+  // runtime for nothing (a caller may be capturing by then).  Best effort: a context may be created with no
+  // GPU present, and the entry point looks the address up itself on a device that was not prepared here.
+  (void)spin_static_scratch_prepare();
   *out = x;
   return SPIN_OK;
 }

@@ -98,6 +98,9 @@ struct spin_resolve_args {
   uint16_t *valid_mask;
   int32_t *npages;
 };
+// Looks the device address of the library's own scratch array up for the current device (kept per device
+// from then on), so that spin_sparse_decode_static need not do it on its first call.
+int spin_static_scratch_prepare(void);
 int spin_select_impl(spin_ctx *ctx, int32_t batch, const float *scores, const int32_t *part_offsets,
                      const int32_t *seq_lens, int32_t *sel, int32_t *nsel, void *workspace, void *stream,
                      bool hist_ready, const spin_resolve_args *res);

@@ -391,6 +391,11 @@ static int static_scratch(void **ptr) {
   return SPIN_OK;
 }
 
+int spin_static_scratch_prepare(void) {
+  void *p = nullptr;
+  return static_scratch(&p);
+}
+
 // clears the words that must be zero when the attention kernel starts (a kernel, not a memset, so
 // that a caller may record the call into a HIP graph)
 __global__ void spin_static_clear_kernel(int32_t *p, int n) {
