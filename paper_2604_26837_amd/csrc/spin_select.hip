@@ -487,8 +487,8 @@ int spin_select_impl(spin_ctx *ctx, int32_t batch, const float *scores, const in
     int32_t *hist = (int32_t *)((char *)workspace + ctx->ws_hist_off);
     const int words_max = ((ctx->max_parts + 63) / 64) * 2;
     const size_t lds = (size_t)words_max * 8 + (size_t)BIG_CAP * 8;
-    // at most 56 KiB for rows of 131072 partitions; the kernel's static arrays (about 5 KiB) come on top
-    if (lds + 6144 > 64 * 1024) return SPIN_ERR_UNSUPPORTED;
+    // at most 56 KiB for rows of 131072 partitions; the kernel's static arrays (under 8 KiB) come on top
+    if (lds + 8192 > 64 * 1024) return SPIN_ERR_UNSUPPORTED;
     if (!hist_ready)   // stage 1 may have counted the bins already while it produced the scores
       spin_launch(ctx, SPIN_K_SELECT_HIST, spin_select_hist_kernel,
                   dim3((unsigned)((ctx->max_parts + BIG_CHUNK - 1) / BIG_CHUNK), (unsigned)rows), dim3(256), 0,
