@@ -128,28 +128,31 @@ __device__ inline int select_reg_row(
     // Suffix scan of the 256-bin histogram `buf`, done by every wavefront for itself: digit of the
     // remaining-th largest candidate (and how many are still wanted inside it), or -1 when the
     // histogram holds fewer.  The result is uniform over the workgroup.
-    auto find_digit = [&](int buf, int &digit) {
+    auto find_digit = [&](int buf, int &digit, int &in_digit) {
       __syncthreads();
       // lane handles digits 255-4*lane .. 252-4*lane, in descending order
       int hv[4], local = 0;
 #pragma unroll
       for (int j = 0; j < 4; ++j) { hv[j] = s_hist[buf][255 - 4 * lane - j]; local += hv[j]; }
       int running = spin_wave_inclusive_scan(local) - local;
-      int my_digit = -1, my_rem = 0;
+      int my_digit = -1, my_rem = 0, my_cnt = 0;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         if (running < remaining && running + hv[j] >= remaining) {
           my_digit = 255 - 4 * lane - j;
           my_rem = remaining - running;
+          my_cnt = hv[j];
         }
         running += hv[j];
       }
       const unsigned long long found = __ballot(my_digit >= 0);
       digit = -1;
+      in_digit = 0;
       if (found) {
         const int src = __ffsll((long long)found) - 1;
         digit = __builtin_amdgcn_readlane(my_digit, src);
         remaining = __builtin_amdgcn_readlane(my_rem, src);
+        in_digit = __builtin_amdgcn_readlane(my_cnt, src);
       }
     };
 #pragma unroll
@@ -186,8 +189,8 @@ __device__ inline int select_reg_row(
             atomicAdd(&s_hist[pass][(key[k] >> lo) & dmask], 1);
         }
       }
-      int digit;
-      find_digit(pass, digit);
+      int digit, in_digit;
+      find_digit(pass, digit, in_digit);
       if (TOP8 && pass == 0 && digit < 0) {          // block-uniform: add the digits not counted yet
         __syncthreads();                             // every wavefront has scanned the partial histogram
 #pragma unroll
@@ -196,13 +199,22 @@ __device__ inline int select_reg_row(
           const uint32_t dg = (key[k] >> lo) & dmask;
           if (p >= ca && p < cb && top_digit - dg >= 8u) atomicAdd(&s_hist[0][dg], 1);
         }
-        find_digit(0, digit);
+        find_digit(0, digit, in_digit);
       }
       prefix = (prefix << width) | (uint32_t)digit;
       hi = lo;
+      // every candidate that shares this prefix is wanted: the digits below cannot change the outcome.  The
+      // threshold becomes the smallest key with the prefix, of which there may be several or none: all are
+      // wanted, and `remaining` (the candidates with the prefix) covers them.
+      if (in_digit == remaining && hi > 0) {         // block-uniform
+        prefix <<= hi;
+        break;
+      }
     }
   }
   const uint32_t T = prefix;
+  // (after the early exit above, keys above T that share the prefix are picked as `key > T` and keys equal to T
+  // within the quota, which is as large as the whole prefix: the same set either way)
   const unsigned need_eq = kprime > 0 ? (unsigned)remaining : 0u;
 
   // counts of this thread: low half = forced or above threshold, high half = equal to it
