@@ -35,11 +35,11 @@ def parse_args():
     ap.add_argument("--cpu-rows", type=int, default=32, help="rows of the workload timed on the CPU oracle")
     ap.add_argument("--cpu-reps", type=int, default=8)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "cfg3", "cfg4", "setup", "cfg1_mean"],
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "cfg3", "cfg4", "setup", "cfg1_mean", "attention_sweep"],
                     help="cfg1: the headline all-resident layer (the metric's workload); cfg2: token partitions scored "
                          "on a key sketch; cfg3: 128-token blocks with representative keys; cfg4: hierarchical HBM "
                          "budget, 64 decode steps; cfg1_mean: cfg1's shape with one mean key per page as the summary; setup: the layout, Index, append, copy and metadata kernels at "
-                         "cfg1's shape")
+                         "cfg1's shape; attention_sweep: stage 4 alone at cfg1's shape with 32 ... 128 pages per row")
     ap.add_argument("--copy-mode", default="both", choices=["memcpy", "gather", "both"])
     ap.add_argument("--budget-frac", type=float, default=0.25)
     ap.add_argument("--four-calls", action="store_true",
@@ -482,6 +482,70 @@ def run_setup(args):
     print(json.dumps(line))
 
 
+def run_attention_sweep(args):
+    """Stage 4 alone at the headline workload's shape, page lists of 32 ... 128 random resident pages per row:
+    the kernel's own duration (HIP events on the launch stream) against the pages per row, and the straight
+    line through it: a fixed part per launch and a rate for the bytes."""
+    import numpy as np
+    import torch
+    from paper_2604_26837_amd import binding, synth
+
+    dev = "cuda:0"
+    w = synth.config1()
+    rows, nslots, pages_per_row = w.rows, w.total_slots, w.pages(0)
+    pool = torch.empty((nslots, 4096), dtype=torch.bfloat16, device=dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    for s0 in range(0, nslots, 32768):
+        n = min(32768, nslots - s0)
+        pool[s0:s0 + n] = torch.randn((n, 4096), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    q = torch.randn((w.batch, w.num_q_heads, w.head_dim), generator=gen, device=dev).to(torch.bfloat16)
+    rng = np.random.default_rng(w.seed)
+    perm = rng.permutation(nslots).astype(np.int32)          # physical order differs from logical order
+    sp = binding.Spin.for_workload(w, decode_splits=args.decode_splits, decode_waves=args.decode_waves,
+                                   decode_depth=args.decode_depth)
+    width = sp.page_stride
+    lists = []
+    for _ in range(args.query_sets):                          # distinct page lists, so that no cache serves the pages
+        sl = np.empty((rows, width), dtype=np.int32)
+        for r in range(rows):
+            sl[r] = perm[r * pages_per_row + np.sort(rng.choice(pages_per_row, size=width, replace=False))]
+        lists.append(torch.from_numpy(sl).to(dev))
+    ws = sp.new_workspace(dev)
+    masks = torch.full((rows, width), -1, dtype=torch.int16, device=dev)
+    out = torch.zeros((w.batch, w.num_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+    points = []
+    for npr in (32, 48, 64, 80, 96, 104, 112, 116, 120, 124, 128):
+        if npr > width:
+            continue
+        npg = torch.full((rows,), npr, dtype=torch.int32, device=dev)
+        for i in range(args.warmup):
+            sp.sparse_decode(w.batch, q, pool, lists[i % len(lists)], masks, npg, out, None, ws)
+        torch.cuda.synchronize()
+        sp.profile_enable(args.steps)
+        for i in range(args.steps):
+            sp.sparse_decode(w.batch, q, pool, lists[i % len(lists)], masks, npg, out, None, ws)
+        torch.cuda.synchronize()
+        n, mean, mn = sp.profile_read("decode")
+        sp.profile_enable(0)
+        nbytes = rows * npr * 8192
+        points.append(dict(pages_per_row=npr, bytes=nbytes, mean_us=round(mean, 2), min_us=round(mn, 2),
+                           gbps=round(nbytes / mean / 1e3, 1), pct_peak=round(nbytes / mean / 1e3 / 80.0, 1)))
+    assert sp.poll_status(ws) == 0, "device fault during the sweep"
+    x = np.array([p["bytes"] for p in points], dtype=np.float64)
+    y = np.array([p["mean_us"] for p in points], dtype=np.float64)
+    slope, fixed = np.polyfit(x, y, 1)                        # us per byte, us
+    resid = y - (fixed + slope * x)
+    print(json.dumps({
+        "metric": "stage-4 kernel duration against the pages per row (cfg1's shape: 128 rows, 8 KiB pages, random slots)",
+        "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg1_attention_pages_per_row_sweep", "rows": rows, "decode_splits": sp.decode_splits,
+                   "decode_waves": args.decode_waves or 8},
+        "points": points,
+        "fit": {"fixed_us_per_launch": round(float(fixed), 2), "marginal_gbps": round(1e-3 / float(slope), 0),
+                "max_abs_residual_us": round(float(np.abs(resid).max()), 2)}}))
+
+
 def main():
     args = parse_args()
     if args.print_source_hash:
@@ -515,6 +579,9 @@ def main():
         return
     if args.workload == "setup":
         run_setup(args)
+        return
+    if args.workload == "attention_sweep":
+        run_attention_sweep(args)
         return
     if args.workload == "cfg1_mean":
         # the headline shape scored the way the paper's page-partition algorithm does: one mean key
